@@ -1,0 +1,173 @@
+"""fp64 CPU oracle for the SnapKV prompt-KV compression step (arXiv 2404.14469).
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain definition the HIP path is
+checked against.  Nothing in the product imports it; it imports nothing from the
+product.  Only tests, the smoke check and the bench's cpu_baseline leg call it.
+
+SnapKV is a heuristic defined by its procedure (Sec. 4.1, Listing 1; Eq. 1-2), so the
+oracle is that procedure, step by step, in the paper's order, in float64 on the exact
+input values (bf16 / fp32 widened exactly):
+
+  1. logits  s[i, j] = q_i . k_j / sqrt(D) for the last W prompt queries against all L
+     keys (Listing 1, the compute_attn call; the scale is the standard one - the paper
+     leaves compute_attn undefined).
+  2. prompt-phase causal mask: window query i sits at position n + i (n = L - W), so key
+     j is hidden when j > n + i.  Only the trailing W x W block is affected.
+  3. row softmax over all L keys ("softmax-normalized attention features", Sec. 4).
+  4. vote[j] = sum over the W window rows, prefix columns j < n only (Eq. 1; the upper
+     limit printed there would give W+1 terms, Listing 1 sums exactly the W rows).
+  5. 1-D pooling with kernel p, stride 1, padding p//2 (Sec. 4.3, Listing 1): max pooling
+     ignores positions outside [0, n); average pooling pads with zeros and always divides
+     by p.  Pooling never sees window columns (they are sliced off before it).
+  6. GQA (the paper's listing has equal head counts): pooled votes are summed over the
+     g = Hq/Hkv query heads of a KV group *after* pooling; selection is per KV head.
+  7. top-(C - W) positions per head (Eq. 2 / Listing 1), ties broken to the lower index,
+     emitted in ascending position order.
+  8. kept rows = selected prefix rows followed by the W window rows (Listing 1, the two
+     gathers and concatenations).
+  9. short prompts (L <= C) are returned unchanged (Listing 1, the first branch).
+
+Pins (tests/test_oracle_*.py): closed forms for all-zero queries (harmonic numbers, both
+pool kinds and the tie rule), softmax rows summing to one, mass conservation, shift
+invariance, permutation equivariance, nested selections, the W=1/p=1 special case against
+a plain sort of raw logits, a planted one-hot key, torch-CPU library routines for the MHA
+case, a pure-Python loop enumeration on tiny inputs and an independently written plain-C
+version (oracle/snapkv_oracle.c).  No function here is unpinned.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+POOL_MAX = 0
+POOL_AVG = 1
+
+
+def widen(x: np.ndarray) -> np.ndarray:
+    """Exact float64 view of the stored values: float arrays as is, uint16 as bf16 bit patterns."""
+    x = np.asarray(x)
+    if x.dtype == np.uint16:
+        return (x.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    if x.dtype in (np.float32, np.float64):
+        return x.astype(np.float64)
+    raise TypeError(f"unsupported storage dtype {x.dtype}")
+
+
+def window_probs(q_h: np.ndarray, k_h: np.ndarray) -> np.ndarray:
+    """Steps 1-3 for one query head: P[W, L], each row a softmax over the keys it may see."""
+    q = widen(q_h)
+    k = widen(k_h)
+    W, D = q.shape
+    L = k.shape[0]
+    n = L - W
+    s = (q @ k.T) / np.sqrt(np.float64(D))                      # step 1
+    j = np.arange(L)[None, :]
+    i = np.arange(W)[:, None]
+    s = np.where(j > n + i, -np.inf, s)                         # step 2
+    s = s - s.max(axis=1, keepdims=True)                        # step 3
+    e = np.exp(s)
+    return e / e.sum(axis=1, keepdims=True)
+
+
+def vote(P: np.ndarray) -> np.ndarray:
+    """Step 4: column sum over the window rows, prefix columns only."""
+    W, L = P.shape
+    return P[:, :L - W].sum(axis=0)
+
+
+def pool1d(x: np.ndarray, pool_kind: int, p: int) -> np.ndarray:
+    """Step 5: stride-1 pooling with padding p//2 over a 1-D score vector."""
+    if p < 1 or p % 2 == 0:
+        raise ValueError("pool kernel must be odd and >= 1")
+    n = x.shape[0]
+    r = p // 2
+    out = np.empty(n, dtype=np.float64)
+    for jj in range(n):
+        lo, hi = max(0, jj - r), min(n - 1, jj + r)
+        seg = x[lo:hi + 1]
+        if pool_kind == POOL_MAX:
+            out[jj] = seg.max()
+        elif pool_kind == POOL_AVG:
+            out[jj] = seg.sum() / p
+        else:
+            raise ValueError("pool_kind must be 0 (max) or 1 (avg)")
+    return out
+
+
+def _pool1d_fast(x: np.ndarray, pool_kind: int, p: int) -> np.ndarray:
+    """Same values as pool1d, vectorised so that 131072-long rows finish quickly.
+
+    Max: out-of-range taps are -inf (bitwise equal to pool1d).  Avg: out-of-range taps are 0;
+    the order in which the p taps are added may differ from pool1d's, so tests compare the
+    two to 1e-14 relative rather than bitwise.
+    """
+    n = x.shape[0]
+    r = p // 2
+    pad = -np.inf if pool_kind == POOL_MAX else 0.0
+    xp = np.concatenate([np.full(r, pad), x, np.full(r, pad)])
+    taps = np.stack([xp[t:t + n] for t in range(p)], axis=0)
+    if pool_kind == POOL_MAX:
+        return taps.max(axis=0)
+    if pool_kind == POOL_AVG:
+        return taps.sum(axis=0) / p
+    raise ValueError("pool_kind must be 0 (max) or 1 (avg)")
+
+
+def pooled_scores(q_win: np.ndarray, k: np.ndarray, W: int, pool_kind: int, p: int,
+                  kv_heads=None) -> np.ndarray:
+    """Steps 1-6: score[Hkv, n] (or only the listed KV heads, in the order given)."""
+    Hq = q_win.shape[0]
+    Hkv, L, _ = k.shape
+    if Hq % Hkv:
+        raise ValueError("Hq must be a multiple of Hkv")
+    if q_win.shape[1] != W or W < 1 or W > L:
+        raise ValueError("bad window")
+    if p < 1 or p % 2 == 0:
+        raise ValueError("pool kernel must be odd and >= 1")
+    g = Hq // Hkv
+    n = L - W
+    heads = range(Hkv) if kv_heads is None else list(kv_heads)
+    out = np.zeros((len(heads), n), dtype=np.float64)
+    for oi, hk in enumerate(heads):
+        for h in range(hk * g, (hk + 1) * g):
+            v_h = vote(window_probs(q_win[h], k[hk]))
+            out[oi] += _pool1d_fast(v_h, pool_kind, p)              # step 6: pool, then group sum
+    return out
+
+
+def select(score: np.ndarray, kcount: int) -> np.ndarray:
+    """Step 7: the kcount best positions under (score descending, index ascending), ascending."""
+    n = score.shape[0]
+    if kcount < 0 or kcount > n:
+        raise ValueError("kcount out of range")
+    order = np.argsort(-score, kind="stable")       # stable: equal scores stay in index order
+    return np.sort(order[:kcount]).astype(np.int64)
+
+
+def compress(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, W: int, pool_kind: int, p: int,
+             C: int, kv_heads=None):
+    """The whole step.  Returns (out_k, out_v, out_idx, kept, score).
+
+    out_k/out_v are [H, kept, D] in the *storage* dtype of k/v (rows copied, never recomputed),
+    out_idx is [H, kept] int64, kept = min(C, L), score is [H, n] float64 (None on bypass).
+    """
+    Hkv, L, D = k.shape
+    if v.shape != k.shape:
+        raise ValueError("k and v must have the same shape")
+    if W > C:
+        raise ValueError("window larger than capacity")
+    heads = list(range(Hkv)) if kv_heads is None else list(kv_heads)
+    if L <= C:                                                     # step 9
+        idx = np.tile(np.arange(L, dtype=np.int64), (len(heads), 1))
+        return k[heads].copy(), v[heads].copy(), idx, L, None
+    n = L - W
+    score = pooled_scores(q_win, k, W, pool_kind, p, kv_heads=heads)
+    out_idx = np.empty((len(heads), C), dtype=np.int64)
+    out_k = np.empty((len(heads), C, D), dtype=k.dtype)
+    out_v = np.empty((len(heads), C, D), dtype=v.dtype)
+    for oi, hk in enumerate(heads):
+        sel = select(score[oi], C - W)                             # step 7
+        idx = np.concatenate([sel, np.arange(n, L, dtype=np.int64)])   # step 8
+        out_idx[oi] = idx
+        out_k[oi] = k[hk][idx]
+        out_v[oi] = v[hk][idx]
+    return out_k, out_v, out_idx, C, score
