@@ -1,0 +1,127 @@
+/*
+ * snapkv.h - C ABI of the MI355X (gfx950) SnapKV prompt-KV compression library.
+ *
+ * The operation is the one defined in Sec. 4.1 / Listing 1 and Eq. 1-2 of "SnapKV: LLM Knows
+ * What You are Looking for Before Generation" (arXiv 2404.14469): for every attention head,
+ * score all prompt keys against the last W prompt queries (the observation window) with a
+ * causal row softmax, sum the probabilities over the window (voting, Eq. 1), pool the votes
+ * along the sequence (Sec. 4.3), keep the top C-W prefix positions per head (Eq. 2) and store
+ * their K/V rows followed by the W window rows.
+ *
+ * Conventions fixed by this library where the paper is silent:
+ *   - logits are scaled by 1/sqrt(D); window query i sits at position (L-W)+i and cannot see
+ *     later keys (prompt-phase causal mask); the softmax runs over all visible keys.
+ *   - pooling is stride 1 with padding p/2: max ignores the padding, average counts it as
+ *     zeros and always divides by p.  p must be odd; p = 1 means no pooling.
+ *   - grouped-query attention: votes are pooled per query head, then summed over the
+ *     g = Hq/Hkv query heads that share a KV head; selection is per KV head.
+ *   - ties in the top-(C-W) go to the lower position; kept positions are emitted ascending.
+ *   - prompts with L <= C are returned unchanged (Listing 1, first branch).
+ *
+ * All pointers named "device" are GPU global memory owned by the caller, row-major and
+ * contiguous, 16-byte aligned.  Inputs are read-only and must not alias outputs.  Calls only
+ * enqueue work on `stream` (a hipStream_t passed as void*, NULL = the default stream) and
+ * never synchronise; outputs are valid once the stream reaches the end of the enqueued work.
+ * Every entry point validates its arguments on the host before touching the GPU and returns
+ * a negative SNAPKV_ERR_* code on failure; nothing has been enqueued in that case unless the
+ * code is SNAPKV_ERR_HIP.
+ */
+#ifndef SNAPKV_H_
+#define SNAPKV_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SNAPKV_POOL_MAX 0
+#define SNAPKV_POOL_AVG 1
+
+#define SNAPKV_DTYPE_BF16 0 /* bfloat16 q/k/v */
+#define SNAPKV_DTYPE_F32 1  /* IEEE float32 q/k/v */
+
+#define SNAPKV_OK 0
+#define SNAPKV_ERR_INVALID_ARG (-1) /* null pointer, L<1, W<1, W>L, W>C, even p, bad pool_kind, Hq%Hkv!=0 */
+#define SNAPKV_ERR_UNSUPPORTED (-2) /* D not in {64,128}, p>129, L>=2^31, too many window rows */
+#define SNAPKV_ERR_MISALIGNED (-3)  /* a q/k/v/out_k/out_v pointer is not 16-byte aligned */
+#define SNAPKV_ERR_WORKSPACE (-4)   /* workspace missing or smaller than snapkv_workspace_bytes() */
+#define SNAPKV_ERR_HIP (-5)         /* a HIP call (allocation or launch) failed */
+
+/* Library version: major*10000 + minor*100 + patch. */
+int snapkv_version(void);
+
+/* Static, human-readable text for a SNAPKV_ERR_* code (never NULL). */
+const char* snapkv_strerror(int code);
+
+/*
+ * The whole compression step for one prompt and one layer (Listing 1; Eq. 1-2), bf16 storage.
+ *
+ *   q_win   [Hq, W, D]   device, bf16: the last W prompt queries of every query head
+ *   k, v    [Hkv, L, D]  device, bf16: all prompt keys / values
+ *   L       prompt length; Hq, Hkv head counts (Hq % Hkv == 0); D in {64, 128}; W window length
+ *   pool_kind SNAPKV_POOL_MAX or SNAPKV_POOL_AVG; p odd pooling width (1..129); C capacity (>= W)
+ *   out_k, out_v [Hkv, C, D] device, bf16: kept rows, prefix rows in ascending position order
+ *                            followed by the W window rows
+ *   out_idx [Hkv, C]     device, int32: the kept positions; the last W are L-W .. L-1
+ *
+ * Returns the number of rows kept per head, min(C, L).  When L <= C the prompt is copied
+ * unchanged into the first L rows of each head of out_k/out_v/out_idx and rows [L, C) are not
+ * written.  Scratch memory comes from a per-device buffer the library allocates on first use
+ * and grows when a larger problem arrives (hipMalloc; see snapkv_compress_ws for a variant that
+ * never allocates); concurrent calls on different streams of one device would share it and race.
+ */
+int64_t snapkv_compress(const void* q_win, const void* k, const void* v, int64_t L, int Hq, int Hkv,
+                        int D, int W, int pool_kind, int p, int64_t C, void* out_k, void* out_v,
+                        int32_t* out_idx, void* stream);
+
+/* Same operation with float32 q/k/v and float32 out_k/out_v. */
+int64_t snapkv_compress_f32(const void* q_win, const void* k, const void* v, int64_t L, int Hq,
+                            int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k,
+                            void* out_v, int32_t* out_idx, void* stream);
+
+/*
+ * Steps 1-3 only (window scores, voting per Eq. 1, pooling per Sec. 4.3, group sum):
+ *   out_scores [Hkv, L-W] device, float32: the pooled score of every prefix position.
+ * These are bit-for-bit the scores snapkv_compress selects from.  Returns SNAPKV_OK or <0.
+ */
+int snapkv_pooled_scores(const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D, int W,
+                         int pool_kind, int p, float* out_scores, void* stream);
+int snapkv_pooled_scores_f32(const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D,
+                             int W, int pool_kind, int p, float* out_scores, void* stream);
+
+/*
+ * Bytes of device scratch one call with these shapes needs (0 if the shapes are invalid).
+ * The size does not depend on dtype, pooling or C.
+ */
+size_t snapkv_workspace_bytes(int64_t L, int Hq, int Hkv, int D, int W);
+
+/*
+ * snapkv_compress / snapkv_compress_f32 with caller-provided scratch: `dtype` is
+ * SNAPKV_DTYPE_*, `workspace` is device memory, 256-byte aligned, of at least
+ * snapkv_workspace_bytes(L, Hq, Hkv, D, W) bytes, owned by the caller and free to reuse once
+ * the enqueued work has finished.  The library keeps no pointer to it after the stream has
+ * drained.  Calls that use distinct workspaces may run concurrently on different streams.
+ */
+int64_t snapkv_compress_ws(int dtype, const void* q_win, const void* k, const void* v, int64_t L,
+                           int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
+                           void* out_k, void* out_v, int32_t* out_idx, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/*
+ * Top-(kcount) selection alone (Eq. 2), exposed for testing the selector on arbitrary scores:
+ *   scores [H, n] device float32, all values >= +0 (their bit patterns are compared as unsigned
+ *   integers); out_idx [H, kcount] device int32: the kcount best positions per row under
+ *   (score descending, position ascending), emitted ascending.  0 <= kcount <= n < 2^31.
+ */
+int snapkv_select_topk(const float* scores, int H, int64_t n, int64_t kcount, int32_t* out_idx,
+                       void* stream);
+
+/* Frees the library's per-device scratch buffers (synchronises each device that has one). */
+void snapkv_release(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SNAPKV_H_ */

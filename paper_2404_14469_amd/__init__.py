@@ -1,0 +1,12 @@
+"""MI355X-native SnapKV prompt-KV compression (arXiv 2404.14469, Sec. 4.1 / Listing 1).
+
+The product is libsnapkv.so (HIP kernels for gfx950 behind the C ABI of include/snapkv.h);
+this package is its thin Python binding plus the seeded synthetic workload generator.
+"""
+from .binding import (DTYPE_BF16, DTYPE_F32, LIB_PATH, POOL_AVG, POOL_MAX, SYMBOLS, SnapKVError,
+                      compress, load, snapkv_compress, snapkv_pooled_scores, snapkv_release,
+                      snapkv_select_topk, snapkv_strerror, snapkv_version, snapkv_workspace_bytes)
+
+__all__ = ["DTYPE_BF16", "DTYPE_F32", "LIB_PATH", "POOL_AVG", "POOL_MAX", "SYMBOLS", "SnapKVError",
+           "compress", "load", "snapkv_compress", "snapkv_pooled_scores", "snapkv_release",
+           "snapkv_select_topk", "snapkv_strerror", "snapkv_version", "snapkv_workspace_bytes"]

@@ -1,0 +1,183 @@
+"""ctypes binding of libsnapkv.so: argument marshalling only, same names as include/snapkv.h.
+
+Every step of the path runs in the HIP kernels behind the C ABI.  PyTorch appears here only as
+the owner of device memory and of the stream the work is enqueued on.  There is no fallback:
+if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libsnapkv.so")
+
+POOL_MAX, POOL_AVG = 0, 1
+DTYPE_BF16, DTYPE_F32 = 0, 1
+
+SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compress_f32",
+           "snapkv_pooled_scores", "snapkv_pooled_scores_f32", "snapkv_workspace_bytes",
+           "snapkv_compress_ws", "snapkv_select_topk", "snapkv_release")
+
+_lib = None
+
+
+class SnapKVError(RuntimeError):
+    def __init__(self, code: int, text: str):
+        super().__init__(f"snapkv error {code}: {text}")
+        self.code = code
+
+
+def load():
+    """Load libsnapkv.so (built in-tree by paper_2404_14469_amd/build.py); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2404_14469_amd.build` "
+            "(there is no CPU fallback)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, sz = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t
+    L.snapkv_version.restype = i32
+    L.snapkv_version.argtypes = []
+    L.snapkv_strerror.restype = ctypes.c_char_p
+    L.snapkv_strerror.argtypes = [i32]
+    for name in ("snapkv_compress", "snapkv_compress_f32"):
+        f = getattr(L, name)
+        f.restype = i64
+        f.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
+    for name in ("snapkv_pooled_scores", "snapkv_pooled_scores_f32"):
+        f = getattr(L, name)
+        f.restype = i32
+        f.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, i32, vp, vp]
+    L.snapkv_workspace_bytes.restype = sz
+    L.snapkv_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
+    L.snapkv_compress_ws.restype = i64
+    L.snapkv_compress_ws.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp,
+                                     vp, vp, sz, vp]
+    L.snapkv_select_topk.restype = i32
+    L.snapkv_select_topk.argtypes = [vp, i32, i64, i64, vp, vp]
+    L.snapkv_release.restype = None
+    L.snapkv_release.argtypes = []
+    _lib = L
+    return L
+
+
+def _check(code: int) -> int:
+    if code < 0:
+        raise SnapKVError(int(code), load().snapkv_strerror(int(code)).decode())
+    return int(code)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream) if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: torch.Tensor, name: str, dtype=None) -> int:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.bfloat16:
+        return DTYPE_BF16
+    if t.dtype == torch.float32:
+        return DTYPE_F32
+    raise ValueError(f"q/k/v must be bfloat16 or float32, got {t.dtype}")
+
+
+def snapkv_version() -> int:
+    return int(load().snapkv_version())
+
+
+def snapkv_strerror(code: int) -> str:
+    return load().snapkv_strerror(int(code)).decode()
+
+
+def snapkv_workspace_bytes(L: int, Hq: int, Hkv: int, D: int, W: int) -> int:
+    return int(load().snapkv_workspace_bytes(L, Hq, Hkv, D, W))
+
+
+def snapkv_release() -> None:
+    load().snapkv_release()
+
+
+def _shapes(q_win, k):
+    Hq, W, D = q_win.shape
+    Hkv, L, D2 = k.shape
+    if D != D2:
+        raise ValueError("q_win and k disagree on head dim")
+    return Hq, Hkv, L, D, W
+
+
+def snapkv_compress(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, pool_kind: int, p: int,
+                    C: int, out_k: torch.Tensor, out_v: torch.Tensor, out_idx: torch.Tensor,
+                    stream=None, workspace: Optional[torch.Tensor] = None) -> int:
+    """q_win [Hq,W,D], k/v [Hkv,L,D] -> out_k/out_v [Hkv,C,D], out_idx [Hkv,C] int32; returns rows kept.
+
+    bf16 tensors go to snapkv_compress, fp32 tensors to snapkv_compress_f32; with `workspace`
+    (a uint8 GPU tensor) the call goes to snapkv_compress_ws and never allocates.
+    """
+    lib = load()
+    Hq, Hkv, L, D, W = _shapes(q_win, k)
+    code = _dtype_code(k)
+    if v.shape != k.shape:
+        raise ValueError("k and v must have the same shape")
+    if tuple(out_k.shape) != (Hkv, C, D) or tuple(out_v.shape) != (Hkv, C, D):
+        raise ValueError("out_k/out_v must be [Hkv, C, D]")
+    if tuple(out_idx.shape) != (Hkv, C):
+        raise ValueError("out_idx must be [Hkv, C]")
+    ptrs = (_dev(q_win, "q_win", k.dtype), _dev(k, "k"), _dev(v, "v", k.dtype))
+    outs = (_dev(out_k, "out_k", k.dtype), _dev(out_v, "out_v", k.dtype),
+            _dev(out_idx, "out_idx", torch.int32))
+    if workspace is not None:
+        wp = _dev(workspace, "workspace", torch.uint8)
+        return _check(lib.snapkv_compress_ws(code, *ptrs, L, Hq, Hkv, D, W, pool_kind, p, C, *outs, wp,
+                                             workspace.numel(), _stream(stream)))
+    fn = lib.snapkv_compress if code == DTYPE_BF16 else lib.snapkv_compress_f32
+    return _check(fn(*ptrs, L, Hq, Hkv, D, W, pool_kind, p, C, *outs, _stream(stream)))
+
+
+def snapkv_pooled_scores(q_win: torch.Tensor, k: torch.Tensor, pool_kind: int, p: int,
+                         out_scores: torch.Tensor, stream=None) -> None:
+    """out_scores [Hkv, L-W] float32."""
+    lib = load()
+    Hq, Hkv, L, D, W = _shapes(q_win, k)
+    code = _dtype_code(k)
+    if tuple(out_scores.shape) != (Hkv, L - W):
+        raise ValueError("out_scores must be [Hkv, L-W]")
+    fn = lib.snapkv_pooled_scores if code == DTYPE_BF16 else lib.snapkv_pooled_scores_f32
+    _check(fn(_dev(q_win, "q_win", k.dtype), _dev(k, "k"), L, Hq, Hkv, D, W, pool_kind, p,
+              _dev(out_scores, "out_scores", torch.float32), _stream(stream)))
+
+
+def snapkv_select_topk(scores: torch.Tensor, kcount: int, out_idx: torch.Tensor, stream=None) -> None:
+    """scores [H, n] float32 (>= +0) -> out_idx [H, kcount] int32, ascending positions."""
+    lib = load()
+    H, n = scores.shape
+    if tuple(out_idx.shape) != (H, kcount):
+        raise ValueError("out_idx must be [H, kcount]")
+    _check(lib.snapkv_select_topk(_dev(scores, "scores", torch.float32), H, n, kcount,
+                                  _dev(out_idx, "out_idx", torch.int32), _stream(stream)))
+
+
+def compress(q_win, k, v, pool_kind: int, p: int, C: int, stream=None
+             ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor, int]:
+    """Convenience wrapper: allocates the outputs with torch and returns (out_k, out_v, out_idx, kept)."""
+    Hkv, L, D = k.shape
+    out_k = torch.empty((Hkv, C, D), dtype=k.dtype, device=k.device)
+    out_v = torch.empty((Hkv, C, D), dtype=k.dtype, device=k.device)
+    out_idx = torch.empty((Hkv, C), dtype=torch.int32, device=k.device)
+    kept = snapkv_compress(q_win, k, v, pool_kind, p, C, out_k, out_v, out_idx, stream=stream)
+    return out_k, out_v, out_idx, kept

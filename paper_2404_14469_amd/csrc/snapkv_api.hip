@@ -1,0 +1,209 @@
+// Host side of the C ABI declared in include/snapkv.h: argument validation, scratch layout and
+// the launch plan.  Nothing here synchronises the stream.
+#include "../../include/snapkv.h"
+#include "snapkv_internal.h"
+
+#include <mutex>
+
+namespace {
+
+using namespace snapkv;
+
+constexpr int kMaxDevices = 64;
+struct DeviceScratch {
+    void* ptr = nullptr;
+    size_t bytes = 0;
+};
+DeviceScratch g_scratch[kMaxDevices];
+std::mutex g_mu;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Shape checks shared by every entry point that scores (steps 1-3).
+int check_score_args(const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D, int W,
+                     int pool_kind, int p) {
+    if (!q_win || !k) return SNAPKV_ERR_INVALID_ARG;
+    if (L < 1 || W < 1 || W > L || Hq < 1 || Hkv < 1 || Hq % Hkv != 0) return SNAPKV_ERR_INVALID_ARG;
+    if (p < 1 || (p & 1) == 0) return SNAPKV_ERR_INVALID_ARG;
+    if (pool_kind != SNAPKV_POOL_MAX && pool_kind != SNAPKV_POOL_AVG) return SNAPKV_ERR_INVALID_ARG;
+    if (D != 64 && D != 128) return SNAPKV_ERR_UNSUPPORTED;
+    if (p > 129) return SNAPKV_ERR_UNSUPPORTED;
+    if (L >= (int64_t)1 << 31) return SNAPKV_ERR_UNSUPPORTED;
+    if ((int64_t)(Hq / Hkv) * ((W + 31) / 32) > 4096) return SNAPKV_ERR_UNSUPPORTED;
+    if (Hkv > 65535) return SNAPKV_ERR_UNSUPPORTED;
+    if (!aligned16(q_win) || !aligned16(k)) return SNAPKV_ERR_MISALIGNED;
+    return SNAPKV_OK;
+}
+
+int internal_scratch(size_t need, void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SNAPKV_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceScratch& s = g_scratch[dev];
+    if (s.bytes < need) {
+        if (s.ptr) {
+            // hipFree waits for the device, so work still reading the old buffer has finished
+            if (hipFree(s.ptr) != hipSuccess) return SNAPKV_ERR_HIP;
+            s.ptr = nullptr;
+            s.bytes = 0;
+        }
+        const size_t want = need + need / 4;
+        if (hipMalloc(&s.ptr, want) != hipSuccess) {
+            s.ptr = nullptr;
+            (void)hipGetLastError();
+            return SNAPKV_ERR_HIP;
+        }
+        s.bytes = want;
+    }
+    *out = s.ptr;
+    return SNAPKV_OK;
+}
+
+int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGeom& G,
+               const Workspace& ws, int pool_kind, int p, float* score, hipStream_t st) {
+    if (launch_score(dtype, D, q_win, k, G, ws, st) != hipSuccess) return SNAPKV_ERR_HIP;
+    if (launch_pool(G, ws.vote, pool_kind, p, score, st) != hipSuccess) return SNAPKV_ERR_HIP;
+    return SNAPKV_OK;
+}
+
+int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v, int64_t L, int Hq,
+                      int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k,
+                      void* out_v, int32_t* out_idx, void* workspace, size_t workspace_bytes,
+                      bool own_scratch, void* stream) {
+    if (dtype != SNAPKV_DTYPE_BF16 && dtype != SNAPKV_DTYPE_F32) return SNAPKV_ERR_INVALID_ARG;
+    int rc = check_score_args(q_win, k, L, Hq, Hkv, D, W, pool_kind, p);
+    if (rc != SNAPKV_OK) return rc;
+    if (!v || !out_k || !out_v || !out_idx) return SNAPKV_ERR_INVALID_ARG;
+    if (C < 1 || W > C) return SNAPKV_ERR_INVALID_ARG;
+    if (C >= (int64_t)1 << 31) return SNAPKV_ERR_UNSUPPORTED;
+    if (!aligned16(v) || !aligned16(out_k) || !aligned16(out_v)) return SNAPKV_ERR_MISALIGNED;
+    if ((reinterpret_cast<uintptr_t>(out_idx) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int row_bytes = D * (dtype == SNAPKV_DTYPE_BF16 ? 2 : 4);
+
+    if (L <= C) {   // Listing 1, first branch: the prompt already fits
+        if (launch_iota(Hkv, L, C, out_idx, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        if (launch_gather(k, v, out_idx, Hkv, L, L, C, row_bytes, out_k, out_v, st) != hipSuccess)
+            return SNAPKV_ERR_HIP;
+        return L;
+    }
+
+    const ScoreGeom G = make_geom(L, Hq, Hkv, D, W);
+    const size_t need = workspace_layout(G, nullptr, nullptr);
+    void* base = workspace;
+    if (own_scratch) {
+        rc = internal_scratch(need, &base);
+        if (rc != SNAPKV_OK) return rc;
+    } else {
+        if (!workspace || workspace_bytes < need) return SNAPKV_ERR_WORKSPACE;
+        if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SNAPKV_ERR_MISALIGNED;
+    }
+    Workspace ws;
+    workspace_layout(G, &ws, base);
+    rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, st);
+    if (rc != SNAPKV_OK) return rc;
+    if (launch_select(ws.score, Hkv, G.n, C - W, C, W, out_idx, st) != hipSuccess) return SNAPKV_ERR_HIP;
+    if (launch_gather(k, v, out_idx, Hkv, L, C, C, row_bytes, out_k, out_v, st) != hipSuccess)
+        return SNAPKV_ERR_HIP;
+    return C;
+}
+
+int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D, int W,
+                int pool_kind, int p, float* out_scores, void* stream) {
+    int rc = check_score_args(q_win, k, L, Hq, Hkv, D, W, pool_kind, p);
+    if (rc != SNAPKV_OK) return rc;
+    if (!out_scores) return SNAPKV_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(out_scores) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
+    if (L == W) return SNAPKV_OK;   // empty prefix: nothing to score
+    const ScoreGeom G = make_geom(L, Hq, Hkv, D, W);
+    void* base = nullptr;
+    rc = internal_scratch(workspace_layout(G, nullptr, nullptr), &base);
+    if (rc != SNAPKV_OK) return rc;
+    Workspace ws;
+    workspace_layout(G, &ws, base);
+    return run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, out_scores, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+int snapkv_version(void) { return 100; }
+
+const char* snapkv_strerror(int code) {
+    switch (code) {
+        case SNAPKV_OK: return "ok";
+        case SNAPKV_ERR_INVALID_ARG: return "invalid argument";
+        case SNAPKV_ERR_UNSUPPORTED: return "unsupported shape";
+        case SNAPKV_ERR_MISALIGNED: return "pointer not sufficiently aligned";
+        case SNAPKV_ERR_WORKSPACE: return "workspace missing or too small";
+        case SNAPKV_ERR_HIP: return "HIP call failed";
+        default: return code > 0 ? "ok" : "unknown error";
+    }
+}
+
+int64_t snapkv_compress(const void* q_win, const void* k, const void* v, int64_t L, int Hq, int Hkv,
+                        int D, int W, int pool_kind, int p, int64_t C, void* out_k, void* out_v,
+                        int32_t* out_idx, void* stream) {
+    return compress_impl(SNAPKV_DTYPE_BF16, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k,
+                         out_v, out_idx, nullptr, 0, true, stream);
+}
+
+int64_t snapkv_compress_f32(const void* q_win, const void* k, const void* v, int64_t L, int Hq,
+                            int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k,
+                            void* out_v, int32_t* out_idx, void* stream) {
+    return compress_impl(SNAPKV_DTYPE_F32, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k,
+                         out_v, out_idx, nullptr, 0, true, stream);
+}
+
+int64_t snapkv_compress_ws(int dtype, const void* q_win, const void* k, const void* v, int64_t L,
+                           int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
+                           void* out_k, void* out_v, int32_t* out_idx, void* workspace,
+                           size_t workspace_bytes, void* stream) {
+    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
+                         workspace, workspace_bytes, false, stream);
+}
+
+int snapkv_pooled_scores(const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D, int W,
+                         int pool_kind, int p, float* out_scores, void* stream) {
+    return scores_impl(SNAPKV_DTYPE_BF16, q_win, k, L, Hq, Hkv, D, W, pool_kind, p, out_scores, stream);
+}
+
+int snapkv_pooled_scores_f32(const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D,
+                             int W, int pool_kind, int p, float* out_scores, void* stream) {
+    return scores_impl(SNAPKV_DTYPE_F32, q_win, k, L, Hq, Hkv, D, W, pool_kind, p, out_scores, stream);
+}
+
+size_t snapkv_workspace_bytes(int64_t L, int Hq, int Hkv, int D, int W) {
+    if (L < 1 || W < 1 || W > L || Hq < 1 || Hkv < 1 || Hq % Hkv != 0) return 0;
+    if (D != 64 && D != 128) return 0;
+    if (L >= (int64_t)1 << 31) return 0;
+    return workspace_layout(make_geom(L, Hq, Hkv, D, W), nullptr, nullptr);
+}
+
+int snapkv_select_topk(const float* scores, int H, int64_t n, int64_t kcount, int32_t* out_idx,
+                       void* stream) {
+    if (!scores || !out_idx) return SNAPKV_ERR_INVALID_ARG;
+    if (H < 1 || n < 1 || kcount < 0 || kcount > n) return SNAPKV_ERR_INVALID_ARG;
+    if (n >= (int64_t)1 << 31) return SNAPKV_ERR_UNSUPPORTED;
+    if (kcount == 0) return SNAPKV_OK;
+    if (launch_select(scores, H, n, kcount, kcount, 0, out_idx, static_cast<hipStream_t>(stream)) !=
+        hipSuccess)
+        return SNAPKV_ERR_HIP;
+    return SNAPKV_OK;
+}
+
+void snapkv_release(void) {
+    std::lock_guard<std::mutex> lock(g_mu);
+    int cur = 0;
+    const bool have_cur = hipGetDevice(&cur) == hipSuccess;
+    for (int d = 0; d < kMaxDevices; ++d) {
+        if (!g_scratch[d].ptr) continue;
+        if (hipSetDevice(d) == hipSuccess) (void)hipFree(g_scratch[d].ptr);
+        g_scratch[d].ptr = nullptr;
+        g_scratch[d].bytes = 0;
+    }
+    if (have_cur) (void)hipSetDevice(cur);
+}
+
+}  // extern "C"

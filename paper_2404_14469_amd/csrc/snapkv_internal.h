@@ -1,0 +1,59 @@
+// Internal declarations shared by the host dispatcher and the kernel translation units.
+// Nothing here is part of the public ABI (include/snapkv.h).
+#ifndef SNAPKV_INTERNAL_H_
+#define SNAPKV_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace snapkv {
+
+// Keys per wave-task in the scoring kernels: KT tiles of 32 keys.
+constexpr int kTileKeys = 32;
+constexpr int kTilesPerChunk = 4;
+constexpr int kChunkKeys = kTileKeys * kTilesPerChunk;
+
+// How the g*W observation-window rows of one KV head are laid onto 32-row MFMA blocks.
+//   W <= 16 ("mode16"): a block holds two query heads, 16 rows each (rows >= W are padding).
+//   W  > 16           : a head takes BH = ceil(W/32) blocks of its own (rows >= W are padding).
+// A "vote row" is one fp32 vector of length n produced by one block (or half block in mode16).
+struct ScoreGeom {
+    int64_t L;       // prompt length
+    int64_t n;       // prefix length L - W
+    int W;           // observation window
+    int g;           // query heads per KV head
+    int Hkv;         // KV heads
+    int mode16;      // 1 when W <= 16
+    int BH;          // 32-row blocks per query head (when !mode16)
+    int R32;         // 32-row blocks per KV head
+    int NV;          // vote rows per KV head
+    int VB;          // vote rows per query head
+    int nchunks;     // ceil(L / kChunkKeys)
+    float c2;        // log2(e) / sqrt(D): logits are kept in the base-2 domain
+};
+
+struct Workspace {
+    float2* part;    // [Hkv][nchunks][R32][32] per-chunk (row max, row sum-exp) in base-2 domain
+    float2* mz;      // [Hkv][R32][32]          (row max, 1 / row sum-exp); (0, 0) for padding rows
+    float* vote;     // [Hkv][NV][n]
+    float* score;    // [Hkv][n]
+};
+
+ScoreGeom make_geom(int64_t L, int Hq, int Hkv, int D, int W);
+size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base);
+
+// All launchers enqueue on `st` and return the launch status.
+hipError_t launch_score(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
+                        const Workspace& ws, hipStream_t st);
+hipError_t launch_pool(const ScoreGeom& G, const float* vote, int pool_kind, int p, float* score,
+                       hipStream_t st);
+hipError_t launch_select(const float* score, int H, int64_t n, int64_t kcount, int64_t out_stride,
+                         int W_tail, int32_t* out_idx, hipStream_t st);
+hipError_t launch_iota(int H, int64_t rows, int64_t out_stride, int32_t* out_idx, hipStream_t st);
+hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H, int64_t L,
+                         int64_t rows, int64_t out_stride, int row_bytes, void* out_k, void* out_v,
+                         hipStream_t st);
+
+}  // namespace snapkv
+#endif
