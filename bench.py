@@ -1,0 +1,165 @@
+#!/usr/bin/env python3
+"""Throughput of the SnapKV prompt-KV compression step on one MI355X.
+
+A step is one call of the whole hot path (score -> vote -> pool -> top-k -> gather) on one layer of
+the workload, inputs resident in HBM.  Steps cycle over several distinct resident layers so that no
+step finds its K/V in a cache left by the previous one.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload long_131k]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def algorithmic_bytes(w):
+    """Bytes the method must move per call: K once, the kept K/V rows read and written, the kept
+    positions, the window queries.  V is never streamed, only gathered."""
+    e = 2 if w.dtype == "bf16" else 4
+    scan = w.Hkv * w.L * w.D * e + w.Hq * w.W * w.D * e
+    gather = w.Hkv * (4 * w.C * w.D * e + 4 * w.C)
+    return scan, gather
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=32)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--workload", default="long_131k",
+                    help="long_131k (default, the configuration the metric is quoted on), "
+                         "llama2_7b_16k, mistral_7b_gqa_32k, tiny")
+    ap.add_argument("--resident-layers", type=int, default=4,
+                    help="distinct layers kept in HBM and cycled through")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (heads, layers and prompts are independent; "
+              "no multi-GPU path exists) - run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import torch
+    import paper_2404_14469_amd as snapkv
+    from paper_2404_14469_amd import workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    snapkv.load()
+    w = workloads.CONFIGS[args.workload]
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    nres = max(1, min(args.resident_layers, max(w.layers, 1) if w.layers > 1 else args.resident_layers))
+    layers = []
+    for l in range(nres):
+        c = workloads.generate(w, layer=l, device=dev)
+        layers.append((c["q_win"], c["k"], c["v"]))
+    torch.cuda.synchronize()
+    out_k = torch.empty((w.Hkv, w.C, w.D), dtype=layers[0][1].dtype, device=dev)
+    out_v = torch.empty_like(out_k)
+    out_idx = torch.empty((w.Hkv, w.C), dtype=torch.int32, device=dev)
+    ws = torch.empty(snapkv.snapkv_workspace_bytes(w.L, w.Hq, w.Hkv, w.D, w.W), dtype=torch.uint8, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step(i):
+        q, k, v = layers[i % nres]
+        snapkv.snapkv_compress(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx, stream=stream,
+                               workspace=ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    positions = w.Hkv * w.L
+    value = positions / (ms_per_step * 1e-3)
+
+    # per-kernel durations from HIP events recorded by the library on the same stream
+    snapkv.snapkv_profile_start(args.steps)
+    for i in range(args.steps):
+        step(i)
+    stage_ms, ncalls = snapkv.snapkv_profile_stop()
+
+    scan_b, gather_b = algorithmic_bytes(w)
+    score_names = [n for n in stage_ms if n.startswith("score") or n == "reduce_rows"]
+    score_ms = sum(stage_ms[n] for n in score_names)
+    achieved = scan_b / (score_ms * 1e-3) / 1e9 if score_ms > 0 else 0.0
+    roofline = {
+        "bound": "hbm",
+        "kernel": "+".join(score_names),
+        "achieved": round(achieved, 1),
+        "peak": HBM_PEAK_GBS,
+        "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBS, 4),
+        "traffic": None,
+        "algorithmic_bytes_per_launch": scan_b,
+        "kernel_ms": round(score_ms, 4),
+        "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        "path_algorithmic_bytes": scan_b + gather_b,
+        "path_frac": round((scan_b + gather_b) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+    }
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import c_oracle
+        q, k, v = layers[0]
+        # bounded sample: a few KV heads of layer 0, sized to ~10-30 s of CPU work
+        heads = min(w.Hkv, max(1, int(2.5e10 // (w.g * w.W * w.L * w.D))))
+        g = w.g
+        qh = workloads.to_numpy_bits(q[: heads * g])
+        kh = workloads.to_numpy_bits(k[:heads])
+        vh = workloads.to_numpy_bits(v[:heads])
+        c0 = time.perf_counter()
+        _, _, oidx, _, _ = c_oracle.compress(qh, kh, vh, w.W, w.pool_kind, w.p, w.C)
+        c1 = time.perf_counter()
+        step(0)
+        torch.cuda.synchronize()
+        gidx = out_idx[:heads].cpu().numpy()
+        same = float((gidx == oidx).mean())
+        cpu = {"value": round(heads * w.L / (c1 - c0), 1), "unit": "KV-head-positions/s",
+               "cores": c_oracle.threads(), "kind": "oracle",
+               "sample": f"layer 0, KV heads 0..{heads - 1} of {w.Hkv} ({heads * w.L} positions), "
+                         f"plain-C fp64 oracle, {c1 - c0:.2f} s wall",
+               "kept_positions_identical_frac": round(same, 6)}
+
+    line = {
+        "metric": "prompt KV positions compressed/sec per GPU",
+        "value": round(value, 1),
+        "unit": "KV-head-positions/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {"workload": w.name, "L": w.L, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "W": w.W,
+                   "pool": ("max" if w.pool_kind == 0 else "avg"), "p": w.p, "C": w.C,
+                   "step": "one layer call", "resident_layers": nres,
+                   "token_layers_per_s": round(w.L / (ms_per_step * 1e-3), 1)},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -118,6 +118,20 @@ int64_t snapkv_compress_ws(int dtype, const void* q_win, const void* k, const vo
 int snapkv_select_topk(const float* scores, int H, int64_t n, int64_t kcount, int32_t* out_idx,
                        void* stream);
 
+/*
+ * Per-stage timing for benchmarks (not part of the method).  Between snapkv_profile_start and
+ * snapkv_profile_stop every compressing call (L > C) records a HIP event on its stream after
+ * each kernel of the path, for at most max_calls (1..4096) calls.  snapkv_profile_stop waits for
+ * the device, writes the mean duration in milliseconds of each stage over the recorded calls to
+ * stage_ms[0 .. snapkv_num_stages()) (host memory, may be NULL) and the number of calls averaged
+ * to *calls (host, may be NULL).  A stage is one kernel; snapkv_stage_name(i) names it.
+ * Not thread-safe; one profiling session at a time.
+ */
+int snapkv_profile_start(int max_calls);
+int snapkv_profile_stop(double* stage_ms, int* calls);
+int snapkv_num_stages(void);
+const char* snapkv_stage_name(int stage);
+
 /* Frees the library's per-device scratch buffers (synchronises each device that has one). */
 void snapkv_release(void);
 

@@ -4,9 +4,10 @@ The product is libsnapkv.so (HIP kernels for gfx950 behind the C ABI of include/
 this package is its thin Python binding plus the seeded synthetic workload generator.
 """
 from .binding import (DTYPE_BF16, DTYPE_F32, LIB_PATH, POOL_AVG, POOL_MAX, SYMBOLS, SnapKVError,
-                      compress, load, snapkv_compress, snapkv_pooled_scores, snapkv_release,
+                      compress, load, snapkv_compress, snapkv_pooled_scores, snapkv_profile_start,
+                      snapkv_profile_stop, snapkv_release,
                       snapkv_select_topk, snapkv_strerror, snapkv_version, snapkv_workspace_bytes)
 
 __all__ = ["DTYPE_BF16", "DTYPE_F32", "LIB_PATH", "POOL_AVG", "POOL_MAX", "SYMBOLS", "SnapKVError",
-           "compress", "load", "snapkv_compress", "snapkv_pooled_scores", "snapkv_release",
+           "compress", "load", "snapkv_compress", "snapkv_pooled_scores", "snapkv_profile_start", "snapkv_profile_stop", "snapkv_release",
            "snapkv_select_topk", "snapkv_strerror", "snapkv_version", "snapkv_workspace_bytes"]

@@ -20,7 +20,8 @@ DTYPE_BF16, DTYPE_F32 = 0, 1
 
 SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compress_f32",
            "snapkv_pooled_scores", "snapkv_pooled_scores_f32", "snapkv_workspace_bytes",
-           "snapkv_compress_ws", "snapkv_select_topk", "snapkv_release")
+           "snapkv_compress_ws", "snapkv_select_topk", "snapkv_release", "snapkv_profile_start",
+           "snapkv_profile_stop", "snapkv_num_stages", "snapkv_stage_name")
 
 _lib = None
 
@@ -63,6 +64,14 @@ def load():
     L.snapkv_select_topk.argtypes = [vp, i32, i64, i64, vp, vp]
     L.snapkv_release.restype = None
     L.snapkv_release.argtypes = []
+    L.snapkv_profile_start.restype = i32
+    L.snapkv_profile_start.argtypes = [i32]
+    L.snapkv_profile_stop.restype = i32
+    L.snapkv_profile_stop.argtypes = [vp, vp]
+    L.snapkv_num_stages.restype = i32
+    L.snapkv_num_stages.argtypes = []
+    L.snapkv_stage_name.restype = ctypes.c_char_p
+    L.snapkv_stage_name.argtypes = [i32]
     _lib = L
     return L
 
@@ -111,6 +120,20 @@ def snapkv_workspace_bytes(L: int, Hq: int, Hkv: int, D: int, W: int) -> int:
 
 def snapkv_release() -> None:
     load().snapkv_release()
+
+
+def snapkv_profile_start(max_calls: int) -> None:
+    _check(load().snapkv_profile_start(int(max_calls)))
+
+
+def snapkv_profile_stop():
+    """Returns ({stage name: mean ms}, calls averaged)."""
+    lib = load()
+    ns = int(lib.snapkv_num_stages())
+    ms = (ctypes.c_double * ns)()
+    calls = ctypes.c_int(0)
+    _check(lib.snapkv_profile_stop(ctypes.cast(ms, ctypes.c_void_p), ctypes.cast(ctypes.byref(calls), ctypes.c_void_p)))
+    return {lib.snapkv_stage_name(i).decode(): float(ms[i]) for i in range(ns)}, int(calls.value)
 
 
 def _shapes(q_win, k):

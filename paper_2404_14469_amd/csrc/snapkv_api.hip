@@ -4,6 +4,7 @@
 #include "snapkv_internal.h"
 
 #include <mutex>
+#include <vector>
 
 namespace {
 
@@ -16,6 +17,17 @@ struct DeviceScratch {
 };
 DeviceScratch g_scratch[kMaxDevices];
 std::mutex g_mu;
+
+// Optional per-stage timing: events recorded on the caller's stream at stage boundaries.
+struct Profile {
+    bool active = false;
+    int max_calls = 0;
+    int calls = 0;            // calls begun
+    bool in_call = false;     // between kStageBegin and kStageGather of a recorded call
+    std::vector<hipEvent_t> ev;   // [max_calls][kNumStageMarks]
+    std::vector<char> set;        // which marks were recorded
+};
+Profile g_prof;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -63,6 +75,7 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
                const Workspace& ws, int pool_kind, int p, float* score, hipStream_t st) {
     if (launch_score(dtype, D, q_win, k, G, ws, st) != hipSuccess) return SNAPKV_ERR_HIP;
     if (launch_pool(G, ws.vote, pool_kind, p, score, st) != hipSuccess) return SNAPKV_ERR_HIP;
+    stage_done(st, kStagePool);
     return SNAPKV_OK;
 }
 
@@ -100,11 +113,14 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     }
     Workspace ws;
     workspace_layout(G, &ws, base);
+    stage_done(st, kStageBegin);
     rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, st);
     if (rc != SNAPKV_OK) return rc;
     if (launch_select(ws.score, Hkv, G.n, C - W, C, W, out_idx, st) != hipSuccess) return SNAPKV_ERR_HIP;
+    stage_done(st, kStageSelect);
     if (launch_gather(k, v, out_idx, Hkv, L, C, C, row_bytes, out_k, out_v, st) != hipSuccess)
         return SNAPKV_ERR_HIP;
+    stage_done(st, kStageGather);
     return C;
 }
 
@@ -126,7 +142,74 @@ int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, 
 
 }  // namespace
 
+namespace snapkv {
+void stage_done(hipStream_t st, int stage) {
+    if (!g_prof.active) return;
+    if (stage == kStageBegin) {
+        if (g_prof.calls >= g_prof.max_calls) return;
+        ++g_prof.calls;
+        g_prof.in_call = true;
+    }
+    if (!g_prof.in_call) return;   // e.g. a scores-only call: not a recorded call
+    const size_t at = (size_t)(g_prof.calls - 1) * kNumStageMarks + stage;
+    if (hipEventRecord(g_prof.ev[at], st) == hipSuccess) g_prof.set[at] = 1;
+    if (stage == kStageGather) g_prof.in_call = false;
+}
+}  // namespace snapkv
+
 extern "C" {
+
+int snapkv_profile_start(int max_calls) {
+    if (max_calls < 1 || max_calls > 4096) return SNAPKV_ERR_INVALID_ARG;
+    if (g_prof.active) return SNAPKV_ERR_INVALID_ARG;
+    g_prof.ev.assign((size_t)max_calls * kNumStageMarks, nullptr);
+    g_prof.set.assign((size_t)max_calls * kNumStageMarks, 0);
+    for (auto& e : g_prof.ev)
+        if (hipEventCreate(&e) != hipSuccess) return SNAPKV_ERR_HIP;
+    g_prof.max_calls = max_calls;
+    g_prof.calls = 0;
+    g_prof.in_call = false;
+    g_prof.active = true;
+    return SNAPKV_OK;
+}
+
+int snapkv_profile_stop(double* stage_ms, int* calls) {
+    if (!g_prof.active) return SNAPKV_ERR_INVALID_ARG;
+    g_prof.active = false;
+    int rc = SNAPKV_OK;
+    if (hipDeviceSynchronize() != hipSuccess) rc = SNAPKV_ERR_HIP;
+    double sum[kNumStageMarks] = {0};
+    int counted = 0;
+    for (int c = 0; c < g_prof.calls && rc == SNAPKV_OK; ++c) {
+        bool whole = true;
+        for (int s = 0; s < kNumStageMarks; ++s) whole = whole && g_prof.set[(size_t)c * kNumStageMarks + s];
+        if (!whole) continue;
+        for (int s = 1; s < kNumStageMarks; ++s) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, g_prof.ev[(size_t)c * kNumStageMarks + s - 1],
+                                    g_prof.ev[(size_t)c * kNumStageMarks + s]) != hipSuccess)
+                rc = SNAPKV_ERR_HIP;
+            sum[s] += ms;
+        }
+        ++counted;
+    }
+    for (auto& e : g_prof.ev)
+        if (e) (void)hipEventDestroy(e);
+    g_prof.ev.clear();
+    g_prof.set.clear();
+    if (stage_ms)
+        for (int s = 1; s < kNumStageMarks; ++s) stage_ms[s - 1] = counted ? sum[s] / counted : 0.0;
+    if (calls) *calls = counted;
+    return rc;
+}
+
+int snapkv_num_stages(void) { return kNumStageMarks - 1; }
+
+const char* snapkv_stage_name(int stage) {
+    static const char* names[] = {"score_pass1", "reduce_rows", "score_pass2", "pool_group",
+                                  "select_topk", "gather_rows"};
+    return stage >= 0 && stage < kNumStageMarks - 1 ? names[stage] : "";
+}
 
 int snapkv_version(void) { return 100; }
 

@@ -43,6 +43,13 @@ struct Workspace {
 ScoreGeom make_geom(int64_t L, int Hq, int Hkv, int D, int W);
 size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base);
 
+// Stage boundaries for the optional per-stage timing (snapkv_profile_start/stop): when timing is
+// active, stage_done records an event on the stream after the stage's launch; otherwise it is a
+// no-op.  kStageBegin marks the start of a call.
+enum Stage { kStageBegin = 0, kStagePass1, kStageReduce, kStagePass2, kStagePool, kStageSelect,
+             kStageGather, kNumStageMarks };
+void stage_done(hipStream_t st, int stage);
+
 // All launchers enqueue on `st` and return the launch status.
 hipError_t launch_score(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                         const Workspace& ws, hipStream_t st);

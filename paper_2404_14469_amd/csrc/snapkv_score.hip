@@ -319,8 +319,11 @@ static hipError_t launch_score_t(const void* q, const void* k, const ScoreGeom& 
     const int64_t tasks = (int64_t)G.Hkv * G.nchunks * G.R32;
     const unsigned blocks = (unsigned)((tasks + 3) / 4);
     hipLaunchKernelGGL((score_pass1<T, D>), dim3(blocks), dim3(256), 0, st, q, k, ws.part, G);
+    stage_done(st, kStagePass1);
     hipLaunchKernelGGL(reduce_rows, dim3(G.R32, G.Hkv), dim3(256), 0, st, ws.part, ws.mz, G);
+    stage_done(st, kStageReduce);
     hipLaunchKernelGGL((score_pass2<T, D>), dim3(blocks), dim3(256), 0, st, q, k, ws.mz, ws.vote, G);
+    stage_done(st, kStagePass2);
     return hipGetLastError();
 }
 

@@ -87,6 +87,31 @@ def check_against_oracle(q, k, v, pool_kind, p, C, scores, out_k, out_v, out_idx
     return band_total
 
 
+def check_self_consistency(q, k, v, C, scores, out_k, out_v, out_idx, kept):
+    """Size-independent properties on every head, computed without the oracle's arithmetic:
+    positions unique/ascending/window-last, the kept set is the exact top-(C-W) of the GPU's own
+    scores with ties to the lower position, and the gathered rows are the inputs' rows bit for bit
+    (compared on the GPU with torch indexing)."""
+    Hkv, L, D = k.shape
+    W = q.shape[1]
+    n = L - W
+    assert kept == min(C, L)
+    if L <= C:
+        return
+    kc = C - W
+    idx_dev = torch.from_numpy(out_idx.astype(np.int64)).to(k.device)
+    for hk in range(Hkv):
+        idx = out_idx[hk].astype(np.int64)
+        assert np.all(np.diff(idx) > 0) and idx[0] >= 0
+        assert np.array_equal(idx[kc:], np.arange(n, L))
+        if kc > 0:
+            s = scores[hk]
+            order = np.argsort(-s.astype(np.float64), kind="stable")[:kc]
+            assert np.array_equal(idx[:kc], np.sort(order)), f"head {hk}: not the exact top-k"
+        assert torch.equal(out_k[hk].view(torch.uint8), k[hk][idx_dev[hk]].view(torch.uint8))
+        assert torch.equal(out_v[hk].view(torch.uint8), v[hk][idx_dev[hk]].view(torch.uint8))
+
+
 def gpu_vs_oracle(pkg, w, layer=0, heads=None, device="cuda"):
     case = workloads.generate(w, layer=layer, device=device)
     q, k, v = case["q_win"], case["k"], case["v"]

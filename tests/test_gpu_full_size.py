@@ -1,0 +1,53 @@
+"""The named configurations at full size, in the launch configuration bench.py times.
+
+The oracle is evaluated on sampled KV heads (one head of the longest configuration is ~1 GFLOP of
+fp64); properties that hold at any size are checked on every head."""
+import pytest
+import torch
+
+from paper_2404_14469_amd import workloads
+
+from parity import check_against_oracle, check_self_consistency, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def _run(snapkv, w, layer, heads):
+    print(f"[full-size] {w.name} layer {layer} L={w.L} Hq={w.Hq} Hkv={w.Hkv} oracle heads {heads}", flush=True)
+    case = workloads.generate(w, layer=layer, device="cuda")
+    q, k, v = case["q_win"], case["k"], case["v"]
+    res = run_gpu(snapkv, q, k, v, w.pool_kind, w.p, w.C)
+    check_self_consistency(q, k, v, w.C, *res)
+    band = check_against_oracle(q, k, v, w.pool_kind, w.p, w.C, *res, heads=heads)
+    print(f"[full-size] {w.name}: positions inside the +-1e-3 band around the threshold: {band}", flush=True)
+    return case, res
+
+
+def test_llama2_7b_16k_all_heads(snapkv):
+    w = workloads.LLAMA2_7B_16K
+    _run(snapkv, w, 0, list(range(w.Hkv)))
+
+
+@pytest.mark.parametrize("layer", [0, 31])
+def test_mistral_7b_gqa_32k(snapkv, layer):
+    w = workloads.MISTRAL_7B_GQA_32K
+    _run(snapkv, w, layer, list(range(w.Hkv)))
+
+
+@pytest.mark.parametrize("layer,heads", [(0, [0, 13, 31]), (17, [5])])
+def test_long_131k_sampled_heads_and_needle(snapkv, layer, heads):
+    w = workloads.LONG_131K
+    case, res = _run(snapkv, w, layer, heads)
+    idx = res[3]
+    for hk, pos in enumerate(case["needle_pos"]):
+        lo, hi = max(0, pos - w.p // 2), min(w.n - 1, pos + w.p // 2)
+        kept = set(idx[hk].tolist())
+        assert set(range(lo, hi + 1)) <= kept, f"head {hk}: needle at {pos} not kept with its neighbours"
+    del case, res
+    torch.cuda.empty_cache()
+
+
+def test_varlen_batch(snapkv):
+    prompts = workloads.varlen_prompts()
+    for i, w in enumerate(prompts):
+        _run(snapkv, w, 0, [i % w.Hkv, (i + 3) % w.Hkv])
