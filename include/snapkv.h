@@ -132,6 +132,21 @@ int snapkv_profile_stop(double* stage_ms, int* calls);
 int snapkv_num_stages(void);
 const char* snapkv_stage_name(int stage);
 
+/*
+ * Scoring scheme.  0 (default): prompts whose window logits fit the chip's register files are
+ * scored by the single-read kernel (K is streamed once), longer ones by the two-pass kernels
+ * (K is streamed twice).  1: always the two-pass kernels.  Both give the scores of Eq. 1 to
+ * within rounding; the setting is process-wide and meant for tests and measurements.
+ */
+int snapkv_set_scoring_scheme(int scheme);
+
+/*
+ * The single-read kernel hands row normalisers between resident workgroups and bounds every
+ * wait; a wait that gives up is counted here (0 in correct operation).  Synchronises the
+ * device.  Returns the count since the library was loaded, or a negative SNAPKV_ERR_* code.
+ */
+int64_t snapkv_sync_timeouts(void);
+
 /* Frees the library's per-device scratch buffers (synchronises each device that has one). */
 void snapkv_release(void);
 

@@ -21,7 +21,8 @@ DTYPE_BF16, DTYPE_F32 = 0, 1
 SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compress_f32",
            "snapkv_pooled_scores", "snapkv_pooled_scores_f32", "snapkv_workspace_bytes",
            "snapkv_compress_ws", "snapkv_select_topk", "snapkv_release", "snapkv_profile_start",
-           "snapkv_profile_stop", "snapkv_num_stages", "snapkv_stage_name")
+           "snapkv_profile_stop", "snapkv_num_stages", "snapkv_stage_name", "snapkv_set_scoring_scheme",
+           "snapkv_sync_timeouts")
 
 _lib = None
 
@@ -68,6 +69,10 @@ def load():
     L.snapkv_profile_start.argtypes = [i32]
     L.snapkv_profile_stop.restype = i32
     L.snapkv_profile_stop.argtypes = [vp, vp]
+    L.snapkv_set_scoring_scheme.restype = i32
+    L.snapkv_set_scoring_scheme.argtypes = [i32]
+    L.snapkv_sync_timeouts.restype = i64
+    L.snapkv_sync_timeouts.argtypes = []
     L.snapkv_num_stages.restype = i32
     L.snapkv_num_stages.argtypes = []
     L.snapkv_stage_name.restype = ctypes.c_char_p
@@ -120,6 +125,15 @@ def snapkv_workspace_bytes(L: int, Hq: int, Hkv: int, D: int, W: int) -> int:
 
 def snapkv_release() -> None:
     load().snapkv_release()
+
+
+def snapkv_set_scoring_scheme(scheme: int) -> None:
+    """0: single-read kernel where it fits (default); 1: always the two-pass kernels."""
+    _check(load().snapkv_set_scoring_scheme(int(scheme)))
+
+
+def snapkv_sync_timeouts() -> int:
+    return _check(load().snapkv_sync_timeouts())
 
 
 def snapkv_profile_start(max_calls: int) -> None:

@@ -28,6 +28,7 @@ struct Profile {
     std::vector<char> set;        // which marks were recorded
 };
 Profile g_prof;
+bool g_allow_fused = true;   // snapkv_set_scoring_scheme: tests can force the two-pass kernels
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -73,8 +74,22 @@ int internal_scratch(size_t need, void** out) {
 
 int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGeom& G,
                const Workspace& ws, int pool_kind, int p, float* score, hipStream_t st) {
-    if (launch_score(dtype, D, q_win, k, G, ws, st) != hipSuccess) return SNAPKV_ERR_HIP;
-    if (launch_pool(G, ws.vote, pool_kind, p, score, st) != hipSuccess) return SNAPKV_ERR_HIP;
+    FusedGeom F;
+    ScoreGeom Gp = G;
+    if (g_allow_fused && fused_plan(G, &F)) {   // K is read once; otherwise two passes over K
+        FusedSync S;
+        fused_sync_layout(G, F, &S, ws.fused);
+        stage_done(st, kStagePass1);
+        stage_done(st, kStageReduce);
+        stage_done(st, kStagePass2);
+        if (launch_score_fused(dtype, D, q_win, k, G, F, S, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        stage_done(st, kStageFused);
+        Gp.NV = G.g;
+        Gp.VB = 1;
+    } else if (launch_score(dtype, D, q_win, k, G, ws, st) != hipSuccess) {
+        return SNAPKV_ERR_HIP;
+    }
+    if (launch_pool(Gp, ws.vote, pool_kind, p, score, st) != hipSuccess) return SNAPKV_ERR_HIP;
     stage_done(st, kStagePool);
     return SNAPKV_OK;
 }
@@ -203,11 +218,22 @@ int snapkv_profile_stop(double* stage_ms, int* calls) {
     return rc;
 }
 
+int snapkv_set_scoring_scheme(int scheme) {
+    if (scheme != 0 && scheme != 1) return SNAPKV_ERR_INVALID_ARG;
+    g_allow_fused = scheme == 0;
+    return SNAPKV_OK;
+}
+
+int64_t snapkv_sync_timeouts(void) {
+    const unsigned v = read_sync_timeouts();
+    return v == ~0u ? (int64_t)SNAPKV_ERR_HIP : (int64_t)v;
+}
+
 int snapkv_num_stages(void) { return kNumStageMarks - 1; }
 
 const char* snapkv_stage_name(int stage) {
-    static const char* names[] = {"score_pass1", "reduce_rows", "score_pass2", "pool_group",
-                                  "select_topk", "gather_rows"};
+    static const char* names[] = {"score_pass1", "reduce_rows", "score_pass2", "score_fused",
+                                  "pool_group", "select_topk", "gather_rows"};
     return stage >= 0 && stage < kNumStageMarks - 1 ? names[stage] : "";
 }
 

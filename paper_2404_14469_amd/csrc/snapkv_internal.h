@@ -33,11 +33,26 @@ struct ScoreGeom {
     float c2;        // log2(e) / sqrt(D): logits are kept in the base-2 domain
 };
 
+// Plan of the single-read scoring kernel (snapkv_fused.hip).  A unit is a KV head; its window
+// rows form RU units of 16 rows (UH per query head), padded to RUW, a power of two; a wave keeps
+// KT tiles of 16 keys per row unit; Gg workgroups share one unit's keys; NG groups run at once.
+struct FusedGeom {
+    int RU, UH, RUW, KT, Gg, NG, NB, units;   // NB: blocks of 32 slices per row (level-1 merges)
+    int64_t ntiles;          // ceil(L / 16)
+    unsigned spin_limit;     // bound on the hand-off wait, in polls
+};
+
+struct FusedSync {
+    float2* part;            // [units][Gg][RUW*16] per-slice (row max, row sum-exp), base-2 domain
+    float2* l1;              // [units][RUW*16][NB] the same merged over blocks of 32 slices
+};
+
 struct Workspace {
     float2* part;    // [Hkv][nchunks][R32][32] per-chunk (row max, row sum-exp) in base-2 domain
     float2* mz;      // [Hkv][R32][32]          (row max, 1 / row sum-exp); (0, 0) for padding rows
-    float* vote;     // [Hkv][NV][n]
+    float* vote;     // [Hkv][NV][n]  (two-pass path) or [Hkv][g][n] (single-read path)
     float* score;    // [Hkv][n]
+    char* fused;     // hand-off buffers of the single-read path (see fused_sync_layout)
 };
 
 ScoreGeom make_geom(int64_t L, int Hq, int Hkv, int D, int W);
@@ -46,13 +61,19 @@ size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base);
 // Stage boundaries for the optional per-stage timing (snapkv_profile_start/stop): when timing is
 // active, stage_done records an event on the stream after the stage's launch; otherwise it is a
 // no-op.  kStageBegin marks the start of a call.
-enum Stage { kStageBegin = 0, kStagePass1, kStageReduce, kStagePass2, kStagePool, kStageSelect,
-             kStageGather, kNumStageMarks };
+enum Stage { kStageBegin = 0, kStagePass1, kStageReduce, kStagePass2, kStageFused, kStagePool,
+             kStageSelect, kStageGather, kNumStageMarks };
 void stage_done(hipStream_t st, int stage);
 
 // All launchers enqueue on `st` and return the launch status.
 hipError_t launch_score(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                         const Workspace& ws, hipStream_t st);
+bool fused_shape(const ScoreGeom& G, FusedGeom* F);
+bool fused_plan(const ScoreGeom& G, FusedGeom* F);
+size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base);
+hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
+                              const FusedGeom& F, const FusedSync& S, float* vote, hipStream_t st);
+unsigned read_sync_timeouts();
 hipError_t launch_pool(const ScoreGeom& G, const float* vote, int pool_kind, int p, float* score,
                        hipStream_t st);
 hipError_t launch_select(const float* score, int H, int64_t n, int64_t kcount, int64_t out_stride,

@@ -304,13 +304,16 @@ size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base) {
     const size_t mz = align_up(sizeof(float2) * (size_t)G.Hkv * G.R32 * 32);
     const size_t vote = align_up(sizeof(float) * (size_t)G.Hkv * G.NV * (size_t)(G.n > 0 ? G.n : 1));
     const size_t score = align_up(sizeof(float) * (size_t)G.Hkv * (size_t)(G.n > 0 ? G.n : 1));
+    FusedGeom F;
+    const size_t fused = fused_shape(G, &F) ? fused_sync_layout(G, F, nullptr, nullptr) : 0;
     if (ws) {
         ws->part = reinterpret_cast<float2*>(b + off);
         ws->mz = reinterpret_cast<float2*>(b + off + part);
         ws->vote = reinterpret_cast<float*>(b + off + part + mz);
         ws->score = reinterpret_cast<float*>(b + off + part + mz + vote);
+        ws->fused = b + off + part + mz + vote + score;
     }
-    return part + mz + vote + score;
+    return part + mz + vote + score + fused;
 }
 
 template <typename T, int D>
@@ -324,6 +327,7 @@ static hipError_t launch_score_t(const void* q, const void* k, const ScoreGeom& 
     stage_done(st, kStageReduce);
     hipLaunchKernelGGL((score_pass2<T, D>), dim3(blocks), dim3(256), 0, st, q, k, ws.mz, ws.vote, G);
     stage_done(st, kStagePass2);
+    stage_done(st, kStageFused);
     return hipGetLastError();
 }
 

@@ -51,3 +51,17 @@ def test_varlen_batch(snapkv):
     prompts = workloads.varlen_prompts()
     for i, w in enumerate(prompts):
         _run(snapkv, w, 0, [i % w.Hkv, (i + 3) % w.Hkv])
+
+
+def test_two_pass_scheme_at_full_size(snapkv):
+    # the kernels that take over when a prompt's logits exceed the register files
+    snapkv.snapkv_set_scoring_scheme(1)
+    try:
+        _run(snapkv, workloads.LLAMA2_7B_16K, 1, [0, 17])
+        _run(snapkv, workloads.MISTRAL_7B_GQA_32K, 2, [3])
+    finally:
+        snapkv.snapkv_set_scoring_scheme(0)
+
+
+def test_no_handoff_wait_gave_up(snapkv):
+    assert snapkv.snapkv_sync_timeouts() == 0

@@ -46,8 +46,17 @@ SMALL_CASES = [
 ]
 
 
+@pytest.fixture(params=[0, 1], ids=["single_read", "two_pass"])
+def scheme(request, snapkv):
+    """Both scoring schemes: the single-read kernel (default where it fits) and the two-pass kernels."""
+    snapkv.snapkv_set_scoring_scheme(request.param)
+    yield request.param
+    snapkv.snapkv_set_scoring_scheme(0)
+    assert snapkv.snapkv_sync_timeouts() == 0
+
+
 @pytest.mark.parametrize("w", SMALL_CASES, ids=lambda w: w.name)
-def test_small_cases_all_heads(snapkv, w):
+def test_small_cases_all_heads(snapkv, scheme, w):
     case, res, band = gpu_vs_oracle(snapkv, w)
     if w.needle:
         idx = res[3]
@@ -73,7 +82,7 @@ def test_bypass_identity(snapkv, L, C):
     assert bool((out_idx[:, L:] == -5).all()) and bool((out_k[:, L:] == 7.0).all())
 
 
-def test_zero_queries_flat_field_tie_rule(snapkv):
+def test_zero_queries_flat_field_tie_rule(snapkv, scheme):
     # all-zero queries: every prefix vote equals H_L - H_n, so max pooling gives a flat field
     # and the tie rule alone decides: positions 0..k-1 (closed form, not an oracle call)
     w = small("flat", L=2000, C=500)
@@ -99,7 +108,7 @@ def test_zero_queries_avgpool_skips_edges(snapkv):
     assert idx[:, :w.C - w.W].min() >= 2 and idx[:, :w.C - w.W].max() <= w.n - 3
 
 
-def test_shift_invariance_large_offset(snapkv):
+def test_shift_invariance_large_offset(snapkv, scheme):
     # one vector added to every key shifts whole rows of logits by a constant (here ~100 nats,
     # enough to overflow a softmax without max subtraction); selection must not change and the
     # scores must still match the oracle evaluated on the shifted bytes
@@ -115,7 +124,7 @@ def test_shift_invariance_large_offset(snapkv):
     check_against_oracle(q, k2, v, 0, 7, w.C, *res)
 
 
-def test_deterministic_bitwise(snapkv):
+def test_deterministic_bitwise(snapkv, scheme):
     w = small("det", Hq=8, Hkv=2, L=3000, C=400)
     case = workloads.generate(w, device="cuda")
     q, k, v = case["q_win"], case["k"], case["v"]
