@@ -76,7 +76,7 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
                const Workspace& ws, int pool_kind, int p, float* score, hipStream_t st) {
     FusedGeom F;
     ScoreGeom Gp = G;
-    if (g_allow_fused && fused_plan(G, &F)) {   // K is read once; otherwise two passes over K
+    if (g_allow_fused && fused_plan(dtype, D, G, &F)) {   // K is read once; otherwise two passes over K
         FusedSync S;
         fused_sync_layout(G, F, &S, ws.fused);
         stage_done(st, kStagePass1);

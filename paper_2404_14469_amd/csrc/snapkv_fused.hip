@@ -35,6 +35,9 @@
 // pieces 4p + l/16 of its row: the four lanes of a row then read 64 contiguous bytes per load.
 #include "snapkv_internal.h"
 
+#include <cstdlib>
+#include <type_traits>
+
 namespace snapkv {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -134,6 +137,7 @@ __device__ long long g_trace[512 * 64 * 12];
 
 constexpr unsigned long long kInvalidPair = ~0ull;   // a sum-exp is never NaN: no real pair looks like this
 constexpr int kSlicesPerBlock = 32;                  // slices merged by one half-wave in step L1
+constexpr int kL1BlocksPadded = 16;                  // level-1 words per row (Gg <= 512)
 
 __device__ __forceinline__ unsigned long long pack_pair(float m, float z) {
     return ((unsigned long long)__float_as_uint(z) << 32) | (unsigned long long)__float_as_uint(m);
@@ -155,7 +159,7 @@ __device__ __forceinline__ unsigned long long await_pair(const float2* p, unsign
                                                          unsigned limit, bool& gave_up) {
     unsigned spins = 0;
     while (bits == kInvalidPair) {
-        if (++spins > limit) {
+        if (gave_up || ++spins > limit) {   // once a wait has given up, later ones do not wait again
             gave_up = true;
             return pack_pair(-INFINITY, 0.f);
         }
@@ -180,6 +184,17 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
+template <int CTRL> __device__ __forceinline__ void dpp_merge(float& m, float& z) {
+    const float om = dpp_move<CTRL>(m), oz = dpp_move<CTRL>(z);
+    merge_pair(m, z, om, oz);
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void load_frag16p(Frag16<T, D>& f, const char* p) {
+#pragma unroll
+    for (int x = 0; x < Frag16<T, D>::NP; ++x) f.v[x] = *reinterpret_cast<const uint4*>(p + 64 * x);
+}
+
 template <typename T, int D, int RUW, int KT, int NW>
 __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ qv,
                                                        const void* __restrict__ kv,
@@ -188,62 +203,91 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     constexpr int R = RUW * 16;          // window rows a workgroup tracks per unit
     constexpr int NT = NW * 64;
     constexpr int NSLOT = RUW * KT;      // accumulator tiles per lane per unit
-    constexpr int NBMAX = 8;             // level-1 blocks per row (Gg <= 256)
-    constexpr int L2PT = (R * NBMAX + NT - 1) / NT;   // level-1 pairs a thread fetches in step P2
+    constexpr int NBP = kL1BlocksPadded; // level-1 words per row (the first F.NB are real)
+    constexpr int L2PT = (R * NBP + NT - 1) / NT;   // level-1 words a thread fetches in step P2
     constexpr int ES = esize<T>::value;
     using Frag = Frag16<T, D>;
 
     extern __shared__ float4 fifo[];     // [2][NSLOT][NT]: e of the two units in flight
-    __shared__ float sm_wmax[NW][R];
-    __shared__ float sm_wsum[NW][R];
-    __shared__ float sm_ref[3][R];
-    __shared__ float2 sm_l1[R * NBMAX];
-    __shared__ float2 sm_fin[R];
+    __shared__ float2 sm_pair[NW][R];    // per wave: (row max, row sum-exp) of the current unit
+    __shared__ float sm_ref[3][NW][R];   // per wave: row maxima of the last three units
+    __shared__ float2 sm_fin[R];         // (row max, 1 / row sum-exp) of the unit in step P2
 
-    const char* q = static_cast<const char*>(qv);
-    const char* k = static_cast<const char*>(kv);
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, n16 = lane & 15, kg = lane >> 4;
+    const int tid = threadIdx.x, lane = tid & 63, n16 = lane & 15, kg = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wg = (int)(blockIdx.x % F.Gg), group = (int)(blockIdx.x / F.Gg);
-    const int64_t tile0 = ((int64_t)wg * NW + w) * KT;
+    const int tile0 = (wg * NW + w) * KT;
     const int nu = group < F.units ? (F.units - group + F.NG - 1) / F.NG : 0;   // units of this group
     if (nu == 0) return;
-    const int tasks = R * F.NB;          // level-1 merges per unit, spread over the group
+    // wave touches window columns, the ragged tail or tiles past the end: masks are needed
+    const bool special = (int64_t)(tile0 + KT) * 16 > G.n;
     const int hw = tid >> 5, l32 = tid & 31;
+    const int real_tasks = R * F.NB;
     bool gave_up = false;
 #ifdef SNAPKV_FUSED_TRACE
     int trace_ui = 0;
 #endif
 
+    // Per-lane row addresses; they advance by one group stride per iteration.  Loads are
+    // unconditional (out-of-range tiles and padding rows re-read a valid row and are masked or
+    // ignored later) so that the number of loads in flight behind a hand-off word is fixed.
+    const char* kp[KT];
+    const char* qp[RUW];
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+        int64_t j = (int64_t)(tile0 + t) * 16 + n16;
+        j = j < G.L ? j : G.L - 1;
+        kp[t] = static_cast<const char*>(kv) + ((int64_t)group * G.L + j) * D * ES + kg * 16;
+    }
+#pragma unroll
+    for (int ru = 0; ru < RUW; ++ru) {
+        int head = ru / F.UH, i = (ru % F.UH) * 16 + n16;
+        head = head < G.g ? head : G.g - 1;
+        i = i < G.W ? i : G.W - 1;
+        qp[ru] = static_cast<const char*>(qv) + ((int64_t)(group * G.g + head) * G.W + i) * D * ES + kg * 16;
+    }
+    const int64_t kstep = (int64_t)F.NG * G.L * D * ES;
+    const int64_t qstep = (int64_t)F.NG * G.g * G.W * D * ES;
+
     Frag kf[KT];
     Frag qf[RUW];
-    auto issue_loads = [&](int unit) {
-        const char* kb = k + (int64_t)unit * G.L * D * ES;
 #pragma unroll
-        for (int t = 0; t < KT; ++t) {
-            const int64_t tile = tile0 + t;
-            if (tile < F.ntiles) {
-                int64_t j = tile * 16 + n16;
-                j = j < G.L ? j : G.L - 1;
-                load_frag16<T, D>(kf[t], kb + j * D * ES, kg);
-            } else {
-                zero_frag16<T, D>(kf[t]);
-            }
-        }
+    for (int t = 0; t < KT; ++t) load_frag16p<T, D>(kf[t], kp[t]);
 #pragma unroll
-        for (int ru = 0; ru < RUW; ++ru) {
-            const int head = ru / F.UH;
-            const int i = (ru % F.UH) * 16 + n16;
-            if (ru < F.RU && i < G.W) {
-                const int64_t row = (int64_t)(unit * G.g + head) * G.W + i;
-                load_frag16<T, D>(qf[ru], q + row * D * ES, kg);
-            } else {
-                zero_frag16<T, D>(qf[ru]);
-            }
-        }
-    };
+    for (int ru = 0; ru < RUW; ++ru) load_frag16p<T, D>(qf[ru], qp[ru]);
 
-    issue_loads(group);
-    for (int it = 0; it < nu + 2; ++it) {
+    // The next unit's K tiles and Q row units are fetched in kLoadSlots portions spread between
+    // the arithmetic of an iteration, so that the memory pipeline sees a steady stream instead of
+    // one burst per iteration (a wave that issues into a full pipeline stalls).
+    constexpr int kLoadSlots = 6;
+    constexpr int kLoadGroups = KT + RUW;
+    auto issue_slot = [&](auto SLOT) {
+#ifndef SNAPKV_EXP_NOLOAD
+        constexpr int slot_id = decltype(SLOT)::value;
+#pragma unroll
+        for (int g = 0; g < kLoadGroups; ++g) {
+            if (g * kLoadSlots / kLoadGroups != slot_id) continue;
+            if (g < KT) {
+                kp[g] += kstep;
+                load_frag16p<T, D>(kf[g], kp[g]);
+            } else {
+                qp[g - KT] += qstep;
+                load_frag16p<T, D>(qf[g - KT], qp[g - KT]);
+            }
+        }
+#endif
+    };
+#define SNAPKV_ISSUE(slot_)                                                  \
+    do {                                                                     \
+        __builtin_amdgcn_sched_barrier(0);                                   \
+        if constexpr (kLoadNext) issue_slot(std::integral_constant<int, slot_>{}); \
+        __builtin_amdgcn_sched_barrier(0);                                   \
+    } while (0)
+
+    // One iteration; LN says (at compile time) whether the next unit's loads are started, so that
+    // the steady-state loop has a fixed number of loads in flight behind the hand-off words.
+    auto iteration = [&](auto LN, const int it) {
+        constexpr bool kLoadNext = decltype(LN)::value;
         const bool has_p1 = it < nu;
         const bool has_l1 = it >= 1 && it - 1 < nu;
         const bool has_p2 = it >= 2;
@@ -252,11 +296,27 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         const int unit_p2 = unit - 2 * F.NG;
         TRACE(0);
 
-        // ---- A. request this iteration's hand-off words (before the next unit's K loads)
+        // ---- B. logits of the slice (waits for this unit's K and Q)
+        f32x4 e[RUW][KT];
+#ifdef SNAPKV_FUSED_TRACE
+        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) only
+        TRACE(8);
+#endif
+        if (has_p1) {
+#pragma unroll
+            for (int ru = 0; ru < RUW; ++ru)
+#pragma unroll
+                for (int t = 0; t < KT; ++t) e[ru][t] = mfma16<D>(qf[ru], kf[t]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        TRACE(9);
+
+        // ---- A. request this iteration's hand-off words first: a wave's loads retire in
+        // order, so waiting for these never waits for the K and Q loads issued after them
         unsigned long long l1_bits = pack_pair(-INFINITY, 0.f);
         const float2* l1_src = nullptr;
         const int task0 = wg + hw * F.Gg;
-        if (has_l1 && task0 < tasks) {
+        if (has_l1 && task0 < real_tasks) {
             const int row = task0 / F.NB, blk = task0 % F.NB;
             const int slice = blk * kSlicesPerBlock + l32;
             if (slice < F.Gg) {
@@ -268,112 +328,103 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 #pragma unroll
         for (int x = 0; x < L2PT; ++x) {
             const int idx = tid + x * NT;
-            p2_bits[x] = has_p2 && idx < tasks ? load_pair_bits(&S.l1[(int64_t)unit_p2 * tasks + idx])
-                                               : kInvalidPair;
+            p2_bits[x] = has_p2 && idx < R * NBP && (idx & (NBP - 1)) < F.NB
+                             ? load_pair_bits(&S.l1[(int64_t)unit_p2 * (R * NBP) + idx])
+                             : pack_pair(-INFINITY, 0.f);
         }
+        __builtin_amdgcn_sched_barrier(0);
 
-        f32x4 e[RUW][KT];
+        // ---- C. the next unit's K and Q follow in portions between the steps below
+        SNAPKV_ISSUE(0);
+        TRACE(1);
+
+        float mref[RUW][4], zs[RUW][4];
         if (has_p1) {
-            // ---- B. logits of the slice; C. start the next unit's loads
+            // ---- D. slice row maxima over this wave's keys (raw logits; scale is positive)
 #pragma unroll
             for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
-                for (int t = 0; t < KT; ++t) e[ru][t] = mfma16<D>(qf[ru], kf[t]);
-            if (it + 1 < nu) issue_loads(unit + F.NG);
-            TRACE(1);
-
-            // ---- D. base-2 logits, causal mask, slice row maxima
-            float mx[RUW][4];
-#pragma unroll
-            for (int ru = 0; ru < RUW; ++ru)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) mx[ru][r] = -INFINITY;
-#pragma unroll
-            for (int t = 0; t < KT; ++t) {
-                const int64_t tile = tile0 + t;
-                const int64_t j = tile * 16 + n16;
-                const bool live = tile < F.ntiles;
-                const bool boundary = tile * 16 + 15 >= G.n;
+                for (int r = 0; r < 4; ++r) mref[ru][r] = -INFINITY;
+            if (!special) {
 #pragma unroll
                 for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        float s = e[ru][t][r] * G.c2;
-                        if (!live) {
-                            s = -INFINITY;
-                        } else if (boundary) {
+                    for (int t = 0; t < KT; ++t)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) mref[ru][r] = fmaxf(mref[ru][r], e[ru][t][r]);
+            } else {
+#pragma unroll
+                for (int t = 0; t < KT; ++t) {
+                    const int64_t j = (int64_t)(tile0 + t) * 16 + n16;
+                    const bool live = tile0 + t < F.ntiles;
+#pragma unroll
+                    for (int ru = 0; ru < RUW; ++ru)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
                             const int i = (ru % F.UH) * 16 + kg * 4 + r;
-                            if (j > G.n + i || j >= G.L) s = -INFINITY;   // prompt-phase causal mask
+                            // prompt-phase causal mask; keys past the end of the prompt
+                            if (!live || j > G.n + i || j >= G.L) e[ru][t][r] = -INFINITY;
+                            mref[ru][r] = fmaxf(mref[ru][r], e[ru][t][r]);
                         }
-                        e[ru][t][r] = s;
-                        mx[ru][r] = fmaxf(mx[ru][r], s);
-                    }
+                }
             }
 #pragma unroll
             for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
-                for (int r = 0; r < 4; ++r) mx[ru][r] = row16_max(mx[ru][r]);
-            if (n16 == 0) {
-#pragma unroll
-                for (int ru = 0; ru < RUW; ++ru)
-                    *reinterpret_cast<float4*>(&sm_wmax[w][ru * 16 + kg * 4]) =
-                        make_float4(mx[ru][0], mx[ru][1], mx[ru][2], mx[ru][3]);
-            }
+                for (int r = 0; r < 4; ++r) mref[ru][r] = row16_max(mref[ru][r]) * G.c2;   // base-2 domain
         }
-        TRACE(2);
-        lds_barrier();
-        TRACE(3);
+        SNAPKV_ISSUE(1);
         if (has_p1) {
-            // workgroup reference, exponentials, slice row sums
-            float zs[RUW][4];
+            // exponentials relative to the wave's own row maxima, and their row sums
 #pragma unroll
-            for (int ru = 0; ru < RUW; ++ru) {
-                float4 m4 = *reinterpret_cast<const float4*>(&sm_wmax[0][ru * 16 + kg * 4]);
-#pragma unroll
-                for (int w2 = 1; w2 < NW; ++w2) {
-                    const float4 o = *reinterpret_cast<const float4*>(&sm_wmax[w2][ru * 16 + kg * 4]);
-                    m4.x = fmaxf(m4.x, o.x);
-                    m4.y = fmaxf(m4.y, o.y);
-                    m4.z = fmaxf(m4.z, o.z);
-                    m4.w = fmaxf(m4.w, o.w);
-                }
-                const float ref[4] = {m4.x == -INFINITY ? 0.f : m4.x, m4.y == -INFINITY ? 0.f : m4.y,
-                                      m4.z == -INFINITY ? 0.f : m4.z, m4.w == -INFINITY ? 0.f : m4.w};
+            for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
+                    const float ref = mref[ru][r] == -INFINITY ? 0.f : mref[ru][r];
                     float z = 0.f;
 #pragma unroll
                     for (int t = 0; t < KT; ++t) {
-                        const float x = __builtin_amdgcn_exp2f(e[ru][t][r] - ref[r]);
+                        const float x = __builtin_amdgcn_exp2f(fmaf(e[ru][t][r], G.c2, -ref));
                         e[ru][t][r] = x;
                         z += x;
                     }
                     zs[ru][r] = row16_sum(z);
                 }
-            }
-            if (n16 == 0) {
+        }
+        SNAPKV_ISSUE(2);
+        if (has_p1 && n16 == 0) {
 #pragma unroll
-                for (int ru = 0; ru < RUW; ++ru)
-                    *reinterpret_cast<float4*>(&sm_wsum[w][ru * 16 + kg * 4]) =
-                        make_float4(zs[ru][0], zs[ru][1], zs[ru][2], zs[ru][3]);
+            for (int ru = 0; ru < RUW; ++ru) {
+                float4* dst = reinterpret_cast<float4*>(&sm_pair[w][ru * 16 + kg * 4]);
+                dst[0] = make_float4(mref[ru][0], zs[ru][0], mref[ru][1], zs[ru][1]);
+                dst[1] = make_float4(mref[ru][2], zs[ru][2], mref[ru][3], zs[ru][3]);
+                *reinterpret_cast<float4*>(&sm_ref[it % 3][w][ru * 16 + kg * 4]) =
+                    make_float4(mref[ru][0], mref[ru][1], mref[ru][2], mref[ru][3]);
             }
         }
+        SNAPKV_ISSUE(3);
+        TRACE(2);
         lds_barrier();
-        TRACE(4);
-        if (has_p1 && tid < R) {   // publish the slice's (max, sum) per row
-            float m = sm_wmax[0][tid], z = sm_wsum[0][tid];
+        TRACE(3);
+        if (has_p1 && tid >= NT - R) {   // the last R threads merge the waves (in wave order) and publish
+            const int row = tid - (NT - R);
+            float2 x[NW];
+            float m = -INFINITY, z = 0.f;
 #pragma unroll
-            for (int w2 = 1; w2 < NW; ++w2) {
-                m = fmaxf(m, sm_wmax[w2][tid]);
-                z += sm_wsum[w2][tid];
+            for (int w2 = 0; w2 < NW; ++w2) {
+                x[w2] = sm_pair[w2][row];
+                m = fmaxf(m, x[w2].x);
             }
-            publish_pair(&S.part[((int64_t)unit * F.Gg + wg) * R + tid], m, z);
-            sm_ref[it % 3][tid] = m;
+#pragma unroll
+            for (int w2 = 0; w2 < NW; ++w2)
+                z += x[w2].x == -INFINITY ? 0.f : x[w2].y * __builtin_amdgcn_exp2f(x[w2].x - m);
+            publish_pair(&S.part[((int64_t)unit * F.Gg + wg) * R + row], m, z);
         }
+        TRACE(4);
 
         // ---- E. step L1 of the previous unit: merge 32 slices of one row per half-wave
         if (has_l1) {
-            for (int task = task0; task < tasks; task += 2 * NW * F.Gg) {
+            for (int task = task0; task < real_tasks; task += 2 * NW * F.Gg) {
                 const int row = task / F.NB, blk = task % F.NB;
                 float m = -INFINITY, z = 0.f;
                 if (task == task0) {
@@ -385,74 +436,104 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                         unpack_pair(await_pair(src, load_pair_bits(src), F.spin_limit, gave_up), m, z);
                     }
                 }
-#pragma unroll
-                for (int d = 1; d < 32; d <<= 1) {   // fixed tree over the half-wave's 32 slices
-                    const float om = __shfl_xor(m, d, 64), oz = __shfl_xor(z, d, 64);
-                    merge_pair(m, z, om, oz);
-                }
-                if (l32 == 0) publish_pair(&S.l1[(int64_t)unit_l1 * tasks + task], m, z);
+                // maximum over the half-wave's 32 slices, then the sums rescaled to it (fixed trees)
+                float mm = row16_max(m);
+                mm = fmaxf(mm, __shfl_xor(mm, 16, 64));
+                float zz = m == -INFINITY ? 0.f : z * __builtin_amdgcn_exp2f(m - mm);
+                zz = row16_sum(zz);
+                zz += __shfl_xor(zz, 16, 64);
+                if (l32 == 0) publish_pair(&S.l1[(int64_t)unit_l1 * (R * NBP) + row * NBP + blk], mm, zz);
             }
         }
+        SNAPKV_ISSUE(4);
         TRACE(5);
 
-        // ---- F. step P2 of the unit before that
+        // ---- F. step P2 of the unit before that: level-1 words of a row sit in 16 neighbouring
+        // lanes; merge them in a fixed tree into (max, 1/sum)
         if (has_p2) {
 #pragma unroll
             for (int x = 0; x < L2PT; ++x) {
                 const int idx = tid + x * NT;
-                if (idx < tasks) {
-                    float m, z;
-                    unpack_pair(await_pair(&S.l1[(int64_t)unit_p2 * tasks + idx], p2_bits[x],
+                float m = -INFINITY, z = 0.f;
+                if (idx < R * NBP && (idx & (NBP - 1)) < F.NB)
+                    unpack_pair(await_pair(&S.l1[(int64_t)unit_p2 * (R * NBP) + idx], p2_bits[x],
                                            F.spin_limit, gave_up), m, z);
-                    sm_l1[idx] = make_float2(m, z);
+                const float mm = row16_max(m);
+                const float zz = row16_sum(m == -INFINITY ? 0.f : z * __builtin_amdgcn_exp2f(m - mm));
+                if (idx < R * NBP && (idx & (NBP - 1)) == 0) {
+                    const int row = idx / NBP, ru = row >> 4;
+                    const int i = (ru % F.UH) * 16 + (row & 15);
+                    const bool real = ru < F.RU && i < G.W && zz > 0.f;
+                    sm_fin[row] = real ? make_float2(mm, 1.0f / zz) : make_float2(0.f, 0.f);
                 }
             }
         }
+        SNAPKV_ISSUE(5);
         lds_barrier();
         TRACE(6);
-        if (has_p2 && tid < R) {   // level-1 pairs of a row, in block order, into (max, 1/sum)
-            float m = -INFINITY, z = 0.f;
-            for (int blk = 0; blk < F.NB; ++blk) {
-                const float2 x = sm_l1[tid * F.NB + blk];
-                merge_pair(m, z, x.x, x.y);
-            }
-            const int ru = tid >> 4;
-            const int i = (ru % F.UH) * 16 + (tid & 15);
-            const bool real = ru < F.RU && i < G.W && z > 0.f;
-            sm_fin[tid] = real ? make_float2(m, 1.0f / z) : make_float2(0.f, 0.f);
-        }
-        lds_barrier();
         float4* slot = fifo + (size_t)(it & 1) * NSLOT * NT + tid;
         if (has_p2) {
             float f[RUW][4];
 #pragma unroll
-            for (int ru = 0; ru < RUW; ++ru)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    const int row = ru * 16 + kg * 4 + r;
-                    const float2 mz = sm_fin[row];
-                    const float ms = sm_ref[(it + 1) % 3][row];   // written two iterations ago
-                    f[ru][r] = ms == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms - mz.x) * mz.y;
-                }
+            for (int ru = 0; ru < RUW; ++ru) {
+                const float4* fin4 = reinterpret_cast<const float4*>(&sm_fin[ru * 16 + kg * 4]);
+                const float4 a = fin4[0], b = fin4[1];   // (m, 1/Z) of rows kg*4 .. kg*4+3
+                const float4 ms = *reinterpret_cast<const float4*>(&sm_ref[(it + 1) % 3][w][ru * 16 + kg * 4]);
+                f[ru][0] = (ms.x == -INFINITY || a.y == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.x - a.x) * a.y;
+                f[ru][1] = (ms.y == -INFINITY || a.w == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.y - a.z) * a.w;
+                f[ru][2] = (ms.z == -INFINITY || b.y == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.z - b.x) * b.y;
+                f[ru][3] = (ms.w == -INFINITY || b.w == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.w - b.z) * b.w;
+            }
             float* vb = vote + (int64_t)unit_p2 * G.g * G.n;
+            float v[KT];
 #pragma unroll
-            for (int t = 0; t < KT; ++t) {
-                const int64_t j = (tile0 + t) * 16 + n16;
-                float v = 0.f;
+            for (int t = 0; t < KT; ++t) v[t] = 0.f;
 #pragma unroll
-                for (int ru = 0; ru < RUW; ++ru) {
+            for (int ru = 0; ru < RUW; ++ru) {
+#pragma unroll
+                for (int t = 0; t < KT; ++t) {
                     const float4 ev = slot[(size_t)(ru * KT + t) * NT];
-                    v = fmaf(ev.x, f[ru][0], v);
-                    v = fmaf(ev.y, f[ru][1], v);
-                    v = fmaf(ev.z, f[ru][2], v);
-                    v = fmaf(ev.w, f[ru][3], v);
-                    if ((ru + 1) % F.UH == 0) {   // last row unit of a query head: finish its vote
-                        v += __shfl_xor(v, 16, 64);
-                        v += __shfl_xor(v, 32, 64);
-                        const int head = ru / F.UH;
-                        if (kg == 0 && head < G.g && j < G.n) vb[(int64_t)head * G.n + j] = v;
-                        v = 0.f;
+                    v[t] = fmaf(ev.x, f[ru][0], v[t]);
+                    v[t] = fmaf(ev.y, f[ru][1], v[t]);
+                    v[t] = fmaf(ev.z, f[ru][2], v[t]);
+                    v[t] = fmaf(ev.w, f[ru][3], v[t]);
+                }
+                if ((ru + 1) % F.UH == 0) {   // last row unit of a query head: finish its votes
+                    const int head = ru / F.UH;
+                    float* vh = vb + (int64_t)head * G.n;
+                    // sum over the four contraction-slice lanes of a column; with several tiles
+                    // the lanes split the tiles between them so that each stores its own share
+                    if constexpr (KT >= 4) {
+                        float a[KT / 2], b[KT / 4];
+#pragma unroll
+                        for (int x = 0; x < KT / 2; ++x) {
+                            const float mine = (kg & 2) ? v[x + KT / 2] : v[x];
+                            const float theirs = (kg & 2) ? v[x] : v[x + KT / 2];
+                            a[x] = mine + __shfl_xor(theirs, 32, 64);
+                        }
+#pragma unroll
+                        for (int x = 0; x < KT / 4; ++x) {
+                            const float mine = (kg & 1) ? a[x + KT / 4] : a[x];
+                            const float theirs = (kg & 1) ? a[x] : a[x + KT / 4];
+                            b[x] = mine + __shfl_xor(theirs, 16, 64);
+                        }
+#pragma unroll
+                        for (int x = 0; x < KT / 4; ++x) {
+                            const int t = ((kg & 2) ? KT / 2 : 0) + ((kg & 1) ? KT / 4 : 0) + x;
+                            const int64_t j = (int64_t)(tile0 + t) * 16 + n16;
+                            if (head < G.g && j < G.n) vh[j] = b[x];
+                        }
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < KT; ++t) {
+                            float s = v[t] + __shfl_xor(v[t], 32, 64);
+                            s += __shfl_xor(s, 16, 64);
+                            const int64_t j = (int64_t)(tile0 + t) * 16 + n16;
+                            if (kg == 0 && head < G.g && j < G.n) vh[j] = s;
+                        }
                     }
+#pragma unroll
+                    for (int t = 0; t < KT; ++t) v[t] = 0.f;
                 }
             }
         }
@@ -468,15 +549,20 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 #ifdef SNAPKV_FUSED_TRACE
         ++trace_ui;
 #endif
-    }
+    };
+
+#undef SNAPKV_ISSUE
+    int it = 0;
+    for (; it + 1 < nu; ++it) iteration(std::true_type{}, it);
+    for (; it < nu + 2; ++it) iteration(std::false_type{}, it);   // last unit, then the two drain steps
     if (gave_up) atomicAdd(&g_sync_timeouts, 1u);
 }
 
 // ---------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------
-constexpr int kFusedWaves = 8;
 constexpr int kFusedSlots = 8;          // RUW * KT: accumulator tiles a wave keeps per unit
+constexpr unsigned kSpinLimit = 1u << 15;   // polls before a hand-off wait gives up (tens of ms)
 
 static int g_cu_count[64] = {0};
 
@@ -491,9 +577,19 @@ static int cu_count() {
     return g_cu_count[dev];
 }
 
-// Device-independent part of the plan: how the rows and keys of a unit map onto a workgroup.
-// Returns false when the window rows of a KV head exceed what one wave tracks.
-bool fused_shape(const ScoreGeom& G, FusedGeom* F) {
+// Waves per workgroup of the single-read kernel: 8 (one workgroup per compute unit) or 4 (two).
+static int fused_waves() {
+    static int nw = 0;
+    if (nw == 0) {
+        const char* e = getenv("SNAPKV_FUSED_WAVES");
+        nw = (e && e[0] == '4') ? 4 : 8;
+    }
+    return nw;
+}
+
+// Device-independent part of the plan: how the rows and keys of a unit map onto a workgroup of
+// NW waves.  Returns false when the window rows of a KV head exceed what one wave tracks.
+static bool fused_shape_nw(const ScoreGeom& G, int NW, FusedGeom* F) {
     const int UH = (G.W + 15) / 16;
     const int RU = G.g * UH;
     if (RU > 8 || G.n <= 0) return false;
@@ -501,39 +597,33 @@ bool fused_shape(const ScoreGeom& G, FusedGeom* F) {
     while (RUW < RU) RUW *= 2;
     const int KT = kFusedSlots / RUW;
     const int64_t ntiles = (G.L + 15) / 16;
-    const int64_t per_wg = (int64_t)kFusedWaves * KT;
+    const int64_t per_wg = (int64_t)NW * KT;
     const int64_t Gg = (ntiles + per_wg - 1) / per_wg;
-    if (Gg > 256) return false;   // level-1 merge blocks per row are capped at 8
+    if (Gg > 32 * kL1BlocksPadded) return false;   // level-1 merge blocks per row are capped
     F->RU = RU;
     F->UH = UH;
     F->RUW = RUW;
     F->KT = KT;
+    F->NW = NW;
     F->Gg = (int)Gg;
     F->NG = 1;
     F->NB = (int)((Gg + 31) / 32);
     F->ntiles = ntiles;
     F->units = G.Hkv;
-    F->spin_limit = 1u << 24;
+    F->spin_limit = kSpinLimit;
     return true;
 }
 
-// Whether the current device can keep a whole group resident (one workgroup per compute unit),
-// and how many groups run side by side.
-bool fused_plan(const ScoreGeom& G, FusedGeom* F) {
-    if (!fused_shape(G, F)) return false;
-    const int cus = cu_count();
-    if (cus <= 0 || F->Gg > cus) return false;   // one head's logits do not fit the register files
-    int NG = cus / F->Gg;
-    if (NG > G.Hkv) NG = G.Hkv;
-    F->NG = NG;
-    return true;
+// Shape used to size the hand-off buffers: the variant with the most slices.
+bool fused_shape(const ScoreGeom& G, FusedGeom* F) {
+    return fused_shape_nw(G, 4, F) || fused_shape_nw(G, 8, F);
 }
 
 size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base) {
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t R = (size_t)F.RUW * 16;
     const size_t part = sizeof(float2) * (size_t)F.units * F.Gg * R;   // l1 follows part directly
-    const size_t l1 = sizeof(float2) * (size_t)F.units * R * F.NB;
+    const size_t l1 = sizeof(float2) * (size_t)F.units * R * kL1BlocksPadded;
     if (S) {
         char* b = static_cast<char*>(base);
         S->part = reinterpret_cast<float2*>(b);
@@ -542,52 +632,99 @@ size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, v
     return up(part + l1);
 }
 
-template <typename T, int D, int RUW>
-static hipError_t launch_fused_t(const void* q, const void* k, const ScoreGeom& G, const FusedGeom& F,
-                                 const FusedSync& S, float* vote, hipStream_t st) {
+struct FusedCall {
+    const void* q;
+    const void* k;
+    const ScoreGeom* G;
+    const FusedGeom* F;
+    const FusedSync* S;
+    float* vote;
+    hipStream_t st;
+};
+
+// call == nullptr: returns in *occ how many workgroups of this instance fit one compute unit
+// (asked of the runtime, so that a launch never exceeds what is resident at the same time).
+template <typename T, int D, int RUW, int NW>
+static hipError_t fused_instance(const FusedCall* call, int* occ) {
     constexpr int KT = kFusedSlots / RUW;
-    auto kern = score_fused<T, D, RUW, KT, kFusedWaves>;
-    // the LDS queue: two units of exponentials; large enough that one workgroup owns a compute unit
-    constexpr int kQueueBytes = 2 * kFusedSlots * kFusedWaves * 64 * 16;
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kQueueBytes);
+    auto kern = score_fused<T, D, RUW, KT, NW>;
+    constexpr int kQueueBytes = 2 * kFusedSlots * NW * 64 * 16;   // the LDS queue: two units of e
+    static int cached_occ = -1;
+    if (cached_occ < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kQueueBytes);
         if (e != hipSuccess) return e;
-        attr_set = true;
+        int n = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, NW * 64, kQueueBytes);
+        if (e != hipSuccess) return e;
+        cached_occ = n;
     }
-    const int64_t npairs = (int64_t)F.units * (F.RUW * 16) * (F.Gg + F.NB);   // part and l1 are adjacent
+    if (occ) *occ = cached_occ;
+    if (!call) return hipSuccess;
+    const FusedGeom& F = *call->F;
+    if ((int64_t)F.NG * F.Gg > (int64_t)cached_occ * cu_count()) return hipErrorCooperativeLaunchTooLarge;
+    const int64_t npairs = (int64_t)F.units * (F.RUW * 16) * (F.Gg + kL1BlocksPadded);   // part and l1 are adjacent
     int64_t blocks = (npairs + 255) / 256;
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(init_sync, dim3((unsigned)blocks), dim3(256), 0, st,
-                       reinterpret_cast<unsigned long long*>(S.part), npairs);
-    hipLaunchKernelGGL(kern, dim3(F.NG * F.Gg), dim3(kFusedWaves * 64), kQueueBytes, st, q, k, vote, S, G, F);
+    hipLaunchKernelGGL(init_sync, dim3((unsigned)blocks), dim3(256), 0, call->st,
+                       reinterpret_cast<unsigned long long*>(call->S->part), npairs);
+    hipLaunchKernelGGL(kern, dim3(F.NG * F.Gg), dim3(NW * 64), kQueueBytes, call->st, call->q, call->k,
+                       call->vote, *call->S, *call->G, F);
     return hipGetLastError();
 }
 
-template <typename T, int D>
-static hipError_t launch_fused_d(const void* q, const void* k, const ScoreGeom& G, const FusedGeom& F,
-                                 const FusedSync& S, float* vote, hipStream_t st) {
-    switch (F.RUW) {
-        case 1: return launch_fused_t<T, D, 1>(q, k, G, F, S, vote, st);
-        case 2: return launch_fused_t<T, D, 2>(q, k, G, F, S, vote, st);
-        case 4: return launch_fused_t<T, D, 4>(q, k, G, F, S, vote, st);
-        case 8: return launch_fused_t<T, D, 8>(q, k, G, F, S, vote, st);
+template <typename T, int D, int NW>
+static hipError_t fused_by_rows(int RUW, const FusedCall* call, int* occ) {
+    switch (RUW) {
+        case 1: return fused_instance<T, D, 1, NW>(call, occ);
+        case 2: return fused_instance<T, D, 2, NW>(call, occ);
+        case 4: return fused_instance<T, D, 4, NW>(call, occ);
+        case 8: return fused_instance<T, D, 8, NW>(call, occ);
     }
     return hipErrorInvalidValue;
+}
+
+template <typename T, int D>
+static hipError_t fused_by_waves(int NW, int RUW, const FusedCall* call, int* occ) {
+    if (NW == 8) return fused_by_rows<T, D, 8>(RUW, call, occ);
+    if (NW == 4) return fused_by_rows<T, D, 4>(RUW, call, occ);
+    return hipErrorInvalidValue;
+}
+
+static hipError_t fused_dispatch(int dtype, int D, int NW, int RUW, const FusedCall* call, int* occ) {
+    if (dtype == 0) {
+        if (D == 128) return fused_by_waves<bf16_k, 128>(NW, RUW, call, occ);
+        if (D == 64) return fused_by_waves<bf16_k, 64>(NW, RUW, call, occ);
+    } else {
+        if (D == 128) return fused_by_waves<f32_k, 128>(NW, RUW, call, occ);
+        if (D == 64) return fused_by_waves<f32_k, 64>(NW, RUW, call, occ);
+    }
+    return hipErrorInvalidValue;
+}
+
+// Whether the current device can keep a whole group of workgroups resident, and how many groups
+// run side by side.  The number of resident workgroups comes from the runtime's occupancy
+// answer for the exact kernel instance, never from an assumption.
+bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
+    if (!fused_shape_nw(G, fused_waves(), F)) return false;
+    int occ = 0;
+    if (fused_dispatch(dtype, D, F->NW, F->RUW, nullptr, &occ) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    const int64_t slots = (int64_t)cu_count() * occ;   // workgroups that are resident together
+    if (slots <= 0 || F->Gg > slots) return false;      // one head's logits do not fit on the chip
+    int64_t NG = slots / F->Gg;
+    if (NG > G.Hkv) NG = G.Hkv;
+    F->NG = (int)NG;
+    return true;
 }
 
 hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                               const FusedGeom& F, const FusedSync& S, float* vote, hipStream_t st) {
     if (G.n <= 0) return hipSuccess;
-    if (dtype == 0) {
-        if (D == 128) return launch_fused_d<bf16_k, 128>(q, k, G, F, S, vote, st);
-        if (D == 64) return launch_fused_d<bf16_k, 64>(q, k, G, F, S, vote, st);
-    } else {
-        if (D == 128) return launch_fused_d<f32_k, 128>(q, k, G, F, S, vote, st);
-        if (D == 64) return launch_fused_d<f32_k, 64>(q, k, G, F, S, vote, st);
-    }
-    return hipErrorInvalidValue;
+    const FusedCall call{q, k, &G, &F, &S, vote, st};
+    return fused_dispatch(dtype, D, F.NW, F.RUW, &call, nullptr);
 }
 
 }  // namespace snapkv

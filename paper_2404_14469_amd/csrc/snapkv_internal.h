@@ -37,7 +37,7 @@ struct ScoreGeom {
 // rows form RU units of 16 rows (UH per query head), padded to RUW, a power of two; a wave keeps
 // KT tiles of 16 keys per row unit; Gg workgroups share one unit's keys; NG groups run at once.
 struct FusedGeom {
-    int RU, UH, RUW, KT, Gg, NG, NB, units;   // NB: blocks of 32 slices per row (level-1 merges)
+    int RU, UH, RUW, KT, NW, Gg, NG, NB, units;   // NW waves per workgroup; NB blocks of 32 slices per row
     int64_t ntiles;          // ceil(L / 16)
     unsigned spin_limit;     // bound on the hand-off wait, in polls
 };
@@ -69,7 +69,7 @@ void stage_done(hipStream_t st, int stage);
 hipError_t launch_score(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                         const Workspace& ws, hipStream_t st);
 bool fused_shape(const ScoreGeom& G, FusedGeom* F);
-bool fused_plan(const ScoreGeom& G, FusedGeom* F);
+bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
 size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base);
 hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                               const FusedGeom& F, const FusedSync& S, float* vote, hipStream_t st);
