@@ -73,7 +73,8 @@ int internal_scratch(size_t need, void** out) {
 }
 
 int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGeom& G,
-               const Workspace& ws, int pool_kind, int p, float* score, hipStream_t st) {
+               const Workspace& ws, int pool_kind, int p, float* score, unsigned* minmax,
+               hipStream_t st) {
     FusedGeom F;
     ScoreGeom Gp = G;
     if (g_allow_fused && fused_plan(dtype, D, G, &F)) {   // K is read once; otherwise two passes over K
@@ -89,7 +90,7 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
     } else if (launch_score(dtype, D, q_win, k, G, ws, st) != hipSuccess) {
         return SNAPKV_ERR_HIP;
     }
-    if (launch_pool(Gp, ws.vote, pool_kind, p, score, st) != hipSuccess) return SNAPKV_ERR_HIP;
+    if (launch_pool(Gp, ws.vote, pool_kind, p, score, minmax, st) != hipSuccess) return SNAPKV_ERR_HIP;
     stage_done(st, kStagePool);
     return SNAPKV_OK;
 }
@@ -129,9 +130,13 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     Workspace ws;
     workspace_layout(G, &ws, base);
     stage_done(st, kStageBegin);
-    rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, st);
+    const bool chunked = select_chunked_ok(G.n);
+    if (chunked && launch_select_init(ws.sel, Hkv, st) != hipSuccess) return SNAPKV_ERR_HIP;
+    rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr, st);
     if (rc != SNAPKV_OK) return rc;
-    if (launch_select(ws.score, Hkv, G.n, C - W, C, W, out_idx, st) != hipSuccess) return SNAPKV_ERR_HIP;
+    const hipError_t se = chunked ? launch_select_chunked(ws.score, Hkv, G.n, C - W, C, W, out_idx, ws.sel, pool_tiles(G.n), st)
+                                  : launch_select(ws.score, Hkv, G.n, C - W, C, W, out_idx, st);
+    if (se != hipSuccess) return SNAPKV_ERR_HIP;
     stage_done(st, kStageSelect);
     if (launch_gather(k, v, out_idx, Hkv, L, C, C, row_bytes, out_k, out_v, st) != hipSuccess)
         return SNAPKV_ERR_HIP;
@@ -152,7 +157,7 @@ int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, 
     if (rc != SNAPKV_OK) return rc;
     Workspace ws;
     workspace_layout(G, &ws, base);
-    return run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, out_scores, static_cast<hipStream_t>(stream));
+    return run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, out_scores, nullptr, static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -296,8 +301,16 @@ int snapkv_select_topk(const float* scores, int H, int64_t n, int64_t kcount, in
     if (H < 1 || n < 1 || kcount < 0 || kcount > n) return SNAPKV_ERR_INVALID_ARG;
     if (n >= (int64_t)1 << 31) return SNAPKV_ERR_UNSUPPORTED;
     if (kcount == 0) return SNAPKV_OK;
-    if (launch_select(scores, H, n, kcount, kcount, 0, out_idx, static_cast<hipStream_t>(stream)) !=
-        hipSuccess)
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (!select_chunked_ok(n))
+        return launch_select(scores, H, n, kcount, kcount, 0, out_idx, st) == hipSuccess ? SNAPKV_OK : SNAPKV_ERR_HIP;
+    void* base = nullptr;
+    const int rc = internal_scratch(select_layout(H, n, nullptr, nullptr), &base);
+    if (rc != SNAPKV_OK) return rc;
+    SelectScratch S;
+    select_layout(H, n, &S, base);
+    if (launch_select_init(S, H, st) != hipSuccess) return SNAPKV_ERR_HIP;
+    if (launch_select_chunked(scores, H, n, kcount, kcount, 0, out_idx, S, 0, st) != hipSuccess)
         return SNAPKV_ERR_HIP;
     return SNAPKV_OK;
 }

@@ -47,12 +47,24 @@ struct FusedSync {
     float2* l1;              // [units][RUW*16][NB] the same merged over blocks of 32 slices
 };
 
+// Scratch of the chunked top-k selection (snapkv_topk.hip), per head h of H heads.
+struct SelectScratch {
+    unsigned* minmax;      // [H][parts][2] smallest / largest score bit pattern per producer part
+    unsigned* hist;        // [H][2048]   first-digit histogram
+    unsigned* cand_count;  // [H]         entries in the candidate list
+    unsigned* info;        // [H][4]      threshold search state; finally {T, -, need_eq, flat}
+    unsigned* chunk_gt;    // [H][chunks] positions in bins above the threshold bin
+    unsigned* chunk_off;   // [H][chunks][2] output offsets: (#greater, #equal) before the chunk
+    uint2* cand;           // [H][n]      (pattern, position) of positions inside the threshold bin
+};
+
 struct Workspace {
     float2* part;    // [Hkv][nchunks][R32][32] per-chunk (row max, row sum-exp) in base-2 domain
     float2* mz;      // [Hkv][R32][32]          (row max, 1 / row sum-exp); (0, 0) for padding rows
     float* vote;     // [Hkv][NV][n]  (two-pass path) or [Hkv][g][n] (single-read path)
     float* score;    // [Hkv][n]
     char* fused;     // hand-off buffers of the single-read path (see fused_sync_layout)
+    SelectScratch sel;
 };
 
 ScoreGeom make_geom(int64_t L, int Hq, int Hkv, int D, int W);
@@ -75,7 +87,14 @@ hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, co
                               const FusedGeom& F, const FusedSync& S, float* vote, hipStream_t st);
 unsigned read_sync_timeouts();
 hipError_t launch_pool(const ScoreGeom& G, const float* vote, int pool_kind, int p, float* score,
-                       hipStream_t st);
+                       unsigned* minmax, hipStream_t st);
+size_t select_layout(int H, int64_t n, SelectScratch* S, void* base);
+bool select_chunked_ok(int64_t n);
+hipError_t launch_select_init(const SelectScratch& S, int H, hipStream_t st);
+hipError_t launch_select_chunked(const float* score, int H, int64_t n, int64_t kcount,
+                                 int64_t out_stride, int W_tail, int32_t* out_idx,
+                                 const SelectScratch& S, int minmax_parts, hipStream_t st);
+int pool_tiles(int64_t n);
 hipError_t launch_select(const float* score, int H, int64_t n, int64_t kcount, int64_t out_stride,
                          int W_tail, int32_t* out_idx, hipStream_t st);
 hipError_t launch_iota(int H, int64_t rows, int64_t out_stride, int32_t* out_idx, hipStream_t st);

@@ -313,7 +313,9 @@ size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base) {
         ws->score = reinterpret_cast<float*>(b + off + part + mz + vote);
         ws->fused = b + off + part + mz + vote + score;
     }
-    return part + mz + vote + score + fused;
+    const size_t sel = select_layout(G.Hkv, G.n, ws ? &ws->sel : nullptr,
+                                     ws ? b + off + part + mz + vote + score + fused : nullptr);
+    return part + mz + vote + score + fused + sel;
 }
 
 template <typename T, int D>

@@ -17,8 +17,10 @@ constexpr int kPoolMaxHalo = 64;   // p <= 129
 
 __global__ __launch_bounds__(256) void pool_group(const float* __restrict__ vote,
                                                   float* __restrict__ score, const ScoreGeom G,
-                                                  const int pool_kind, const int p) {
+                                                  const int pool_kind, const int p,
+                                                  unsigned* __restrict__ minmax) {
     __shared__ float sh[kPoolTile + 2 * kPoolMaxHalo];
+    __shared__ unsigned sh_lo[4], sh_hi[4];
     const int hkv = blockIdx.y;
     const int64_t t0 = (int64_t)blockIdx.x * kPoolTile;
     const int r = p >> 1;
@@ -55,18 +57,49 @@ __global__ __launch_bounds__(256) void pool_group(const float* __restrict__ vote
         }
         __syncthreads();
     }
+    unsigned lo = 0xFFFFFFFFu, hi = 0u;
 #pragma unroll
     for (int e = 0; e < kPoolTile / 256; ++e) {
         const int64_t j = t0 + threadIdx.x + e * 256;
-        if (j < G.n) score[(int64_t)hkv * G.n + j] = acc[e];
+        if (j < G.n) {
+            score[(int64_t)hkv * G.n + j] = acc[e];
+            const unsigned x = __float_as_uint(acc[e]);
+            lo = x < lo ? x : lo;
+            hi = x > hi ? x : hi;
+        }
+    }
+    if (minmax) {   // range of this tile's score bit patterns, for the selection that follows
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const unsigned a = __shfl_xor(lo, d, 64), b = __shfl_xor(hi, d, 64);
+            lo = a < lo ? a : lo;
+            hi = b > hi ? b : hi;
+        }
+        if ((threadIdx.x & 63) == 0) {
+            sh_lo[threadIdx.x >> 6] = lo;
+            sh_hi[threadIdx.x >> 6] = hi;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < 4; ++w) {
+                lo = sh_lo[w] < lo ? sh_lo[w] : lo;
+                hi = sh_hi[w] > hi ? sh_hi[w] : hi;
+            }
+            unsigned* mm = minmax + 2 * ((int64_t)hkv * gridDim.x + blockIdx.x);
+            mm[0] = lo;
+            mm[1] = hi;
+        }
     }
 }
 
+int pool_tiles(int64_t n) { return (int)((n + kPoolTile - 1) / kPoolTile); }
+
 hipError_t launch_pool(const ScoreGeom& G, const float* vote, int pool_kind, int p, float* score,
-                       hipStream_t st) {
+                       unsigned* minmax, hipStream_t st) {
     if (G.n <= 0) return hipSuccess;
     const unsigned tiles = (unsigned)((G.n + kPoolTile - 1) / kPoolTile);
-    hipLaunchKernelGGL(pool_group, dim3(tiles, G.Hkv), dim3(256), 0, st, vote, score, G, pool_kind, p);
+    hipLaunchKernelGGL(pool_group, dim3(tiles, G.Hkv), dim3(256), 0, st, vote, score, G, pool_kind, p,
+                       minmax);
     return hipGetLastError();
 }
 
