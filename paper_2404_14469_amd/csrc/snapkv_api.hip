@@ -77,9 +77,13 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
                hipStream_t st) {
     FusedGeom F;
     ScoreGeom Gp = G;
-    if (g_allow_fused && fused_plan(dtype, D, G, &F)) {   // K is read once; otherwise two passes over K
-        FusedSync S;
-        fused_sync_layout(G, F, &S, ws.fused);
+    const bool fused = g_allow_fused && fused_plan(dtype, D, G, &F);
+    FusedSync S;
+    if (fused) fused_sync_layout(G, F, &S, ws.fused);
+    if (launch_prepare(fused ? S.part : nullptr, fused ? fused_sync_pairs(F) : 0, minmax ? &ws.sel : nullptr,
+                       G.Hkv, st) != hipSuccess)
+        return SNAPKV_ERR_HIP;
+    if (fused) {   // K is read once; otherwise two passes over K
         stage_done(st, kStagePass1);
         stage_done(st, kStageReduce);
         stage_done(st, kStagePass2);
@@ -131,7 +135,6 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     workspace_layout(G, &ws, base);
     stage_done(st, kStageBegin);
     const bool chunked = select_chunked_ok(G.n);
-    if (chunked && launch_select_init(ws.sel, Hkv, st) != hipSuccess) return SNAPKV_ERR_HIP;
     rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr, st);
     if (rc != SNAPKV_OK) return rc;
     const hipError_t se = chunked ? launch_select_chunked(ws.score, Hkv, G.n, C - W, C, W, out_idx, ws.sel, pool_tiles(G.n), st)

@@ -169,13 +169,6 @@ __device__ __forceinline__ unsigned long long await_pair(const float2* p, unsign
     return bits;
 }
 
-// pair buffers to the invalid pattern
-__global__ void init_sync(unsigned long long* pairs, int64_t npairs) {
-    for (int64_t j = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; j < npairs;
-         j += (int64_t)gridDim.x * blockDim.x)
-        pairs[j] = kInvalidPair;
-}
-
 // LDS-only barrier: orders LDS traffic between the waves of the workgroup without draining the
 // global loads in flight.
 __device__ __forceinline__ void lds_barrier() {
@@ -284,6 +277,24 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         __builtin_amdgcn_sched_barrier(0);                                   \
     } while (0)
 
+    // Loop-invariant parts of the hand-off addressing.  Step L1: this half-wave's first merge task
+    // (further ones, for small groups, are addressed in the loop); step P2: this thread's words.
+    const int task0 = wg + hw * F.Gg;
+    const bool l1_mine = task0 < real_tasks;
+    const int l1_row = l1_mine ? task0 / F.NB : 0, l1_blk = l1_mine ? task0 % F.NB : 0;
+    const int l1_slice = l1_blk * kSlicesPerBlock + l32;
+    const bool l1_lane = l1_mine && l1_slice < F.Gg;
+    const float2* const l1_base = S.part + ((int64_t)group * F.Gg + (l1_lane ? l1_slice : 0)) * R + l1_row;
+    const int64_t l1_step = (int64_t)F.NG * F.Gg * R;
+    const float2* const p2_base = S.l1 + (int64_t)group * (R * NBP) + tid;
+    const int64_t p2_step = (int64_t)F.NG * (R * NBP);
+    bool p2_ok[L2PT];
+#pragma unroll
+    for (int x = 0; x < L2PT; ++x) {
+        const int idx = tid + x * NT;
+        p2_ok[x] = idx < R * NBP && (idx & (NBP - 1)) < F.NB;
+    }
+
     // One iteration; LN says (at compile time) whether the next unit's loads are started, so that
     // the steady-state loop has a fixed number of loads in flight behind the hand-off words.
     auto iteration = [&](auto LN, const int it) {
@@ -295,6 +306,20 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         const int unit_l1 = unit - F.NG;
         const int unit_p2 = unit - 2 * F.NG;
         TRACE(0);
+
+        // ---- A. request this iteration's hand-off words at the very top: they are needed after
+        // the arithmetic of step D, about one memory latency from now.  A wave's loads retire in
+        // order: these are younger than this unit's K and Q (waited for next) and older than the
+        // next unit's (issued below), so waiting for them never waits for those.
+        unsigned long long l1_bits = pack_pair(-INFINITY, 0.f);
+        const float2* const l1_src = l1_base + (int64_t)(it - 1) * l1_step;
+        if (has_l1 && l1_lane) l1_bits = load_pair_bits(l1_src);
+        unsigned long long p2_bits[L2PT];
+#pragma unroll
+        for (int x = 0; x < L2PT; ++x)
+            p2_bits[x] = has_p2 && p2_ok[x] ? load_pair_bits(p2_base + (int64_t)(it - 2) * p2_step + x * NT)
+                                            : pack_pair(-INFINITY, 0.f);
+        __builtin_amdgcn_sched_barrier(0);
 
         // ---- B. logits of the slice (waits for this unit's K and Q)
         f32x4 e[RUW][KT];
@@ -311,35 +336,16 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         __builtin_amdgcn_sched_barrier(0);
         TRACE(9);
 
-        // ---- A. request this iteration's hand-off words first: a wave's loads retire in
-        // order, so waiting for these never waits for the K and Q loads issued after them
-        unsigned long long l1_bits = pack_pair(-INFINITY, 0.f);
-        const float2* l1_src = nullptr;
-        const int task0 = wg + hw * F.Gg;
-        if (has_l1 && task0 < real_tasks) {
-            const int row = task0 / F.NB, blk = task0 % F.NB;
-            const int slice = blk * kSlicesPerBlock + l32;
-            if (slice < F.Gg) {
-                l1_src = &S.part[((int64_t)unit_l1 * F.Gg + slice) * R + row];
-                l1_bits = load_pair_bits(l1_src);
-            }
-        }
-        unsigned long long p2_bits[L2PT];
-#pragma unroll
-        for (int x = 0; x < L2PT; ++x) {
-            const int idx = tid + x * NT;
-            p2_bits[x] = has_p2 && idx < R * NBP && (idx & (NBP - 1)) < F.NB
-                             ? load_pair_bits(&S.l1[(int64_t)unit_p2 * (R * NBP) + idx])
-                             : pack_pair(-INFINITY, 0.f);
-        }
-        __builtin_amdgcn_sched_barrier(0);
-
         // ---- C. the next unit's K and Q follow in portions between the steps below
         SNAPKV_ISSUE(0);
         TRACE(1);
 
         float mref[RUW][4], zs[RUW][4];
+#ifdef SNAPKV_EXP_NOD
+        if (false) {
+#else
         if (has_p1) {
+#endif
             // ---- D. slice row maxima over this wave's keys (raw logits; scale is positive)
 #pragma unroll
             for (int ru = 0; ru < RUW; ++ru)
@@ -353,17 +359,22 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 #pragma unroll
                         for (int r = 0; r < 4; ++r) mref[ru][r] = fmaxf(mref[ru][r], e[ru][t][r]);
             } else {
+                // The lane's key position is made opaque to the optimiser here: otherwise the
+                // (loop-invariant) mask of every accumulator element is hoisted out of the unit
+                // loop and held in scalar registers for its whole duration.
+                int jlane = tile0 * 16 + n16;
+                asm volatile("" : "+v"(jlane));
+                const int nn = (int)G.n, LL = (int)G.L;
 #pragma unroll
                 for (int t = 0; t < KT; ++t) {
-                    const int64_t j = (int64_t)(tile0 + t) * 16 + n16;
-                    const bool live = tile0 + t < F.ntiles;
+                    const int j = jlane + t * 16;
 #pragma unroll
                     for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
                             const int i = (ru % F.UH) * 16 + kg * 4 + r;
                             // prompt-phase causal mask; keys past the end of the prompt
-                            if (!live || j > G.n + i || j >= G.L) e[ru][t][r] = -INFINITY;
+                            if (j > nn + i || j >= LL) e[ru][t][r] = -INFINITY;
                             mref[ru][r] = fmaxf(mref[ru][r], e[ru][t][r]);
                         }
                 }
@@ -374,7 +385,11 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                 for (int r = 0; r < 4; ++r) mref[ru][r] = row16_max(mref[ru][r]) * G.c2;   // base-2 domain
         }
         SNAPKV_ISSUE(1);
+#ifdef SNAPKV_EXP_NOD
+        if (false) {
+#else
         if (has_p1) {
+#endif
             // exponentials relative to the wave's own row maxima, and their row sums
 #pragma unroll
             for (int ru = 0; ru < RUW; ++ru)
@@ -409,27 +424,42 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         if (has_p1 && tid >= NT - R) {   // the last R threads merge the waves (in wave order) and publish
             const int row = tid - (NT - R);
             float2 x[NW];
-            float m = -INFINITY, z = 0.f;
+            float mm[NW], zz[NW];
 #pragma unroll
             for (int w2 = 0; w2 < NW; ++w2) {
                 x[w2] = sm_pair[w2][row];
-                m = fmaxf(m, x[w2].x);
+                mm[w2] = x[w2].x;
             }
 #pragma unroll
+            for (int d = 1; d < NW; d <<= 1)   // balanced trees: short dependency chains
+#pragma unroll
+                for (int w2 = 0; w2 + d < NW; w2 += 2 * d) mm[w2] = fmaxf(mm[w2], mm[w2 + d]);
+            const float m = mm[0];
+#pragma unroll
             for (int w2 = 0; w2 < NW; ++w2)
-                z += x[w2].x == -INFINITY ? 0.f : x[w2].y * __builtin_amdgcn_exp2f(x[w2].x - m);
-            publish_pair(&S.part[((int64_t)unit * F.Gg + wg) * R + row], m, z);
+                zz[w2] = x[w2].x == -INFINITY ? 0.f : x[w2].y * __builtin_amdgcn_exp2f(x[w2].x - m);
+#pragma unroll
+            for (int d = 1; d < NW; d <<= 1)
+#pragma unroll
+                for (int w2 = 0; w2 + d < NW; w2 += 2 * d) zz[w2] += zz[w2 + d];
+            publish_pair(&S.part[((int64_t)unit * F.Gg + wg) * R + row], m, zz[0]);
         }
         TRACE(4);
 
         // ---- E. step L1 of the previous unit: merge 32 slices of one row per half-wave
+#ifdef SNAPKV_EXP_NOE
+        if (false) {
+#else
         if (has_l1) {
+#endif
             for (int task = task0; task < real_tasks; task += 2 * NW * F.Gg) {
-                const int row = task / F.NB, blk = task % F.NB;
+                int row = l1_row, blk = l1_blk;
                 float m = -INFINITY, z = 0.f;
                 if (task == task0) {
-                    if (l1_src) unpack_pair(await_pair(l1_src, l1_bits, F.spin_limit, gave_up), m, z);
+                    if (l1_lane) unpack_pair(await_pair(l1_src, l1_bits, F.spin_limit, gave_up), m, z);
                 } else {
+                    row = task / F.NB;
+                    blk = task % F.NB;
                     const int slice = blk * kSlicesPerBlock + l32;
                     if (slice < F.Gg) {
                         const float2* src = &S.part[((int64_t)unit_l1 * F.Gg + slice) * R + row];
@@ -450,13 +480,17 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 
         // ---- F. step P2 of the unit before that: level-1 words of a row sit in 16 neighbouring
         // lanes; merge them in a fixed tree into (max, 1/sum)
+#ifdef SNAPKV_EXP_NOP2
+        if (false) {
+#else
         if (has_p2) {
+#endif
 #pragma unroll
             for (int x = 0; x < L2PT; ++x) {
                 const int idx = tid + x * NT;
                 float m = -INFINITY, z = 0.f;
-                if (idx < R * NBP && (idx & (NBP - 1)) < F.NB)
-                    unpack_pair(await_pair(&S.l1[(int64_t)unit_p2 * (R * NBP) + idx], p2_bits[x],
+                if (p2_ok[x])
+                    unpack_pair(await_pair(p2_base + (int64_t)(it - 2) * p2_step + x * NT, p2_bits[x],
                                            F.spin_limit, gave_up), m, z);
                 const float mm = row16_max(m);
                 const float zz = row16_sum(m == -INFINITY ? 0.f : z * __builtin_amdgcn_exp2f(m - mm));
@@ -472,7 +506,11 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         lds_barrier();
         TRACE(6);
         float4* slot = fifo + (size_t)(it & 1) * NSLOT * NT + tid;
+#ifdef SNAPKV_EXP_NOP2
+        if (false) {
+#else
         if (has_p2) {
+#endif
             float f[RUW][4];
 #pragma unroll
             for (int ru = 0; ru < RUW; ++ru) {
@@ -485,6 +523,9 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                 f[ru][3] = (ms.w == -INFINITY || b.w == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.w - b.z) * b.w;
             }
             float* vb = vote + (int64_t)unit_p2 * G.g * G.n;
+            int jst = tile0 * 16 + n16;       // opaque for the same reason as above
+            asm volatile("" : "+v"(jst));
+            const int nst = (int)G.n;
             float v[KT];
 #pragma unroll
             for (int t = 0; t < KT; ++t) v[t] = 0.f;
@@ -520,16 +561,16 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 #pragma unroll
                         for (int x = 0; x < KT / 4; ++x) {
                             const int t = ((kg & 2) ? KT / 2 : 0) + ((kg & 1) ? KT / 4 : 0) + x;
-                            const int64_t j = (int64_t)(tile0 + t) * 16 + n16;
-                            if (head < G.g && j < G.n) vh[j] = b[x];
+                            const int j = jst + t * 16;
+                            if (head < G.g && j < nst) vh[j] = b[x];
                         }
                     } else {
 #pragma unroll
                         for (int t = 0; t < KT; ++t) {
                             float s = v[t] + __shfl_xor(v[t], 32, 64);
                             s += __shfl_xor(s, 16, 64);
-                            const int64_t j = (int64_t)(tile0 + t) * 16 + n16;
-                            if (kg == 0 && head < G.g && j < G.n) vh[j] = s;
+                            const int j = jst + t * 16;
+                            if (kg == 0 && head < G.g && j < nst) vh[j] = s;
                         }
                     }
 #pragma unroll
@@ -538,7 +579,11 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
             }
         }
         // ---- G. queue this unit's exponentials (each lane owns its queue entries)
+#ifdef SNAPKV_EXP_NOG
+        if (false) {
+#else
         if (has_p1) {
+#endif
 #pragma unroll
             for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
@@ -561,7 +606,8 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 // ---------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------
-constexpr int kFusedSlots = 8;          // RUW * KT: accumulator tiles a wave keeps per unit
+constexpr int kFusedSlots = 8;          // RUW * KT: accumulator tiles a wave keeps per unit (8 waves)
+constexpr int kFusedSlotsWide = 16;     // the same for the 4-wave variant: twice the keys per wave
 constexpr unsigned kSpinLimit = 1u << 15;   // polls before a hand-off wait gives up (tens of ms)
 
 static int g_cu_count[64] = {0};
@@ -595,7 +641,7 @@ static bool fused_shape_nw(const ScoreGeom& G, int NW, FusedGeom* F) {
     if (RU > 8 || G.n <= 0) return false;
     int RUW = 1;
     while (RUW < RU) RUW *= 2;
-    const int KT = kFusedSlots / RUW;
+    const int KT = (NW == 4 ? kFusedSlotsWide : kFusedSlots) / RUW;
     const int64_t ntiles = (G.L + 15) / 16;
     const int64_t per_wg = (int64_t)NW * KT;
     const int64_t Gg = (ntiles + per_wg - 1) / per_wg;
@@ -632,6 +678,11 @@ size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, v
     return up(part + l1);
 }
 
+// Hand-off words (part and l1, adjacent) that must hold the "not published" pattern at launch.
+int64_t fused_sync_pairs(const FusedGeom& F) {
+    return (int64_t)F.units * (F.RUW * 16) * (F.Gg + kL1BlocksPadded);
+}
+
 struct FusedCall {
     const void* q;
     const void* k;
@@ -646,9 +697,10 @@ struct FusedCall {
 // (asked of the runtime, so that a launch never exceeds what is resident at the same time).
 template <typename T, int D, int RUW, int NW>
 static hipError_t fused_instance(const FusedCall* call, int* occ) {
-    constexpr int KT = kFusedSlots / RUW;
+    constexpr int SLOTS = NW == 4 ? kFusedSlotsWide : kFusedSlots;
+    constexpr int KT = SLOTS / RUW;
     auto kern = score_fused<T, D, RUW, KT, NW>;
-    constexpr int kQueueBytes = 2 * kFusedSlots * NW * 64 * 16;   // the LDS queue: two units of e
+    constexpr int kQueueBytes = 2 * SLOTS * NW * 64 * 16;   // the LDS queue: two units of e
     static int cached_occ = -1;
     if (cached_occ < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -663,11 +715,6 @@ static hipError_t fused_instance(const FusedCall* call, int* occ) {
     if (!call) return hipSuccess;
     const FusedGeom& F = *call->F;
     if ((int64_t)F.NG * F.Gg > (int64_t)cached_occ * cu_count()) return hipErrorCooperativeLaunchTooLarge;
-    const int64_t npairs = (int64_t)F.units * (F.RUW * 16) * (F.Gg + kL1BlocksPadded);   // part and l1 are adjacent
-    int64_t blocks = (npairs + 255) / 256;
-    if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(init_sync, dim3((unsigned)blocks), dim3(256), 0, call->st,
-                       reinterpret_cast<unsigned long long*>(call->S->part), npairs);
     hipLaunchKernelGGL(kern, dim3(F.NG * F.Gg), dim3(NW * 64), kQueueBytes, call->st, call->q, call->k,
                        call->vote, *call->S, *call->G, F);
     return hipGetLastError();

@@ -51,11 +51,11 @@ struct FusedSync {
 struct SelectScratch {
     unsigned* minmax;      // [H][parts][2] smallest / largest score bit pattern per producer part
     unsigned* hist;        // [H][2048]   first-digit histogram
-    unsigned* cand_count;  // [H]         entries in the candidate list
+    unsigned* cand_count;  // [H][chunks] entries in each chunk's part of the candidate list
     unsigned* info;        // [H][4]      threshold search state; finally {T, -, need_eq, flat}
     unsigned* chunk_gt;    // [H][chunks] positions in bins above the threshold bin
     unsigned* chunk_off;   // [H][chunks][2] output offsets: (#greater, #equal) before the chunk
-    uint2* cand;           // [H][n]      (pattern, position) of positions inside the threshold bin
+    uint2* cand;           // [H][n]      (pattern, position) of positions inside the threshold bin, by chunk
 };
 
 struct Workspace {
@@ -91,6 +91,8 @@ hipError_t launch_pool(const ScoreGeom& G, const float* vote, int pool_kind, int
 size_t select_layout(int H, int64_t n, SelectScratch* S, void* base);
 bool select_chunked_ok(int64_t n);
 hipError_t launch_select_init(const SelectScratch& S, int H, hipStream_t st);
+hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, int H, hipStream_t st);
+int64_t fused_sync_pairs(const FusedGeom& F);
 hipError_t launch_select_chunked(const float* score, int H, int64_t n, int64_t kcount,
                                  int64_t out_stride, int W_tail, int32_t* out_idx,
                                  const SelectScratch& S, int minmax_parts, hipStream_t st);

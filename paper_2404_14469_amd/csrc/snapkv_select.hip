@@ -6,60 +6,68 @@
 namespace snapkv {
 
 // ------------------------------------------------------------------------------------------
-// Pooling.  One workgroup produces kPoolTile consecutive scores of one KV head.  For each query
-// head of the group the head's votes (the sum of its VB vote rows) are staged in LDS with a
-// halo of p/2 on both sides, pooled, and added to the running group sum in head order.
-// Max pooling ignores positions outside [0, n); average pooling counts them as zeros and
-// divides by p.
+// Pooling.  One workgroup produces kPoolTile consecutive scores of one KV head; a thread owns
+// positions tile + t, tile + t + 256, ... so that every load and store is lane-contiguous.  For
+// each query head of the group the 2*(p/2)+1 taps of a position are read straight from the
+// head's votes (neighbouring lanes read neighbouring words, so the taps are L1 hits), pooled,
+// and added to the running group sum in head order.  Max pooling ignores positions outside
+// [0, n); average pooling counts them as zeros and divides by p.
 // ------------------------------------------------------------------------------------------
 constexpr int kPoolTile = 1024;
-constexpr int kPoolMaxHalo = 64;   // p <= 129
+constexpr int kPoolPerThread = kPoolTile / 256;
 
+// P > 0: pooling width known at compile time (taps unrolled, their loads issued together);
+// P == 0: width taken from the argument p.
+template <int P>
 __global__ __launch_bounds__(256) void pool_group(const float* __restrict__ vote,
                                                   float* __restrict__ score, const ScoreGeom G,
-                                                  const int pool_kind, const int p,
+                                                  const int pool_kind, const int p_arg,
                                                   unsigned* __restrict__ minmax) {
-    __shared__ float sh[kPoolTile + 2 * kPoolMaxHalo];
     __shared__ unsigned sh_lo[4], sh_hi[4];
     const int hkv = blockIdx.y;
     const int64_t t0 = (int64_t)blockIdx.x * kPoolTile;
+    const int p = P > 0 ? P : p_arg;
     const int r = p >> 1;
-    const int span = kPoolTile + 2 * r;
     const float pad = pool_kind == 0 ? -INFINITY : 0.f;
-    float acc[kPoolTile / 256];
+    float acc[kPoolPerThread];
 #pragma unroll
-    for (int e = 0; e < kPoolTile / 256; ++e) acc[e] = 0.f;
+    for (int e = 0; e < kPoolPerThread; ++e) acc[e] = 0.f;
     for (int h = 0; h < G.g; ++h) {
         const float* vb = vote + ((int64_t)hkv * G.NV + (int64_t)h * G.VB) * G.n;
-        for (int x = threadIdx.x; x < span; x += 256) {
-            const int64_t j = t0 - r + x;
-            float val = pad;
-            if (j >= 0 && j < G.n) {
-                val = vb[j];
-                for (int b = 1; b < G.VB; ++b) val += vb[(int64_t)b * G.n + j];
-            }
-            sh[x] = val;
-        }
-        __syncthreads();
 #pragma unroll
-        for (int e = 0; e < kPoolTile / 256; ++e) {
-            const int x = threadIdx.x + e * 256;   // position t0 + x, taps sh[x .. x + 2r]
+        for (int e = 0; e < kPoolPerThread; ++e) {
+            const int64_t j = t0 + threadIdx.x + e * 256;
+            if (j >= G.n) continue;
             float val;
-            if (pool_kind == 0) {
-                val = sh[x];
-                for (int d = 1; d <= 2 * r; ++d) val = fmaxf(val, sh[x + d]);
+            if (P > 0 && G.VB == 1) {
+                float tap[P > 0 ? P : 1];
+#pragma unroll
+                for (int d = 0; d < P; ++d) {
+                    const int64_t x = j + d - P / 2;
+                    tap[d] = (x >= 0 && x < G.n) ? vb[x] : pad;
+                }
+                val = tap[0];
+#pragma unroll
+                for (int d = 1; d < P; ++d) val = pool_kind == 0 ? fmaxf(val, tap[d]) : val + tap[d];
             } else {
-                val = 0.f;
-                for (int d = 0; d <= 2 * r; ++d) val += sh[x + d];
-                val = val / (float)p;
+                val = pad;
+                for (int d = -r; d <= r; ++d) {
+                    const int64_t x = j + d;
+                    float tap = pad;
+                    if (x >= 0 && x < G.n) {
+                        tap = vb[x];
+                        for (int b = 1; b < G.VB; ++b) tap += vb[(int64_t)b * G.n + x];
+                    }
+                    val = d == -r ? tap : (pool_kind == 0 ? fmaxf(val, tap) : val + tap);
+                }
             }
+            if (pool_kind != 0) val = val / (float)p;
             acc[e] += val;
         }
-        __syncthreads();
     }
     unsigned lo = 0xFFFFFFFFu, hi = 0u;
 #pragma unroll
-    for (int e = 0; e < kPoolTile / 256; ++e) {
+    for (int e = 0; e < kPoolPerThread; ++e) {
         const int64_t j = t0 + threadIdx.x + e * 256;
         if (j < G.n) {
             score[(int64_t)hkv * G.n + j] = acc[e];
@@ -92,14 +100,116 @@ __global__ __launch_bounds__(256) void pool_group(const float* __restrict__ vote
     }
 }
 
+// Variant for rows whose length is a multiple of four (so that every row is 16-byte aligned) and
+// one vote row per query head: a thread owns four consecutive positions and reads them and their
+// taps as float4, an order of magnitude fewer instructions per position.  The first and last
+// tiles of a row take the element-wise path.
+template <int P>
+__global__ __launch_bounds__(256) void pool_group4(const float* __restrict__ vote,
+                                                   float* __restrict__ score, const ScoreGeom G,
+                                                   const int pool_kind, unsigned* __restrict__ minmax) {
+    constexpr int r = P / 2;
+    constexpr int RQ = (r + 3) / 4;             // float4 loads on each side of the centre one
+    constexpr int NV4 = 2 * RQ + 1;
+    __shared__ unsigned sh_lo[4], sh_hi[4];
+    const int hkv = blockIdx.y;
+    const int64_t t0 = (int64_t)blockIdx.x * kPoolTile;
+    const int64_t j0 = t0 + 4 * threadIdx.x;
+    const bool interior = t0 >= 4 * RQ && t0 + kPoolTile + 4 * RQ <= G.n;
+    const float pad = pool_kind == 0 ? -INFINITY : 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int h = 0; h < G.g; ++h) {
+        const float* vb = vote + ((int64_t)hkv * G.NV + h) * G.n;
+        float v[NV4 * 4];
+        if (interior) {
+#pragma unroll
+            for (int x = 0; x < NV4; ++x) {
+                const float4 q = *reinterpret_cast<const float4*>(vb + j0 + 4 * (x - RQ));
+                v[4 * x] = q.x;
+                v[4 * x + 1] = q.y;
+                v[4 * x + 2] = q.z;
+                v[4 * x + 3] = q.w;
+            }
+        } else {
+#pragma unroll
+            for (int x = 0; x < NV4 * 4; ++x) {
+                const int64_t j = j0 + x - 4 * RQ;
+                v[x] = (j >= 0 && j < G.n) ? vb[j] : pad;
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float val = v[4 * RQ + i - r];
+#pragma unroll
+            for (int d = 1; d < P; ++d)
+                val = pool_kind == 0 ? fmaxf(val, v[4 * RQ + i - r + d]) : val + v[4 * RQ + i - r + d];
+            if (pool_kind != 0) val = val / (float)P;
+            acc[i] += val;
+        }
+    }
+    unsigned lo = 0xFFFFFFFFu, hi = 0u;
+    if (j0 + 3 < G.n) {
+        *reinterpret_cast<float4*>(score + (int64_t)hkv * G.n + j0) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (j0 + i < G.n) score[(int64_t)hkv * G.n + j0 + i] = acc[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+        if (j0 + i < G.n) {
+            const unsigned x = __float_as_uint(acc[i]);
+            lo = x < lo ? x : lo;
+            hi = x > hi ? x : hi;
+        }
+    if (minmax) {   // range of this tile's score bit patterns, for the selection that follows
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const unsigned a = __shfl_xor(lo, d, 64), b = __shfl_xor(hi, d, 64);
+            lo = a < lo ? a : lo;
+            hi = b > hi ? b : hi;
+        }
+        if ((threadIdx.x & 63) == 0) {
+            sh_lo[threadIdx.x >> 6] = lo;
+            sh_hi[threadIdx.x >> 6] = hi;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            for (int w = 1; w < 4; ++w) {
+                lo = sh_lo[w] < lo ? sh_lo[w] : lo;
+                hi = sh_hi[w] > hi ? sh_hi[w] : hi;
+            }
+            unsigned* mm = minmax + 2 * ((int64_t)hkv * gridDim.x + blockIdx.x);
+            mm[0] = lo;
+            mm[1] = hi;
+        }
+    }
+}
+
 int pool_tiles(int64_t n) { return (int)((n + kPoolTile - 1) / kPoolTile); }
 
 hipError_t launch_pool(const ScoreGeom& G, const float* vote, int pool_kind, int p, float* score,
                        unsigned* minmax, hipStream_t st) {
     if (G.n <= 0) return hipSuccess;
     const unsigned tiles = (unsigned)((G.n + kPoolTile - 1) / kPoolTile);
-    hipLaunchKernelGGL(pool_group, dim3(tiles, G.Hkv), dim3(256), 0, st, vote, score, G, pool_kind, p,
-                       minmax);
+    const dim3 grid(tiles, G.Hkv);
+    if (G.n % 4 == 0 && G.VB == 1 && (reinterpret_cast<uintptr_t>(vote) & 15u) == 0 &&
+        (reinterpret_cast<uintptr_t>(score) & 15u) == 0) {
+        switch (p) {
+            case 1: hipLaunchKernelGGL(pool_group4<1>, grid, dim3(256), 0, st, vote, score, G, pool_kind, minmax); return hipGetLastError();
+            case 5: hipLaunchKernelGGL(pool_group4<5>, grid, dim3(256), 0, st, vote, score, G, pool_kind, minmax); return hipGetLastError();
+            case 7: hipLaunchKernelGGL(pool_group4<7>, grid, dim3(256), 0, st, vote, score, G, pool_kind, minmax); return hipGetLastError();
+            case 13: hipLaunchKernelGGL(pool_group4<13>, grid, dim3(256), 0, st, vote, score, G, pool_kind, minmax); return hipGetLastError();
+            default: break;
+        }
+    }
+    switch (p) {   // the widths the paper uses (Sec. 5) get unrolled taps
+        case 1: hipLaunchKernelGGL(pool_group<1>, grid, dim3(256), 0, st, vote, score, G, pool_kind, p, minmax); break;
+        case 5: hipLaunchKernelGGL(pool_group<5>, grid, dim3(256), 0, st, vote, score, G, pool_kind, p, minmax); break;
+        case 7: hipLaunchKernelGGL(pool_group<7>, grid, dim3(256), 0, st, vote, score, G, pool_kind, p, minmax); break;
+        case 13: hipLaunchKernelGGL(pool_group<13>, grid, dim3(256), 0, st, vote, score, G, pool_kind, p, minmax); break;
+        default: hipLaunchKernelGGL(pool_group<0>, grid, dim3(256), 0, st, vote, score, G, pool_kind, p, minmax); break;
+    }
     return hipGetLastError();
 }
 
