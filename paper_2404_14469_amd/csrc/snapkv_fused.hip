@@ -203,7 +203,10 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     constexpr int ES = esize<T>::value;
     using Frag = Frag16<T, D>;
 
-    extern __shared__ float4 fifo[];     // [2][NSLOT][NT]: e of the two units in flight
+    constexpr int NP = Frag::NP;         // 16-byte pieces per lane per row
+    constexpr int QCH = RUW * NP;        // 1 KB chunks of a unit's Q block, in the order the MFMAs read them
+    constexpr int QPW = (QCH + NW - 1) / NW;   // chunks a wave fetches per unit
+    extern __shared__ uint4 qbuf[];      // [2][QCH][64]: Q block of the current and the next unit
     __shared__ float2 sm_pair[NW][R];    // per wave: (row max, row sum-exp) of the current unit
     __shared__ float sm_ref[3][NW][R];   // per wave: row maxima of the last three units
     __shared__ float2 sm_fin[R];         // (row max, 1 / row sum-exp) of the unit in step P2
@@ -227,47 +230,65 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     // unconditional (out-of-range tiles and padding rows re-read a valid row and are masked or
     // ignored later) so that the number of loads in flight behind a hand-off word is fixed.
     const char* kp[KT];
-    const char* qp[RUW];
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
         int64_t j = (int64_t)(tile0 + t) * 16 + n16;
         j = j < G.L ? j : G.L - 1;
         kp[t] = static_cast<const char*>(kv) + ((int64_t)group * G.L + j) * D * ES + kg * 16;
     }
+    // Q is shared by the waves: each fetches QPW of the unit's 1 KB chunks (chunk c = row unit c / NP,
+    // piece c % NP, lane l = row l % 16, contraction slice l / 16) and leaves them in LDS.
+    const char* qp[QPW];
 #pragma unroll
-    for (int ru = 0; ru < RUW; ++ru) {
+    for (int x = 0; x < QPW; ++x) {
+        int c = w + x * NW;
+        c = c < QCH ? c : QCH - 1;
+        const int ru = c / NP, pc = c % NP;
         int head = ru / F.UH, i = (ru % F.UH) * 16 + n16;
         head = head < G.g ? head : G.g - 1;
         i = i < G.W ? i : G.W - 1;
-        qp[ru] = static_cast<const char*>(qv) + ((int64_t)(group * G.g + head) * G.W + i) * D * ES + kg * 16;
+        qp[x] = static_cast<const char*>(qv) + ((int64_t)(group * G.g + head) * G.W + i) * D * ES + (4 * pc + kg) * 16;
     }
     const int64_t kstep = (int64_t)F.NG * G.L * D * ES;
     const int64_t qstep = (int64_t)F.NG * G.g * G.W * D * ES;
 
     Frag kf[KT];
-    Frag qf[RUW];
+    uint4 qland[QPW];
 #pragma unroll
     for (int t = 0; t < KT; ++t) load_frag16p<T, D>(kf[t], kp[t]);
 #pragma unroll
-    for (int ru = 0; ru < RUW; ++ru) load_frag16p<T, D>(qf[ru], qp[ru]);
+    for (int x = 0; x < QPW; ++x) qland[x] = *reinterpret_cast<const uint4*>(qp[x]);
+#pragma unroll
+    for (int x = 0; x < QPW; ++x)
+        if (w + x * NW < QCH) qbuf[(w + x * NW) * 64 + lane] = qland[x];
+    __syncthreads();
+    // exponentials of the two previous units stay in registers until their votes are taken
+    f32x4 e1[RUW][KT], e2[RUW][KT];
+#pragma unroll
+    for (int ru = 0; ru < RUW; ++ru)
+#pragma unroll
+        for (int t = 0; t < KT; ++t) e1[ru][t] = e2[ru][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // The next unit's K tiles and Q row units are fetched in kLoadSlots portions spread between
     // the arithmetic of an iteration, so that the memory pipeline sees a steady stream instead of
     // one burst per iteration (a wave that issues into a full pipeline stalls).
     constexpr int kLoadSlots = 6;
-    constexpr int kLoadGroups = KT + RUW;
+    constexpr int kLoadGroups = KT + 1;
     auto issue_slot = [&](auto SLOT) {
 #ifndef SNAPKV_EXP_NOLOAD
         constexpr int slot_id = decltype(SLOT)::value;
 #pragma unroll
         for (int g = 0; g < kLoadGroups; ++g) {
             if (g * kLoadSlots / kLoadGroups != slot_id) continue;
-            if (g < KT) {
-                kp[g] += kstep;
-                load_frag16p<T, D>(kf[g], kp[g]);
+            if (g == 0) {
+#pragma unroll
+                for (int x = 0; x < QPW; ++x) {
+                    qp[x] += qstep;
+                    qland[x] = *reinterpret_cast<const uint4*>(qp[x]);
+                }
             } else {
-                qp[g - KT] += qstep;
-                load_frag16p<T, D>(qf[g - KT], qp[g - KT]);
+                kp[g - 1] += kstep;
+                load_frag16p<T, D>(kf[g - 1], kp[g - 1]);
             }
         }
 #endif
@@ -331,9 +352,13 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 #endif
         if (has_p1) {
 #pragma unroll
-            for (int ru = 0; ru < RUW; ++ru)
+            for (int ru = 0; ru < RUW; ++ru) {
+                Frag qf;
 #pragma unroll
-                for (int t = 0; t < KT; ++t) e[ru][t] = mfma16<D>(qf[ru], kf[t]);
+                for (int pc = 0; pc < NP; ++pc) qf.v[pc] = qbuf[((it & 1) * QCH + ru * NP + pc) * 64 + lane];
+#pragma unroll
+                for (int t = 0; t < KT; ++t) e[ru][t] = mfma16<D>(qf, kf[t]);
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
         TRACE(9);
@@ -505,9 +530,13 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
             }
         }
         SNAPKV_ISSUE(5);
+        if constexpr (kLoadNext) {   // the next unit's Q chunks, visible to all waves after the barrier
+#pragma unroll
+            for (int x = 0; x < QPW; ++x)
+                if (w + x * NW < QCH) qbuf[(((it + 1) & 1) * QCH + w + x * NW) * 64 + lane] = qland[x];
+        }
         lds_barrier();
         TRACE(6);
-        float4* slot = fifo + (size_t)(it & 1) * NSLOT * NT + tid;
 #ifdef SNAPKV_EXP_NOP2
         if (false) {
 #else
@@ -535,11 +564,11 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
             for (int ru = 0; ru < RUW; ++ru) {
 #pragma unroll
                 for (int t = 0; t < KT; ++t) {
-                    const float4 ev = slot[(size_t)(ru * KT + t) * NT];
-                    v[t] = fmaf(ev.x, f[ru][0], v[t]);
-                    v[t] = fmaf(ev.y, f[ru][1], v[t]);
-                    v[t] = fmaf(ev.z, f[ru][2], v[t]);
-                    v[t] = fmaf(ev.w, f[ru][3], v[t]);
+                    const f32x4 ev = e2[ru][t];
+                    v[t] = fmaf(ev[0], f[ru][0], v[t]);
+                    v[t] = fmaf(ev[1], f[ru][1], v[t]);
+                    v[t] = fmaf(ev[2], f[ru][2], v[t]);
+                    v[t] = fmaf(ev[3], f[ru][3], v[t]);
                 }
                 if ((ru + 1) % F.UH == 0) {   // last row unit of a query head: finish its votes
                     const int head = ru / F.UH;
@@ -580,18 +609,14 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                 }
             }
         }
-        // ---- G. queue this unit's exponentials (each lane owns its queue entries)
-#ifdef SNAPKV_EXP_NOG
-        if (false) {
-#else
-        if (has_p1) {
-#endif
+        // ---- G. age the kept exponentials by one unit
 #pragma unroll
-            for (int ru = 0; ru < RUW; ++ru)
+        for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
-                for (int t = 0; t < KT; ++t)
-                    slot[(size_t)(ru * KT + t) * NT] = make_float4(e[ru][t][0], e[ru][t][1], e[ru][t][2], e[ru][t][3]);
-        }
+            for (int t = 0; t < KT; ++t) {
+                e2[ru][t] = e1[ru][t];
+                e1[ru][t] = e[ru][t];
+            }
         TRACE(7);
 #ifdef SNAPKV_FUSED_TRACE
         ++trace_ui;
@@ -606,453 +631,9 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------
-// Streaming variant for the common shape (bf16, D = 128, two row units: MHA with 17..32 window
-// rows).  Same steps, hand-off words and results as score_fused, but the K stream is decoupled
-// from the arithmetic: a workgroup has four compute waves and four loader waves.  A loader wave
-// feeds one compute wave: it keeps a whole unit of that wave's K tiles in flight in its own
-// registers, hands each tile over through a two-buffer LDS ring as soon as it has landed and the
-// buffer is free, and immediately requests the same tile of the next unit.  Loader waves are the
-// only ones that ever stall on the memory pipeline, which therefore always has requests pending;
-// compute waves read K (and Q) from LDS only.  The newest unit's exponentials stay in registers
-// for one iteration before they go to the (single) LDS queue slot.
-// ---------------------------------------------------------------------------------------------
-constexpr int kStreamCW = 4;                 // compute waves (waves 0..3); loaders are waves 4..7
-constexpr int kStreamKT = 8;                 // 16-key tiles per compute wave per unit
-constexpr int kStreamRUW = 2;
-
-__device__ __forceinline__ int lds_load_relaxed(const int* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-__device__ __forceinline__ void lds_store_release(int* p, int v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_WORKGROUP);
-}
-// Bounded like every other wait here: a protocol error must not be able to hang the GPU.
-constexpr int kLdsSpinLimit = 1 << 20;
-__device__ __forceinline__ void lds_wait_at_least(const int* p, int v, bool& gave_up) {
-    int spins = 0;
-    while (lds_load_relaxed(p) < v) {
-        if (gave_up || ++spins > kLdsSpinLimit) {
-            gave_up = true;
-            break;
-        }
-        __builtin_amdgcn_s_sleep(1);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-// Barrier among the compute waves only (the loader waves never take part): arrivals are counted in
-// LDS; `epoch` is the number of barriers this wave has passed.
-__device__ __forceinline__ void compute_barrier(int* counter, int& epoch, int waves, int lane,
-                                                bool& gave_up) {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    if (lane == 0) __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-    ++epoch;
-    int spins = 0;
-    while (lds_load_relaxed(counter) < epoch * waves) {
-        if (gave_up || ++spins > kLdsSpinLimit) {
-            gave_up = true;
-            break;
-        }
-        __builtin_amdgcn_s_sleep(0);
-    }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
-
-__global__ __launch_bounds__(512) void score_stream(const void* __restrict__ qv,
-                                                    const void* __restrict__ kv,
-                                                    float* __restrict__ vote, const FusedSync S,
-                                                    const ScoreGeom G, const FusedGeom F) {
-    constexpr int RUW = kStreamRUW, KT = kStreamKT, NWC = kStreamCW;
-    constexpr int R = RUW * 16, NT = NWC * 64, NSLOT = RUW * KT, NBP = kL1BlocksPadded;
-    constexpr int L2PT = (R * NBP + NT - 1) / NT;
-    constexpr int D = 128, ES = 2;
-    using Frag = Frag16<bf16_k, D>;
-
-    extern __shared__ float4 dyn[];
-    float4* const fifo = dyn;                                          // [NSLOT][NT]   64 KB
-    uint4* const ring = reinterpret_cast<uint4*>(dyn + NSLOT * NT);    // [NWC][2][4][64] 32 KB
-    uint4* const qbuf = ring + NWC * 2 * 4 * 64;                       // [2][RUW*4][64]  16 KB
-    __shared__ float2 sm_pair[NWC][R];
-    __shared__ float sm_ref[3][NWC][R];
-    __shared__ float2 sm_fin[R];
-    __shared__ int sm_prod[NWC], sm_cons[NWC], sm_qprod[NWC];
-    __shared__ int sm_bar;
-
-    const int tid = threadIdx.x, lane = tid & 63, n16 = lane & 15, kg = lane >> 4;
-    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wg = (int)(blockIdx.x % F.Gg), group = (int)(blockIdx.x / F.Gg);
-    const int nu = group < F.units ? (F.units - group + F.NG - 1) / F.NG : 0;
-    if (nu == 0) return;
-#ifdef SNAPKV_FUSED_TRACE
-#define TRS(slot_, it_) do { if (tid == 0 || tid == 256) g_trace[((int64_t)blockIdx.x * 64 + (it_)) * 12 + (slot_)] = wall_clock64(); } while (0)
-#else
-#define TRS(slot_, it_) do { } while (0)
-#endif
-    if (tid < NWC) {
-        sm_prod[tid] = 0;
-        sm_cons[tid] = 0;
-        sm_qprod[tid] = 0;
-    }
-    if (tid == 0) sm_bar = 0;
-    __syncthreads();
-
-    if (w >= NWC) {
-        // ================================ loader wave ================================
-        const int cw = w - NWC;
-        const int tile0 = (wg * NWC + cw) * KT;
-        int koff[KT];                           // byte offset of this lane's row piece in a unit's K
-#pragma unroll
-        for (int t = 0; t < KT; ++t) {
-            int64_t j = (int64_t)(tile0 + t) * 16 + n16;
-            j = j < G.L ? j : G.L - 1;          // rows past the end re-read the last row (masked later)
-            koff[t] = (int)(j * (D * ES)) + kg * 16;
-        }
-        // this loader's quarter of the unit's Q block: chunks c = 2cw, 2cw+1 (row unit c/4, piece c%4)
-        int qoff[2];
-#pragma unroll
-        for (int x = 0; x < 2; ++x) {
-            const int c = 2 * cw + x, ru = c >> 2, pc = c & 3;
-            int head = ru / F.UH, i = (ru % F.UH) * 16 + n16;
-            head = head < G.g ? head : G.g - 1;
-            i = i < G.W ? i : G.W - 1;
-            qoff[x] = (head * G.W + i) * (D * ES) + (4 * pc + kg) * 16;
-        }
-        const char* kb = static_cast<const char*>(kv) + (int64_t)group * G.L * D * ES;
-        const char* qb = static_cast<const char*>(qv) + (int64_t)group * G.g * G.W * D * ES;
-        const int64_t kstep = (int64_t)F.NG * G.L * D * ES;
-        const int64_t qstep = (int64_t)F.NG * G.g * G.W * D * ES;
-        uint4* const myring = ring + cw * (2 * 4 * 64) + lane;
-
-        bool lgave_up = false;
-        uint4 r[KT][4];
-        uint4 qr[2];
-#pragma unroll
-        for (int x = 0; x < 2; ++x) qr[x] = *reinterpret_cast<const uint4*>(qb + qoff[x]);
-#pragma unroll
-        for (int t = 0; t < KT; ++t)
-#pragma unroll
-            for (int pc = 0; pc < 4; ++pc) r[t][pc] = *reinterpret_cast<const uint4*>(kb + koff[t] + 64 * pc);
-
-        // One unit: publish the Q quarter fetched earlier, hand the landed K tiles to the compute
-        // wave as fast as it takes them, then (LN) request the next unit - the only place where a
-        // wave of this workgroup may stall on the memory pipeline.
-        auto loader_unit = [&](auto LN, const int it) {
-            constexpr bool kLoadNext = decltype(LN)::value;
-            TRS(8, it);
-#pragma unroll
-            for (int x = 0; x < 2; ++x) qbuf[(it & 1) * (RUW * 4 * 64) + (2 * cw + x) * 64 + lane] = qr[x];
-            lds_store_release(&sm_qprod[cw], it + 1);
-#pragma unroll
-            for (int t = 0; t < KT; ++t) {
-                const int gidx = it * KT + t;
-                lds_wait_at_least(&sm_cons[cw], gidx - 1, lgave_up);      // ring buffer gidx & 1 is free again
-                uint4* dst = myring + (gidx & 1) * (4 * 64);
-#pragma unroll
-                for (int pc = 0; pc < 4; ++pc) dst[pc * 64] = r[t][pc];
-                lds_store_release(&sm_prod[cw], gidx + 1);
-            }
-            TRS(9, it);
-            if constexpr (kLoadNext) {
-                qb += qstep;
-                kb += kstep;
-#pragma unroll
-                for (int x = 0; x < 2; ++x) qr[x] = *reinterpret_cast<const uint4*>(qb + qoff[x]);
-#pragma unroll
-                for (int t = 0; t < KT; ++t)
-#pragma unroll
-                    for (int pc = 0; pc < 4; ++pc)
-                        r[t][pc] = *reinterpret_cast<const uint4*>(kb + koff[t] + 64 * pc);
-            }
-            TRS(10, it);
-        };
-        int it = 0;
-        for (; it + 1 < nu; ++it) loader_unit(std::true_type{}, it);
-        loader_unit(std::false_type{}, it);
-        if (lgave_up) atomicAdd(&g_sync_timeouts, 1u);
-        return;
-    }
-
-    // ================================ compute wave ================================
-    const int tile0 = (wg * NWC + w) * KT;
-    const bool special = (int64_t)(tile0 + KT) * 16 > G.n;
-    const int hw = tid >> 5, l32 = tid & 31;
-    const int real_tasks = R * F.NB;
-    bool gave_up = false;
-    int bar_epoch = 0;
-    const uint4* const myring = ring + w * (2 * 4 * 64) + lane;
-
-    const int task0 = wg + hw * F.Gg;
-    const bool l1_mine = task0 < real_tasks;
-    const int l1_row = l1_mine ? task0 / F.NB : 0, l1_blk = l1_mine ? task0 % F.NB : 0;
-    const int l1_slice = l1_blk * kSlicesPerBlock + l32;
-    const bool l1_lane = l1_mine && l1_slice < F.Gg;
-    const float2* const l1_base = S.part + ((int64_t)group * F.Gg + (l1_lane ? l1_slice : 0)) * R + l1_row;
-    const int64_t l1_step = (int64_t)F.NG * F.Gg * R;
-    const float2* const p2_base = S.l1 + (int64_t)group * (R * NBP) + tid;
-    const int64_t p2_step = (int64_t)F.NG * (R * NBP);
-    bool p2_ok[L2PT];
-#pragma unroll
-    for (int x = 0; x < L2PT; ++x) {
-        const int idx = tid + x * NT;
-        p2_ok[x] = idx < R * NBP && (idx & (NBP - 1)) < F.NB;
-    }
-
-    f32x4 eprev[RUW][KT];   // exponentials of the previous unit (go to the LDS queue one step later)
-#pragma unroll
-    for (int ru = 0; ru < RUW; ++ru)
-#pragma unroll
-        for (int t = 0; t < KT; ++t) eprev[ru][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    for (int it = 0; it < nu + 2; ++it) {
-        const bool has_p1 = it < nu;
-        const bool has_l1 = it >= 1 && it - 1 < nu;
-        const bool has_p2 = it >= 2;
-        const int unit = group + it * F.NG;
-        const int unit_l1 = unit - F.NG;
-        const int unit_p2 = unit - 2 * F.NG;
-
-        TRS(0, it);
-        // ---- A. this iteration's hand-off words
-        unsigned long long l1_bits = pack_pair(-INFINITY, 0.f);
-        const float2* const l1_src = l1_base + (int64_t)(it - 1) * l1_step;
-        if (has_l1 && l1_lane) l1_bits = load_pair_bits(l1_src);
-        unsigned long long p2_bits[L2PT];
-#pragma unroll
-        for (int x = 0; x < L2PT; ++x)
-            p2_bits[x] = has_p2 && p2_ok[x] ? load_pair_bits(p2_base + (int64_t)(it - 2) * p2_step + x * NT)
-                                            : pack_pair(-INFINITY, 0.f);
-
-        // ---- B. logits: Q from its LDS buffer, K tile by tile from this wave's ring
-        f32x4 e[RUW][KT];
-        float mref[RUW][4], zs[RUW][4];
-        if (has_p1) {
-#pragma unroll
-            for (int c = 0; c < NWC; ++c) lds_wait_at_least(&sm_qprod[c], it + 1, gave_up);
-            TRS(1, it);
-            Frag qf[RUW];
-#pragma unroll
-            for (int ru = 0; ru < RUW; ++ru)
-#pragma unroll
-                for (int pc = 0; pc < 4; ++pc)
-                    qf[ru].v[pc] = qbuf[(it & 1) * (RUW * 4 * 64) + (ru * 4 + pc) * 64 + lane];
-#pragma unroll
-            for (int t = 0; t < KT; ++t) {
-                const int gidx = it * KT + t;
-                lds_wait_at_least(&sm_prod[w], gidx + 1, gave_up);
-                Frag kf;
-                const uint4* src = myring + (gidx & 1) * (4 * 64);
-#pragma unroll
-                for (int pc = 0; pc < 4; ++pc) kf.v[pc] = src[pc * 64];
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");   // reads done before the hand-back
-                lds_store_release(&sm_cons[w], gidx + 1);
-#pragma unroll
-                for (int ru = 0; ru < RUW; ++ru) e[ru][t] = mfma16<D>(qf[ru], kf);
-            }
-
-            TRS(2, it);
-            // ---- D. slice row maxima (raw logits; the scale is positive), exponentials, row sums
-#pragma unroll
-            for (int ru = 0; ru < RUW; ++ru)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) mref[ru][r] = -INFINITY;
-            if (!special) {
-#pragma unroll
-                for (int ru = 0; ru < RUW; ++ru)
-#pragma unroll
-                    for (int t = 0; t < KT; ++t)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) mref[ru][r] = fmaxf(mref[ru][r], e[ru][t][r]);
-            } else {
-                int jlane = tile0 * 16 + n16;   // opaque: keeps the masks out of scalar registers
-                asm volatile("" : "+v"(jlane));
-                const int nn = (int)G.n, LL = (int)G.L;
-#pragma unroll
-                for (int t = 0; t < KT; ++t) {
-                    const int j = jlane + t * 16;
-#pragma unroll
-                    for (int ru = 0; ru < RUW; ++ru)
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const int i = (ru % F.UH) * 16 + kg * 4 + r;
-                            if (j > nn + i || j >= LL) e[ru][t][r] = -INFINITY;   // causal mask, tail
-                            mref[ru][r] = fmaxf(mref[ru][r], e[ru][t][r]);
-                        }
-                }
-            }
-#pragma unroll
-            for (int ru = 0; ru < RUW; ++ru)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    mref[ru][r] = row16_max(mref[ru][r]) * G.c2;   // base-2 domain
-                    const float ref = mref[ru][r] == -INFINITY ? 0.f : mref[ru][r];
-                    float z = 0.f;
-#pragma unroll
-                    for (int t = 0; t < KT; ++t) {
-                        const float x = __builtin_amdgcn_exp2f(fmaf(e[ru][t][r], G.c2, -ref));
-                        e[ru][t][r] = x;
-                        z += x;
-                    }
-                    zs[ru][r] = row16_sum(z);
-                }
-            if (n16 == 0) {
-#pragma unroll
-                for (int ru = 0; ru < RUW; ++ru) {
-                    float4* dst = reinterpret_cast<float4*>(&sm_pair[w][ru * 16 + kg * 4]);
-                    dst[0] = make_float4(mref[ru][0], zs[ru][0], mref[ru][1], zs[ru][1]);
-                    dst[1] = make_float4(mref[ru][2], zs[ru][2], mref[ru][3], zs[ru][3]);
-                    *reinterpret_cast<float4*>(&sm_ref[it % 3][w][ru * 16 + kg * 4]) =
-                        make_float4(mref[ru][0], mref[ru][1], mref[ru][2], mref[ru][3]);
-                }
-            }
-        }
-        TRS(3, it);
-        compute_barrier(&sm_bar, bar_epoch, NWC, lane, gave_up);
-        TRS(4, it);
-        if (has_p1 && tid >= NT - R) {   // merge the compute waves (balanced trees) and publish the slice's pair
-            const int row = tid - (NT - R);
-            float2 x[NWC];
-            float mm[NWC], zz[NWC];
-#pragma unroll
-            for (int w2 = 0; w2 < NWC; ++w2) {
-                x[w2] = sm_pair[w2][row];
-                mm[w2] = x[w2].x;
-            }
-            const float m = fmaxf(fmaxf(mm[0], mm[1]), fmaxf(mm[2], mm[3]));
-#pragma unroll
-            for (int w2 = 0; w2 < NWC; ++w2)
-                zz[w2] = x[w2].x == -INFINITY ? 0.f : x[w2].y * __builtin_amdgcn_exp2f(x[w2].x - m);
-            publish_pair(&S.part[((int64_t)unit * F.Gg + wg) * R + row], m, (zz[0] + zz[1]) + (zz[2] + zz[3]));
-        }
-
-        // ---- E. step L1 of the previous unit
-        if (has_l1) {
-            for (int task = task0; task < real_tasks; task += 2 * NWC * F.Gg) {
-                int row = l1_row, blk = l1_blk;
-                float m = -INFINITY, z = 0.f;
-                if (task == task0) {
-                    if (l1_lane) unpack_pair(await_pair(l1_src, l1_bits, F.spin_limit, gave_up), m, z);
-                } else {
-                    row = task / F.NB;
-                    blk = task % F.NB;
-                    const int slice = blk * kSlicesPerBlock + l32;
-                    if (slice < F.Gg) {
-                        const float2* src = &S.part[((int64_t)unit_l1 * F.Gg + slice) * R + row];
-                        unpack_pair(await_pair(src, load_pair_bits(src), F.spin_limit, gave_up), m, z);
-                    }
-                }
-                float mm = row16_max(m);
-                mm = fmaxf(mm, __shfl_xor(mm, 16, 64));
-                float zz = m == -INFINITY ? 0.f : z * __builtin_amdgcn_exp2f(m - mm);
-                zz = row16_sum(zz);
-                zz += __shfl_xor(zz, 16, 64);
-                if (l32 == 0) publish_pair(&S.l1[(int64_t)unit_l1 * (R * NBP) + row * NBP + blk], mm, zz);
-            }
-        }
-
-        TRS(5, it);
-        // ---- F. step P2 of the unit before that
-        if (has_p2) {
-#pragma unroll
-            for (int x = 0; x < L2PT; ++x) {
-                const int idx = tid + x * NT;
-                float m = -INFINITY, z = 0.f;
-                if (p2_ok[x])
-                    unpack_pair(await_pair(p2_base + (int64_t)(it - 2) * p2_step + x * NT, p2_bits[x],
-                                           F.spin_limit, gave_up), m, z);
-                const float mm = row16_max(m);
-                const float zz = row16_sum(m == -INFINITY ? 0.f : z * __builtin_amdgcn_exp2f(m - mm));
-                if (idx < R * NBP && (idx & (NBP - 1)) == 0) {
-                    const int row = idx / NBP, ru = row >> 4;
-                    const int i = (ru % F.UH) * 16 + (row & 15);
-                    const bool real = ru < F.RU && i < G.W && zz > 0.f;
-                    sm_fin[row] = real ? make_float2(mm, 1.0f / zz) : make_float2(0.f, 0.f);
-                }
-            }
-        }
-        compute_barrier(&sm_bar, bar_epoch, NWC, lane, gave_up);
-        TRS(6, it);
-        float4* const slot = fifo + tid;
-        if (has_p2) {
-            float f[RUW][4];
-#pragma unroll
-            for (int ru = 0; ru < RUW; ++ru) {
-                const float4* fin4 = reinterpret_cast<const float4*>(&sm_fin[ru * 16 + kg * 4]);
-                const float4 a = fin4[0], b = fin4[1];
-                const float4 ms = *reinterpret_cast<const float4*>(&sm_ref[(it + 1) % 3][w][ru * 16 + kg * 4]);
-                f[ru][0] = (ms.x == -INFINITY || a.y == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.x - a.x) * a.y;
-                f[ru][1] = (ms.y == -INFINITY || a.w == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.y - a.z) * a.w;
-                f[ru][2] = (ms.z == -INFINITY || b.y == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.z - b.x) * b.y;
-                f[ru][3] = (ms.w == -INFINITY || b.w == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.w - b.z) * b.w;
-            }
-            float* vb = vote + (int64_t)unit_p2 * G.g * G.n;
-            int jst = tile0 * 16 + n16;
-            asm volatile("" : "+v"(jst));
-            const int nst = (int)G.n;
-            float v[KT];
-#pragma unroll
-            for (int t = 0; t < KT; ++t) v[t] = 0.f;
-#pragma unroll
-            for (int ru = 0; ru < RUW; ++ru) {
-#pragma unroll
-                for (int t = 0; t < KT; ++t) {
-                    const float4 ev = slot[(size_t)(ru * KT + t) * NT];
-                    v[t] = fmaf(ev.x, f[ru][0], v[t]);
-                    v[t] = fmaf(ev.y, f[ru][1], v[t]);
-                    v[t] = fmaf(ev.z, f[ru][2], v[t]);
-                    v[t] = fmaf(ev.w, f[ru][3], v[t]);
-                }
-                if ((ru + 1) % F.UH == 0) {   // last row unit of a query head: finish its votes
-                    const int head = ru / F.UH;
-                    float* vh = vb + (int64_t)head * G.n;
-                    float a[KT / 2], b[KT / 4];
-#pragma unroll
-                    for (int x = 0; x < KT / 2; ++x) {
-                        const float mine = (kg & 2) ? v[x + KT / 2] : v[x];
-                        const float theirs = (kg & 2) ? v[x] : v[x + KT / 2];
-                        a[x] = mine + __shfl_xor(theirs, 32, 64);
-                    }
-#pragma unroll
-                    for (int x = 0; x < KT / 4; ++x) {
-                        const float mine = (kg & 1) ? a[x + KT / 4] : a[x];
-                        const float theirs = (kg & 1) ? a[x] : a[x + KT / 4];
-                        b[x] = mine + __shfl_xor(theirs, 16, 64);
-                    }
-#pragma unroll
-                    for (int x = 0; x < KT / 4; ++x) {
-                        const int t = ((kg & 2) ? KT / 2 : 0) + ((kg & 1) ? KT / 4 : 0) + x;
-                        const int j = jst + t * 16;
-                        if (head < G.g && j < nst) vh[j] = b[x];
-                    }
-#pragma unroll
-                    for (int t = 0; t < KT; ++t) v[t] = 0.f;
-                }
-            }
-        }
-        // ---- G. the previous unit's exponentials go to the queue slot just read; this unit's
-        // stay in registers until the next iteration
-        if (has_l1) {
-#pragma unroll
-            for (int ru = 0; ru < RUW; ++ru)
-#pragma unroll
-                for (int t = 0; t < KT; ++t)
-                    slot[(size_t)(ru * KT + t) * NT] = make_float4(eprev[ru][t][0], eprev[ru][t][1], eprev[ru][t][2], eprev[ru][t][3]);
-        }
-        if (has_p1) {
-#pragma unroll
-            for (int ru = 0; ru < RUW; ++ru)
-#pragma unroll
-                for (int t = 0; t < KT; ++t) eprev[ru][t] = e[ru][t];
-        }
-        TRS(7, it);
-    }
-    if (gave_up) atomicAdd(&g_sync_timeouts, 1u);
-}
-
-// ---------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------
 constexpr int kFusedSlots = 8;          // RUW * KT: accumulator tiles a wave keeps per unit (8 waves)
-constexpr int kFusedSlotsWide = 16;     // the same for the 4-wave variant: twice the keys per wave
 constexpr unsigned kSpinLimit = 1u << 15;   // polls before a hand-off wait gives up (tens of ms)
 
 static int g_cu_count[64] = {0};
@@ -1068,15 +649,7 @@ static int cu_count() {
     return g_cu_count[dev];
 }
 
-// Waves per workgroup of the single-read kernel: 8 (one workgroup per compute unit) or 4 (two).
-static int fused_waves() {
-    static int nw = 0;
-    if (nw == 0) {
-        const char* e = getenv("SNAPKV_FUSED_WAVES");
-        nw = (e && e[0] == '4') ? 4 : 8;
-    }
-    return nw;
-}
+constexpr int kFusedWaves = 8;          // waves per workgroup (two per SIMD): measured best
 
 // Device-independent part of the plan: how the rows and keys of a unit map onto a workgroup of
 // NW waves.  Returns false when the window rows of a KV head exceed what one wave tracks.
@@ -1086,7 +659,7 @@ static bool fused_shape_nw(const ScoreGeom& G, int NW, FusedGeom* F) {
     if (RU > 8 || G.n <= 0) return false;
     int RUW = 1;
     while (RUW < RU) RUW *= 2;
-    const int KT = (NW == 4 ? kFusedSlotsWide : kFusedSlots) / RUW;
+    const int KT = kFusedSlots / RUW;
     const int64_t ntiles = (G.L + 15) / 16;
     const int64_t per_wg = (int64_t)NW * KT;
     const int64_t Gg = (ntiles + per_wg - 1) / per_wg;
@@ -1102,14 +675,11 @@ static bool fused_shape_nw(const ScoreGeom& G, int NW, FusedGeom* F) {
     F->ntiles = ntiles;
     F->units = G.Hkv;
     F->spin_limit = kSpinLimit;
-    F->stream = 0;
     return true;
 }
 
-// Shape used to size the hand-off buffers: the variant with the most slices.
-bool fused_shape(const ScoreGeom& G, FusedGeom* F) {
-    return fused_shape_nw(G, 4, F) || fused_shape_nw(G, 8, F);
-}
+// Shape used to size the hand-off buffers.
+bool fused_shape(const ScoreGeom& G, FusedGeom* F) { return fused_shape_nw(G, kFusedWaves, F); }
 
 size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base) {
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
@@ -1143,10 +713,9 @@ struct FusedCall {
 // (asked of the runtime, so that a launch never exceeds what is resident at the same time).
 template <typename T, int D, int RUW, int NW>
 static hipError_t fused_instance(const FusedCall* call, int* occ) {
-    constexpr int SLOTS = NW == 4 ? kFusedSlotsWide : kFusedSlots;
-    constexpr int KT = SLOTS / RUW;
+    constexpr int KT = kFusedSlots / RUW;
     auto kern = score_fused<T, D, RUW, KT, NW>;
-    constexpr int kQueueBytes = 2 * SLOTS * NW * 64 * 16;   // the LDS queue: two units of e
+    constexpr int kQueueBytes = 2 * RUW * (D * (std::is_same<T, bf16_k>::value ? 2 : 4) / 64) * 64 * 16;   // Q blocks of two units
     static int cached_occ = -1;
     if (cached_occ < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1179,8 +748,7 @@ static hipError_t fused_by_rows(int RUW, const FusedCall* call, int* occ) {
 
 template <typename T, int D>
 static hipError_t fused_by_waves(int NW, int RUW, const FusedCall* call, int* occ) {
-    if (NW == 8) return fused_by_rows<T, D, 8>(RUW, call, occ);
-    if (NW == 4) return fused_by_rows<T, D, 4>(RUW, call, occ);
+    if (NW == kFusedWaves) return fused_by_rows<T, D, kFusedWaves>(RUW, call, occ);
     return hipErrorInvalidValue;
 }
 
@@ -1195,70 +763,11 @@ static hipError_t fused_dispatch(int dtype, int D, int NW, int RUW, const FusedC
     return hipErrorInvalidValue;
 }
 
-constexpr int kStreamLdsBytes = (kStreamRUW * kStreamKT * kStreamCW * 64 + kStreamCW * 2 * 4 * 64 +
-                                 2 * kStreamRUW * 4 * 64) * 16;   // queue slot + K rings + Q buffers
-
-static int stream_occupancy() {
-    static int occ = -1;
-    if (occ < 0) {
-        if (hipFuncSetAttribute(reinterpret_cast<const void*>(score_stream),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, kStreamLdsBytes) != hipSuccess) {
-            (void)hipGetLastError();
-            occ = 0;
-            return occ;
-        }
-        int n = 0;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, score_stream, 2 * kStreamCW * 64,
-                                                         kStreamLdsBytes) != hipSuccess) {
-            (void)hipGetLastError();
-            n = 0;
-        }
-        occ = n;
-    }
-    return occ;
-}
-
-// The streaming variant applies to bf16, D = 128 and two row units per KV head.
-static bool stream_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
-    static int enabled = -1;
-    if (enabled < 0) {
-        const char* e = getenv("SNAPKV_STREAM");
-        enabled = (e && e[0] == '0') ? 0 : 1;
-    }
-    if (!enabled || dtype != 0 || D != 128 || G.n <= 0) return false;
-    const int UH = (G.W + 15) / 16;
-    const int RU = G.g * UH;
-    if (RU != kStreamRUW) return false;
-    if (G.L * 256 >= ((int64_t)1 << 31)) return false;      // 32-bit row offsets inside a unit
-    const int64_t ntiles = (G.L + 15) / 16;
-    const int64_t per_wg = (int64_t)kStreamCW * kStreamKT;
-    const int64_t Gg = (ntiles + per_wg - 1) / per_wg;
-    if (Gg > 32 * kL1BlocksPadded) return false;
-    const int64_t slots = (int64_t)cu_count() * stream_occupancy();
-    if (slots <= 0 || Gg > slots) return false;
-    int64_t NG = slots / Gg;
-    if (NG > G.Hkv) NG = G.Hkv;
-    F->RU = RU;
-    F->UH = UH;
-    F->RUW = kStreamRUW;
-    F->KT = kStreamKT;
-    F->NW = kStreamCW;
-    F->Gg = (int)Gg;
-    F->NG = (int)NG;
-    F->NB = (int)((Gg + 31) / 32);
-    F->ntiles = ntiles;
-    F->units = G.Hkv;
-    F->spin_limit = kSpinLimit;
-    F->stream = 1;
-    return true;
-}
-
 // Whether the current device can keep a whole group of workgroups resident, and how many groups
 // run side by side.  The number of resident workgroups comes from the runtime's occupancy
 // answer for the exact kernel instance, never from an assumption.
 bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
-    if (stream_plan(dtype, D, G, F)) return true;
-    if (!fused_shape_nw(G, fused_waves(), F)) return false;
+    if (!fused_shape_nw(G, kFusedWaves, F)) return false;
     int occ = 0;
     if (fused_dispatch(dtype, D, F->NW, F->RUW, nullptr, &occ) != hipSuccess) {
         (void)hipGetLastError();
@@ -1275,12 +784,6 @@ bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
 hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                               const FusedGeom& F, const FusedSync& S, float* vote, hipStream_t st) {
     if (G.n <= 0) return hipSuccess;
-    if (F.stream) {
-        if ((int64_t)F.NG * F.Gg > (int64_t)stream_occupancy() * cu_count()) return hipErrorCooperativeLaunchTooLarge;
-        hipLaunchKernelGGL(score_stream, dim3(F.NG * F.Gg), dim3(2 * kStreamCW * 64), kStreamLdsBytes, st, q, k,
-                           vote, S, G, F);
-        return hipGetLastError();
-    }
     const FusedCall call{q, k, &G, &F, &S, vote, st};
     return fused_dispatch(dtype, D, F.NW, F.RUW, &call, nullptr);
 }

@@ -38,7 +38,6 @@ struct ScoreGeom {
 // KT tiles of 16 keys per row unit; Gg workgroups share one unit's keys; NG groups run at once.
 struct FusedGeom {
     int RU, UH, RUW, KT, NW, Gg, NG, NB, units;   // NW waves per workgroup; NB blocks of 32 slices per row
-    int stream;              // 1: producer/consumer variant (loader waves feed compute waves)
     int64_t ntiles;          // ceil(L / 16)
     unsigned spin_limit;     // bound on the hand-off wait, in polls
 };
