@@ -124,7 +124,8 @@ int snapkv_select_topk(const float* scores, int H, int64_t n, int64_t kcount, in
  * each kernel of the path, for at most max_calls (1..4096) calls.  snapkv_profile_stop waits for
  * the device, writes the mean duration in milliseconds of each stage over the recorded calls to
  * stage_ms[0 .. snapkv_num_stages()) (host memory, may be NULL) and the number of calls averaged
- * to *calls (host, may be NULL).  A stage is one kernel; snapkv_stage_name(i) names it.
+ * to *calls (host, may be NULL).  A stage is one kernel (the selection stage: its few kernels);
+ * snapkv_stage_name(i) names it, and a stage the calls did not run reports 0.
  * Not thread-safe; one profiling session at a time.
  */
 int snapkv_profile_start(int max_calls);

@@ -83,10 +83,8 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
     if (launch_prepare(fused ? S.part : nullptr, fused ? fused_sync_pairs(F) : 0, minmax ? &ws.sel : nullptr,
                        G.Hkv, st) != hipSuccess)
         return SNAPKV_ERR_HIP;
+    stage_done(st, kStagePrepare);
     if (fused) {   // K is read once; otherwise two passes over K
-        stage_done(st, kStagePass1);
-        stage_done(st, kStageReduce);
-        stage_done(st, kStagePass2);
         if (launch_score_fused(dtype, D, q_win, k, G, F, S, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
         stage_done(st, kStageFused);
         Gp.NV = G.g;
@@ -204,15 +202,16 @@ int snapkv_profile_stop(double* stage_ms, int* calls) {
     double sum[kNumStageMarks] = {0};
     int counted = 0;
     for (int c = 0; c < g_prof.calls && rc == SNAPKV_OK; ++c) {
-        bool whole = true;
-        for (int s = 0; s < kNumStageMarks; ++s) whole = whole && g_prof.set[(size_t)c * kNumStageMarks + s];
-        if (!whole) continue;
+        const size_t base = (size_t)c * kNumStageMarks;
+        if (!g_prof.set[base + kStageBegin] || !g_prof.set[base + kStageGather]) continue;
+        int prev = kStageBegin;   // a stage that did not run has no mark and keeps a zero duration
         for (int s = 1; s < kNumStageMarks; ++s) {
+            if (!g_prof.set[base + s]) continue;
             float ms = 0.f;
-            if (hipEventElapsedTime(&ms, g_prof.ev[(size_t)c * kNumStageMarks + s - 1],
-                                    g_prof.ev[(size_t)c * kNumStageMarks + s]) != hipSuccess)
+            if (hipEventElapsedTime(&ms, g_prof.ev[base + prev], g_prof.ev[base + s]) != hipSuccess)
                 rc = SNAPKV_ERR_HIP;
             sum[s] += ms;
+            prev = s;
         }
         ++counted;
     }
@@ -240,7 +239,7 @@ int64_t snapkv_sync_timeouts(void) {
 int snapkv_num_stages(void) { return kNumStageMarks - 1; }
 
 const char* snapkv_stage_name(int stage) {
-    static const char* names[] = {"score_pass1", "reduce_rows", "score_pass2", "score_fused",
+    static const char* names[] = {"prepare_scratch", "score_pass1", "reduce_rows", "score_pass2", "score_fused",
                                   "pool_group", "select_topk", "gather_rows"};
     return stage >= 0 && stage < kNumStageMarks - 1 ? names[stage] : "";
 }

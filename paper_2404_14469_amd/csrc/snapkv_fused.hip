@@ -207,9 +207,12 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     constexpr int QCH = RUW * NP;        // 1 KB chunks of a unit's Q block, in the order the MFMAs read them
     constexpr int QPW = (QCH + NW - 1) / NW;   // chunks a wave fetches per unit
     extern __shared__ uint4 qbuf[];      // [2][QCH][64]: Q block of the current and the next unit
-    __shared__ float2 sm_pair[NW][R];    // per wave: (row max, row sum-exp) of the current unit
-    __shared__ float sm_ref[3][NW][R];   // per wave: row maxima of the last three units
-    __shared__ float2 sm_fin[R];         // (row max, 1 / row sum-exp) of the unit in step P2
+    // One workgroup barrier per iteration: what is written before it is read after it, and the
+    // buffers alternate between iterations so that a fast wave's next write cannot overtake a
+    // slow wave's read (the two are always separated by the following barrier).
+    __shared__ float2 sm_pair[2][NW][R]; // per wave: (row max, row sum-exp) of the current unit
+    __shared__ float sm_ref[3][NW][R];   // per wave: row maxima of the last three units (own wave only)
+    __shared__ float2 sm_fin[2][R];      // (row max, 1 / row sum-exp) of the unit in step P2
 
     const int tid = threadIdx.x, lane = tid & 63, n16 = lane & 15, kg = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -252,8 +255,16 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     const int64_t kstep = (int64_t)F.NG * G.L * D * ES;
     const int64_t qstep = (int64_t)F.NG * G.g * G.W * D * ES;
 
+    // K tiles are consumed in two halves so that the memory pipeline never runs dry: the lower
+    // KL tiles of a unit meet Q at the end of the previous iteration (their accumulators take
+    // the registers the vote has just freed) and are re-requested at once for the unit after;
+    // the upper tiles meet Q at the top of the unit's own iteration and are re-requested in
+    // portions spread over its first steps.  Every K load so has about one iteration to land,
+    // and at least half of a wave's tile buffers are in flight at any time.
+    constexpr int KL = KT / 2;           // lower tiles (none when a wave holds a single tile)
     Frag kf[KT];
     uint4 qland[QPW];
+    f32x4 e[RUW][KT];                    // logits, then exponentials, of the unit in step P1
 #pragma unroll
     for (int t = 0; t < KT; ++t) load_frag16p<T, D>(kf[t], kp[t]);
 #pragma unroll
@@ -267,13 +278,44 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 #pragma unroll
     for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
-        for (int t = 0; t < KT; ++t) e1[ru][t] = e2[ru][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < KT; ++t) e[ru][t] = e1[ru][t] = e2[ru][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // The next unit's K tiles and Q row units are fetched in kLoadSlots portions spread between
-    // the arithmetic of an iteration, so that the memory pipeline sees a steady stream instead of
-    // one burst per iteration (a wave that issues into a full pipeline stalls).
-    constexpr int kLoadSlots = 6;
-    constexpr int kLoadGroups = KT + 1;
+    // logits of tiles [T0, T1) of the unit whose Q block sits in half `par` of qbuf
+    auto mfma_tiles = [&](auto T0, auto T1, const int par) {
+        constexpr int t0 = decltype(T0)::value, t1 = decltype(T1)::value;
+        if constexpr (t0 < t1) {
+#pragma unroll
+            for (int ru = 0; ru < RUW; ++ru) {
+                Frag qf;
+#pragma unroll
+                for (int pc = 0; pc < NP; ++pc) qf.v[pc] = qbuf[(par * QCH + ru * NP + pc) * 64 + lane];
+#pragma unroll
+                for (int t = t0; t < t1; ++t) e[ru][t] = mfma16<D>(qf, kf[t]);
+            }
+        }
+    };
+    auto issue_tiles = [&](auto T0, auto T1) {
+#ifndef SNAPKV_EXP_NOLOAD
+        constexpr int t0 = decltype(T0)::value, t1 = decltype(T1)::value;
+#pragma unroll
+        for (int t = t0; t < t1; ++t) {
+            kp[t] += kstep;
+            load_frag16p<T, D>(kf[t], kp[t]);
+        }
+#endif
+    };
+    using IC0 = std::integral_constant<int, 0>;
+    using ICL = std::integral_constant<int, KL>;
+    using ICT = std::integral_constant<int, KT>;
+    mfma_tiles(IC0{}, ICL{}, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (nu > 1) issue_tiles(IC0{}, ICL{});
+    __builtin_amdgcn_sched_barrier(0);
+
+    // The next unit's Q chunk and upper K tiles are requested in kLoadSlots portions between the
+    // first steps of an iteration (a wave that issues a burst into a full pipeline stalls).
+    constexpr int kLoadSlots = 3;
+    constexpr int kLoadGroups = KT - KL + 1;
     auto issue_slot = [&](auto SLOT) {
 #ifndef SNAPKV_EXP_NOLOAD
         constexpr int slot_id = decltype(SLOT)::value;
@@ -287,8 +329,8 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                     qland[x] = *reinterpret_cast<const uint4*>(qp[x]);
                 }
             } else {
-                kp[g - 1] += kstep;
-                load_frag16p<T, D>(kf[g - 1], kp[g - 1]);
+                kp[KL + g - 1] += kstep;
+                load_frag16p<T, D>(kf[KL + g - 1], kp[KL + g - 1]);
             }
         }
 #endif
@@ -296,7 +338,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 #define SNAPKV_ISSUE(slot_)                                                  \
     do {                                                                     \
         __builtin_amdgcn_sched_barrier(0);                                   \
-        if constexpr (kLoadNext) issue_slot(std::integral_constant<int, slot_>{}); \
+        if constexpr (kNext1) issue_slot(std::integral_constant<int, slot_>{}); \
         __builtin_amdgcn_sched_barrier(0);                                   \
     } while (0)
 
@@ -318,10 +360,12 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         p2_ok[x] = idx < R * NBP && (idx & (NBP - 1)) < F.NB;
     }
 
-    // One iteration; LN says (at compile time) whether the next unit's loads are started, so that
-    // the steady-state loop has a fixed number of loads in flight behind the hand-off words.
-    auto iteration = [&](auto LN, const int it) {
-        constexpr bool kLoadNext = decltype(LN)::value;
+    // One iteration; MODE says (at compile time) whether the units one (bit 0) and two (bit 1)
+    // steps ahead exist, so that every variant of the loop body has a fixed number of loads in
+    // flight behind the hand-off words.
+    auto iteration = [&](auto MODE, const int it) {
+        constexpr bool kNext1 = (decltype(MODE)::value & 1) != 0;
+        constexpr bool kNext2 = (decltype(MODE)::value & 2) != 0;
         const bool has_p1 = it < nu;
         const bool has_l1 = it >= 1 && it - 1 < nu;
         const bool has_p2 = it >= 2;
@@ -344,26 +388,16 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                                             : pack_pair(-INFINITY, 0.f);
         __builtin_amdgcn_sched_barrier(0);
 
-        // ---- B. logits of the slice (waits for this unit's K and Q)
-        f32x4 e[RUW][KT];
+        // ---- B. logits of the upper tiles of the slice (waits for their K; the lower tiles were
+        // done at the end of the previous iteration)
 #ifdef SNAPKV_FUSED_TRACE
-        __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0) only
         TRACE(8);
 #endif
-        if (has_p1) {
-#pragma unroll
-            for (int ru = 0; ru < RUW; ++ru) {
-                Frag qf;
-#pragma unroll
-                for (int pc = 0; pc < NP; ++pc) qf.v[pc] = qbuf[((it & 1) * QCH + ru * NP + pc) * 64 + lane];
-#pragma unroll
-                for (int t = 0; t < KT; ++t) e[ru][t] = mfma16<D>(qf, kf[t]);
-            }
-        }
+        if (has_p1) mfma_tiles(ICL{}, ICT{}, it & 1);
         __builtin_amdgcn_sched_barrier(0);
         TRACE(9);
 
-        // ---- C. the next unit's K and Q follow in portions between the steps below
+        // ---- C. the next unit's Q and upper K tiles follow in portions between the steps below
         SNAPKV_ISSUE(0);
         TRACE(1);
 
@@ -434,17 +468,46 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                 }
         }
         SNAPKV_ISSUE(2);
+        TRACE(10);
+        // ---- E. step P2 of the unit two back: level-1 words of a row sit in 16 neighbouring
+        // lanes; merge them in a fixed tree into (max, 1/sum)
+#ifdef SNAPKV_EXP_NOP2
+        if (false) {
+#else
+        if (has_p2) {
+#endif
+#pragma unroll
+            for (int x = 0; x < L2PT; ++x) {
+                const int idx = tid + x * NT;
+                float m = -INFINITY, z = 0.f;
+                if (p2_ok[x])
+                    unpack_pair(await_pair(p2_base + (int64_t)(it - 2) * p2_step + x * NT, p2_bits[x],
+                                           F.spin_limit, gave_up), m, z);
+                const float mm = row16_max(m);
+                const float zz = row16_sum(m == -INFINITY ? 0.f : z * __builtin_amdgcn_exp2f(m - mm));
+                if (idx < R * NBP && (idx & (NBP - 1)) == 0) {
+                    const int row = idx / NBP, ru = row >> 4;
+                    const int i = (ru % F.UH) * 16 + (row & 15);
+                    const bool real = ru < F.RU && i < G.W && zz > 0.f;
+                    sm_fin[it & 1][row] = real ? make_float2(mm, 1.0f / zz) : make_float2(0.f, 0.f);
+                }
+            }
+        }
+        if constexpr (kNext1) {   // the next unit's Q chunks, visible to all waves after the barrier
+#pragma unroll
+            for (int x = 0; x < QPW; ++x)
+                if (w + x * NW < QCH) qbuf[(((it + 1) & 1) * QCH + w + x * NW) * 64 + lane] = qland[x];
+        }
         if (has_p1 && n16 == 0) {
 #pragma unroll
             for (int ru = 0; ru < RUW; ++ru) {
-                float4* dst = reinterpret_cast<float4*>(&sm_pair[w][ru * 16 + kg * 4]);
+                float4* dst = reinterpret_cast<float4*>(&sm_pair[it & 1][w][ru * 16 + kg * 4]);
                 dst[0] = make_float4(mref[ru][0], zs[ru][0], mref[ru][1], zs[ru][1]);
                 dst[1] = make_float4(mref[ru][2], zs[ru][2], mref[ru][3], zs[ru][3]);
                 *reinterpret_cast<float4*>(&sm_ref[it % 3][w][ru * 16 + kg * 4]) =
                     make_float4(mref[ru][0], mref[ru][1], mref[ru][2], mref[ru][3]);
             }
         }
-        SNAPKV_ISSUE(3);
         TRACE(2);
         lds_barrier();
         TRACE(3);
@@ -454,7 +517,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
             float mm[NW], zz[NW];
 #pragma unroll
             for (int w2 = 0; w2 < NW; ++w2) {
-                x[w2] = sm_pair[w2][row];
+                x[w2] = sm_pair[it & 1][w2][row];
                 mm[w2] = x[w2].x;
             }
 #pragma unroll
@@ -473,7 +536,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         }
         TRACE(4);
 
-        // ---- E. step L1 of the previous unit: merge 32 slices of one row per half-wave
+        // ---- F. step L1 of the previous unit: merge 32 slices of one row per half-wave
 #ifdef SNAPKV_EXP_NOE
         if (false) {
 #else
@@ -502,41 +565,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                 if (l32 == 0) publish_pair(&S.l1[(int64_t)unit_l1 * (R * NBP) + row * NBP + blk], mm, zz);
             }
         }
-        SNAPKV_ISSUE(4);
         TRACE(5);
-
-        // ---- F. step P2 of the unit before that: level-1 words of a row sit in 16 neighbouring
-        // lanes; merge them in a fixed tree into (max, 1/sum)
-#ifdef SNAPKV_EXP_NOP2
-        if (false) {
-#else
-        if (has_p2) {
-#endif
-#pragma unroll
-            for (int x = 0; x < L2PT; ++x) {
-                const int idx = tid + x * NT;
-                float m = -INFINITY, z = 0.f;
-                if (p2_ok[x])
-                    unpack_pair(await_pair(p2_base + (int64_t)(it - 2) * p2_step + x * NT, p2_bits[x],
-                                           F.spin_limit, gave_up), m, z);
-                const float mm = row16_max(m);
-                const float zz = row16_sum(m == -INFINITY ? 0.f : z * __builtin_amdgcn_exp2f(m - mm));
-                if (idx < R * NBP && (idx & (NBP - 1)) == 0) {
-                    const int row = idx / NBP, ru = row >> 4;
-                    const int i = (ru % F.UH) * 16 + (row & 15);
-                    const bool real = ru < F.RU && i < G.W && zz > 0.f;
-                    sm_fin[row] = real ? make_float2(mm, 1.0f / zz) : make_float2(0.f, 0.f);
-                }
-            }
-        }
-        SNAPKV_ISSUE(5);
-        if constexpr (kLoadNext) {   // the next unit's Q chunks, visible to all waves after the barrier
-#pragma unroll
-            for (int x = 0; x < QPW; ++x)
-                if (w + x * NW < QCH) qbuf[(((it + 1) & 1) * QCH + w + x * NW) * 64 + lane] = qland[x];
-        }
-        lds_barrier();
-        TRACE(6);
 #ifdef SNAPKV_EXP_NOP2
         if (false) {
 #else
@@ -545,7 +574,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
             float f[RUW][4];
 #pragma unroll
             for (int ru = 0; ru < RUW; ++ru) {
-                const float4* fin4 = reinterpret_cast<const float4*>(&sm_fin[ru * 16 + kg * 4]);
+                const float4* fin4 = reinterpret_cast<const float4*>(&sm_fin[it & 1][ru * 16 + kg * 4]);
                 const float4 a = fin4[0], b = fin4[1];   // (m, 1/Z) of rows kg*4 .. kg*4+3
                 const float4 ms = *reinterpret_cast<const float4*>(&sm_ref[(it + 1) % 3][w][ru * 16 + kg * 4]);
                 f[ru][0] = (ms.x == -INFINITY || a.y == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.x - a.x) * a.y;
@@ -617,6 +646,14 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                 e2[ru][t] = e1[ru][t];
                 e1[ru][t] = e[ru][t];
             }
+        TRACE(6);
+        // ---- H. the next unit's lower tiles meet its Q (in LDS since the barrier) and their
+        // buffers are requested again for the unit after it
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (kNext1) mfma_tiles(IC0{}, ICL{}, (it + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (kNext2) issue_tiles(IC0{}, ICL{});
+        __builtin_amdgcn_sched_barrier(0);
         TRACE(7);
 #ifdef SNAPKV_FUSED_TRACE
         ++trace_ui;
@@ -625,8 +662,9 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 
 #undef SNAPKV_ISSUE
     int it = 0;
-    for (; it + 1 < nu; ++it) iteration(std::true_type{}, it);
-    for (; it < nu + 2; ++it) iteration(std::false_type{}, it);   // last unit, then the two drain steps
+    for (; it + 2 < nu; ++it) iteration(std::integral_constant<int, 3>{}, it);
+    for (; it + 1 < nu; ++it) iteration(std::integral_constant<int, 1>{}, it);   // last but one unit
+    for (; it < nu + 2; ++it) iteration(std::integral_constant<int, 0>{}, it);   // last unit, two drain steps
     if (gave_up) atomicAdd(&g_sync_timeouts, 1u);
 }
 

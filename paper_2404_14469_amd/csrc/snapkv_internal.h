@@ -73,8 +73,8 @@ size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base);
 // Stage boundaries for the optional per-stage timing (snapkv_profile_start/stop): when timing is
 // active, stage_done records an event on the stream after the stage's launch; otherwise it is a
 // no-op.  kStageBegin marks the start of a call.
-enum Stage { kStageBegin = 0, kStagePass1, kStageReduce, kStagePass2, kStageFused, kStagePool,
-             kStageSelect, kStageGather, kNumStageMarks };
+enum Stage { kStageBegin = 0, kStagePrepare, kStagePass1, kStageReduce, kStagePass2, kStageFused,
+             kStagePool, kStageSelect, kStageGather, kNumStageMarks };
 void stage_done(hipStream_t st, int stage);
 
 // All launchers enqueue on `st` and return the launch status.

@@ -329,7 +329,6 @@ static hipError_t launch_score_t(const void* q, const void* k, const ScoreGeom& 
     stage_done(st, kStageReduce);
     hipLaunchKernelGGL((score_pass2<T, D>), dim3(blocks), dim3(256), 0, st, q, k, ws.mz, ws.vote, G);
     stage_done(st, kStagePass2);
-    stage_done(st, kStageFused);
     return hipGetLastError();
 }
 
