@@ -217,11 +217,19 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     const int tid = threadIdx.x, lane = tid & 63, n16 = lane & 15, kg = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wg = (int)(blockIdx.x % F.Gg), group = (int)(blockIdx.x / F.Gg);
-    const int tile0 = (wg * NW + w) * KT;
+    // Tile t of this wave is key tile tile0 + t * TS: the waves of the whole group work on the same
+    // t at about the same time, and this way what they request together is one contiguous stretch
+    // of K instead of one 4 KB piece out of every wave's 16 KB (which loads only part of the memory
+    // channels at any moment).
+    const int TS = F.Gg * NW;
+    // Workgroups are handed to the chip's eight dies in turn; those of one die take neighbouring
+    // stretches of keys so that the die's cache channels are loaded evenly.
+    const int vwg = (F.Gg % 8 == 0) ? (wg % 8) * (F.Gg / 8) + wg / 8 : wg;
+    const int tile0 = vwg * NW + w;
     const int nu = group < F.units ? (F.units - group + F.NG - 1) / F.NG : 0;   // units of this group
     if (nu == 0) return;
     // wave touches window columns, the ragged tail or tiles past the end: masks are needed
-    const bool special = (int64_t)(tile0 + KT) * 16 > G.n;
+    const bool special = ((int64_t)(KT - 1) * TS + tile0 + 1) * 16 > G.n;
     const int hw = tid >> 5, l32 = tid & 31;
     const int real_tasks = R * F.NB;
     bool gave_up = false;
@@ -235,7 +243,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     const char* kp[KT];
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
-        int64_t j = (int64_t)(tile0 + t) * 16 + n16;
+        int64_t j = ((int64_t)t * TS + tile0) * 16 + n16;
         j = j < G.L ? j : G.L - 1;
         kp[t] = static_cast<const char*>(kv) + ((int64_t)group * G.L + j) * D * ES + kg * 16;
     }
@@ -294,12 +302,12 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
             }
         }
     };
-    auto issue_tiles = [&](auto T0, auto T1) {
+    auto issue_tiles = [&](auto T0, auto T1, const int64_t step) {
 #ifndef SNAPKV_EXP_NOLOAD
         constexpr int t0 = decltype(T0)::value, t1 = decltype(T1)::value;
 #pragma unroll
         for (int t = t0; t < t1; ++t) {
-            kp[t] += kstep;
+            kp[t] += step;
             load_frag16p<T, D>(kf[t], kp[t]);
         }
 #endif
@@ -309,7 +317,10 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     using ICT = std::integral_constant<int, KT>;
     mfma_tiles(IC0{}, ICL{}, 0);
     __builtin_amdgcn_sched_barrier(0);
-    if (nu > 1) issue_tiles(IC0{}, ICL{});
+    // Unconditional (a group with a single unit re-reads it): the compiler derives how long a wait
+    // for older loads must be from the loads that certainly follow them on every path, so no load
+    // of the steady state may sit behind a branch.
+    issue_tiles(IC0{}, ICL{}, nu > 1 ? kstep : 0);
     __builtin_amdgcn_sched_barrier(0);
 
     // The next unit's Q chunk and upper K tiles are requested in kLoadSlots portions between the
@@ -351,13 +362,15 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     const bool l1_lane = l1_mine && l1_slice < F.Gg;
     const float2* const l1_base = S.part + ((int64_t)group * F.Gg + (l1_lane ? l1_slice : 0)) * R + l1_row;
     const int64_t l1_step = (int64_t)F.NG * F.Gg * R;
-    const float2* const p2_base = S.l1 + (int64_t)group * (R * NBP) + tid;
+    const float2* const p2_base = S.l1 + (int64_t)group * (R * NBP);
     const int64_t p2_step = (int64_t)F.NG * (R * NBP);
     bool p2_ok[L2PT];
+    int p2_at[L2PT];                     // word this thread fetches (threads without one re-read word 0)
 #pragma unroll
     for (int x = 0; x < L2PT; ++x) {
         const int idx = tid + x * NT;
         p2_ok[x] = idx < R * NBP && (idx & (NBP - 1)) < F.NB;
+        p2_at[x] = idx < R * NBP ? idx : 0;
     }
 
     // One iteration; MODE says (at compile time) whether the units one (bit 0) and two (bit 1)
@@ -378,14 +391,14 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         // the arithmetic of step D, about one memory latency from now.  A wave's loads retire in
         // order: these are younger than this unit's K and Q (waited for next) and older than the
         // next unit's (issued below), so waiting for them never waits for those.
-        unsigned long long l1_bits = pack_pair(-INFINITY, 0.f);
-        const float2* const l1_src = l1_base + (int64_t)(it - 1) * l1_step;
-        if (has_l1 && l1_lane) l1_bits = load_pair_bits(l1_src);
+        // The loads are unconditional (lanes and iterations without a word re-read a valid one and
+        // ignore it) so that their number is the same on every path.
+        const float2* const l1_src = l1_base + (int64_t)(has_l1 ? it - 1 : 0) * l1_step;
+        const unsigned long long l1_bits = load_pair_bits(l1_src);
+        const float2* const p2_src = p2_base + (int64_t)(has_p2 ? it - 2 : 0) * p2_step;
         unsigned long long p2_bits[L2PT];
 #pragma unroll
-        for (int x = 0; x < L2PT; ++x)
-            p2_bits[x] = has_p2 && p2_ok[x] ? load_pair_bits(p2_base + (int64_t)(it - 2) * p2_step + x * NT)
-                                            : pack_pair(-INFINITY, 0.f);
+        for (int x = 0; x < L2PT; ++x) p2_bits[x] = load_pair_bits(p2_src + p2_at[x]);
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- B. logits of the upper tiles of the slice (waits for their K; the lower tiles were
@@ -428,7 +441,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                 const int nn = (int)G.n, LL = (int)G.L;
 #pragma unroll
                 for (int t = 0; t < KT; ++t) {
-                    const int j = jlane + t * 16;
+                    const int j = jlane + t * TS * 16;
 #pragma unroll
                     for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
@@ -480,9 +493,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
             for (int x = 0; x < L2PT; ++x) {
                 const int idx = tid + x * NT;
                 float m = -INFINITY, z = 0.f;
-                if (p2_ok[x])
-                    unpack_pair(await_pair(p2_base + (int64_t)(it - 2) * p2_step + x * NT, p2_bits[x],
-                                           F.spin_limit, gave_up), m, z);
+                if (p2_ok[x]) unpack_pair(await_pair(p2_src + p2_at[x], p2_bits[x], F.spin_limit, gave_up), m, z);
                 const float mm = row16_max(m);
                 const float zz = row16_sum(m == -INFINITY ? 0.f : z * __builtin_amdgcn_exp2f(m - mm));
                 if (idx < R * NBP && (idx & (NBP - 1)) == 0) {
@@ -621,7 +632,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 #pragma unroll
                         for (int x = 0; x < KT / 4; ++x) {
                             const int t = ((kg & 2) ? KT / 2 : 0) + ((kg & 1) ? KT / 4 : 0) + x;
-                            const int j = jst + t * 16;
+                            const int j = jst + t * TS * 16;
                             if (head < G.g && j < nst) vh[j] = b[x];
                         }
                     } else {
@@ -629,7 +640,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                         for (int t = 0; t < KT; ++t) {
                             float s = v[t] + __shfl_xor(v[t], 32, 64);
                             s += __shfl_xor(s, 16, 64);
-                            const int j = jst + t * 16;
+                            const int j = jst + t * TS * 16;
                             if (kg == 0 && head < G.g && j < nst) vh[j] = s;
                         }
                     }
@@ -652,7 +663,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (kNext1) mfma_tiles(IC0{}, ICL{}, (it + 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (kNext2) issue_tiles(IC0{}, ICL{});
+        if constexpr (kNext2) issue_tiles(IC0{}, ICL{}, kstep);
         __builtin_amdgcn_sched_barrier(0);
         TRACE(7);
 #ifdef SNAPKV_FUSED_TRACE
