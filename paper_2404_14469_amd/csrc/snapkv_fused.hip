@@ -169,14 +169,29 @@ __device__ __forceinline__ unsigned long long await_pair(const float2* p, unsign
     return bits;
 }
 
-// LDS-only barrier: orders LDS traffic between the waves of the workgroup without draining the
-// global loads in flight.
-__device__ __forceinline__ void lds_barrier() {
-#ifndef SNAPKV_EXP_NOBAR
+// Hand-offs between the waves of a workgroup go through LDS without a barrier: a wave writes
+// its data, then stamps its flag with the iteration number; a reader waits (bounded) until the
+// flags of all waves have reached the stamp it needs.  The fences order LDS traffic only, so
+// that no wave ever drains its global loads in flight for them.
+__device__ __forceinline__ void lds_release() {
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
+}
+__device__ __forceinline__ void lds_stamp(int* flag, int value) {
+    __hip_atomic_store(flag, value, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+template <int NW>
+__device__ __forceinline__ void lds_await_all(int* flags, int need, unsigned limit, bool& gave_up) {
+    static_assert((NW & (NW - 1)) == 0, "waves per workgroup must be a power of two");
+    int* mine = flags + (threadIdx.x & (NW - 1));
+    unsigned spins = 0;
+    while (__hip_atomic_load(mine, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP) < need) {
+        if (gave_up || ++spins > limit) {
+            gave_up = true;
+            break;
+        }
+        __builtin_amdgcn_s_sleep(1);
+    }
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-#endif
 }
 
 template <int CTRL> __device__ __forceinline__ void dpp_merge(float& m, float& z) {
@@ -206,13 +221,18 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     constexpr int NP = Frag::NP;         // 16-byte pieces per lane per row
     constexpr int QCH = RUW * NP;        // 1 KB chunks of a unit's Q block, in the order the MFMAs read them
     constexpr int QPW = (QCH + NW - 1) / NW;   // chunks a wave fetches per unit
-    extern __shared__ uint4 qbuf[];      // [2][QCH][64]: Q block of the current and the next unit
-    // One workgroup barrier per iteration: what is written before it is read after it, and the
-    // buffers alternate between iterations so that a fast wave's next write cannot overtake a
-    // slow wave's read (the two are always separated by the following barrier).
+    extern __shared__ uint4 qbuf[];      // [3][QCH][64]: Q blocks of three consecutive units
+    // No barrier inside the loop.  Why the buffers may be reused when they are: a wave writes
+    // them only after step E of an iteration, which has waited for level-1 words of the unit two
+    // back; those exist only once every workgroup, this one included, has published that unit's
+    // slice, i.e. once all its waves have passed step D of the iteration two back.  Hence a
+    // buffer read up to the end of iteration `it` may be rewritten from iteration it + 3 on
+    // (qbuf, sm_fin: three copies), and one read by the publishing wave before it publishes
+    // from iteration it + 2 on (sm_pair: two copies).
     __shared__ float2 sm_pair[2][NW][R]; // per wave: (row max, row sum-exp) of the current unit
     __shared__ float sm_ref[3][NW][R];   // per wave: row maxima of the last three units (own wave only)
-    __shared__ float2 sm_fin[2][R];      // (row max, 1 / row sum-exp) of the unit in step P2
+    __shared__ float2 sm_fin[3][R];      // (row max, 1 / row sum-exp) of the unit in step P2
+    __shared__ int sm_flag[3][NW];       // per wave: Q chunks / sm_pair / sm_fin written up to this stamp
 
     const int tid = threadIdx.x, lane = tid & 63, n16 = lane & 15, kg = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -280,6 +300,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 #pragma unroll
     for (int x = 0; x < QPW; ++x)
         if (w + x * NW < QCH) qbuf[(w + x * NW) * 64 + lane] = qland[x];
+    if (tid < 3 * NW) sm_flag[tid / NW][tid % NW] = tid < NW ? 1 : 0;   // Q of unit 0 is in place
     __syncthreads();
     // exponentials of the two previous units stay in registers until their votes are taken
     f32x4 e1[RUW][KT], e2[RUW][KT];
@@ -365,12 +386,12 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     const float2* const p2_base = S.l1 + (int64_t)group * (R * NBP);
     const int64_t p2_step = (int64_t)F.NG * (R * NBP);
     bool p2_ok[L2PT];
-    int p2_at[L2PT];                     // word this thread fetches (threads without one re-read word 0)
+    int p2_at[L2PT];                     // word this thread fetches (threads without one take word 0)
 #pragma unroll
     for (int x = 0; x < L2PT; ++x) {
         const int idx = tid + x * NT;
         p2_ok[x] = idx < R * NBP && (idx & (NBP - 1)) < F.NB;
-        p2_at[x] = idx < R * NBP ? idx : 0;
+        p2_at[x] = p2_ok[x] ? idx : 0;   // word 0 always exists: every wave waits for at least that one
     }
 
     // One iteration; MODE says (at compile time) whether the units one (bit 0) and two (bit 1)
@@ -406,7 +427,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 #ifdef SNAPKV_FUSED_TRACE
         TRACE(8);
 #endif
-        if (has_p1) mfma_tiles(ICL{}, ICT{}, it & 1);
+        if (has_p1) mfma_tiles(ICL{}, ICT{}, it % 3);
         __builtin_amdgcn_sched_barrier(0);
         TRACE(9);
 
@@ -493,21 +514,22 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
             for (int x = 0; x < L2PT; ++x) {
                 const int idx = tid + x * NT;
                 float m = -INFINITY, z = 0.f;
-                if (p2_ok[x]) unpack_pair(await_pair(p2_src + p2_at[x], p2_bits[x], F.spin_limit, gave_up), m, z);
+                const unsigned long long got = await_pair(p2_src + p2_at[x], p2_bits[x], F.spin_limit, gave_up);
+                if (p2_ok[x]) unpack_pair(got, m, z);
                 const float mm = row16_max(m);
                 const float zz = row16_sum(m == -INFINITY ? 0.f : z * __builtin_amdgcn_exp2f(m - mm));
                 if (idx < R * NBP && (idx & (NBP - 1)) == 0) {
                     const int row = idx / NBP, ru = row >> 4;
                     const int i = (ru % F.UH) * 16 + (row & 15);
                     const bool real = ru < F.RU && i < G.W && zz > 0.f;
-                    sm_fin[it & 1][row] = real ? make_float2(mm, 1.0f / zz) : make_float2(0.f, 0.f);
+                    sm_fin[it % 3][row] = real ? make_float2(mm, 1.0f / zz) : make_float2(0.f, 0.f);
                 }
             }
         }
-        if constexpr (kNext1) {   // the next unit's Q chunks, visible to all waves after the barrier
+        if constexpr (kNext1) {   // the next unit's Q chunks
 #pragma unroll
             for (int x = 0; x < QPW; ++x)
-                if (w + x * NW < QCH) qbuf[(((it + 1) & 1) * QCH + w + x * NW) * 64 + lane] = qland[x];
+                if (w + x * NW < QCH) qbuf[(((it + 1) % 3) * QCH + w + x * NW) * 64 + lane] = qland[x];
         }
         if (has_p1 && n16 == 0) {
 #pragma unroll
@@ -519,11 +541,14 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                     make_float4(mref[ru][0], mref[ru][1], mref[ru][2], mref[ru][3]);
             }
         }
+        // what this wave has written up to here is complete: stamp its three flags
+        lds_release();
+        if (lane < 3) lds_stamp(&sm_flag[lane][w], lane == 0 ? it + 2 : it + 1);
         TRACE(2);
-        lds_barrier();
         TRACE(3);
         if (has_p1 && tid >= NT - R) {   // the last R threads merge the waves (in wave order) and publish
             const int row = tid - (NT - R);
+            lds_await_all<NW>(sm_flag[1], it + 1, F.spin_limit, gave_up);
             float2 x[NW];
             float mm[NW], zz[NW];
 #pragma unroll
@@ -582,10 +607,11 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 #else
         if (has_p2) {
 #endif
+            lds_await_all<NW>(sm_flag[2], it + 1, F.spin_limit, gave_up);
             float f[RUW][4];
 #pragma unroll
             for (int ru = 0; ru < RUW; ++ru) {
-                const float4* fin4 = reinterpret_cast<const float4*>(&sm_fin[it & 1][ru * 16 + kg * 4]);
+                const float4* fin4 = reinterpret_cast<const float4*>(&sm_fin[it % 3][ru * 16 + kg * 4]);
                 const float4 a = fin4[0], b = fin4[1];   // (m, 1/Z) of rows kg*4 .. kg*4+3
                 const float4 ms = *reinterpret_cast<const float4*>(&sm_ref[(it + 1) % 3][w][ru * 16 + kg * 4]);
                 f[ru][0] = (ms.x == -INFINITY || a.y == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.x - a.x) * a.y;
@@ -661,7 +687,10 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         // ---- H. the next unit's lower tiles meet its Q (in LDS since the barrier) and their
         // buffers are requested again for the unit after it
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (kNext1) mfma_tiles(IC0{}, ICL{}, (it + 1) & 1);
+        if constexpr (kNext1) {
+            lds_await_all<NW>(sm_flag[0], it + 2, F.spin_limit, gave_up);   // Q of the next unit
+            mfma_tiles(IC0{}, ICL{}, (it + 1) % 3);
+        }
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (kNext2) issue_tiles(IC0{}, ICL{}, kstep);
         __builtin_amdgcn_sched_barrier(0);
@@ -764,7 +793,7 @@ template <typename T, int D, int RUW, int NW>
 static hipError_t fused_instance(const FusedCall* call, int* occ) {
     constexpr int KT = kFusedSlots / RUW;
     auto kern = score_fused<T, D, RUW, KT, NW>;
-    constexpr int kQueueBytes = 2 * RUW * (D * (std::is_same<T, bf16_k>::value ? 2 : 4) / 64) * 64 * 16;   // Q blocks of two units
+    constexpr int kQueueBytes = 3 * RUW * (D * (std::is_same<T, bf16_k>::value ? 2 : 4) / 64) * 64 * 16;   // Q blocks of three units
     static int cached_occ = -1;
     if (cached_occ < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
