@@ -3,19 +3,18 @@
 //
 // The softmax normaliser of a window row needs all L logits of that row before any probability
 // can be summed down a column.  Instead of reading K twice, this kernel keeps the exponentials
-// of the logits on the chip (registers, then an LDS queue) across a device-wide hand-off:
+// of the logits in registers across a device-wide hand-off of the row normalisers:
 //
 //   * a KV head is a "unit".  The keys of a unit are cut into slices, one per workgroup of a
 //     group of Gg workgroups; NG groups work on different units at the same time.  Every
-//     workgroup stays resident (one workgroup per compute unit, the grid never exceeds the
-//     number of compute units).
+//     workgroup stays resident (the grid never exceeds what the device keeps resident at once).
 //   * step P1 of a unit: the slice of K, loaded once, meets the window queries on MFMA
 //     (16x16x32 bf16 or 16x16x4 fp32, fp32 accumulate); the slice's row maxima m_s are taken,
-//     e = 2^(s - m_s) goes into the LDS queue and (m_s, sum e) per row is published.
+//     e = 2^(s - m_s) stays in the wave's registers and (m_s, sum e) per row is published.
 //   * step L1, one unit later: the Gg slices of a row are merged 32 at a time by half-waves
 //     spread evenly over the workgroups of the group, and the merged pairs published.
 //   * step P2, another unit later: every workgroup merges the few level-1 pairs of each row
-//     into (m, 1/Z), scales the queued e by 2^(m_s - m)/Z and sums them over the window rows
+//     into (m, 1/Z), scales the kept e by 2^(m_s - m)/Z and sums them over the window rows
 //     of each query head: the vote of Eq. 1, stored for prefix columns.
 //   All workgroups do the same amount of merging, so none falls behind the others, and what a
 //   step reads was published a whole unit earlier, so the waits normally end at once.
@@ -25,9 +24,16 @@
 // (the host side fills the buffers with an all-ones pattern no real pair can have), so no
 // ordering between different addresses is needed and the kernel issues no cache write-backs or
 // invalidates.  The hand-off words of a step are requested at the top of an iteration, before
-// the K loads of the next unit, so that waiting for them never waits for K (a wave's loads
-// retire in order).  Every wait is bounded: if one gives up, a counter is raised and the
-// kernel still terminates.
+// the K loads issued in it, so that waiting for them never waits for those (a wave's loads
+// retire in order).  Inside a workgroup the waves exchange their partial results through LDS
+// with per-wave flags instead of barriers.  Every wait is bounded: if one gives up, a counter
+// is raised and the kernel still terminates.
+//
+// Keeping K in flight.  A wave's K tile buffers (registers) are the landing space of the
+// stream: half of them are consumed by MFMAs at the top of an iteration, half at its end, and
+// each is requested again at one of four points spread over the iteration.  All loads of the
+// steady state are unconditional, so that the compiler can count, on every path, how many
+// younger loads may stay in flight when it waits for an older one.
 //
 // MFMA layout (16x16 shapes, 64 lanes): lane l supplies row/column l%16 and contraction slice
 // l/16; accumulator register r of lane l is row (l/16)*4 + r, column l%16.  Which head-dim
@@ -336,41 +342,36 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     using IC0 = std::integral_constant<int, 0>;
     using ICL = std::integral_constant<int, KL>;
     using ICT = std::integral_constant<int, KT>;
+    using ICLA = std::integral_constant<int, (KL + 1) / 2>;              // lower tiles [0, LA) | [LA, KL)
+    using ICUA = std::integral_constant<int, KL + (KT - KL + 1) / 2>;    // upper tiles [KL, UA) | [UA, KT)
     mfma_tiles(IC0{}, ICL{}, 0);
     __builtin_amdgcn_sched_barrier(0);
     // Unconditional (a group with a single unit re-reads it): the compiler derives how long a wait
     // for older loads must be from the loads that certainly follow them on every path, so no load
     // of the steady state may sit behind a branch.
-    issue_tiles(IC0{}, ICL{}, nu > 1 ? kstep : 0);
+    issue_tiles(IC0{}, ICLA{}, nu > 1 ? kstep : 0);
     __builtin_amdgcn_sched_barrier(0);
 
-    // The next unit's Q chunk and upper K tiles are requested in kLoadSlots portions between the
-    // first steps of an iteration (a wave that issues a burst into a full pipeline stalls).
-    constexpr int kLoadSlots = 3;
-    constexpr int kLoadGroups = KT - KL + 1;
-    auto issue_slot = [&](auto SLOT) {
+    // K requests are paced: the tile buffers are requested again at four points spread evenly
+    // over an iteration (a quarter of the tiles each) instead of as soon as they are free, so
+    // that the compute unit's memory pipeline sees a steady stream rather than bursts it cannot
+    // absorb (a wave that issues into a full pipeline stalls).  Point 3 follows the lower tiles'
+    // MFMAs at the end of an iteration (first half of the lower tiles, for the unit two ahead),
+    // point 0 comes a quarter of an iteration later (their second half, by then for the next
+    // unit), points 1 and 2 re-request the halves of the upper tiles for the next unit.
+    auto issue_q = [&]() {
 #ifndef SNAPKV_EXP_NOLOAD
-        constexpr int slot_id = decltype(SLOT)::value;
 #pragma unroll
-        for (int g = 0; g < kLoadGroups; ++g) {
-            if (g * kLoadSlots / kLoadGroups != slot_id) continue;
-            if (g == 0) {
-#pragma unroll
-                for (int x = 0; x < QPW; ++x) {
-                    qp[x] += qstep;
-                    qland[x] = *reinterpret_cast<const uint4*>(qp[x]);
-                }
-            } else {
-                kp[KL + g - 1] += kstep;
-                load_frag16p<T, D>(kf[KL + g - 1], kp[KL + g - 1]);
-            }
+        for (int x = 0; x < QPW; ++x) {
+            qp[x] += qstep;
+            qland[x] = *reinterpret_cast<const uint4*>(qp[x]);
         }
 #endif
     };
-#define SNAPKV_ISSUE(slot_)                                                  \
+#define SNAPKV_ISSUE(cond_, what_)                                           \
     do {                                                                     \
         __builtin_amdgcn_sched_barrier(0);                                   \
-        if constexpr (kNext1) issue_slot(std::integral_constant<int, slot_>{}); \
+        if constexpr (cond_) { what_; }                                      \
         __builtin_amdgcn_sched_barrier(0);                                   \
     } while (0)
 
@@ -432,7 +433,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         TRACE(9);
 
         // ---- C. the next unit's Q and upper K tiles follow in portions between the steps below
-        SNAPKV_ISSUE(0);
+        SNAPKV_ISSUE(kNext1, issue_q());
         TRACE(1);
 
         float mref[RUW][4], zs[RUW][4];
@@ -479,7 +480,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 #pragma unroll
                 for (int r = 0; r < 4; ++r) mref[ru][r] = row16_max(mref[ru][r]) * G.c2;   // base-2 domain
         }
-        SNAPKV_ISSUE(1);
+        SNAPKV_ISSUE(kNext1, issue_tiles(ICLA{}, ICL{}, kstep));   // point 0
 #ifdef SNAPKV_EXP_NOD
         if (false) {
 #else
@@ -501,7 +502,6 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                     zs[ru][r] = row16_sum(z);
                 }
         }
-        SNAPKV_ISSUE(2);
         TRACE(10);
         // ---- E. step P2 of the unit two back: level-1 words of a row sit in 16 neighbouring
         // lanes; merge them in a fixed tree into (max, 1/sum)
@@ -545,6 +545,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         lds_release();
         if (lane < 3) lds_stamp(&sm_flag[lane][w], lane == 0 ? it + 2 : it + 1);
         TRACE(2);
+        SNAPKV_ISSUE(kNext1, issue_tiles(ICL{}, ICUA{}, kstep));   // point 1
         TRACE(3);
         if (has_p1 && tid >= NT - R) {   // the last R threads merge the waves (in wave order) and publish
             const int row = tid - (NT - R);
@@ -601,6 +602,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                 if (l32 == 0) publish_pair(&S.l1[(int64_t)unit_l1 * (R * NBP) + row * NBP + blk], mm, zz);
             }
         }
+        SNAPKV_ISSUE(kNext1, issue_tiles(ICUA{}, ICT{}, kstep));   // point 2
         TRACE(5);
 #ifdef SNAPKV_EXP_NOP2
         if (false) {
@@ -622,7 +624,11 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
             float* vb = vote + (int64_t)unit_p2 * G.g * G.n;
             int jst = tile0 * 16 + n16;       // opaque for the same reason as above
             asm volatile("" : "+v"(jst));
+#ifdef SNAPKV_EXP_NOVOTE
+            const int nst = (int)G.n - (int)G.L;   // timing experiment: no lane stores its votes
+#else
             const int nst = (int)G.n;
+#endif
             float v[KT];
 #pragma unroll
             for (int t = 0; t < KT; ++t) v[t] = 0.f;
@@ -692,7 +698,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
             mfma_tiles(IC0{}, ICL{}, (it + 1) % 3);
         }
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (kNext2) issue_tiles(IC0{}, ICL{}, kstep);
+        if constexpr (kNext2) issue_tiles(IC0{}, ICLA{}, kstep);   // point 3
         __builtin_amdgcn_sched_barrier(0);
         TRACE(7);
 #ifdef SNAPKV_FUSED_TRACE
