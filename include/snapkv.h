@@ -134,16 +134,20 @@ int snapkv_num_stages(void);
 const char* snapkv_stage_name(int stage);
 
 /*
- * Scoring scheme.  0 (default): prompts whose window logits fit the chip's register files are
- * scored by the single-read kernel (K is streamed once), longer ones by the two-pass kernels
- * (K is streamed twice).  1: always the two-pass kernels.  Both give the scores of Eq. 1 to
- * within rounding; the setting is process-wide and meant for tests and measurements.
+ * Kernel scheme, a bit set (default 0).  Bit 0 clear: prompts whose window logits fit the chip's
+ * register files are scored by the single-read kernel (K is streamed once), longer ones by the
+ * two-pass kernels (K is streamed twice); bit 0 set: always the two-pass kernels.  Bit 1 clear:
+ * pooling and top-k selection run as one cooperative launch where a head's scores fit the
+ * resident workgroups, otherwise as separate kernels; bit 1 set: always the separate kernels.
+ * All schemes give the scores of Eq. 1 to within rounding, and the selection of Eq. 2 exactly
+ * for the scores they computed; the setting is process-wide and meant for tests and measurements.
  */
 int snapkv_set_scoring_scheme(int scheme);
 
 /*
- * The single-read kernel hands row normalisers between resident workgroups and bounds every
- * wait; a wait that gives up is counted here (0 in correct operation).  Synchronises the
+ * The single-read scoring kernel and the cooperative pooling + selection kernel hand data
+ * between resident workgroups and bound every wait; a wait that gives up is counted here (0 in
+ * correct operation; the results of such a call are invalid).  Synchronises the
  * device.  Returns the count since the library was loaded, or a negative SNAPKV_ERR_* code.
  */
 int64_t snapkv_sync_timeouts(void);

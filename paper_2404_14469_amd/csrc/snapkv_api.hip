@@ -29,6 +29,7 @@ struct Profile {
 };
 Profile g_prof;
 bool g_allow_fused = true;   // snapkv_set_scoring_scheme: tests can force the two-pass kernels
+bool g_allow_pool_select = true;   // ... and the separate pooling and selection kernels
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -72,16 +73,18 @@ int internal_scratch(size_t need, void** out) {
     return SNAPKV_OK;
 }
 
+// Steps 1-3.  With score == nullptr the pooling kernel is left out (the caller pools and selects
+// in one launch) and *Gv tells how the votes are laid out.
 int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGeom& G,
                const Workspace& ws, int pool_kind, int p, float* score, unsigned* minmax,
-               hipStream_t st) {
+               bool prepare_select, ScoreGeom* Gv, hipStream_t st) {
     FusedGeom F;
     ScoreGeom Gp = G;
     const bool fused = g_allow_fused && fused_plan(dtype, D, G, &F);
     FusedSync S;
     if (fused) fused_sync_layout(G, F, &S, ws.fused);
-    if (launch_prepare(fused ? S.part : nullptr, fused ? fused_sync_pairs(F) : 0, minmax ? &ws.sel : nullptr,
-                       G.Hkv, st) != hipSuccess)
+    if (launch_prepare(fused ? S.part : nullptr, fused ? fused_sync_pairs(F) : 0,
+                       prepare_select ? &ws.sel : nullptr, G.Hkv, st) != hipSuccess)
         return SNAPKV_ERR_HIP;
     stage_done(st, kStagePrepare);
     if (fused) {   // K is read once; otherwise two passes over K
@@ -92,6 +95,8 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
     } else if (launch_score(dtype, D, q_win, k, G, ws, st) != hipSuccess) {
         return SNAPKV_ERR_HIP;
     }
+    if (Gv) *Gv = Gp;
+    if (!score) return SNAPKV_OK;
     if (launch_pool(Gp, ws.vote, pool_kind, p, score, minmax, st) != hipSuccess) return SNAPKV_ERR_HIP;
     stage_done(st, kStagePool);
     return SNAPKV_OK;
@@ -133,10 +138,19 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     workspace_layout(G, &ws, base);
     stage_done(st, kStageBegin);
     const bool chunked = select_chunked_ok(G.n);
-    rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr, st);
-    if (rc != SNAPKV_OK) return rc;
-    const hipError_t se = chunked ? launch_select_chunked(ws.score, Hkv, G.n, C - W, C, W, out_idx, ws.sel, pool_tiles(G.n), st)
-                                  : launch_select(ws.score, Hkv, G.n, C - W, C, W, out_idx, st);
+    hipError_t se;
+    if (g_allow_pool_select && pool_select_ok(G, p, C - W)) {   // pooling and selection in one launch
+        ScoreGeom Gv = G;
+        rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, true, &Gv, st);
+        if (rc != SNAPKV_OK) return rc;
+        se = launch_pool_select(Gv, ws.vote, pool_kind, p, C - W, C, W, out_idx, ws.sel, st);
+    } else {
+        rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr,
+                        chunked, nullptr, st);
+        if (rc != SNAPKV_OK) return rc;
+        se = chunked ? launch_select_chunked(ws.score, Hkv, G.n, C - W, C, W, out_idx, ws.sel, pool_tiles(G.n), st)
+                     : launch_select(ws.score, Hkv, G.n, C - W, C, W, out_idx, st);
+    }
     if (se != hipSuccess) return SNAPKV_ERR_HIP;
     stage_done(st, kStageSelect);
     if (launch_gather(k, v, out_idx, Hkv, L, C, C, row_bytes, out_k, out_v, st) != hipSuccess)
@@ -158,7 +172,8 @@ int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, 
     if (rc != SNAPKV_OK) return rc;
     Workspace ws;
     workspace_layout(G, &ws, base);
-    return run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, out_scores, nullptr, static_cast<hipStream_t>(stream));
+    return run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, out_scores, nullptr, false, nullptr,
+                      static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -226,14 +241,15 @@ int snapkv_profile_stop(double* stage_ms, int* calls) {
 }
 
 int snapkv_set_scoring_scheme(int scheme) {
-    if (scheme != 0 && scheme != 1) return SNAPKV_ERR_INVALID_ARG;
-    g_allow_fused = scheme == 0;
+    if (scheme < 0 || scheme > 3) return SNAPKV_ERR_INVALID_ARG;
+    g_allow_fused = (scheme & 1) == 0;
+    g_allow_pool_select = (scheme & 2) == 0;
     return SNAPKV_OK;
 }
 
 int64_t snapkv_sync_timeouts(void) {
-    const unsigned v = read_sync_timeouts();
-    return v == ~0u ? (int64_t)SNAPKV_ERR_HIP : (int64_t)v;
+    const unsigned v = read_sync_timeouts(), u = read_select_timeouts();
+    return (v == ~0u || u == ~0u) ? (int64_t)SNAPKV_ERR_HIP : (int64_t)v + (int64_t)u;
 }
 
 int snapkv_num_stages(void) { return kNumStageMarks - 1; }

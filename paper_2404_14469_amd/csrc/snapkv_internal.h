@@ -56,6 +56,15 @@ struct SelectScratch {
     unsigned* chunk_gt;    // [H][chunks] positions in bins above the threshold bin
     unsigned* chunk_off;   // [H][chunks][2] output offsets: (#greater, #equal) before the chunk
     uint2* cand;           // [H][n]      (pattern, position) of positions inside the threshold bin, by chunk
+    // scratch of the cooperative pooling + selection kernel (pool_select); the first three arrays
+    // are contiguous and must be zero when the kernel starts (ps_zero_words words from ps_arrive)
+    unsigned* ps_arrive;   // [H][8]        arrival counters of the group-wide rendezvous points
+    unsigned* ps_cand_n;   // [H]           entries in the head's candidate list
+    unsigned* ps_hist;     // [H][3][2048]  digit histograms, one per refinement level
+    unsigned* ps_range;    // [H][512][2]   per-workgroup (smallest, largest) score bit pattern
+    unsigned* ps_part;     // [H][512][2]   per-workgroup (#above the threshold bin, #inside it)
+    uint2* ps_cand;        // [H][4096]     (pattern, position) of positions inside the threshold bin
+    int64_t ps_zero_words;
 };
 
 struct Workspace {
@@ -93,6 +102,13 @@ bool select_chunked_ok(int64_t n);
 hipError_t launch_select_init(const SelectScratch& S, int H, hipStream_t st);
 hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, int H, hipStream_t st);
 int64_t fused_sync_pairs(const FusedGeom& F);
+// Pooling and selection in one cooperative launch (reads votes, writes the kept positions).
+// pool_select_ok says whether the shape fits and the grid can be resident on the current device.
+bool pool_select_ok(const ScoreGeom& G, int p, int64_t kcount);
+hipError_t launch_pool_select(const ScoreGeom& G, const float* vote, int pool_kind, int p, int64_t kcount,
+                              int64_t out_stride, int W_tail, int32_t* out_idx, const SelectScratch& S,
+                              hipStream_t st);
+unsigned read_select_timeouts();
 hipError_t launch_select_chunked(const float* score, int H, int64_t n, int64_t kcount,
                                  int64_t out_stride, int W_tail, int32_t* out_idx,
                                  const SelectScratch& S, int minmax_parts, hipStream_t st);

@@ -23,11 +23,24 @@ constexpr int kSelChunk = 4096;        // positions per workgroup in the chunked
 constexpr int kSelBins1 = 512;         // first digit (whole row, global histogram): 9 bits
 constexpr int kSelBins = 2048;         // later digits (candidates only, LDS histogram): 11 bits
 constexpr int kSelMaxChunks = 4096;    // LDS arrays of sel_threshold; longer rows use one workgroup
+constexpr int kPsThreads = 1024;       // cooperative pooling + selection kernel: threads per workgroup
+constexpr int kPsCandCap = 4096;       //   candidates of a head that fit its LDS list
+constexpr int kPsBinBits = 11;         //   bits per refinement level
+constexpr int kPsBins = 1 << kPsBinBits;
+constexpr int kPsLevels = 3;           //   refinement levels (cover all 32 bits)
+constexpr int kPsStages = 8;           //   rendezvous points per head: ranges, levels, final
+constexpr int kPsMaxGroup = 512;       //   workgroups per head at most
 
 __device__ __forceinline__ int range_shift(unsigned range) {
     // smallest shift with (range >> shift) < kSelBins1
     const int bits = 32 - __clz(range | 1u);
     return bits > 9 ? bits - 9 : 0;
+}
+
+__device__ __forceinline__ int range_shift_bits(unsigned range, int digit_bits) {
+    // smallest shift with (range >> shift) < 2^digit_bits
+    const int bits = 32 - __clz(range | 1u);
+    return bits > digit_bits ? bits - digit_bits : 0;
 }
 
 // Exclusive prefix sum over the block (NT threads, NT a multiple of 64, at most 1024); returns
@@ -471,6 +484,526 @@ __global__ __launch_bounds__(256) void sel_emit(const float* __restrict__ score,
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------
+// Pooling (Sec. 4.3), group sum and top-k selection (Eq. 2) in ONE cooperative launch.
+//
+// The Wh workgroups of a KV head each pool a contiguous chunk of the head's votes straight into
+// registers (the pooled scores are never written to memory), then agree on the threshold through
+// a few rendezvous points in global memory: the head's range of bit patterns, one 512-bin digit
+// histogram per refinement level, and finally the few positions inside the threshold bin (or, when
+// the bin is a single value, only their number).  Every workgroup then knows the threshold T, how
+// many positions equal to T are kept, and how many kept positions lie before its chunk, and emits
+// its own kept positions in order.  The arithmetic of the pooled score is that of pool_group, in
+// the same order, so the scores are bit-identical to snapkv_pooled_scores; everything after it is
+// integer work on bit patterns and does not depend on timing.
+//
+// All workgroups of the grid must be resident at once (checked by the host).  Waits are bounded:
+// if one gives up, later ones are skipped, a counter is raised and the kernel still ends.
+// ------------------------------------------------------------------------------------------------
+__device__ unsigned g_select_timeouts = 0;
+
+// Optional timestamps for tuning builds (-DSNAPKV_FUSED_TRACE); not compiled by default.
+#ifdef SNAPKV_FUSED_TRACE
+__device__ long long g_ps_trace[1024 * 16];
+#define PS_TRACE(slot_) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_ps_trace[blockIdx.x * 16 + (slot_)] = wall_clock64(); } while (0)
+#else
+#define PS_TRACE(slot_) do { } while (0)
+#endif
+
+unsigned read_select_timeouts() {
+    unsigned v = 0;
+    if (hipMemcpyFromSymbol(&v, HIP_SYMBOL(g_select_timeouts), sizeof v) != hipSuccess) return ~0u;
+    return v;
+}
+
+__device__ __forceinline__ unsigned coherent_load(const unsigned* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void coherent_store(unsigned* p, unsigned v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Rendezvous of the `expect` workgroups that share `ctr` (zero before the first arrival).  What a
+// workgroup handed over before the call with coherent_store / device-scope atomics can be read
+// by all of them after it with coherent_load.  No cache write-back or invalidate is involved: those
+// accesses are performed at the device's coherence point, and a wave's memory counter only
+// reaches zero once they have been acknowledged, which is what the workgroup-scope fence waits for
+// before thread 0 counts the workgroup in.
+__device__ __forceinline__ void group_rendezvous(unsigned* ctr, unsigned expect, unsigned limit,
+                                                 unsigned* gave_up) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (threadIdx.x == 0 && !*gave_up) {
+        __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        unsigned spins = 0;
+        while (__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < expect) {
+            if (++spins > limit) {
+                *gave_up = 1u;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(4);
+        }
+    }
+    __syncthreads();
+}
+
+// Sums of up to three values over the block, one barrier pair for all of them; every thread gets
+// the totals.  sh needs 3 * NT / 64 words and may be reused right after the call returns.
+template <int NT>
+__device__ __forceinline__ void block_sum3(unsigned& a, unsigned& b, unsigned& c, unsigned* sh) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        a += __shfl_xor(a, d, 64);
+        b += __shfl_xor(b, d, 64);
+        c += __shfl_xor(c, d, 64);
+    }
+    __syncthreads();
+    if (lane == 0) {
+        sh[wave] = a;
+        sh[NT / 64 + wave] = b;
+        sh[2 * (NT / 64) + wave] = c;
+    }
+    __syncthreads();
+    a = b = c = 0u;
+#pragma unroll
+    for (int w2 = 0; w2 < NT / 64; ++w2) {
+        a += sh[w2];
+        b += sh[NT / 64 + w2];
+        c += sh[2 * (NT / 64) + w2];
+    }
+}
+
+template <int EPT, int P>
+__global__ __launch_bounds__(kPsThreads) void pool_select(
+    const float* __restrict__ vote, const ScoreGeom G, const int pool_kind, const int p_arg,
+    const int64_t kcount, const int64_t out_stride, const int W_tail, int32_t* __restrict__ out_idx,
+    const SelectScratch S, const int Wh, const int chunk, const unsigned spin_limit) {
+    constexpr int NT = kPsThreads;
+    constexpr int NWV = NT / 64;
+    // One dynamic LDS block, used in turn as the staging area of the votes (chunk plus a halo of
+    // p/2 positions on either side) and, once the scores sit in registers, as digit histogram
+    // (kPsBins words) followed by the candidate list (kPsCandCap pairs).
+    extern __shared__ unsigned ps_lds[];
+    float* const stage = reinterpret_cast<float*>(ps_lds);
+    unsigned* const sh_hist = ps_lds;
+    uint2* const sh_cand = reinterpret_cast<uint2*>(ps_lds + kPsBins);
+    __shared__ unsigned sh_tab[2][(EPT / 4) * NWV]; // per (run row, wave) counts for the ordered emission
+    __shared__ unsigned sh_scan[16], sh_out[2], sh_red[3 * NWV], sh_gave_up;
+    __shared__ unsigned sh_off[kPsMaxGroup + 1];    // start of each workgroup's candidates in the merged list
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int h = blockIdx.x / Wh, c = blockIdx.x % Wh;
+    const int64_t n = G.n;
+    const int64_t chunk0 = (int64_t)c * chunk;
+    const int64_t chunk1 = chunk0 + chunk < n ? chunk0 + chunk : n;
+    const int len = chunk1 > chunk0 ? (int)(chunk1 - chunk0) : 0;
+    int32_t* out = out_idx + (int64_t)h * out_stride;
+    if (c == 0)   // window positions follow the selected prefix positions
+        for (int t = tid; t < W_tail; t += NT) out[kcount + t] = (int32_t)(n + t);
+    if (kcount <= 0) return;
+    if (tid == 0) sh_gave_up = 0u;
+    PS_TRACE(0);
+
+    // ---- pooled, group-summed scores of this thread's positions, in the arithmetic and order of
+    // pool_group.  A thread owns EPT / 4 runs of four consecutive positions: element e = 4 * e4 + k
+    // is position chunk0 + e4 * 4 * NT + 4 * tid + k, so that position order is (e4, thread, k).
+    // Per query head the chunk's votes and a halo on either side pass through LDS once (as
+    // 16-byte pieces where the rows are aligned); the taps of four positions are then a few
+    // 16-byte LDS reads.
+    static_assert(EPT % 4 == 0, "positions are owned in runs of four");
+    constexpr int E4 = EPT / 4;
+    const int p = P > 0 ? P : p_arg;
+    const int r = p >> 1;
+    const int HQ = 4 * ((r + 3) / 4);            // halo, rounded up to whole 16-byte pieces
+    const float pad = pool_kind == 0 ? -INFINITY : 0.f;
+    const int nf4 = ((len + 3) / 4) + 2 * (HQ / 4);   // 16-byte pieces to stage
+    const bool rows_aligned = (n & 3) == 0 && (reinterpret_cast<uintptr_t>(vote) & 15u) == 0;
+    auto pos_local = [&](int e) { return (e >> 2) * (4 * NT) + 4 * tid + (e & 3); };
+    unsigned x[EPT];
+    {
+        float acc[EPT];
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) acc[e] = 0.f;
+        for (int hq = 0; hq < G.g; ++hq) {
+            const float* vb = vote + ((int64_t)h * G.NV + (int64_t)hq * G.VB) * n;
+            if (hq > 0) __syncthreads();          // the previous head's taps have been read
+            float4 land[E4 + 1];                  // all loads are in flight before the first LDS write
+#pragma unroll
+            for (int e4 = 0; e4 <= E4; ++e4) {
+                const int f = e4 * NT + tid;
+                const int64_t q0 = chunk0 - HQ + 4 * (int64_t)f;
+                float4 t4 = make_float4(pad, pad, pad, pad);
+                if (f < nf4) {
+                    if (P > 0 && rows_aligned) {
+                        if (q0 >= 0 && q0 < n) t4 = *reinterpret_cast<const float4*>(vb + q0);
+                    } else {
+                        float t[4];
+#pragma unroll
+                        for (int k = 0; k < 4; ++k) {
+                            const int64_t q = q0 + k;
+                            t[k] = pad;
+                            if (q >= 0 && q < n) {
+                                t[k] = vb[q];
+                                if (P == 0)   // several vote rows per query head only reach the loop form
+                                    for (int b = 1; b < G.VB; ++b) t[k] += vb[(int64_t)b * n + q];
+                            }
+                        }
+                        t4 = make_float4(t[0], t[1], t[2], t[3]);
+                    }
+                }
+                land[e4] = t4;
+            }
+#pragma unroll
+            for (int e4 = 0; e4 <= E4; ++e4) {
+                const int f = e4 * NT + tid;
+                if (f < nf4) reinterpret_cast<float4*>(stage)[f] = land[e4];
+            }
+            __syncthreads();
+            PS_TRACE(13);
+#pragma unroll
+            for (int e4 = 0; e4 < E4; ++e4) {
+                const int i0 = e4 * (4 * NT) + 4 * tid;      // first of the four positions; its taps
+                if (i0 >= len) continue;                     // start at stage[i0 + HQ - r]
+                if (P > 0) {
+                    constexpr int RQ = (P / 2 + 3) / 4, NV4 = 2 * RQ + 1;
+                    float v[4 * NV4];
+#pragma unroll
+                    for (int b4 = 0; b4 < NV4; ++b4) {
+                        const float4 q4 = reinterpret_cast<const float4*>(stage)[(i0 >> 2) + b4];
+                        v[4 * b4] = q4.x;
+                        v[4 * b4 + 1] = q4.y;
+                        v[4 * b4 + 2] = q4.z;
+                        v[4 * b4 + 3] = q4.w;
+                    }
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        float val = v[4 * RQ + k - P / 2];
+#pragma unroll
+                        for (int d = 1; d < P; ++d)
+                            val = pool_kind == 0 ? fmaxf(val, v[4 * RQ + k - P / 2 + d]) : val + v[4 * RQ + k - P / 2 + d];
+                        if (pool_kind != 0) val = val / (float)P;
+                        acc[4 * e4 + k] += val;
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < 4; ++k) {
+                        const int s0 = i0 + k + HQ - r;
+                        float val = stage[s0];
+                        for (int d = 1; d < p; ++d) val = pool_kind == 0 ? fmaxf(val, stage[s0 + d]) : val + stage[s0 + d];
+                        if (pool_kind != 0) val = val / (float)p;
+                        acc[4 * e4 + k] += val;
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) x[e] = __float_as_uint(acc[e]);
+    }
+    unsigned active = 0;        // bit e: position e is valid and still inside the searched range
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+        if (pos_local(e) < len) active |= 1u << e;
+    const unsigned valid = active;
+    PS_TRACE(1);
+
+    // ---- the head's range of bit patterns
+    unsigned lo = 0xFFFFFFFFu, hi = 0u;
+#pragma unroll
+    for (int e = 0; e < EPT; ++e)
+        if (valid >> e & 1u) {
+            lo = x[e] < lo ? x[e] : lo;
+            hi = x[e] > hi ? x[e] : hi;
+        }
+    auto block_range = [&]() {
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) {
+            const unsigned a = __shfl_xor(lo, d, 64), b = __shfl_xor(hi, d, 64);
+            lo = a < lo ? a : lo;
+            hi = b > hi ? b : hi;
+        }
+        __syncthreads();
+        if (lane == 0) {
+            sh_red[2 * wave] = lo;
+            sh_red[2 * wave + 1] = hi;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int w2 = 0; w2 < NWV; ++w2) {
+            lo = sh_red[2 * w2] < lo ? sh_red[2 * w2] : lo;
+            hi = sh_red[2 * w2 + 1] > hi ? sh_red[2 * w2 + 1] : hi;
+        }
+    };
+    block_range();
+    if (tid == 0) {
+        coherent_store(&S.ps_range[2 * ((int64_t)h * kPsMaxGroup + c)], lo);
+        coherent_store(&S.ps_range[2 * ((int64_t)h * kPsMaxGroup + c) + 1], hi);
+    }
+    unsigned* arrive = S.ps_arrive + (int64_t)h * kPsStages;
+    PS_TRACE(2);
+    group_rendezvous(arrive + 0, (unsigned)Wh, spin_limit, &sh_gave_up);
+    PS_TRACE(3);
+    lo = 0xFFFFFFFFu;
+    hi = 0u;
+    for (int i = lane; i < Wh; i += 64) {     // every wave reads all of them: no barrier needed
+        const unsigned a = coherent_load(&S.ps_range[2 * ((int64_t)h * kPsMaxGroup + i)]);
+        const unsigned b = coherent_load(&S.ps_range[2 * ((int64_t)h * kPsMaxGroup + i) + 1]);
+        lo = a < lo ? a : lo;
+        hi = b > hi ? b : hi;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const unsigned a = __shfl_xor(lo, d, 64), b = __shfl_xor(hi, d, 64);
+        lo = a < lo ? a : lo;
+        hi = b > hi ? b : hi;
+    }
+
+    // ---- threshold bin: 11 bits per level until the bin is a single value or holds few positions
+    unsigned cur_lo = lo, krem = (unsigned)kcount, above = 0, bin_count = 0, T = lo, need_eq = 0;
+    int cur_sh = hi > lo ? range_shift_bits(hi - lo, kPsBinBits) : 0;
+    bool exact = hi <= lo;      // T is known exactly (all remaining positions are equal to it)
+    if (exact) need_eq = krem;
+    for (int lvl = 0; lvl < kPsLevels && !exact; ++lvl) {
+        __syncthreads();
+        for (int b = tid; b < kPsBins; b += NT) sh_hist[b] = 0u;
+        if (tid == 0) {
+            sh_out[0] = 0u;
+            sh_out[1] = 1u;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+            if (active >> e & 1u) atomicAdd(&sh_hist[((x[e] - cur_lo) >> cur_sh) & (kPsBins - 1)], 1u);
+        __syncthreads();
+        unsigned* gh = S.ps_hist + ((int64_t)h * kPsLevels + lvl) * kPsBins;
+        for (int b = tid; b < kPsBins; b += NT) {
+            const unsigned cnt = sh_hist[b];
+            if (cnt) atomicAdd(&gh[b], cnt);
+        }
+        PS_TRACE(4 + 2 * (lvl < 2 ? lvl : 1));
+        group_rendezvous(arrive + 1 + lvl, (unsigned)Wh, spin_limit, &sh_gave_up);
+        PS_TRACE(5 + 2 * (lvl < 2 ? lvl : 1));
+        unsigned bins[kPsBins / NT];
+#pragma unroll
+        for (int e = 0; e < kPsBins / NT; ++e)
+            bins[e] = coherent_load(&gh[kPsBins - 1 - (tid * (kPsBins / NT) + e)]);
+        find_bin_from_top<NT, kPsBins>(bins, krem, sh_scan, sh_out);
+        const unsigned b1 = sh_out[0] & (kPsBins - 1);
+        krem = sh_out[1];
+        bin_count = coherent_load(&gh[b1]);
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+            if (active >> e & 1u) {
+                const unsigned d = ((x[e] - cur_lo) >> cur_sh) & (kPsBins - 1);
+                if (d > b1) ++above;
+                if (d != b1) active &= ~(1u << e);
+            }
+        cur_lo += b1 << cur_sh;
+        if (cur_sh == 0) {
+            exact = true;
+            T = cur_lo;
+            need_eq = krem;
+        } else if (bin_count <= (unsigned)kPsCandCap) {
+            break;
+        } else {
+            cur_sh = range_shift_bits((1u << cur_sh) - 1u, kPsBinBits);
+        }
+    }
+    PS_TRACE(8);
+
+    // ---- final exchange: counts per workgroup, and the candidates unless T is already exact
+    const unsigned mine_in = (unsigned)__popc(active);
+    unsigned in_total = 0;
+    const unsigned in_before = block_exclusive_scan<NT>(mine_in, sh_scan, &in_total);
+    unsigned above_total = above, z1 = 0, z2 = 0;
+    block_sum3<NT>(above_total, z1, z2, sh_red);
+    if (!exact) {   // this workgroup's candidates go to the start of its own stretch of the head's list
+        unsigned slot = in_before;
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+            if (active >> e & 1u) {
+                if (slot < (unsigned)len)
+                    __hip_atomic_store(reinterpret_cast<unsigned long long*>(&S.cand[(int64_t)h * n + chunk0 + slot]),
+                                       ((unsigned long long)(unsigned)(chunk0 + pos_local(e)) << 32) | x[e],
+                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ++slot;
+            }
+    }
+    if (tid == 0) {
+        coherent_store(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + c)], above_total);
+        coherent_store(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + c) + 1], in_total);
+    }
+    PS_TRACE(9);
+    group_rendezvous(arrive + 1 + kPsLevels, (unsigned)Wh, spin_limit, &sh_gave_up);
+    PS_TRACE(10);
+
+    // kept positions of the head before this chunk.  Every wave sums the per-workgroup counts
+    // itself (no barrier); without an exact T the candidates are fetched, workgroup by workgroup.
+    unsigned gt_before = 0, eq_before = 0;
+    for (int i = lane; i < c; i += 64) {
+        gt_before += coherent_load(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + i)]);
+        eq_before += coherent_load(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + i) + 1]);
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        gt_before += __shfl_xor(gt_before, d, 64);
+        eq_before += __shfl_xor(eq_before, d, 64);
+    }
+    if (!exact) {
+        eq_before = 0;              // positions inside the bin are counted from the candidate list
+        const unsigned m = bin_count < (unsigned)kPsCandCap ? bin_count : (unsigned)kPsCandCap;
+        __syncthreads();            // sh_hist / sh_cand share the LDS block
+        // where each workgroup's candidates start in the merged list (wave 0 scans the counts)
+        if (wave == 0) {
+            unsigned run = 0;
+            for (int base = 0; base < Wh; base += 64) {
+                const int i = base + lane;
+                const unsigned cnt = i < Wh ? coherent_load(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + i) + 1]) : 0u;
+                unsigned inc = cnt;
+#pragma unroll
+                for (int d = 1; d < 64; d <<= 1) {
+                    const unsigned up = __shfl_up(inc, d, 64);
+                    if (lane >= d) inc += up;
+                }
+                if (i < Wh) sh_off[i] = run + inc - cnt;
+                run += __shfl(inc, 63, 64);
+            }
+            if (lane == 0) sh_off[Wh] = run;
+        }
+        __syncthreads();
+        for (unsigned i = tid; i < m; i += NT) {
+            int a2 = 0, b2 = Wh;            // largest c2 with sh_off[c2] <= i
+            while (b2 - a2 > 1) {
+                const int mid = (a2 + b2) >> 1;
+                if (sh_off[mid] <= i) a2 = mid; else b2 = mid;
+            }
+            const unsigned long long both = __hip_atomic_load(
+                reinterpret_cast<const unsigned long long*>(&S.cand[(int64_t)h * n + (int64_t)a2 * chunk + (i - sh_off[a2])]),
+                __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            sh_cand[i] = make_uint2((unsigned)(both & 0xffffffffull), (unsigned)(both >> 32));
+        }
+        int rem_sh = cur_sh;            // bits of the pattern still undecided inside the bin
+        while (rem_sh > 0) {
+            const int nsh = rem_sh > kPsBinBits ? rem_sh - kPsBinBits : 0;
+            for (int b = tid; b < kPsBins; b += NT) sh_hist[b] = 0u;
+            if (tid == 0) {
+                sh_out[0] = 0u;
+                sh_out[1] = 1u;
+            }
+            __syncthreads();
+            for (unsigned i = tid; i < m; i += NT) {
+                const unsigned v = sh_cand[i].x;
+                if (v >= cur_lo && ((v - cur_lo) >> rem_sh) == 0u)
+                    atomicAdd(&sh_hist[((v - cur_lo) >> nsh) & (kPsBins - 1)], 1u);
+            }
+            __syncthreads();
+            unsigned bins[kPsBins / NT];
+            load_bins_from_top<NT, kPsBins>(sh_hist, bins);
+            find_bin_from_top<NT, kPsBins>(bins, krem, sh_scan, sh_out);
+            cur_lo += (sh_out[0] & (kPsBins - 1)) << nsh;
+            krem = sh_out[1];
+            rem_sh = nsh;
+            __syncthreads();
+        }
+        __syncthreads();
+        T = cur_lo;
+        need_eq = krem;
+        unsigned g2 = 0, q2 = 0, z = 0;   // candidates before this chunk: greater than / equal to T
+        for (unsigned i = tid; i < m; i += NT) {
+            const uint2 cd = sh_cand[i];
+            if ((int64_t)cd.y < chunk0) {
+                g2 += cd.x > T;
+                q2 += cd.x == T;
+            }
+        }
+        block_sum3<NT>(g2, q2, z, sh_red);
+        gt_before += g2;
+        eq_before = q2;
+    }
+    PS_TRACE(11);
+
+    // ---- ordered emission: position order is (run e4, wave, lane, k).  Every wave leaves the
+    // counts of its part of each run row in a table; lane e4 of a wave then turns row e4 of the
+    // table into the number of kept positions before the wave's part of that row.
+    unsigned inc_g[E4], inc_q[E4], cnt_g[E4], cnt_q[E4];   // per row: this thread's counts, scanned over the wave
+#pragma unroll
+    for (int e4 = 0; e4 < E4; ++e4) {
+        unsigned cg = 0, cq = 0;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int e = 4 * e4 + k;
+            const bool ok = valid >> e & 1u;
+            cg += ok && x[e] > T;
+            cq += ok && x[e] == T;
+        }
+        unsigned ig = cg, iq = cq;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const unsigned ug = __shfl_up(ig, d, 64), uq = __shfl_up(iq, d, 64);
+            if (lane >= d) {
+                ig += ug;
+                iq += uq;
+            }
+        }
+        cnt_g[e4] = cg;
+        cnt_q[e4] = cq;
+        inc_g[e4] = ig;
+        inc_q[e4] = iq;
+        if (lane == 63) {
+            sh_tab[0][e4 * NWV + wave] = ig;
+            sh_tab[1][e4 * NWV + wave] = iq;
+        }
+    }
+    __syncthreads();
+    unsigned base_gt = 0, base_eq = 0;          // lane e4 < E4: kept positions before (row e4, this wave)
+    {
+        unsigned row_gt = 0, row_eq = 0, mine_gt = 0, mine_eq = 0;
+        if (lane < E4) {
+#pragma unroll
+            for (int w2 = 0; w2 < NWV; ++w2) {
+                const unsigned a2 = sh_tab[0][lane * NWV + w2], q2 = sh_tab[1][lane * NWV + w2];
+                row_gt += a2;
+                row_eq += q2;
+                if (w2 < wave) {
+                    mine_gt += a2;
+                    mine_eq += q2;
+                }
+            }
+        }
+        unsigned ig = row_gt, iq = row_eq;      // inclusive scan over the rows (lanes 0..E4-1)
+#pragma unroll
+        for (int d = 1; d < E4; d <<= 1) {
+            const unsigned ug = __shfl_up(ig, d, 64), uq = __shfl_up(iq, d, 64);
+            if (lane >= d) {
+                ig += ug;
+                iq += uq;
+            }
+        }
+        base_gt = gt_before + ig - row_gt + mine_gt;
+        base_eq = eq_before + iq - row_eq + mine_eq;
+    }
+#pragma unroll
+    for (int e4 = 0; e4 < E4; ++e4) {
+        unsigned gb = __shfl(base_gt, e4, 64) + inc_g[e4] - cnt_g[e4];
+        unsigned qb = __shfl(base_eq, e4, 64) + inc_q[e4] - cnt_q[e4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int e = 4 * e4 + k;
+            const bool ok = valid >> e & 1u;
+            const bool gt = ok && x[e] > T, eq = ok && x[e] == T;
+            if (gt || (eq && qb < need_eq)) {
+                const unsigned at = gb + (qb < need_eq ? qb : need_eq);
+                if ((int64_t)at < kcount) out[at] = (int32_t)(chunk0 + pos_local(e));
+            }
+            gb += gt;
+            qb += eq;
+        }
+    }
+    PS_TRACE(12);
+    if (tid == 0 && sh_gave_up) atomicAdd(&g_select_timeouts, 1u);
+}
+
 static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 size_t select_layout(int H, int64_t n, SelectScratch* S, void* base) {
@@ -483,6 +1016,9 @@ size_t select_layout(int H, int64_t n, SelectScratch* S, void* base) {
     const size_t cgt = up256(sizeof(unsigned) * (size_t)H * nch);
     const size_t coff = up256(sizeof(unsigned) * 2 * (size_t)H * nch);
     const size_t cand = up256(sizeof(uint2) * (size_t)H * nn);
+    const size_t ps_zero = up256(sizeof(unsigned) * (size_t)H * (kPsStages + 1 + kPsLevels * kPsBins));
+    const size_t ps_range = up256(sizeof(unsigned) * 2 * (size_t)H * kPsMaxGroup);
+    const size_t ps_cand = up256(sizeof(uint2) * (size_t)H * kPsCandCap);
     if (S) {
         char* b = static_cast<char*>(base);
         S->minmax = reinterpret_cast<unsigned*>(b);
@@ -492,8 +1028,16 @@ size_t select_layout(int H, int64_t n, SelectScratch* S, void* base) {
         S->chunk_gt = reinterpret_cast<unsigned*>(b + minmax + hist + count + info);
         S->chunk_off = reinterpret_cast<unsigned*>(b + minmax + hist + count + info + cgt);
         S->cand = reinterpret_cast<uint2*>(b + minmax + hist + count + info + cgt + coff);
+        char* q = b + minmax + hist + count + info + cgt + coff + cand;
+        S->ps_arrive = reinterpret_cast<unsigned*>(q);
+        S->ps_cand_n = S->ps_arrive + (size_t)H * kPsStages;
+        S->ps_hist = S->ps_cand_n + H;
+        S->ps_zero_words = (int64_t)H * (kPsStages + 1 + kPsLevels * kPsBins);
+        S->ps_range = reinterpret_cast<unsigned*>(q + ps_zero);
+        S->ps_part = reinterpret_cast<unsigned*>(q + ps_zero + ps_range);
+        S->ps_cand = reinterpret_cast<uint2*>(q + ps_zero + 2 * ps_range);
     }
-    return minmax + hist + count + info + cgt + coff + cand;
+    return minmax + hist + count + info + cgt + coff + cand + ps_zero + 2 * ps_range + ps_cand;
 }
 
 bool select_chunked_ok(int64_t n) { return (n + kSelChunk - 1) / kSelChunk <= kSelMaxChunks; }
@@ -502,25 +1046,149 @@ bool select_chunked_ok(int64_t n) { return (n + kSelChunk - 1) / kSelChunk <= kS
 // kernel (all-ones = "not published yet") and the selection's histogram and list counters (zero).
 __global__ __launch_bounds__(256) void prepare_scratch(unsigned long long* pairs, int64_t npairs,
                                                       unsigned* hist, int nhist, unsigned* cand_count,
-                                                      int H) {
+                                                      int H, unsigned* ps_zero, int64_t ps_words) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t j = i; j < npairs; j += stride) pairs[j] = ~0ull;
     for (int64_t j = i; j < nhist; j += stride) hist[j] = 0u;
+    for (int64_t j = i; j < ps_words; j += stride) ps_zero[j] = 0u;
     if (i < H) cand_count[i] = 0u;
 }
 
 hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, int H, hipStream_t st) {
     const int nhist = S ? H * kSelBins1 : 0;
     int64_t work = npairs > nhist ? npairs : nhist;
+    if (S && work < S->ps_zero_words) work = S->ps_zero_words;
     if (work < H) work = H;
     if (work <= 0) return hipSuccess;
     int64_t blocks = (work + 255) / 256;
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(prepare_scratch, dim3((unsigned)blocks), dim3(256), 0, st,
                        static_cast<unsigned long long*>(pairs), npairs, S ? S->hist : nullptr, nhist,
-                       S ? S->cand_count : nullptr, S ? H : 0);
+                       S ? S->cand_count : nullptr, S ? H : 0, S ? S->ps_arrive : nullptr,
+                       S ? S->ps_zero_words : 0);
     return hipGetLastError();
+}
+
+// ---- host side of the cooperative kernel
+struct PoolSelCall {
+    const float* vote;
+    const ScoreGeom* G;
+    int pool_kind, p;
+    int64_t kcount, out_stride;
+    int W_tail;
+    int32_t* out_idx;
+    const SelectScratch* S;
+    int Wh, chunk;
+    hipStream_t st;
+};
+
+constexpr unsigned kPsSpinLimit = 1u << 14;    // polls before a rendezvous gives up (tens of ms)
+
+// With call == nullptr: returns in *occ how many workgroups of this instantiation one compute unit
+// keeps resident.  Otherwise launches.
+template <int EPT, int P>
+static hipError_t pool_select_instance(const PoolSelCall* call, int* occ) {
+    auto kern = pool_select<EPT, P>;
+    // staging area of the votes (chunk + halo for p <= 129) or histogram + candidate list
+    constexpr size_t kStage = sizeof(float) * ((size_t)EPT * kPsThreads + 128);
+    constexpr size_t kSearch = sizeof(unsigned) * kPsBins + sizeof(uint2) * kPsCandCap;
+    constexpr size_t kLds = kStage > kSearch ? kStage : kSearch;
+    if (!call) {
+        static int cached[64] = {0};
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) return e;
+        if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+        if (cached[dev] == 0) {
+            int nb = 0;
+            e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLds);
+            if (e != hipSuccess) return e;
+            e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, kern, kPsThreads, kLds);
+            if (e != hipSuccess) return e;
+            cached[dev] = nb > 0 ? nb : -1;
+        }
+        *occ = cached[dev] > 0 ? cached[dev] : 0;
+        return hipSuccess;
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(call->G->Hkv * call->Wh)), dim3(kPsThreads), kLds, call->st,
+                       call->vote, *call->G, call->pool_kind, call->p, call->kcount, call->out_stride,
+                       call->W_tail, call->out_idx, *call->S, call->Wh, call->chunk, kPsSpinLimit);
+    return hipGetLastError();
+}
+
+template <int EPT>
+static hipError_t pool_select_by_width(int pw, const PoolSelCall* call, int* occ) {
+    switch (pw) {   // the widths the paper uses (Sec. 5) get unrolled taps
+        case 5: return pool_select_instance<EPT, 5>(call, occ);
+        case 7: return pool_select_instance<EPT, 7>(call, occ);
+        case 13:   // 13 taps of 16 positions do not fit the registers: the loop form is faster there
+            if constexpr (EPT <= 4) return pool_select_instance<EPT, 13>(call, occ);
+            return pool_select_instance<EPT, 0>(call, occ);
+        default: return pool_select_instance<EPT, 0>(call, occ);
+    }
+}
+
+static hipError_t pool_select_dispatch(int ept, int pw, const PoolSelCall* call, int* occ) {
+    if (ept == 4) return pool_select_by_width<4>(pw, call, occ);
+    return pool_select_by_width<16>(pw, call, occ);
+}
+
+static int ps_cu_count() {
+    static int cached[64] = {0};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cached[dev] == 0) {
+        int nc = 0;
+        if (hipDeviceGetAttribute(&nc, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+        cached[dev] = nc;
+    }
+    return cached[dev];
+}
+
+// Width the kernel is instantiated for: the unrolled taps need one vote row per query head.
+static int ps_width(const ScoreGeom& G, int p) { return (G.VB == 1 && (p == 5 || p == 7 || p == 13)) ? p : 0; }
+
+static bool pool_select_plan(const ScoreGeom& G, int p, int64_t kcount, int* Wh, int* chunk, int* ept) {
+    if (G.n < 1 || kcount < 0 || kcount > G.n || G.Hkv < 1) return false;
+    const int cus = ps_cu_count();
+    if (cus <= 0) return false;
+    for (int e : {4, 16}) {   // positions per thread: the lighter variant when the chunks allow it
+        int occ = 0;
+        if (pool_select_dispatch(e, ps_width(G, p), nullptr, &occ) != hipSuccess) {
+            (void)hipGetLastError();
+            continue;
+        }
+        const int64_t resident = (int64_t)cus * occ;
+        if (occ <= 0 || G.Hkv > resident) continue;
+        int64_t w = resident / G.Hkv;
+        if (w > kPsMaxGroup) w = kPsMaxGroup;
+        const int64_t want = G.n / 2048 > 1 ? G.n / 2048 : 1;   // at least 2048 positions per workgroup
+        if (w > want) w = want;
+        const int64_t ch = ((G.n + w - 1) / w + 3) & ~(int64_t)3;   // whole runs of four positions
+        if (ch > (int64_t)e * kPsThreads) continue;   // does not fit the workgroups' registers
+        *Wh = (int)w;
+        *chunk = (int)ch;
+        *ept = e;
+        return true;
+    }
+    return false;
+}
+
+bool pool_select_ok(const ScoreGeom& G, int p, int64_t kcount) {
+    int Wh = 0, chunk = 0, ept = 0;
+    return pool_select_plan(G, p, kcount, &Wh, &chunk, &ept);
+}
+
+hipError_t launch_pool_select(const ScoreGeom& G, const float* vote, int pool_kind, int p, int64_t kcount,
+                              int64_t out_stride, int W_tail, int32_t* out_idx, const SelectScratch& S,
+                              hipStream_t st) {
+    int Wh = 0, chunk = 0, ept = 0;
+    if (!pool_select_plan(G, p, kcount, &Wh, &chunk, &ept)) return hipErrorInvalidValue;
+    const PoolSelCall call{vote, &G, pool_kind, p, kcount, out_stride, W_tail, out_idx, &S, Wh, chunk, st};
+    int occ = 0;
+    return pool_select_dispatch(ept, ps_width(G, p), &call, &occ);
 }
 
 hipError_t launch_select_init(const SelectScratch& S, int H, hipStream_t st) {
@@ -552,3 +1220,10 @@ hipError_t launch_select_chunked(const float* score, int H, int64_t n, int64_t k
 }
 
 }  // namespace snapkv
+
+#ifdef SNAPKV_FUSED_TRACE
+extern "C" int snapkv_debug_ps_trace(long long* out, int n) {
+    if (n > 1024 * 16) n = 1024 * 16;
+    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(snapkv::g_ps_trace), sizeof(long long) * n);
+}
+#endif

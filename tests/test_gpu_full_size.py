@@ -63,5 +63,15 @@ def test_two_pass_scheme_at_full_size(snapkv):
         snapkv.snapkv_set_scoring_scheme(0)
 
 
+def test_separate_pool_and_select_kernels_at_full_size(snapkv):
+    # the kernels that take over when a head does not fit the cooperative pooling + selection launch
+    snapkv.snapkv_set_scoring_scheme(2)
+    try:
+        _run(snapkv, workloads.LLAMA2_7B_16K, 1, [5, 31])
+        _run(snapkv, workloads.LONG_131K, 3, [9])
+    finally:
+        snapkv.snapkv_set_scoring_scheme(0)
+
+
 def test_no_handoff_wait_gave_up(snapkv):
     assert snapkv.snapkv_sync_timeouts() == 0

@@ -46,9 +46,10 @@ SMALL_CASES = [
 ]
 
 
-@pytest.fixture(params=[0, 1], ids=["single_read", "two_pass"])
+@pytest.fixture(params=[0, 1, 2], ids=["single_read", "two_pass", "separate_pool_select"])
 def scheme(request, snapkv):
-    """Both scoring schemes: the single-read kernel (default where it fits) and the two-pass kernels."""
+    """The default path (single-read scoring, pooling + selection in one launch), the two-pass scoring
+    kernels, and the separate pooling and selection kernels."""
     snapkv.snapkv_set_scoring_scheme(request.param)
     yield request.param
     snapkv.snapkv_set_scoring_scheme(0)
