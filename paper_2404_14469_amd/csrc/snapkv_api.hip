@@ -139,7 +139,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     stage_done(st, kStageBegin);
     const bool chunked = select_chunked_ok(G.n);
     hipError_t se;
-    if (g_allow_pool_select && pool_select_ok(G, p, C - W)) {   // pooling and selection in one launch
+    if (g_allow_pool_select && pool_select_ok(G, pool_kind, p, C - W)) {   // pooling and selection in one launch
         ScoreGeom Gv = G;
         rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, true, &Gv, st);
         if (rc != SNAPKV_OK) return rc;

@@ -104,7 +104,7 @@ hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, i
 int64_t fused_sync_pairs(const FusedGeom& F);
 // Pooling and selection in one cooperative launch (reads votes, writes the kept positions).
 // pool_select_ok says whether the shape fits and the grid can be resident on the current device.
-bool pool_select_ok(const ScoreGeom& G, int p, int64_t kcount);
+bool pool_select_ok(const ScoreGeom& G, int pool_kind, int p, int64_t kcount);
 hipError_t launch_pool_select(const ScoreGeom& G, const float* vote, int pool_kind, int p, int64_t kcount,
                               int64_t out_stride, int W_tail, int32_t* out_idx, const SelectScratch& S,
                               hipStream_t st);

@@ -78,7 +78,7 @@ __device__ __forceinline__ void load_bins_from_top(const unsigned* hist, unsigne
 
 template <int NT, int NBINS>
 __device__ __forceinline__ void find_bin_from_top(const unsigned (&c)[NBINS / NT], unsigned krem,
-                                                  unsigned* sh, unsigned* out) {
+                                                  unsigned* sh, unsigned* out, unsigned* out_count = nullptr) {
     constexpr int BPT = NBINS / NT;
     const int tid = threadIdx.x;
     unsigned mine = 0;
@@ -90,6 +90,7 @@ __device__ __forceinline__ void find_bin_from_top(const unsigned (&c)[NBINS / NT
         if (above < krem && krem <= above + c[e]) {
             out[0] = (unsigned)(NBINS - 1 - (tid * BPT + e));
             out[1] = krem - above;
+            if (out_count) *out_count = c[e];
         }
         above += c[e];
     }
@@ -576,9 +577,9 @@ __device__ __forceinline__ void block_sum3(unsigned& a, unsigned& b, unsigned& c
     }
 }
 
-template <int EPT, int P>
+template <int EPT, int P, int KIND>   // KIND: 0 max pooling, 1 average pooling
 __global__ __launch_bounds__(kPsThreads) void pool_select(
-    const float* __restrict__ vote, const ScoreGeom G, const int pool_kind, const int p_arg,
+    const float* __restrict__ vote, const ScoreGeom G, const int p_arg,
     const int64_t kcount, const int64_t out_stride, const int W_tail, int32_t* __restrict__ out_idx,
     const SelectScratch S, const int Wh, const int chunk, const unsigned spin_limit) {
     constexpr int NT = kPsThreads;
@@ -586,12 +587,12 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
     // One dynamic LDS block, used in turn as the staging area of the votes (chunk plus a halo of
     // p/2 positions on either side) and, once the scores sit in registers, as digit histogram
     // (kPsBins words) followed by the candidate list (kPsCandCap pairs).
-    extern __shared__ unsigned ps_lds[];
+    extern __shared__ __attribute__((aligned(16))) unsigned ps_lds[];
     float* const stage = reinterpret_cast<float*>(ps_lds);
     unsigned* const sh_hist = ps_lds;
     uint2* const sh_cand = reinterpret_cast<uint2*>(ps_lds + kPsBins);
     __shared__ unsigned sh_tab[2][(EPT / 4) * NWV]; // per (run row, wave) counts for the ordered emission
-    __shared__ unsigned sh_scan[16], sh_out[2], sh_red[3 * NWV], sh_gave_up;
+    __shared__ unsigned sh_scan[16], sh_out[2], sh_red[3 * NWV], sh_gave_up, sh_bin_count;
     __shared__ unsigned sh_off[kPsMaxGroup + 1];    // start of each workgroup's candidates in the merged list
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = blockIdx.x / Wh, c = blockIdx.x % Wh;
@@ -617,10 +618,12 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
     const int p = P > 0 ? P : p_arg;
     const int r = p >> 1;
     const int HQ = 4 * ((r + 3) / 4);            // halo, rounded up to whole 16-byte pieces
-    const float pad = pool_kind == 0 ? -INFINITY : 0.f;
+    constexpr int pool_kind = KIND;
+    const float pad = KIND == 0 ? -INFINITY : 0.f;
     const int nf4 = ((len + 3) / 4) + 2 * (HQ / 4);   // 16-byte pieces to stage
     const bool rows_aligned = (n & 3) == 0 && (reinterpret_cast<uintptr_t>(vote) & 15u) == 0;
     auto pos_local = [&](int e) { return (e >> 2) * (4 * NT) + 4 * tid + (e & 3); };
+    const int nn = (int)n, kc = (int)kcount;
     unsigned x[EPT];
     {
         float acc[EPT];
@@ -633,18 +636,18 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
 #pragma unroll
             for (int e4 = 0; e4 <= E4; ++e4) {
                 const int f = e4 * NT + tid;
-                const int64_t q0 = chunk0 - HQ + 4 * (int64_t)f;
+                const int q0 = (int)chunk0 - HQ + 4 * f;     // positions fit 32 bits (n < 2^31)
                 float4 t4 = make_float4(pad, pad, pad, pad);
                 if (f < nf4) {
                     if (P > 0 && rows_aligned) {
-                        if (q0 >= 0 && q0 < n) t4 = *reinterpret_cast<const float4*>(vb + q0);
+                        if (q0 >= 0 && q0 < nn) t4 = *reinterpret_cast<const float4*>(vb + q0);
                     } else {
                         float t[4];
 #pragma unroll
                         for (int k = 0; k < 4; ++k) {
-                            const int64_t q = q0 + k;
+                            const int q = q0 + k;
                             t[k] = pad;
-                            if (q >= 0 && q < n) {
+                            if (q >= 0 && q < nn) {
                                 t[k] = vb[q];
                                 if (P == 0)   // several vote rows per query head only reach the loop form
                                     for (int b = 1; b < G.VB; ++b) t[k] += vb[(int64_t)b * n + q];
@@ -736,6 +739,7 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
         }
     };
     block_range();
+    PS_TRACE(14);
     if (tid == 0) {
         coherent_store(&S.ps_range[2 * ((int64_t)h * kPsMaxGroup + c)], lo);
         coherent_store(&S.ps_range[2 * ((int64_t)h * kPsMaxGroup + c) + 1], hi);
@@ -770,12 +774,14 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
         if (tid == 0) {
             sh_out[0] = 0u;
             sh_out[1] = 1u;
+            sh_bin_count = 0u;
         }
         __syncthreads();
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
             if (active >> e & 1u) atomicAdd(&sh_hist[((x[e] - cur_lo) >> cur_sh) & (kPsBins - 1)], 1u);
         __syncthreads();
+        PS_TRACE(15);
         unsigned* gh = S.ps_hist + ((int64_t)h * kPsLevels + lvl) * kPsBins;
         for (int b = tid; b < kPsBins; b += NT) {
             const unsigned cnt = sh_hist[b];
@@ -788,10 +794,10 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
 #pragma unroll
         for (int e = 0; e < kPsBins / NT; ++e)
             bins[e] = coherent_load(&gh[kPsBins - 1 - (tid * (kPsBins / NT) + e)]);
-        find_bin_from_top<NT, kPsBins>(bins, krem, sh_scan, sh_out);
+        find_bin_from_top<NT, kPsBins>(bins, krem, sh_scan, sh_out, &sh_bin_count);
         const unsigned b1 = sh_out[0] & (kPsBins - 1);
         krem = sh_out[1];
-        bin_count = coherent_load(&gh[b1]);
+        bin_count = sh_bin_count;
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
             if (active >> e & 1u) {
@@ -820,12 +826,13 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
     block_sum3<NT>(above_total, z1, z2, sh_red);
     if (!exact) {   // this workgroup's candidates go to the start of its own stretch of the head's list
         unsigned slot = in_before;
+        unsigned long long* const my_cand = reinterpret_cast<unsigned long long*>(S.cand + (int64_t)h * n + chunk0);
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
             if (active >> e & 1u) {
                 if (slot < (unsigned)len)
-                    __hip_atomic_store(reinterpret_cast<unsigned long long*>(&S.cand[(int64_t)h * n + chunk0 + slot]),
-                                       ((unsigned long long)(unsigned)(chunk0 + pos_local(e)) << 32) | x[e],
+                    __hip_atomic_store(my_cand + slot,
+                                       ((unsigned long long)(unsigned)((int)chunk0 + pos_local(e)) << 32) | x[e],
                                        __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 ++slot;
             }
@@ -841,25 +848,20 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
     // kept positions of the head before this chunk.  Every wave sums the per-workgroup counts
     // itself (no barrier); without an exact T the candidates are fetched, workgroup by workgroup.
     unsigned gt_before = 0, eq_before = 0;
-    for (int i = lane; i < c; i += 64) {
-        gt_before += coherent_load(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + i)]);
-        eq_before += coherent_load(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + i) + 1]);
-    }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        gt_before += __shfl_xor(gt_before, d, 64);
-        eq_before += __shfl_xor(eq_before, d, 64);
-    }
-    if (!exact) {
-        eq_before = 0;              // positions inside the bin are counted from the candidate list
-        const unsigned m = bin_count < (unsigned)kPsCandCap ? bin_count : (unsigned)kPsCandCap;
-        __syncthreads();            // sh_hist / sh_cand share the LDS block
-        // where each workgroup's candidates start in the merged list (wave 0 scans the counts)
-        if (wave == 0) {
-            unsigned run = 0;
-            for (int base = 0; base < Wh; base += 64) {
-                const int i = base + lane;
-                const unsigned cnt = i < Wh ? coherent_load(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + i) + 1]) : 0u;
+    {
+        unsigned run = 0;           // candidates of the workgroups before `base`
+        for (int base = 0; base < Wh; base += 64) {
+            const int i = base + lane;
+            unsigned ab = 0, cnt = 0;
+            if (i < Wh) {
+                ab = coherent_load(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + i)]);
+                cnt = coherent_load(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + i) + 1]);
+            }
+            if (i < c) {
+                gt_before += ab;
+                eq_before += cnt;
+            }
+            if (!exact && wave == 0) {   // where each workgroup's candidates start in the merged list
                 unsigned inc = cnt;
 #pragma unroll
                 for (int d = 1; d < 64; d <<= 1) {
@@ -869,8 +871,17 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
                 if (i < Wh) sh_off[i] = run + inc - cnt;
                 run += __shfl(inc, 63, 64);
             }
-            if (lane == 0) sh_off[Wh] = run;
         }
+        if (!exact && wave == 0 && lane == 0) sh_off[Wh] = run;
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        gt_before += __shfl_xor(gt_before, d, 64);
+        eq_before += __shfl_xor(eq_before, d, 64);
+    }
+    if (!exact) {
+        eq_before = 0;              // positions inside the bin are counted from the candidate list
+        const unsigned m = bin_count < (unsigned)kPsCandCap ? bin_count : (unsigned)kPsCandCap;
         __syncthreads();
         for (unsigned i = tid; i < m; i += NT) {
             int a2 = 0, b2 = Wh;            // largest c2 with sh_off[c2] <= i
@@ -926,6 +937,7 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
     // ---- ordered emission: position order is (run e4, wave, lane, k).  Every wave leaves the
     // counts of its part of each run row in a table; lane e4 of a wave then turns row e4 of the
     // table into the number of kept positions before the wave's part of that row.
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
     unsigned inc_g[E4], inc_q[E4], cnt_g[E4], cnt_q[E4];   // per row: this thread's counts, scanned over the wave
 #pragma unroll
     for (int e4 = 0; e4 < E4; ++e4) {
@@ -937,14 +949,12 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
             cg += ok && x[e] > T;
             cq += ok && x[e] == T;
         }
+        // counts are at most 4: the wave-wide inclusive scan is three ballots per count
         unsigned ig = cg, iq = cq;
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const unsigned ug = __shfl_up(ig, d, 64), uq = __shfl_up(iq, d, 64);
-            if (lane >= d) {
-                ig += ug;
-                iq += uq;
-            }
+        for (int bit = 0; bit < 3; ++bit) {
+            ig += (unsigned)__popcll(__ballot(cg >> bit & 1u) & lt_mask) << bit;
+            iq += (unsigned)__popcll(__ballot(cq >> bit & 1u) & lt_mask) << bit;
         }
         cnt_g[e4] = cg;
         cnt_q[e4] = cq;
@@ -994,7 +1004,7 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
             const bool gt = ok && x[e] > T, eq = ok && x[e] == T;
             if (gt || (eq && qb < need_eq)) {
                 const unsigned at = gb + (qb < need_eq ? qb : need_eq);
-                if ((int64_t)at < kcount) out[at] = (int32_t)(chunk0 + pos_local(e));
+                if (at < (unsigned)kc) out[at] = (int32_t)chunk0 + pos_local(e);
             }
             gb += gt;
             qb += eq;
@@ -1087,9 +1097,9 @@ constexpr unsigned kPsSpinLimit = 1u << 14;    // polls before a rendezvous give
 
 // With call == nullptr: returns in *occ how many workgroups of this instantiation one compute unit
 // keeps resident.  Otherwise launches.
-template <int EPT, int P>
+template <int EPT, int P, int KIND>
 static hipError_t pool_select_instance(const PoolSelCall* call, int* occ) {
-    auto kern = pool_select<EPT, P>;
+    auto kern = pool_select<EPT, P, KIND>;
     // staging area of the votes (chunk + halo for p <= 129) or histogram + candidate list
     constexpr size_t kStage = sizeof(float) * ((size_t)EPT * kPsThreads + 128);
     constexpr size_t kSearch = sizeof(unsigned) * kPsBins + sizeof(uint2) * kPsCandCap;
@@ -1113,26 +1123,26 @@ static hipError_t pool_select_instance(const PoolSelCall* call, int* occ) {
         return hipSuccess;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(call->G->Hkv * call->Wh)), dim3(kPsThreads), kLds, call->st,
-                       call->vote, *call->G, call->pool_kind, call->p, call->kcount, call->out_stride,
+                       call->vote, *call->G, call->p, call->kcount, call->out_stride,
                        call->W_tail, call->out_idx, *call->S, call->Wh, call->chunk, kPsSpinLimit);
     return hipGetLastError();
 }
 
-template <int EPT>
+template <int EPT, int KIND>
 static hipError_t pool_select_by_width(int pw, const PoolSelCall* call, int* occ) {
     switch (pw) {   // the widths the paper uses (Sec. 5) get unrolled taps
-        case 5: return pool_select_instance<EPT, 5>(call, occ);
-        case 7: return pool_select_instance<EPT, 7>(call, occ);
+        case 5: return pool_select_instance<EPT, 5, KIND>(call, occ);
+        case 7: return pool_select_instance<EPT, 7, KIND>(call, occ);
         case 13:   // 13 taps of 16 positions do not fit the registers: the loop form is faster there
-            if constexpr (EPT <= 4) return pool_select_instance<EPT, 13>(call, occ);
-            return pool_select_instance<EPT, 0>(call, occ);
-        default: return pool_select_instance<EPT, 0>(call, occ);
+            if constexpr (EPT <= 4) return pool_select_instance<EPT, 13, KIND>(call, occ);
+            return pool_select_instance<EPT, 0, KIND>(call, occ);
+        default: return pool_select_instance<EPT, 0, KIND>(call, occ);
     }
 }
 
-static hipError_t pool_select_dispatch(int ept, int pw, const PoolSelCall* call, int* occ) {
-    if (ept == 4) return pool_select_by_width<4>(pw, call, occ);
-    return pool_select_by_width<16>(pw, call, occ);
+static hipError_t pool_select_dispatch(int ept, int pw, int kind, const PoolSelCall* call, int* occ) {
+    if (ept == 4) return kind == 0 ? pool_select_by_width<4, 0>(pw, call, occ) : pool_select_by_width<4, 1>(pw, call, occ);
+    return kind == 0 ? pool_select_by_width<16, 0>(pw, call, occ) : pool_select_by_width<16, 1>(pw, call, occ);
 }
 
 static int ps_cu_count() {
@@ -1150,13 +1160,13 @@ static int ps_cu_count() {
 // Width the kernel is instantiated for: the unrolled taps need one vote row per query head.
 static int ps_width(const ScoreGeom& G, int p) { return (G.VB == 1 && (p == 5 || p == 7 || p == 13)) ? p : 0; }
 
-static bool pool_select_plan(const ScoreGeom& G, int p, int64_t kcount, int* Wh, int* chunk, int* ept) {
+static bool pool_select_plan(const ScoreGeom& G, int pool_kind, int p, int64_t kcount, int* Wh, int* chunk, int* ept) {
     if (G.n < 1 || kcount < 0 || kcount > G.n || G.Hkv < 1) return false;
     const int cus = ps_cu_count();
     if (cus <= 0) return false;
     for (int e : {4, 16}) {   // positions per thread: the lighter variant when the chunks allow it
         int occ = 0;
-        if (pool_select_dispatch(e, ps_width(G, p), nullptr, &occ) != hipSuccess) {
+        if (pool_select_dispatch(e, ps_width(G, p), pool_kind, nullptr, &occ) != hipSuccess) {
             (void)hipGetLastError();
             continue;
         }
@@ -1176,19 +1186,19 @@ static bool pool_select_plan(const ScoreGeom& G, int p, int64_t kcount, int* Wh,
     return false;
 }
 
-bool pool_select_ok(const ScoreGeom& G, int p, int64_t kcount) {
+bool pool_select_ok(const ScoreGeom& G, int pool_kind, int p, int64_t kcount) {
     int Wh = 0, chunk = 0, ept = 0;
-    return pool_select_plan(G, p, kcount, &Wh, &chunk, &ept);
+    return pool_select_plan(G, pool_kind, p, kcount, &Wh, &chunk, &ept);
 }
 
 hipError_t launch_pool_select(const ScoreGeom& G, const float* vote, int pool_kind, int p, int64_t kcount,
                               int64_t out_stride, int W_tail, int32_t* out_idx, const SelectScratch& S,
                               hipStream_t st) {
     int Wh = 0, chunk = 0, ept = 0;
-    if (!pool_select_plan(G, p, kcount, &Wh, &chunk, &ept)) return hipErrorInvalidValue;
+    if (!pool_select_plan(G, pool_kind, p, kcount, &Wh, &chunk, &ept)) return hipErrorInvalidValue;
     const PoolSelCall call{vote, &G, pool_kind, p, kcount, out_stride, W_tail, out_idx, &S, Wh, chunk, st};
     int occ = 0;
-    return pool_select_dispatch(ept, ps_width(G, p), &call, &occ);
+    return pool_select_dispatch(ept, ps_width(G, p), pool_kind, &call, &occ);
 }
 
 hipError_t launch_select_init(const SelectScratch& S, int H, hipStream_t st) {
