@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--resident-layers", type=int, default=4,
                     help="distinct layers kept in HBM and cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--explicit-workspace", action="store_true",
+                    help="time snapkv_compress_ws with a caller-provided workspace instead of snapkv_compress")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="run only a plain device copy of MIB mebibytes (8 launches) and exit: the "
                          "known-size kernel the HBM traffic counters are calibrated on")
@@ -91,7 +93,9 @@ def main() -> int:
     out_k = torch.empty((w.Hkv, w.C, w.D), dtype=layers[0][1].dtype, device=dev)
     out_v = torch.empty_like(out_k)
     out_idx = torch.empty((w.Hkv, w.C), dtype=torch.int32, device=dev)
-    ws = torch.empty(snapkv.snapkv_workspace_bytes(w.L, w.Hq, w.Hkv, w.D, w.W), dtype=torch.uint8, device=dev)
+    ws = None
+    if args.explicit_workspace:
+        ws = torch.empty(snapkv.snapkv_workspace_bytes(w.L, w.Hq, w.Hkv, w.D, w.W), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
     def step(i):

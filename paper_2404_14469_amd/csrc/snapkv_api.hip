@@ -14,6 +14,10 @@ constexpr int kMaxDevices = 64;
 struct DeviceScratch {
     void* ptr = nullptr;
     size_t bytes = 0;
+    // Non-zero: the last call on this buffer had this shape and its final kernel left the
+    // hand-off words and counters ready, so the next call of the same shape needs no preparing
+    // launch.  Anything else that touches the buffer resets it.
+    uint64_t clean_key = 0;
 };
 DeviceScratch g_scratch[kMaxDevices];
 std::mutex g_mu;
@@ -49,11 +53,16 @@ int check_score_args(const void* q_win, const void* k, int64_t L, int Hq, int Hk
     return SNAPKV_OK;
 }
 
-int internal_scratch(size_t need, void** out) {
+// Hands out the device's buffer.  Whoever takes it may leave it in any state, so the record of a
+// ready-made state is handed to the caller (*was_clean, may be null) and dropped.
+int internal_scratch(size_t need, void** out, uint64_t* was_clean = nullptr) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SNAPKV_ERR_HIP;
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceScratch& s = g_scratch[dev];
+    if (s.bytes < need) s.clean_key = 0;
+    if (was_clean) *was_clean = s.clean_key;
+    s.clean_key = 0;
     if (s.bytes < need) {
         if (s.ptr) {
             // hipFree waits for the device, so work still reading the old buffer has finished
@@ -77,16 +86,23 @@ int internal_scratch(size_t need, void** out) {
 // in one launch) and *Gv tells how the votes are laid out.
 int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGeom& G,
                const Workspace& ws, int pool_kind, int p, float* score, unsigned* minmax,
-               bool prepare_select, ScoreGeom* Gv, hipStream_t st) {
+               bool prepare_select, ScoreGeom* Gv, hipStream_t st, bool already_prepared = false,
+               CleanJob* clean = nullptr) {
     FusedGeom F;
     ScoreGeom Gp = G;
     const bool fused = g_allow_fused && fused_plan(dtype, D, G, &F);
     FusedSync S;
     if (fused) fused_sync_layout(G, F, &S, ws.fused);
-    if (launch_prepare(fused ? S.part : nullptr, fused ? fused_sync_pairs(F) : 0,
-                       prepare_select ? &ws.sel : nullptr, G.Hkv, st) != hipSuccess)
-        return SNAPKV_ERR_HIP;
-    stage_done(st, kStagePrepare);
+    if (!already_prepared) {
+        if (launch_prepare(fused ? S.part : nullptr, fused ? fused_sync_pairs(F) : 0,
+                           prepare_select ? &ws.sel : nullptr, G.Hkv, st) != hipSuccess)
+            return SNAPKV_ERR_HIP;
+        stage_done(st, kStagePrepare);
+    }
+    if (clean && fused) {
+        clean->ones = reinterpret_cast<unsigned long long*>(S.part);
+        clean->nones = fused_sync_pairs(F);
+    }
     if (fused) {   // K is read once; otherwise two passes over K
         if (launch_score_fused(dtype, D, q_win, k, G, F, S, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
         stage_done(st, kStageFused);
@@ -119,7 +135,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
 
     if (L <= C) {   // Listing 1, first branch: the prompt already fits
         if (launch_iota(Hkv, L, C, out_idx, st) != hipSuccess) return SNAPKV_ERR_HIP;
-        if (launch_gather(k, v, out_idx, Hkv, L, L, C, row_bytes, out_k, out_v, st) != hipSuccess)
+        if (launch_gather(k, v, out_idx, Hkv, L, L, C, row_bytes, out_k, out_v, CleanJob{}, st) != hipSuccess)
             return SNAPKV_ERR_HIP;
         return L;
     }
@@ -127,8 +143,9 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     const ScoreGeom G = make_geom(L, Hq, Hkv, D, W);
     const size_t need = workspace_layout(G, nullptr, nullptr);
     void* base = workspace;
+    uint64_t was_clean = 0;
     if (own_scratch) {
-        rc = internal_scratch(need, &base);
+        rc = internal_scratch(need, &base, &was_clean);
         if (rc != SNAPKV_OK) return rc;
     } else {
         if (!workspace || workspace_bytes < need) return SNAPKV_ERR_WORKSPACE;
@@ -139,11 +156,30 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     stage_done(st, kStageBegin);
     const bool chunked = select_chunked_ok(G.n);
     hipError_t se;
+    CleanJob clean;
+    DeviceScratch* mine = nullptr;      // the library's own buffer: its state is tracked between calls
+    uint64_t key = 0;
     if (g_allow_pool_select && pool_select_ok(G, pool_kind, p, C - W)) {   // pooling and selection in one launch
+        bool prepared = false;
+        FusedGeom Fp;
+        if (own_scratch && g_allow_fused && fused_plan(dtype, D, G, &Fp)) {
+            int dev = 0;
+            if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
+                key = 0x9E3779B97F4A7C15ull ^ ((uint64_t)L * 1000003ull) ^ ((uint64_t)Hq << 50) ^ ((uint64_t)Hkv << 40) ^
+                      ((uint64_t)D << 32) ^ ((uint64_t)W << 20) ^ ((uint64_t)dtype << 19);
+                mine = &g_scratch[dev];
+                prepared = was_clean == key;
+            }
+        }
         ScoreGeom Gv = G;
-        rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, true, &Gv, st);
+        rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, true, &Gv, st, prepared,
+                        mine ? &clean : nullptr);
         if (rc != SNAPKV_OK) return rc;
         se = launch_pool_select(Gv, ws.vote, pool_kind, p, C - W, C, W, out_idx, ws.sel, st);
+        if (mine) {
+            clean.zeros = ws.sel.ps_arrive;
+            clean.nzeros = ws.sel.ps_zero_words;
+        }
     } else {
         rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr,
                         chunked, nullptr, st);
@@ -153,8 +189,12 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     }
     if (se != hipSuccess) return SNAPKV_ERR_HIP;
     stage_done(st, kStageSelect);
-    if (launch_gather(k, v, out_idx, Hkv, L, C, C, row_bytes, out_k, out_v, st) != hipSuccess)
+    if (launch_gather(k, v, out_idx, Hkv, L, C, C, row_bytes, out_k, out_v, clean, st) != hipSuccess)
         return SNAPKV_ERR_HIP;
+    if (mine && clean.ones) {
+        std::lock_guard<std::mutex> lock(g_mu);
+        mine->clean_key = key;
+    }
     stage_done(st, kStageGather);
     return C;
 }
@@ -342,6 +382,7 @@ void snapkv_release(void) {
         if (hipSetDevice(d) == hipSuccess) (void)hipFree(g_scratch[d].ptr);
         g_scratch[d].ptr = nullptr;
         g_scratch[d].bytes = 0;
+        g_scratch[d].clean_key = 0;
     }
     if (have_cur) (void)hipSetDevice(cur);
 }

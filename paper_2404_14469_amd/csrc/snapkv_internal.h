@@ -116,9 +116,17 @@ int pool_tiles(int64_t n);
 hipError_t launch_select(const float* score, int H, int64_t n, int64_t kcount, int64_t out_stride,
                          int W_tail, int32_t* out_idx, hipStream_t st);
 hipError_t launch_iota(int H, int64_t rows, int64_t out_stride, int32_t* out_idx, hipStream_t st);
+// Scratch a call's last kernel puts back into the state the next call expects (hand-off words
+// all-ones, counters zero); all-null = nothing to do.
+struct CleanJob {
+    unsigned long long* ones = nullptr;
+    int64_t nones = 0;
+    unsigned* zeros = nullptr;
+    int64_t nzeros = 0;
+};
 hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H, int64_t L,
                          int64_t rows, int64_t out_stride, int row_bytes, void* out_k, void* out_v,
-                         hipStream_t st);
+                         const CleanJob& clean, hipStream_t st);
 
 }  // namespace snapkv
 #endif

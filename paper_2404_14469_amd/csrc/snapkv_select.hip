@@ -390,7 +390,7 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
                                                    const int64_t rows, const int64_t out_stride,
                                                    const int pieces /* 16-byte pieces per row */,
                                                    uint4* __restrict__ out_k,
-                                                   uint4* __restrict__ out_v) {
+                                                   uint4* __restrict__ out_v, const CleanJob clean) {
     const int h = blockIdx.y;
     const int64_t total = rows * pieces;
     const uint4* kb = k + (int64_t)h * L * pieces;
@@ -405,11 +405,16 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
         okb[r * pieces + c] = kb[src * pieces + c];
         ovb[r * pieces + c] = vb[src * pieces + c];
     }
+    // the call's scratch is no longer read by anything: leave it ready for the next call
+    const int64_t gid = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
+    const int64_t gsz = (int64_t)gridDim.y * gridDim.x * 256;
+    for (int64_t j = gid; j < clean.nones; j += gsz) clean.ones[j] = ~0ull;
+    for (int64_t j = gid; j < clean.nzeros; j += gsz) clean.zeros[j] = 0u;
 }
 
 hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H, int64_t L,
                          int64_t rows, int64_t out_stride, int row_bytes, void* out_k, void* out_v,
-                         hipStream_t st) {
+                         const CleanJob& clean, hipStream_t st) {
     if (H <= 0 || rows <= 0) return hipSuccess;
     const int pieces = row_bytes / 16;
     const int64_t total = rows * pieces;
@@ -417,7 +422,7 @@ hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H
     if (bx > 4096) bx = 4096;
     hipLaunchKernelGGL(gather_rows, dim3(bx, H), dim3(256), 0, st, static_cast<const uint4*>(k),
                        static_cast<const uint4*>(v), idx, L, rows, out_stride, pieces,
-                       static_cast<uint4*>(out_k), static_cast<uint4*>(out_v));
+                       static_cast<uint4*>(out_k), static_cast<uint4*>(out_v), clean);
     return hipGetLastError();
 }
 

@@ -136,6 +136,56 @@ def test_deterministic_bitwise(snapkv, scheme):
     assert torch.equal(a[1], b[1]) and torch.equal(a[2], b[2])
 
 
+def _compress_only(snapkv, case, w):
+    q, k, v = case["q_win"], case["k"], case["v"]
+    out_k = torch.zeros((w.Hkv, w.C, w.D), dtype=k.dtype, device="cuda")
+    out_v = torch.zeros_like(out_k)
+    out_idx = torch.full((w.Hkv, w.C), -1, dtype=torch.int32, device="cuda")
+    kept = snapkv.snapkv_compress(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx)
+    torch.cuda.synchronize()
+    assert kept == w.C
+    return out_idx.cpu().numpy(), out_k, out_v
+
+
+def test_back_to_back_calls_reuse_the_scratch_state(snapkv):
+    """Consecutive calls of one shape skip the preparing launch (the previous call's last kernel
+    left the scratch ready); other shapes, other entry points and other schemes in between must
+    not leave anything stale behind."""
+    wa = small("b2b_a", Hq=8, Hkv=4, L=5000, C=600)
+    wb = small("b2b_b", Hq=4, Hkv=4, L=3100, C=200, pool_kind=1, p=5)
+    ca = workloads.generate(wa, device="cuda")
+    ca2 = workloads.generate(wa.with_(seed=wa.seed + 7), device="cuda")
+    cb = workloads.generate(wb, device="cuda")
+    ref_a = run_gpu(snapkv, ca["q_win"], ca["k"], ca["v"], wa.pool_kind, wa.p, wa.C)
+    check_against_oracle(ca["q_win"], ca["k"], ca["v"], wa.pool_kind, wa.p, wa.C, *ref_a)
+    ref_a2 = run_gpu(snapkv, ca2["q_win"], ca2["k"], ca2["v"], wa.pool_kind, wa.p, wa.C)
+    ref_b = run_gpu(snapkv, cb["q_win"], cb["k"], cb["v"], wb.pool_kind, wb.p, wb.C)
+
+    def same(got, ref):
+        assert np.array_equal(got[0], ref[3])
+        assert torch.equal(got[1], ref[1]) and torch.equal(got[2], ref[2])
+
+    for _ in range(3):                                  # same shape, back to back
+        same(_compress_only(snapkv, ca, wa), ref_a)
+        same(_compress_only(snapkv, ca2, wa), ref_a2)
+    same(_compress_only(snapkv, cb, wb), ref_b)         # another shape in between
+    same(_compress_only(snapkv, ca, wa), ref_a)
+    same(_compress_only(snapkv, ca, wa), ref_a)
+    sc = torch.empty((wa.Hkv, wa.n), dtype=torch.float32, device="cuda")
+    snapkv.snapkv_pooled_scores(ca["q_win"], ca["k"], wa.pool_kind, wa.p, sc)   # another entry point
+    same(_compress_only(snapkv, ca2, wa), ref_a2)
+    same(_compress_only(snapkv, ca2, wa), ref_a2)
+    for sch in (1, 2, 0):                               # other schemes in between
+        snapkv.snapkv_set_scoring_scheme(sch)
+        try:
+            got = _compress_only(snapkv, ca, wa)
+        finally:
+            snapkv.snapkv_set_scoring_scheme(0)
+        assert np.array_equal(got[0], ref_a[3]) or sch == 1   # two-pass scores may differ in the last bit
+        same(_compress_only(snapkv, ca, wa), ref_a)
+    assert snapkv.snapkv_sync_timeouts() == 0
+
+
 def test_explicit_workspace_matches(snapkv):
     w = small("ws", Hq=8, Hkv=4, L=2500, C=300)
     case = workloads.generate(w, device="cuda")
