@@ -52,6 +52,8 @@ def main() -> int:
     ap.add_argument("--resident-layers", type=int, default=4,
                     help="distinct layers kept in HBM and cycled through")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scheme", type=int, default=0,
+                    help="kernel scheme bits for measurements (see snapkv_set_scoring_scheme); 0 = default")
     ap.add_argument("--explicit-workspace", action="store_true",
                     help="time snapkv_compress_ws with a caller-provided workspace instead of snapkv_compress")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
@@ -82,6 +84,8 @@ def main() -> int:
                           "launches": 8}))
         return 0
     snapkv.load()
+    if args.scheme:
+        snapkv.snapkv_set_scoring_scheme(args.scheme)
     w = workloads.CONFIGS[args.workload]
 
     nres = max(1, min(args.resident_layers, max(w.layers, 1) if w.layers > 1 else args.resident_layers))
@@ -185,7 +189,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "L": w.L, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "W": w.W,
                    "pool": ("max" if w.pool_kind == 0 else "avg"), "p": w.p, "C": w.C,
-                   "step": "one layer call", "resident_layers": nres,
+                   "step": "one layer call", "resident_layers": nres, "scheme": args.scheme,
                    "token_layers_per_s": round(w.L / (ms_per_step * 1e-3), 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,

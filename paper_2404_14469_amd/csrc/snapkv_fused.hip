@@ -5,7 +5,10 @@
 // can be summed down a column.  Instead of reading K twice, this kernel keeps the exponentials
 // of the logits in registers across a device-wide hand-off of the row normalisers:
 //
-//   * a KV head is a "unit".  The keys of a unit are cut into slices, one per workgroup of a
+//   * a "unit" is a KV head, or, when the query heads of a KV head have more window rows than a
+//     wave tracks well, one of `split` equal parts of its query heads (units of one KV head then
+//     run side by side in neighbouring groups, so that its keys are fetched from memory once and
+//     found in the cache by the others).  The keys of a unit are cut into slices, one per workgroup of a
 //     group of Gg workgroups; NG groups work on different units at the same time.  Every
 //     workgroup stays resident (the grid never exceeds what the device keeps resident at once).
 //   * step P1 of a unit: the slice of K, loaded once, meets the window queries on MFMA
@@ -271,7 +274,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     for (int t = 0; t < KT; ++t) {
         int64_t j = ((int64_t)t * TS + tile0) * 16 + n16;
         j = j < G.L ? j : G.L - 1;
-        kp[t] = static_cast<const char*>(kv) + ((int64_t)group * G.L + j) * D * ES + kg * 16;
+        kp[t] = static_cast<const char*>(kv) + ((int64_t)(group / F.split) * G.L + j) * D * ES + kg * 16;
     }
     // Q is shared by the waves: each fetches QPW of the unit's 1 KB chunks (chunk c = row unit c / NP,
     // piece c % NP, lane l = row l % 16, contraction slice l / 16) and leaves them in LDS.
@@ -282,12 +285,12 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         c = c < QCH ? c : QCH - 1;
         const int ru = c / NP, pc = c % NP;
         int head = ru / F.UH, i = (ru % F.UH) * 16 + n16;
-        head = head < G.g ? head : G.g - 1;
+        head = head < F.gs ? head : F.gs - 1;
         i = i < G.W ? i : G.W - 1;
-        qp[x] = static_cast<const char*>(qv) + ((int64_t)(group * G.g + head) * G.W + i) * D * ES + (4 * pc + kg) * 16;
+        qp[x] = static_cast<const char*>(qv) + ((int64_t)(group * F.gs + head) * G.W + i) * D * ES + (4 * pc + kg) * 16;
     }
-    const int64_t kstep = (int64_t)F.NG * G.L * D * ES;
-    const int64_t qstep = (int64_t)F.NG * G.g * G.W * D * ES;
+    const int64_t kstep = (int64_t)(F.NG / F.split) * G.L * D * ES;   // NG is a multiple of split
+    const int64_t qstep = (int64_t)F.NG * F.gs * G.W * D * ES;
 
     // K tiles are consumed in two halves so that the memory pipeline never runs dry: the lower
     // KL tiles of a unit meet Q at the end of the previous iteration (their accumulators take
@@ -621,7 +624,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                 f[ru][2] = (ms.z == -INFINITY || b.y == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.z - b.x) * b.y;
                 f[ru][3] = (ms.w == -INFINITY || b.w == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.w - b.z) * b.w;
             }
-            float* vb = vote + (int64_t)unit_p2 * G.g * G.n;
+            float* vb = vote + (int64_t)unit_p2 * F.gs * G.n;
             int jst = tile0 * 16 + n16;       // opaque for the same reason as above
             asm volatile("" : "+v"(jst));
 #ifdef SNAPKV_EXP_NOVOTE
@@ -665,7 +668,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                         for (int x = 0; x < KT / 4; ++x) {
                             const int t = ((kg & 2) ? KT / 2 : 0) + ((kg & 1) ? KT / 4 : 0) + x;
                             const int j = jst + t * TS * 16;
-                            if (head < G.g && j < nst) vh[j] = b[x];
+                            if (head < F.gs && j < nst) vh[j] = b[x];
                         }
                     } else {
 #pragma unroll
@@ -673,7 +676,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                             float s = v[t] + __shfl_xor(v[t], 32, 64);
                             s += __shfl_xor(s, 16, 64);
                             const int j = jst + t * TS * 16;
-                            if (kg == 0 && head < G.g && j < nst) vh[j] = s;
+                            if (kg == 0 && head < F.gs && j < nst) vh[j] = s;
                         }
                     }
 #pragma unroll
@@ -737,9 +740,11 @@ constexpr int kFusedWaves = 8;          // waves per workgroup (two per SIMD): m
 
 // Device-independent part of the plan: how the rows and keys of a unit map onto a workgroup of
 // NW waves.  Returns false when the window rows of a KV head exceed what one wave tracks.
-static bool fused_shape_nw(const ScoreGeom& G, int NW, FusedGeom* F) {
+static bool fused_shape_nw(const ScoreGeom& G, int NW, int split, FusedGeom* F) {
+    if (split < 1 || G.g % split != 0) return false;
     const int UH = (G.W + 15) / 16;
-    const int RU = G.g * UH;
+    const int gs = G.g / split;          // query heads per unit
+    const int RU = gs * UH;
     if (RU > 8 || G.n <= 0) return false;
     int RUW = 1;
     while (RUW < RU) RUW *= 2;
@@ -754,16 +759,61 @@ static bool fused_shape_nw(const ScoreGeom& G, int NW, FusedGeom* F) {
     F->KT = KT;
     F->NW = NW;
     F->Gg = (int)Gg;
-    F->NG = 1;
+    F->NG = split;
     F->NB = (int)((Gg + 31) / 32);
     F->ntiles = ntiles;
-    F->units = G.Hkv;
+    F->units = G.Hkv * split;
+    F->split = split;
+    F->gs = gs;
     F->spin_limit = kSpinLimit;
     return true;
 }
 
-// Shape used to size the hand-off buffers.
-bool fused_shape(const ScoreGeom& G, FusedGeom* F) { return fused_shape_nw(G, kFusedWaves, F); }
+// Splits worth trying, best first: the finest one whose units still have two row units (the
+// kernel's leanest form), then the others from fine to coarse.  Returns how many (at most 8).
+static int fused_split_candidates(const ScoreGeom& G, int* out) {
+    const int UH = (G.W + 15) / 16;
+    int all[8], na = 0;
+    for (int s = G.g; s >= 1 && na < 8; --s)
+        if (G.g % s == 0 && (G.g / s) * UH <= 8) all[na++] = s;
+    if (na == 0) return 0;
+    int best = na - 1;
+    for (int i = 0; i < na; ++i)
+        if ((G.g / all[i]) * UH >= 2) {
+            best = i;
+            break;
+        }
+    int nc = 0;
+    out[nc++] = all[best];
+    for (int i = 0; i < na; ++i)
+        if (i != best) out[nc++] = all[i];
+    return nc;
+}
+
+// Whether any split fits; *F gets the first candidate's shape.
+bool fused_shape(const ScoreGeom& G, FusedGeom* F) {
+    int cand[8];
+    const int nc = fused_split_candidates(G, cand);
+    for (int i = 0; i < nc; ++i)
+        if (fused_shape_nw(G, kFusedWaves, cand[i], F)) return true;
+    return false;
+}
+
+size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base);
+
+// Bytes of hand-off buffers that cover whichever split the launch plan ends up choosing.
+size_t fused_sync_bytes(const ScoreGeom& G) {
+    int cand[8];
+    const int nc = fused_split_candidates(G, cand);
+    size_t most = 0;
+    for (int i = 0; i < nc; ++i) {
+        FusedGeom F;
+        if (!fused_shape_nw(G, kFusedWaves, cand[i], &F)) continue;
+        const size_t b = fused_sync_layout(G, F, nullptr, nullptr);
+        most = b > most ? b : most;
+    }
+    return most;
+}
 
 size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base) {
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
@@ -851,18 +901,25 @@ static hipError_t fused_dispatch(int dtype, int D, int NW, int RUW, const FusedC
 // run side by side.  The number of resident workgroups comes from the runtime's occupancy
 // answer for the exact kernel instance, never from an assumption.
 bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
-    if (!fused_shape_nw(G, kFusedWaves, F)) return false;
-    int occ = 0;
-    if (fused_dispatch(dtype, D, F->NW, F->RUW, nullptr, &occ) != hipSuccess) {
-        (void)hipGetLastError();
-        return false;
+    int cand[8];
+    const int nc = fused_split_candidates(G, cand);
+    for (int c = 0; c < nc; ++c) {
+        if (!fused_shape_nw(G, kFusedWaves, cand[c], F)) continue;
+        int occ = 0;
+        if (fused_dispatch(dtype, D, F->NW, F->RUW, nullptr, &occ) != hipSuccess) {
+            (void)hipGetLastError();
+            continue;
+        }
+        const int64_t slots = (int64_t)cu_count() * occ;   // workgroups that are resident together
+        if (slots <= 0 || F->Gg > slots) continue;          // one unit's logits do not fit on the chip
+        int64_t NG = slots / F->Gg;
+        if (NG > F->units) NG = F->units;
+        NG -= NG % F->split;      // the parts of a KV head run side by side, in neighbouring groups
+        if (NG < F->split) continue;
+        F->NG = (int)NG;
+        return true;
     }
-    const int64_t slots = (int64_t)cu_count() * occ;   // workgroups that are resident together
-    if (slots <= 0 || F->Gg > slots) return false;      // one head's logits do not fit on the chip
-    int64_t NG = slots / F->Gg;
-    if (NG > G.Hkv) NG = G.Hkv;
-    F->NG = (int)NG;
-    return true;
+    return false;
 }
 
 hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,

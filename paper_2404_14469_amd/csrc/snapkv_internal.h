@@ -33,11 +33,13 @@ struct ScoreGeom {
     float c2;        // log2(e) / sqrt(D): logits are kept in the base-2 domain
 };
 
-// Plan of the single-read scoring kernel (snapkv_fused.hip).  A unit is a KV head; its window
+// Plan of the single-read scoring kernel (snapkv_fused.hip).  A unit is a KV head or one of
+// `split` equal parts of its query heads; its window
 // rows form RU units of 16 rows (UH per query head), padded to RUW, a power of two; a wave keeps
 // KT tiles of 16 keys per row unit; Gg workgroups share one unit's keys; NG groups run at once.
 struct FusedGeom {
     int RU, UH, RUW, KT, NW, Gg, NG, NB, units;   // NW waves per workgroup; NB blocks of 32 slices per row
+    int split, gs;           // units per KV head; query heads per unit (g = split * gs)
     int64_t ntiles;          // ceil(L / 16)
     unsigned spin_limit;     // bound on the hand-off wait, in polls
 };
@@ -90,6 +92,7 @@ void stage_done(hipStream_t st, int stage);
 hipError_t launch_score(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                         const Workspace& ws, hipStream_t st);
 bool fused_shape(const ScoreGeom& G, FusedGeom* F);
+size_t fused_sync_bytes(const ScoreGeom& G);
 bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
 size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base);
 hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,

@@ -304,8 +304,7 @@ size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base) {
     const size_t mz = align_up(sizeof(float2) * (size_t)G.Hkv * G.R32 * 32);
     const size_t vote = align_up(sizeof(float) * (size_t)G.Hkv * G.NV * (size_t)(G.n > 0 ? G.n : 1));
     const size_t score = align_up(sizeof(float) * (size_t)G.Hkv * (size_t)(G.n > 0 ? G.n : 1));
-    FusedGeom F;
-    const size_t fused = fused_shape(G, &F) ? fused_sync_layout(G, F, nullptr, nullptr) : 0;
+    const size_t fused = fused_sync_bytes(G);
     if (ws) {
         ws->part = reinterpret_cast<float2*>(b + off);
         ws->mz = reinterpret_cast<float2*>(b + off + part);
