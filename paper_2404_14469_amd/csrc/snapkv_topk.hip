@@ -889,8 +889,10 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
                 const int mid = (a2 + b2) >> 1;
                 if (sh_off[mid] <= i) a2 = mid; else b2 = mid;
             }
+            int64_t at = (int64_t)a2 * chunk + (i - sh_off[a2]);
+            at = at < n ? at : n - 1;       // only counts that a failed rendezvous left inconsistent get here
             const unsigned long long both = __hip_atomic_load(
-                reinterpret_cast<const unsigned long long*>(&S.cand[(int64_t)h * n + (int64_t)a2 * chunk + (i - sh_off[a2])]),
+                reinterpret_cast<const unsigned long long*>(&S.cand[(int64_t)h * n + at]),
                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             sh_cand[i] = make_uint2((unsigned)(both & 0xffffffffull), (unsigned)(both >> 32));
         }
