@@ -27,6 +27,13 @@ input values (bf16 / fp32 widened exactly):
      gathers and concatenations).
   9. short prompts (L <= C) are returned unchanged (Listing 1, the first branch).
 
+A second form takes the window rows' log-sum-exp as an input (window_lse / window_probs_given_lse;
+pooled_scores and compress with lse=...): the quantity a block-wise attention prefill already
+holds for every query row (Sec. 4.1 runs the step at the end of prompt encoding), which makes
+step 3 a single exponential.  It is pinned to a hand-worked two-key case, to a library
+log-sum-exp over the visible keys, to the softmax path (true lse changes nothing) and to the
+row-scaling law of an offset lse.
+
 Pins (tests/test_oracle_*.py): closed forms for all-zero queries (harmonic numbers, both
 pool kinds and the tie rule), softmax rows summing to one, mass conservation, shift
 invariance, permutation equivariance, nested selections, the W=1/p=1 special case against
@@ -112,9 +119,43 @@ def _pool1d_fast(x: np.ndarray, pool_kind: int, p: int) -> np.ndarray:
     raise ValueError("pool_kind must be 0 (max) or 1 (avg)")
 
 
+def window_lse(q_h: np.ndarray, k_h: np.ndarray) -> np.ndarray:
+    """Natural log of each window row's softmax denominator, lse[i] = log sum_j exp(s[i, j]) over the
+    keys row i may see (steps 1-2, then the logarithm of step 3's normaliser).  This is the quantity
+    an attention prefill that works block by block keeps per query row."""
+    q = widen(q_h)
+    k = widen(k_h)
+    W, D = q.shape
+    L = k.shape[0]
+    n = L - W
+    s = (q @ k.T) / np.sqrt(np.float64(D))
+    j = np.arange(L)[None, :]
+    i = np.arange(W)[:, None]
+    s = np.where(j > n + i, -np.inf, s)
+    m = s.max(axis=1)
+    return m + np.log(np.exp(s - m[:, None]).sum(axis=1))
+
+
+def window_probs_given_lse(q_h: np.ndarray, k_h: np.ndarray, lse_h: np.ndarray) -> np.ndarray:
+    """Steps 1-3 when the rows' log-sum-exp is handed in instead of computed: P = exp(s - lse),
+    masked keys 0.  With lse = window_lse(q_h, k_h) this is window_probs(q_h, k_h); any other lse
+    scales row i by exp(true_lse[i] - lse[i])."""
+    q = widen(q_h)
+    k = widen(k_h)
+    W, D = q.shape
+    L = k.shape[0]
+    n = L - W
+    s = (q @ k.T) / np.sqrt(np.float64(D))
+    j = np.arange(L)[None, :]
+    i = np.arange(W)[:, None]
+    s = np.where(j > n + i, -np.inf, s)
+    return np.exp(s - np.asarray(lse_h, dtype=np.float64)[:, None])
+
+
 def pooled_scores(q_win: np.ndarray, k: np.ndarray, W: int, pool_kind: int, p: int,
-                  kv_heads=None) -> np.ndarray:
-    """Steps 1-6: score[Hkv, n] (or only the listed KV heads, in the order given)."""
+                  kv_heads=None, lse=None) -> np.ndarray:
+    """Steps 1-6: score[Hkv, n] (or only the listed KV heads, in the order given).  With lse
+    [Hq, W] the softmax denominators are taken from it (window_probs_given_lse)."""
     Hq = q_win.shape[0]
     Hkv, L, _ = k.shape
     if Hq % Hkv:
@@ -129,7 +170,8 @@ def pooled_scores(q_win: np.ndarray, k: np.ndarray, W: int, pool_kind: int, p: i
     out = np.zeros((len(heads), n), dtype=np.float64)
     for oi, hk in enumerate(heads):
         for h in range(hk * g, (hk + 1) * g):
-            v_h = vote(window_probs(q_win[h], k[hk]))
+            P = window_probs(q_win[h], k[hk]) if lse is None else window_probs_given_lse(q_win[h], k[hk], lse[h])
+            v_h = vote(P)
             out[oi] += _pool1d_fast(v_h, pool_kind, p)              # step 6: pool, then group sum
     return out
 
@@ -144,7 +186,7 @@ def select(score: np.ndarray, kcount: int) -> np.ndarray:
 
 
 def compress(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, W: int, pool_kind: int, p: int,
-             C: int, kv_heads=None):
+             C: int, kv_heads=None, lse=None):
     """The whole step.  Returns (out_k, out_v, out_idx, kept, score).
 
     out_k/out_v are [H, kept, D] in the *storage* dtype of k/v (rows copied, never recomputed),
@@ -160,7 +202,7 @@ def compress(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, W: int, pool_kind:
         idx = np.tile(np.arange(L, dtype=np.int64), (len(heads), 1))
         return k[heads].copy(), v[heads].copy(), idx, L, None
     n = L - W
-    score = pooled_scores(q_win, k, W, pool_kind, p, kv_heads=heads)
+    score = pooled_scores(q_win, k, W, pool_kind, p, kv_heads=heads, lse=lse)
     out_idx = np.empty((len(heads), C), dtype=np.int64)
     out_k = np.empty((len(heads), C, D), dtype=k.dtype)
     out_v = np.empty((len(heads), C, D), dtype=v.dtype)

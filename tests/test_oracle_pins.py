@@ -395,6 +395,66 @@ def test_brute_force_three_writings(Hq, Hkv, L, D, W, kind, p, C, dtype):
     assert ok.dtype == k.dtype
 
 
+# ----------------------------------------------------------------------------- handed-in log-sum-exp
+def test_lse_two_key_closed_form():
+    # one query, two visible keys: lse = log(e^s0 + e^s1), written out by hand.
+    # catches: a missing scale, a base-2 / base-e mix-up, max-subtraction left in the result
+    D = 4
+    q = np.array([[1.0, 2.0, -1.0, 0.5]], dtype=np.float32)
+    k = np.array([[0.5, 0.25, 1.0, 2.0], [1.0, -1.0, 0.0, 3.0]], dtype=np.float32)
+    s0 = (0.5 + 0.5 - 1.0 + 1.0) / math.sqrt(D)
+    s1 = (1.0 - 2.0 + 0.0 + 1.5) / math.sqrt(D)
+    lse = orc.window_lse(q, k)
+    assert lse.shape == (1,)
+    assert abs(lse[0] - math.log(math.exp(s0) + math.exp(s1))) < 1e-15
+    P = orc.window_probs_given_lse(q, k, lse)
+    assert abs(P[0, 0] - math.exp(s0) / (math.exp(s0) + math.exp(s1))) < 1e-15
+
+
+def test_lse_matches_library_logsumexp_over_visible_keys():
+    # catches: the causal mask missing from (or off by one in) the log-sum-exp
+    from scipy.special import logsumexp
+    W, L, D = 6, 40, 8
+    q, k, _ = rand_case(61, 1, 1, L, D, W)
+    lse = orc.window_lse(q[0], k[0])
+    s = (q[0].astype(np.float64) @ k[0].astype(np.float64).T) / math.sqrt(D)
+    for i in range(W):
+        assert abs(lse[i] - logsumexp(s[i, : L - W + i + 1])) < 1e-13
+
+
+@pytest.mark.parametrize("dtype,kind,p", [("f32", 0, 7), ("bf16", 1, 5)])
+def test_true_lse_reproduces_the_softmax_path(dtype, kind, p):
+    # handing in the rows' own log-sum-exp must change nothing: same scores, same kept positions
+    Hq, Hkv, L, D, W, C = 4, 2, 300, 16, 16, 60
+    q, k, v = rand_case(62, Hq, Hkv, L, D, W, dtype)
+    lse = np.stack([orc.window_lse(q[h], k[h // 2]) for h in range(Hq)])
+    for h in range(Hq):
+        assert np.allclose(orc.window_probs_given_lse(q[h], k[h // 2], lse[h]), orc.window_probs(q[h], k[h // 2]),
+                           rtol=1e-12, atol=1e-300)
+    a = orc.compress(q, k, v, W, kind, p, C)
+    b = orc.compress(q, k, v, W, kind, p, C, lse=lse)
+    assert np.allclose(a[4], b[4], rtol=1e-12, atol=0)
+    assert np.array_equal(a[2], b[2]) and np.array_equal(a[0], b[0]) and np.array_equal(a[1], b[1])
+
+
+def test_lse_offset_scales_each_row():
+    # raising row i's lse by d_i scales that row's probabilities by exp(-d_i): the votes become the
+    # correspondingly weighted column sum.  catches: lse applied per column, or with the wrong sign
+    W, L, D = 5, 64, 8
+    q, k, _ = rand_case(63, 1, 1, L, D, W)
+    lse = orc.window_lse(q[0], k[0])
+    d = np.array([0.0, math.log(2.0), -0.5, 3.0, 1.25])
+    P = orc.window_probs(q[0], k[0])
+    got = orc.vote(orc.window_probs_given_lse(q[0], k[0], lse + d))
+    want = (P[:, : L - W] * np.exp(-d)[:, None]).sum(axis=0)
+    assert np.allclose(got, want, rtol=1e-13, atol=0)
+    # a common offset rescales every vote alike and cannot change the selection
+    s0 = orc.pooled_scores(q, k, W, 0, 3)
+    s1 = orc.pooled_scores(q, k, W, 0, 3, lse=(lse + math.log(2.0))[None, :])
+    assert np.allclose(s1, 0.5 * s0, rtol=1e-13, atol=0)
+    assert np.array_equal(orc.select(s0[0], 10), orc.select(s1[0], 10))
+
+
 # ----------------------------------------------------------------------------- C oracle vs numpy oracle, larger
 @pytest.mark.parametrize("dtype,kind,p,W", [("bf16", 0, 7, 32), ("f32", 1, 5, 16), ("bf16", 0, 13, 64)])
 def test_c_and_numpy_oracles_agree(dtype, kind, p, W):
