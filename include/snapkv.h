@@ -110,6 +110,28 @@ int64_t snapkv_compress_ws(int dtype, const void* q_win, const void* k, const vo
                            size_t workspace_bytes, void* stream);
 
 /*
+ * The same step when the softmax normalisers of the window rows are already known (an attention
+ * prefill that works block by block keeps, for every query row, the log of its softmax
+ * denominator; Sec. 4.1 runs the compression at the end of prompt encoding, so they exist).
+ *
+ *   lse [Hq, W] device, float32: natural-log-sum-exp of window row i of query head h over the keys
+ *   it may see, lse[h][i] = log sum_{j <= L-W+i} exp(q_win[h][i] . k[kv(h)][j] / sqrt(D)).
+ *
+ * Probabilities are then exp(logit - lse) (Sec. 4; Eq. 1 sums them unchanged), so K is streamed once
+ * with no exchange between workgroups.  All other arguments, the outputs and the return values are
+ * those of snapkv_compress / snapkv_pooled_scores; `dtype` is SNAPKV_DTYPE_*.  An lse that is not
+ * the rows' own scales row i of the probabilities by exp(true - given); the library does not check
+ * it.  SNAPKV_ERR_UNSUPPORTED if the window rows of a query head exceed what a wave tracks
+ * (W > 128).  Scratch comes from the library's per-device buffer, as for snapkv_compress.
+ */
+int64_t snapkv_compress_lse(int dtype, const void* q_win, const void* k, const void* v, const float* lse,
+                            int64_t L, int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
+                            void* out_k, void* out_v, int32_t* out_idx, void* stream);
+int snapkv_pooled_scores_lse(int dtype, const void* q_win, const void* k, const float* lse, int64_t L,
+                             int Hq, int Hkv, int D, int W, int pool_kind, int p, float* out_scores,
+                             void* stream);
+
+/*
  * Top-(kcount) selection alone (Eq. 2), exposed for testing the selector on arbitrary scores:
  *   scores [H, n] device float32, all values >= +0 (their bit patterns are compared as unsigned
  *   integers); out_idx [H, kcount] device int32: the kcount best positions per row under

@@ -22,7 +22,7 @@ SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compr
            "snapkv_pooled_scores", "snapkv_pooled_scores_f32", "snapkv_workspace_bytes",
            "snapkv_compress_ws", "snapkv_select_topk", "snapkv_release", "snapkv_profile_start",
            "snapkv_profile_stop", "snapkv_num_stages", "snapkv_stage_name", "snapkv_set_scoring_scheme",
-           "snapkv_sync_timeouts")
+           "snapkv_sync_timeouts", "snapkv_compress_lse", "snapkv_pooled_scores_lse")
 
 _lib = None
 
@@ -56,6 +56,10 @@ def load():
         f = getattr(L, name)
         f.restype = i32
         f.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, i32, vp, vp]
+    L.snapkv_compress_lse.restype = i64
+    L.snapkv_compress_lse.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
+    L.snapkv_pooled_scores_lse.restype = i32
+    L.snapkv_pooled_scores_lse.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, vp, vp]
     L.snapkv_workspace_bytes.restype = sz
     L.snapkv_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
     L.snapkv_compress_ws.restype = i64
@@ -128,7 +132,7 @@ def snapkv_release() -> None:
 
 
 def snapkv_set_scoring_scheme(scheme: int) -> None:
-    """0: single-read kernel where it fits (default); 1: always the two-pass kernels."""
+    """Bit 0: always the two-pass scoring kernels; bit 1: always separate pooling and selection kernels."""
     _check(load().snapkv_set_scoring_scheme(int(scheme)))
 
 
@@ -184,6 +188,44 @@ def snapkv_compress(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, pool_
                                              workspace.numel(), _stream(stream)))
     fn = lib.snapkv_compress if code == DTYPE_BF16 else lib.snapkv_compress_f32
     return _check(fn(*ptrs, L, Hq, Hkv, D, W, pool_kind, p, C, *outs, _stream(stream)))
+
+
+def _lse_ptr(lse: torch.Tensor, Hq: int, W: int) -> int:
+    if tuple(lse.shape) != (Hq, W):
+        raise ValueError("lse must be [Hq, W]")
+    return _dev(lse, "lse", torch.float32)
+
+
+def snapkv_compress_lse(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, lse: torch.Tensor,
+                        pool_kind: int, p: int, C: int, out_k: torch.Tensor, out_v: torch.Tensor,
+                        out_idx: torch.Tensor, stream=None) -> int:
+    """snapkv_compress with the window rows' log-sum-exp handed in (lse [Hq, W] float32)."""
+    lib = load()
+    Hq, Hkv, L, D, W = _shapes(q_win, k)
+    code = _dtype_code(k)
+    if v.shape != k.shape:
+        raise ValueError("k and v must have the same shape")
+    if tuple(out_k.shape) != (Hkv, C, D) or tuple(out_v.shape) != (Hkv, C, D):
+        raise ValueError("out_k/out_v must be [Hkv, C, D]")
+    if tuple(out_idx.shape) != (Hkv, C):
+        raise ValueError("out_idx must be [Hkv, C]")
+    return _check(lib.snapkv_compress_lse(
+        code, _dev(q_win, "q_win", k.dtype), _dev(k, "k"), _dev(v, "v", k.dtype), _lse_ptr(lse, Hq, W),
+        L, Hq, Hkv, D, W, pool_kind, p, C, _dev(out_k, "out_k", k.dtype), _dev(out_v, "out_v", k.dtype),
+        _dev(out_idx, "out_idx", torch.int32), _stream(stream)))
+
+
+def snapkv_pooled_scores_lse(q_win: torch.Tensor, k: torch.Tensor, lse: torch.Tensor, pool_kind: int,
+                             p: int, out_scores: torch.Tensor, stream=None) -> None:
+    """snapkv_pooled_scores with the window rows' log-sum-exp handed in."""
+    lib = load()
+    Hq, Hkv, L, D, W = _shapes(q_win, k)
+    code = _dtype_code(k)
+    if tuple(out_scores.shape) != (Hkv, L - W):
+        raise ValueError("out_scores must be [Hkv, L-W]")
+    _check(lib.snapkv_pooled_scores_lse(code, _dev(q_win, "q_win", k.dtype), _dev(k, "k"), _lse_ptr(lse, Hq, W),
+                                        L, Hq, Hkv, D, W, pool_kind, p,
+                                        _dev(out_scores, "out_scores", torch.float32), _stream(stream)))
 
 
 def snapkv_pooled_scores(q_win: torch.Tensor, k: torch.Tensor, pool_kind: int, p: int,

@@ -87,9 +87,25 @@ int internal_scratch(size_t need, void** out, uint64_t* was_clean = nullptr) {
 int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGeom& G,
                const Workspace& ws, int pool_kind, int p, float* score, unsigned* minmax,
                bool prepare_select, ScoreGeom* Gv, hipStream_t st, bool already_prepared = false,
-               CleanJob* clean = nullptr) {
+               CleanJob* clean = nullptr, const float* lse = nullptr) {
     FusedGeom F;
     ScoreGeom Gp = G;
+    if (lse) {   // the rows' normalisers are given: one streaming pass, nothing handed between workgroups
+        if (!lse_plan(dtype, D, G, &F)) return SNAPKV_ERR_UNSUPPORTED;
+        if (!already_prepared && prepare_select) {
+            if (launch_prepare(nullptr, 0, &ws.sel, G.Hkv, st) != hipSuccess) return SNAPKV_ERR_HIP;
+            stage_done(st, kStagePrepare);
+        }
+        if (launch_score_lse(dtype, D, q_win, k, lse, G, F, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        stage_done(st, kStageFused);
+        Gp.NV = G.g;
+        Gp.VB = 1;
+        if (Gv) *Gv = Gp;
+        if (!score) return SNAPKV_OK;
+        if (launch_pool(Gp, ws.vote, pool_kind, p, score, minmax, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        stage_done(st, kStagePool);
+        return SNAPKV_OK;
+    }
     const bool fused = g_allow_fused && fused_plan(dtype, D, G, &F);
     FusedSync S;
     if (fused) fused_sync_layout(G, F, &S, ws.fused);
@@ -121,8 +137,10 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
 int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v, int64_t L, int Hq,
                       int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k,
                       void* out_v, int32_t* out_idx, void* workspace, size_t workspace_bytes,
-                      bool own_scratch, void* stream) {
+                      bool own_scratch, void* stream, const float* lse = nullptr, bool with_lse = false) {
     if (dtype != SNAPKV_DTYPE_BF16 && dtype != SNAPKV_DTYPE_F32) return SNAPKV_ERR_INVALID_ARG;
+    if (with_lse && !lse) return SNAPKV_ERR_INVALID_ARG;
+    if (with_lse && (reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
     int rc = check_score_args(q_win, k, L, Hq, Hkv, D, W, pool_kind, p);
     if (rc != SNAPKV_OK) return rc;
     if (!v || !out_k || !out_v || !out_idx) return SNAPKV_ERR_INVALID_ARG;
@@ -162,18 +180,19 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     if (g_allow_pool_select && pool_select_ok(G, pool_kind, p, C - W)) {   // pooling and selection in one launch
         bool prepared = false;
         FusedGeom Fp;
-        if (own_scratch && g_allow_fused && fused_plan(dtype, D, G, &Fp)) {
+        if (own_scratch && (lse ? lse_plan(dtype, D, G, &Fp) : (g_allow_fused && fused_plan(dtype, D, G, &Fp)))) {
             int dev = 0;
             if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
                 key = 0x9E3779B97F4A7C15ull ^ ((uint64_t)L * 1000003ull) ^ ((uint64_t)Hq << 50) ^ ((uint64_t)Hkv << 40) ^
                       ((uint64_t)D << 32) ^ ((uint64_t)W << 20) ^ ((uint64_t)dtype << 19);
+                if (lse) key ^= 0x5555ull;   // that path leaves only the counters ready, not the hand-off words
                 mine = &g_scratch[dev];
                 prepared = was_clean == key;
             }
         }
         ScoreGeom Gv = G;
         rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, true, &Gv, st, prepared,
-                        mine ? &clean : nullptr);
+                        mine ? &clean : nullptr, lse);
         if (rc != SNAPKV_OK) return rc;
         se = launch_pool_select(Gv, ws.vote, pool_kind, p, C - W, C, W, out_idx, ws.sel, st);
         if (mine) {
@@ -182,7 +201,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
         }
     } else {
         rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr,
-                        chunked, nullptr, st);
+                        chunked, nullptr, st, false, nullptr, lse);
         if (rc != SNAPKV_OK) return rc;
         se = chunked ? launch_select_chunked(ws.score, Hkv, G.n, C - W, C, W, out_idx, ws.sel, pool_tiles(G.n), st)
                      : launch_select(ws.score, Hkv, G.n, C - W, C, W, out_idx, st);
@@ -191,7 +210,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     stage_done(st, kStageSelect);
     if (launch_gather(k, v, out_idx, Hkv, L, C, C, row_bytes, out_k, out_v, clean, st) != hipSuccess)
         return SNAPKV_ERR_HIP;
-    if (mine && clean.ones) {
+    if (mine && (clean.ones || lse) && clean.zeros) {
         std::lock_guard<std::mutex> lock(g_mu);
         mine->clean_key = key;
     }
@@ -200,9 +219,13 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
 }
 
 int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D, int W,
-                int pool_kind, int p, float* out_scores, void* stream) {
+                int pool_kind, int p, float* out_scores, void* stream, const float* lse = nullptr,
+                bool with_lse = false) {
+    if (dtype != SNAPKV_DTYPE_BF16 && dtype != SNAPKV_DTYPE_F32) return SNAPKV_ERR_INVALID_ARG;
     int rc = check_score_args(q_win, k, L, Hq, Hkv, D, W, pool_kind, p);
     if (rc != SNAPKV_OK) return rc;
+    if (with_lse && !lse) return SNAPKV_ERR_INVALID_ARG;
+    if (with_lse && (reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
     if (!out_scores) return SNAPKV_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(out_scores) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
     if (L == W) return SNAPKV_OK;   // empty prefix: nothing to score
@@ -213,7 +236,7 @@ int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, 
     Workspace ws;
     workspace_layout(G, &ws, base);
     return run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, out_scores, nullptr, false, nullptr,
-                      static_cast<hipStream_t>(stream));
+                      static_cast<hipStream_t>(stream), false, nullptr, lse);
 }
 
 }  // namespace
@@ -344,6 +367,19 @@ int snapkv_pooled_scores(const void* q_win, const void* k, int64_t L, int Hq, in
 int snapkv_pooled_scores_f32(const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D,
                              int W, int pool_kind, int p, float* out_scores, void* stream) {
     return scores_impl(SNAPKV_DTYPE_F32, q_win, k, L, Hq, Hkv, D, W, pool_kind, p, out_scores, stream);
+}
+
+int64_t snapkv_compress_lse(int dtype, const void* q_win, const void* k, const void* v, const float* lse,
+                            int64_t L, int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
+                            void* out_k, void* out_v, int32_t* out_idx, void* stream) {
+    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
+                         nullptr, 0, true, stream, lse, true);
+}
+
+int snapkv_pooled_scores_lse(int dtype, const void* q_win, const void* k, const float* lse, int64_t L,
+                             int Hq, int Hkv, int D, int W, int pool_kind, int p, float* out_scores,
+                             void* stream) {
+    return scores_impl(dtype, q_win, k, L, Hq, Hkv, D, W, pool_kind, p, out_scores, stream, lse, true);
 }
 
 size_t snapkv_workspace_bytes(int64_t L, int Hq, int Hkv, int D, int W) {

@@ -718,6 +718,254 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 }
 
 // ---------------------------------------------------------------------------------------------
+// Scoring and voting when the window rows' log-sum-exp is handed in (the normalisers a block-wise
+// attention prefill keeps per query row).  P[i, j] = exp(s[i, j] - lse[i]) needs nothing from other
+// keys, so K is streamed once with no hand-off between workgroups at all: logits on MFMA, one
+// exponential per logit, the column sum over the window rows of each query head (Eq. 1), store.
+// Units, slices, the tile-to-key mapping, the shared Q block and the way K tile buffers are
+// consumed in two halves and requested again at points spread over an iteration are those of
+// score_fused; the waves of a workgroup meet at one LDS-only barrier per unit (for the Q block).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ void lds_barrier() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
+template <typename T, int D, int RUW, int KT, int NW>
+__global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv,
+                                                     const void* __restrict__ kv,
+                                                     const float* __restrict__ lse,
+                                                     float* __restrict__ vote, const ScoreGeom G,
+                                                     const FusedGeom F) {
+    constexpr int R = RUW * 16;
+    constexpr int NT = NW * 64;
+    constexpr int ES = esize<T>::value;
+    using Frag = Frag16<T, D>;
+    constexpr int NP = Frag::NP;
+    constexpr int QCH = RUW * NP;
+    constexpr int QPW = (QCH + NW - 1) / NW;
+    constexpr int KL = KT / 2;
+    static_assert(R <= NT, "one thread per window row stages its log-sum-exp");
+    extern __shared__ uint4 qbuf[];      // [2][QCH][64]: Q blocks of two consecutive units
+    __shared__ __attribute__((aligned(16))) float sm_lse[2][R];   // base-2 log-sum-exp per row, +inf for padding rows
+
+    const int tid = threadIdx.x, lane = tid & 63, n16 = lane & 15, kg = lane >> 4;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wg = (int)(blockIdx.x % F.Gg), group = (int)(blockIdx.x / F.Gg);
+    const int TS = F.Gg * NW;
+    const int vwg = (F.Gg % 8 == 0) ? (wg % 8) * (F.Gg / 8) + wg / 8 : wg;
+    const int tile0 = vwg * NW + w;
+    const int nu = group < F.units ? (F.units - group + F.NG - 1) / F.NG : 0;
+    if (nu == 0) return;
+    const bool special = ((int64_t)(KT - 1) * TS + tile0 + 1) * 16 > G.n;
+
+    const char* kp[KT];
+#pragma unroll
+    for (int t = 0; t < KT; ++t) {
+        int64_t j = ((int64_t)t * TS + tile0) * 16 + n16;
+        j = j < G.L ? j : G.L - 1;
+        kp[t] = static_cast<const char*>(kv) + ((int64_t)(group / F.split) * G.L + j) * D * ES + kg * 16;
+    }
+    const char* qp[QPW];
+#pragma unroll
+    for (int x = 0; x < QPW; ++x) {
+        int c = w + x * NW;
+        c = c < QCH ? c : QCH - 1;
+        const int ru = c / NP, pc = c % NP;
+        int head = ru / F.UH, i = (ru % F.UH) * 16 + n16;
+        head = head < F.gs ? head : F.gs - 1;
+        i = i < G.W ? i : G.W - 1;
+        qp[x] = static_cast<const char*>(qv) + ((int64_t)(group * F.gs + head) * G.W + i) * D * ES + (4 * pc + kg) * 16;
+    }
+    // the window row whose log-sum-exp this thread stages (threads beyond R re-read row 0)
+    const int lrow = tid < R ? tid : 0;
+    const int lru = lrow >> 4, lhead = lru / F.UH, li = (lru % F.UH) * 16 + (lrow & 15);
+    const bool lreal = tid < R && lru < F.RU && lhead < F.gs && li < G.W;
+    const float* lp = lse + (int64_t)(group * F.gs + (lhead < F.gs ? lhead : F.gs - 1)) * G.W + (li < G.W ? li : G.W - 1);
+    const int64_t kstep = (int64_t)(F.NG / F.split) * G.L * D * ES;
+    const int64_t qstep = (int64_t)F.NG * F.gs * G.W * D * ES;
+    const int64_t lstep = (int64_t)F.NG * F.gs * G.W;
+    constexpr float kLog2e = 1.4426950408889634f;
+
+    Frag kf[KT];
+    uint4 qland[QPW];
+    float lland;
+    f32x4 e[RUW][KT];
+#pragma unroll
+    for (int t = 0; t < KT; ++t) load_frag16p<T, D>(kf[t], kp[t]);
+#pragma unroll
+    for (int x = 0; x < QPW; ++x) qland[x] = *reinterpret_cast<const uint4*>(qp[x]);
+    lland = *lp;
+#pragma unroll
+    for (int x = 0; x < QPW; ++x)
+        if (w + x * NW < QCH) qbuf[(w + x * NW) * 64 + lane] = qland[x];
+    if (tid < R) sm_lse[0][tid] = lreal ? lland * kLog2e : INFINITY;
+    __syncthreads();
+#pragma unroll
+    for (int ru = 0; ru < RUW; ++ru)
+#pragma unroll
+        for (int t = 0; t < KT; ++t) e[ru][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    auto mfma_tiles = [&](auto T0, auto T1, const int par) {
+        constexpr int t0 = decltype(T0)::value, t1 = decltype(T1)::value;
+        if constexpr (t0 < t1) {
+#pragma unroll
+            for (int ru = 0; ru < RUW; ++ru) {
+                Frag qf;
+#pragma unroll
+                for (int pc = 0; pc < NP; ++pc) qf.v[pc] = qbuf[(par * QCH + ru * NP + pc) * 64 + lane];
+#pragma unroll
+                for (int t = t0; t < t1; ++t) e[ru][t] = mfma16<D>(qf, kf[t]);
+            }
+        }
+    };
+    auto issue_tiles = [&](auto T0, auto T1, const int64_t step) {
+        constexpr int t0 = decltype(T0)::value, t1 = decltype(T1)::value;
+#pragma unroll
+        for (int t = t0; t < t1; ++t) {
+            kp[t] += step;
+            load_frag16p<T, D>(kf[t], kp[t]);
+        }
+    };
+    using IC0 = std::integral_constant<int, 0>;
+    using ICL = std::integral_constant<int, KL>;
+    using ICT = std::integral_constant<int, KT>;
+    using ICLA = std::integral_constant<int, (KL + 1) / 2>;
+    using ICUA = std::integral_constant<int, KL + (KT - KL + 1) / 2>;
+    mfma_tiles(IC0{}, ICL{}, 0);
+    __builtin_amdgcn_sched_barrier(0);
+    issue_tiles(IC0{}, ICLA{}, nu > 1 ? kstep : 0);   // unconditional: see score_fused
+    __builtin_amdgcn_sched_barrier(0);
+
+#define SNAPKV_LSE_ISSUE(cond_, what_)                                       \
+    do {                                                                     \
+        __builtin_amdgcn_sched_barrier(0);                                   \
+        if constexpr (cond_) { what_; }                                      \
+        __builtin_amdgcn_sched_barrier(0);                                   \
+    } while (0)
+
+    auto iteration = [&](auto MODE, const int it) {
+        constexpr bool kNext1 = (decltype(MODE)::value & 1) != 0;
+        constexpr bool kNext2 = (decltype(MODE)::value & 2) != 0;
+        const int unit = group + it * F.NG;
+        mfma_tiles(ICL{}, ICT{}, it & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (kNext1) {   // the next unit's Q chunk and log-sum-exp
+#pragma unroll
+            for (int x = 0; x < QPW; ++x) {
+                qp[x] += qstep;
+                qland[x] = *reinterpret_cast<const uint4*>(qp[x]);
+            }
+            lp += lstep;
+            lland = *lp;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        SNAPKV_LSE_ISSUE(kNext1, issue_tiles(ICLA{}, ICL{}, kstep));   // point 0
+
+        // probabilities: one exponential per logit, in the base-2 domain
+        if (special) {
+            int jlane = tile0 * 16 + n16;
+            asm volatile("" : "+v"(jlane));
+            const int nn = (int)G.n, LL = (int)G.L;
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+                const int j = jlane + t * TS * 16;
+#pragma unroll
+                for (int ru = 0; ru < RUW; ++ru)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int i = (ru % F.UH) * 16 + kg * 4 + r;
+                        if (j > nn + i || j >= LL) e[ru][t][r] = -INFINITY;   // prompt-phase causal mask
+                    }
+            }
+        }
+#pragma unroll
+        for (int ru = 0; ru < RUW; ++ru) {
+            const float4 l2 = *reinterpret_cast<const float4*>(&sm_lse[it & 1][ru * 16 + kg * 4]);
+            const float l[4] = {l2.x, l2.y, l2.z, l2.w};
+#pragma unroll
+            for (int t = 0; t < KT; ++t)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) e[ru][t][r] = __builtin_amdgcn_exp2f(fmaf(e[ru][t][r], G.c2, -l[r]));
+        }
+        SNAPKV_LSE_ISSUE(kNext1, issue_tiles(ICL{}, ICUA{}, kstep));   // point 1
+
+        // votes: sum over the window rows of each query head, then over the four lanes of a column
+        {
+            float* vb = vote + (int64_t)unit * F.gs * G.n;
+            int jst = tile0 * 16 + n16;
+            asm volatile("" : "+v"(jst));
+            const int nst = (int)G.n;
+            float v[KT];
+#pragma unroll
+            for (int t = 0; t < KT; ++t) v[t] = 0.f;
+#pragma unroll
+            for (int ru = 0; ru < RUW; ++ru) {
+#pragma unroll
+                for (int t = 0; t < KT; ++t) {
+                    const f32x4 ev = e[ru][t];
+                    v[t] += (ev[0] + ev[1]) + (ev[2] + ev[3]);
+                }
+                if ((ru + 1) % F.UH == 0) {
+                    const int head = ru / F.UH;
+                    float* vh = vb + (int64_t)head * G.n;
+                    if constexpr (KT >= 4) {
+                        float a[KT / 2], b[KT / 4];
+#pragma unroll
+                        for (int x = 0; x < KT / 2; ++x) {
+                            const float mine = (kg & 2) ? v[x + KT / 2] : v[x];
+                            const float theirs = (kg & 2) ? v[x] : v[x + KT / 2];
+                            a[x] = mine + __shfl_xor(theirs, 32, 64);
+                        }
+#pragma unroll
+                        for (int x = 0; x < KT / 4; ++x) {
+                            const float mine = (kg & 1) ? a[x + KT / 4] : a[x];
+                            const float theirs = (kg & 1) ? a[x] : a[x + KT / 4];
+                            b[x] = mine + __shfl_xor(theirs, 16, 64);
+                        }
+#pragma unroll
+                        for (int x = 0; x < KT / 4; ++x) {
+                            const int t = ((kg & 2) ? KT / 2 : 0) + ((kg & 1) ? KT / 4 : 0) + x;
+                            const int j = jst + t * TS * 16;
+                            if (head < F.gs && j < nst) vh[j] = b[x];
+                        }
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < KT; ++t) {
+                            float sum = v[t] + __shfl_xor(v[t], 32, 64);
+                            sum += __shfl_xor(sum, 16, 64);
+                            const int j = jst + t * TS * 16;
+                            if (kg == 0 && head < F.gs && j < nst) vh[j] = sum;
+                        }
+                    }
+#pragma unroll
+                    for (int t = 0; t < KT; ++t) v[t] = 0.f;
+                }
+            }
+        }
+        SNAPKV_LSE_ISSUE(kNext1, issue_tiles(ICUA{}, ICT{}, kstep));   // point 2
+        if constexpr (kNext1) {
+#pragma unroll
+            for (int x = 0; x < QPW; ++x)
+                if (w + x * NW < QCH) qbuf[(((it + 1) & 1) * QCH + w + x * NW) * 64 + lane] = qland[x];
+            if (tid < R) sm_lse[(it + 1) & 1][tid] = lreal ? lland * kLog2e : INFINITY;
+        }
+        lds_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (kNext1) mfma_tiles(IC0{}, ICL{}, (it + 1) & 1);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (kNext2) issue_tiles(IC0{}, ICLA{}, kstep);   // point 3
+        __builtin_amdgcn_sched_barrier(0);
+    };
+#undef SNAPKV_LSE_ISSUE
+    int it = 0;
+    for (; it + 2 < nu; ++it) iteration(std::integral_constant<int, 3>{}, it);
+    for (; it + 1 < nu; ++it) iteration(std::integral_constant<int, 1>{}, it);
+    for (; it < nu; ++it) iteration(std::integral_constant<int, 0>{}, it);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------
 constexpr int kFusedSlots = 8;          // RUW * KT: accumulator tiles a wave keeps per unit (8 waves)
@@ -927,6 +1175,94 @@ hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, co
     if (G.n <= 0) return hipSuccess;
     const FusedCall call{q, k, &G, &F, &S, vote, st};
     return fused_dispatch(dtype, D, F.NW, F.RUW, &call, nullptr);
+}
+
+// ---- the variant with handed-in log-sum-exp
+struct LseCall {
+    const void* q;
+    const void* k;
+    const float* lse;
+    const ScoreGeom* G;
+    const FusedGeom* F;
+    float* vote;
+    hipStream_t st;
+};
+
+template <typename T, int D, int RUW, int NW>
+static hipError_t lse_instance(const LseCall* call, int* occ) {
+    constexpr int KT = kFusedSlots / RUW;
+    auto kern = score_lse<T, D, RUW, KT, NW>;
+    constexpr int kQBytes = 2 * RUW * (D * (std::is_same<T, bf16_k>::value ? 2 : 4) / 64) * 64 * 16;   // Q blocks of two units
+    static int cached_occ = -1;
+    if (cached_occ < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kQBytes);
+        if (e != hipSuccess) return e;
+        int n = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, NW * 64, kQBytes);
+        if (e != hipSuccess) return e;
+        cached_occ = n;
+    }
+    if (occ) *occ = cached_occ;
+    if (!call) return hipSuccess;
+    const FusedGeom& F = *call->F;
+    hipLaunchKernelGGL(kern, dim3(F.NG * F.Gg), dim3(NW * 64), kQBytes, call->st, call->q, call->k,
+                       call->lse, call->vote, *call->G, F);
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t lse_by_rows(int RUW, const LseCall* call, int* occ) {
+    switch (RUW) {
+        case 1: return lse_instance<T, D, 1, kFusedWaves>(call, occ);
+        case 2: return lse_instance<T, D, 2, kFusedWaves>(call, occ);
+        case 4: return lse_instance<T, D, 4, kFusedWaves>(call, occ);
+        case 8: return lse_instance<T, D, 8, kFusedWaves>(call, occ);
+    }
+    return hipErrorInvalidValue;
+}
+
+static hipError_t lse_dispatch(int dtype, int D, int RUW, const LseCall* call, int* occ) {
+    if (dtype == 0) {
+        if (D == 128) return lse_by_rows<bf16_k, 128>(RUW, call, occ);
+        if (D == 64) return lse_by_rows<bf16_k, 64>(RUW, call, occ);
+    } else {
+        if (D == 128) return lse_by_rows<f32_k, 128>(RUW, call, occ);
+        if (D == 64) return lse_by_rows<f32_k, 64>(RUW, call, occ);
+    }
+    return hipErrorInvalidValue;
+}
+
+// Launch plan of score_lse.  Nothing waits across workgroups, so residency is not a condition; the
+// grid is still sized to what is resident so that every workgroup streams from start to end.
+bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
+    int cand[8];
+    const int nc = fused_split_candidates(G, cand);
+    for (int c = 0; c < nc; ++c) {
+        if (!fused_shape_nw(G, kFusedWaves, cand[c], F)) continue;
+        int occ = 0;
+        if (lse_dispatch(dtype, D, F->RUW, nullptr, &occ) != hipSuccess) {
+            (void)hipGetLastError();
+            continue;
+        }
+        const int64_t slots = (int64_t)cu_count() * occ;
+        if (slots <= 0) continue;
+        int64_t NG = slots / F->Gg;
+        if (NG < F->split) NG = F->split;    // more workgroups than fit at once simply queue up
+        if (NG > F->units) NG = F->units;
+        NG -= NG % F->split;
+        if (NG < F->split) continue;
+        F->NG = (int)NG;
+        return true;
+    }
+    return false;
+}
+
+hipError_t launch_score_lse(int dtype, int D, const void* q, const void* k, const float* lse,
+                            const ScoreGeom& G, const FusedGeom& F, float* vote, hipStream_t st) {
+    if (G.n <= 0) return hipSuccess;
+    const LseCall call{q, k, lse, &G, &F, vote, st};
+    return lse_dispatch(dtype, D, F.RUW, &call, nullptr);
 }
 
 }  // namespace snapkv

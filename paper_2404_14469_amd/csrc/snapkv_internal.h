@@ -105,6 +105,9 @@ bool select_chunked_ok(int64_t n);
 hipError_t launch_select_init(const SelectScratch& S, int H, hipStream_t st);
 hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, int H, hipStream_t st);
 int64_t fused_sync_pairs(const FusedGeom& F);
+bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
+hipError_t launch_score_lse(int dtype, int D, const void* q, const void* k, const float* lse,
+                            const ScoreGeom& G, const FusedGeom& F, float* vote, hipStream_t st);
 // Pooling and selection in one cooperative launch (reads votes, writes the kept positions).
 // pool_select_ok says whether the shape fits and the grid can be resident on the current device.
 bool pool_select_ok(const ScoreGeom& G, int pool_kind, int p, int64_t kcount);

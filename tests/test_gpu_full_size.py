@@ -63,6 +63,34 @@ def test_two_pass_scheme_at_full_size(snapkv):
         snapkv.snapkv_set_scoring_scheme(0)
 
 
+def test_lse_entry_at_full_size(snapkv):
+    # the entry point that takes the window rows' log-sum-exp, on the longest configuration and on GQA
+    import numpy as np
+    from oracle import snapkv_oracle as orc
+    for w, layer, heads in ((workloads.LONG_131K, 2, [1, 30]), (workloads.MISTRAL_7B_GQA_32K, 5, [0, 7])):
+        print(f"[full-size] lse entry {w.name} layer {layer} oracle heads {heads}", flush=True)
+        case = workloads.generate(w, layer=layer, device="cuda")
+        q, k, v = case["q_win"], case["k"], case["v"]
+        lse = np.zeros((w.Hq, w.W), dtype=np.float32)      # rows of the sampled KV heads come from the oracle,
+        g = w.Hq // w.Hkv                                   # the others stay 0 and are not compared
+        for hk in heads:
+            kn = workloads.to_numpy_bits(k[hk])
+            for h in range(hk * g, (hk + 1) * g):
+                lse[h] = orc.window_lse(workloads.to_numpy_bits(q[h]), kn).astype(np.float32)
+        lt = torch.from_numpy(lse).cuda()
+        sc = torch.empty((w.Hkv, w.n), dtype=torch.float32, device="cuda")
+        snapkv.snapkv_pooled_scores_lse(q, k, lt, w.pool_kind, w.p, sc)
+        out_k = torch.zeros((w.Hkv, w.C, w.D), dtype=k.dtype, device="cuda")
+        out_v = torch.zeros_like(out_k)
+        out_idx = torch.full((w.Hkv, w.C), -1, dtype=torch.int32, device="cuda")
+        kept = snapkv.snapkv_compress_lse(q, k, v, lt, w.pool_kind, w.p, w.C, out_k, out_v, out_idx)
+        torch.cuda.synchronize()
+        res = (sc.cpu().numpy(), out_k, out_v, out_idx.cpu().numpy(), kept)
+        check_against_oracle(q, k, v, w.pool_kind, w.p, w.C, *res, heads=heads)
+        del case, q, k, v, out_k, out_v, sc
+        torch.cuda.empty_cache()
+
+
 def test_separate_pool_and_select_kernels_at_full_size(snapkv):
     # the kernels that take over when a head does not fit the cooperative pooling + selection launch
     snapkv.snapkv_set_scoring_scheme(2)

@@ -207,6 +207,57 @@ def test_explicit_workspace_matches(snapkv):
     assert e.value.code == -4
 
 
+# ----------------------------------------------------------------------------- handed-in log-sum-exp
+def _oracle_lse(q, k):
+    """[Hq, W] float32 from the fp64 oracle (never from the GPU)."""
+    qn, kn = workloads.to_numpy_bits(q), workloads.to_numpy_bits(k)
+    g = qn.shape[0] // kn.shape[0]
+    return np.stack([orc.window_lse(qn[h], kn[h // g]) for h in range(qn.shape[0])]).astype(np.float32)
+
+
+def _run_lse(snapkv, q, k, v, lse, pool_kind, p, C):
+    Hkv, L, D = k.shape
+    W = q.shape[1]
+    sc = torch.full((Hkv, L - W), float("nan"), dtype=torch.float32, device="cuda")
+    snapkv.snapkv_pooled_scores_lse(q, k, lse, pool_kind, p, sc)
+    out_k = torch.zeros((Hkv, C, D), dtype=k.dtype, device="cuda")
+    out_v = torch.zeros_like(out_k)
+    out_idx = torch.full((Hkv, C), -1, dtype=torch.int32, device="cuda")
+    kept = snapkv.snapkv_compress_lse(q, k, v, lse, pool_kind, p, C, out_k, out_v, out_idx)
+    torch.cuda.synchronize()
+    return sc.cpu().numpy(), out_k, out_v, out_idx.cpu().numpy(), kept
+
+
+LSE_CASES = [w for w in SMALL_CASES if w.L > w.C and w.L > w.W]
+
+
+@pytest.mark.parametrize("w", LSE_CASES, ids=lambda w: w.name)
+def test_lse_entry_small_cases(snapkv, w):
+    # with the rows' own log-sum-exp the result must meet the same bar against the same oracle
+    case = workloads.generate(w, device="cuda")
+    q, k, v = case["q_win"], case["k"], case["v"]
+    lse = torch.from_numpy(_oracle_lse(q, k)).cuda()
+    res = _run_lse(snapkv, q, k, v, lse, w.pool_kind, w.p, w.C)
+    check_against_oracle(q, k, v, w.pool_kind, w.p, w.C, *res)
+
+
+def test_lse_offset_scales_rows_on_the_gpu(snapkv):
+    # the oracle's row-scaling law: lse + d_i scales row i by exp(-d_i); compared with the oracle
+    # given the same (wrong on purpose) lse
+    w = small("lse_off", Hq=4, Hkv=2, L=1500, C=200, W=16, p=5)
+    case = workloads.generate(w, device="cuda")
+    q, k, v = case["q_win"], case["k"], case["v"]
+    lse = _oracle_lse(q, k)
+    rng = np.random.default_rng(5)
+    lse_off = (lse + rng.uniform(-1.0, 2.0, size=lse.shape)).astype(np.float32)
+    sc = torch.empty((w.Hkv, w.n), dtype=torch.float32, device="cuda")
+    snapkv.snapkv_pooled_scores_lse(q, k, torch.from_numpy(lse_off).cuda(), w.pool_kind, w.p, sc)
+    torch.cuda.synchronize()
+    want = orc.pooled_scores(workloads.to_numpy_bits(q), workloads.to_numpy_bits(k), w.W, w.pool_kind, w.p,
+                             lse=lse_off.astype(np.float64))
+    assert np.allclose(sc.cpu().numpy(), want, rtol=1e-3, atol=1e-30)
+
+
 # ----------------------------------------------------------------------------- selector alone
 def _select_case(snapkv, scores_np, kcount):
     s = torch.from_numpy(scores_np).cuda()

@@ -63,6 +63,13 @@ def test_scores_and_select_reject_bad_arguments():
     assert lib.snapkv_pooled_scores(FAKE, FAKE, 4096, 8, 8, 128, 32, 0, 6, FAKE, None) == -1
     assert lib.snapkv_pooled_scores_f32(FAKE, FAKE, 4096, 8, 8, 100, 32, 0, 7, FAKE, None) == -2
     assert lib.snapkv_pooled_scores(FAKE, FAKE, 32, 8, 8, 128, 32, 0, 7, FAKE, None) == 0   # empty prefix
+    # handed-in log-sum-exp: missing, misaligned, bad dtype code, too many window rows per query head
+    lse_args = (4096, 8, 8, 128, 32, 0, 7)
+    assert lib.snapkv_pooled_scores_lse(0, FAKE, FAKE, None, *lse_args, FAKE, None) == -1
+    assert lib.snapkv_pooled_scores_lse(0, FAKE, FAKE, FAKE + 2, *lse_args, FAKE, None) == -3
+    assert lib.snapkv_pooled_scores_lse(5, FAKE, FAKE, FAKE, *lse_args, FAKE, None) == -1
+    assert lib.snapkv_compress_lse(0, FAKE, FAKE, FAKE, None, *lse_args, 512, FAKE, FAKE, FAKE, None) == -1
+    assert lib.snapkv_compress_lse(0, FAKE, FAKE, FAKE, FAKE, 4096, 8, 8, 128, 32, 0, 6, 512, FAKE, FAKE, FAKE, None) == -1
     assert lib.snapkv_select_topk(None, 1, 10, 2, FAKE, None) == -1
     assert lib.snapkv_select_topk(FAKE, 1, 10, 11, FAKE, None) == -1
     assert lib.snapkv_select_topk(FAKE, 1, 10, 0, FAKE, None) == 0
