@@ -55,6 +55,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scheme", type=int, default=0,
                     help="kernel scheme bits for measurements (see snapkv_set_scoring_scheme); 0 = default")
+    ap.add_argument("--entry", default="compress", choices=["compress", "lse"],
+                    help="compress (default): snapkv_compress, the headline path; lse: snapkv_compress_lse, "
+                         "the variant that is handed the window rows' log-sum-exp (a separate measurement)")
     ap.add_argument("--explicit-workspace", action="store_true",
                     help="time snapkv_compress_ws with a caller-provided workspace instead of snapkv_compress")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
@@ -103,8 +106,28 @@ def main() -> int:
         ws = torch.empty(snapkv.snapkv_workspace_bytes(w.L, w.Hq, w.Hkv, w.D, w.W), dtype=torch.uint8, device=dev)
     stream = torch.cuda.current_stream()
 
+    lses = None
+    if args.entry == "lse":
+        # inputs of that entry point: the rows' log-sum-exp, here from plain torch ops on the GPU
+        # (input preparation outside the timed region; the parity tests take it from the oracle)
+        lses = []
+        for q, k, v in layers:
+            g = w.Hq // w.Hkv
+            kk = k.float().repeat_interleave(g, dim=0)
+            s_ = torch.einsum("hwd,hld->hwl", q.float(), kk) / (w.D ** 0.5)
+            jj = torch.arange(w.L, device=dev)[None, None, :]
+            ii = torch.arange(w.W, device=dev)[None, :, None]
+            s_ = s_.masked_fill(jj > (w.L - w.W) + ii, float("-inf"))
+            lses.append(torch.logsumexp(s_.double(), dim=2).float().contiguous())
+            del kk, s_
+        torch.cuda.synchronize()
+
     def step(i):
         q, k, v = layers[i % nres]
+        if lses is not None:
+            snapkv.snapkv_compress_lse(q, k, v, lses[i % nres], w.pool_kind, w.p, w.C, out_k, out_v, out_idx,
+                                       stream=stream)
+            return
         snapkv.snapkv_compress(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx, stream=stream,
                                workspace=ws)
 
@@ -133,11 +156,11 @@ def main() -> int:
     achieved = scan_b / (score_ms * 1e-3) / 1e9 if score_ms > 0 else 0.0
     traffic = None
     t = MEASURED_TRAFFIC.get(w.name)
-    if t and score_names == [t["kernel"]]:
+    if t and score_names == [t["kernel"]] and args.entry == "compress":
         traffic = int((t["fetch_kib"] * t["fetch_scale"] + t["write_kib"] * t["write_scale"]) * 1024)
     roofline = {
         "bound": "hbm",
-        "kernel": "+".join(score_names),
+        "kernel": "+".join(score_names).replace("score_fused", "score_lse" if args.entry == "lse" else "score_fused"),
         "achieved": round(achieved, 1),
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
@@ -190,7 +213,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "L": w.L, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "W": w.W,
                    "pool": ("max" if w.pool_kind == 0 else "avg"), "p": w.p, "C": w.C,
-                   "step": "one layer call", "resident_layers": nres, "scheme": args.scheme,
+                   "step": "one layer call", "entry": args.entry, "resident_layers": nres, "scheme": args.scheme,
                    "token_layers_per_s": round(w.L / (ms_per_step * 1e-3), 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,
