@@ -124,7 +124,15 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
         stage_done(st, kStageFused);
         Gp.NV = G.g;
         Gp.VB = 1;
-    } else if (launch_score(dtype, D, q_win, k, G, ws, st) != hipSuccess) {
+    } else if (lse_plan(dtype, D, G, &F)) {
+        // two streaming passes over K with nothing handed between workgroups: the rows'
+        // log-sum-exp first, then the probabilities from it
+        if (launch_row_lse(dtype, D, q_win, k, G, F, ws.stat_part, ws.lse, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        if (launch_score_lse(dtype, D, q_win, k, ws.lse, G, F, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        stage_done(st, kStagePass2);
+        Gp.NV = G.g;
+        Gp.VB = 1;
+    } else if (launch_score(dtype, D, q_win, k, G, ws, st) != hipSuccess) {   // more window rows than a wave tracks
         return SNAPKV_ERR_HIP;
     }
     if (Gv) *Gv = Gp;

@@ -732,11 +732,12 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <typename T, int D, int RUW, int KT, int NW>
+template <typename T, int D, int RUW, int KT, int NW, bool STAT>
 __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv,
                                                      const void* __restrict__ kv,
                                                      const float* __restrict__ lse,
-                                                     float* __restrict__ vote, const ScoreGeom G,
+                                                     float* __restrict__ vote,
+                                                     float2* __restrict__ stat_part, const ScoreGeom G,
                                                      const FusedGeom F) {
     constexpr int R = RUW * 16;
     constexpr int NT = NW * 64;
@@ -749,6 +750,7 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
     static_assert(R <= NT, "one thread per window row stages its log-sum-exp");
     extern __shared__ uint4 qbuf[];      // [2][QCH][64]: Q blocks of two consecutive units
     __shared__ __attribute__((aligned(16))) float sm_lse[2][R];   // base-2 log-sum-exp per row, +inf for padding rows
+    __shared__ __attribute__((aligned(16))) float2 sm_stat[2][STAT ? NW : 1][R];   // STAT: per wave (row max, row sum-exp)
 
     const int tid = threadIdx.x, lane = tid & 63, n16 = lane & 15, kg = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -796,7 +798,7 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
     for (int t = 0; t < KT; ++t) load_frag16p<T, D>(kf[t], kp[t]);
 #pragma unroll
     for (int x = 0; x < QPW; ++x) qland[x] = *reinterpret_cast<const uint4*>(qp[x]);
-    lland = *lp;
+    lland = STAT ? 0.f : *lp;
 #pragma unroll
     for (int x = 0; x < QPW; ++x)
         if (w + x * NW < QCH) qbuf[(w + x * NW) * 64 + lane] = qland[x];
@@ -857,13 +859,15 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
                 qp[x] += qstep;
                 qland[x] = *reinterpret_cast<const uint4*>(qp[x]);
             }
-            lp += lstep;
-            lland = *lp;
+            if constexpr (!STAT) {
+                lp += lstep;
+                lland = *lp;
+            }
         }
         __builtin_amdgcn_sched_barrier(0);
         SNAPKV_LSE_ISSUE(kNext1, issue_tiles(ICLA{}, ICL{}, kstep));   // point 0
 
-        // probabilities: one exponential per logit, in the base-2 domain
+        // masked logits; then probabilities (one exponential per logit, base-2 domain) or row statistics
         if (special) {
             int jlane = tile0 * 16 + n16;
             asm volatile("" : "+v"(jlane));
@@ -880,19 +884,48 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
                     }
             }
         }
+        if constexpr (STAT) {
+            // row maxima and sums of exponentials of this wave's keys (base-2 domain), left in LDS
+            // for the merge over the waves after the barrier
 #pragma unroll
-        for (int ru = 0; ru < RUW; ++ru) {
-            const float4 l2 = *reinterpret_cast<const float4*>(&sm_lse[it & 1][ru * 16 + kg * 4]);
-            const float l[4] = {l2.x, l2.y, l2.z, l2.w};
+            for (int ru = 0; ru < RUW; ++ru) {
+                float mref[4], zs[4];
 #pragma unroll
-            for (int t = 0; t < KT; ++t)
+                for (int r = 0; r < 4; ++r) {
+                    float m = -INFINITY;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) e[ru][t][r] = __builtin_amdgcn_exp2f(fmaf(e[ru][t][r], G.c2, -l[r]));
+                    for (int t = 0; t < KT; ++t) m = fmaxf(m, e[ru][t][r]);
+                    mref[r] = row16_max(m) * G.c2;
+                }
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const float ref = mref[r] == -INFINITY ? 0.f : mref[r];
+                    float z = 0.f;
+#pragma unroll
+                    for (int t = 0; t < KT; ++t) z += __builtin_amdgcn_exp2f(fmaf(e[ru][t][r], G.c2, -ref));
+                    zs[r] = row16_sum(z);
+                }
+                if (n16 == 0) {
+                    float4* dst = reinterpret_cast<float4*>(&sm_stat[it & 1][w][ru * 16 + kg * 4]);
+                    dst[0] = make_float4(mref[0], zs[0], mref[1], zs[1]);
+                    dst[1] = make_float4(mref[2], zs[2], mref[3], zs[3]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int ru = 0; ru < RUW; ++ru) {
+                const float4 l2 = *reinterpret_cast<const float4*>(&sm_lse[it & 1][ru * 16 + kg * 4]);
+                const float l[4] = {l2.x, l2.y, l2.z, l2.w};
+#pragma unroll
+                for (int t = 0; t < KT; ++t)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) e[ru][t][r] = __builtin_amdgcn_exp2f(fmaf(e[ru][t][r], G.c2, -l[r]));
+            }
         }
         SNAPKV_LSE_ISSUE(kNext1, issue_tiles(ICL{}, ICUA{}, kstep));   // point 1
 
         // votes: sum over the window rows of each query head, then over the four lanes of a column
-        {
+        if constexpr (!STAT) {
             float* vb = vote + (int64_t)unit * F.gs * G.n;
             int jst = tile0 * 16 + n16;
             asm volatile("" : "+v"(jst));
@@ -949,9 +982,35 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
 #pragma unroll
             for (int x = 0; x < QPW; ++x)
                 if (w + x * NW < QCH) qbuf[(((it + 1) & 1) * QCH + w + x * NW) * 64 + lane] = qland[x];
-            if (tid < R) sm_lse[(it + 1) & 1][tid] = lreal ? lland * kLog2e : INFINITY;
+            if (!STAT && tid < R) sm_lse[(it + 1) & 1][tid] = lreal ? lland * kLog2e : INFINITY;
         }
         lds_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (STAT) {
+            if (tid >= NT - R) {   // the last R threads merge the waves (fixed trees) and store the slice's pair
+                const int row = tid - (NT - R);
+                float2 x[NW];
+                float mm[NW], zz[NW];
+#pragma unroll
+                for (int w2 = 0; w2 < NW; ++w2) {
+                    x[w2] = sm_stat[it & 1][w2][row];
+                    mm[w2] = x[w2].x;
+                }
+#pragma unroll
+                for (int d = 1; d < NW; d <<= 1)
+#pragma unroll
+                    for (int w2 = 0; w2 + d < NW; w2 += 2 * d) mm[w2] = fmaxf(mm[w2], mm[w2 + d]);
+                const float m = mm[0];
+#pragma unroll
+                for (int w2 = 0; w2 < NW; ++w2)
+                    zz[w2] = x[w2].x == -INFINITY ? 0.f : x[w2].y * __builtin_amdgcn_exp2f(x[w2].x - m);
+#pragma unroll
+                for (int d = 1; d < NW; d <<= 1)
+#pragma unroll
+                    for (int w2 = 0; w2 + d < NW; w2 += 2 * d) zz[w2] += zz[w2 + d];
+                stat_part[((int64_t)unit * F.Gg + wg) * R + row] = make_float2(m, zz[0]);
+            }
+        }
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (kNext1) mfma_tiles(IC0{}, ICL{}, (it + 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
@@ -988,7 +1047,7 @@ constexpr int kFusedWaves = 8;          // waves per workgroup (two per SIMD): m
 
 // Device-independent part of the plan: how the rows and keys of a unit map onto a workgroup of
 // NW waves.  Returns false when the window rows of a KV head exceed what one wave tracks.
-static bool fused_shape_nw(const ScoreGeom& G, int NW, int split, FusedGeom* F) {
+static bool fused_shape_nw(const ScoreGeom& G, int NW, int split, FusedGeom* F, bool capped = true) {
     if (split < 1 || G.g % split != 0) return false;
     const int UH = (G.W + 15) / 16;
     const int gs = G.g / split;          // query heads per unit
@@ -1000,7 +1059,8 @@ static bool fused_shape_nw(const ScoreGeom& G, int NW, int split, FusedGeom* F) 
     const int64_t ntiles = (G.L + 15) / 16;
     const int64_t per_wg = (int64_t)NW * KT;
     const int64_t Gg = (ntiles + per_wg - 1) / per_wg;
-    if (Gg > 32 * kL1BlocksPadded) return false;   // level-1 merge blocks per row are capped
+    if (capped && Gg > 32 * kL1BlocksPadded) return false;   // level-1 merge blocks per row are capped
+    if (Gg > (1 << 20)) return false;
     F->RU = RU;
     F->UH = UH;
     F->RUW = RUW;
@@ -1177,7 +1237,34 @@ hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, co
     return fused_dispatch(dtype, D, F.NW, F.RUW, &call, nullptr);
 }
 
-// ---- the variant with handed-in log-sum-exp
+// ---- the streaming kernel: probabilities from a given log-sum-exp, or the row statistics that give it
+// Per window row: merge the slices' (max, sum-exp) pairs (base-2 domain) in a fixed order and store
+// the row's natural log-sum-exp.  One workgroup per unit; 256 / R threads share a row.
+__global__ __launch_bounds__(256) void lse_from_parts(const float2* __restrict__ part, float* __restrict__ lse,
+                                                      const ScoreGeom G, const FusedGeom F) {
+    __shared__ float2 sh[256];
+    const int unit = blockIdx.x, tid = threadIdx.x;
+    const int R = F.RUW * 16, S = 256 / R;
+    const int row = tid % R, sub = tid / R;
+    float m = -INFINITY, z = 0.f;
+    if (sub < S)
+        for (int sl = sub; sl < F.Gg; sl += S) {
+            const float2 pc = part[((int64_t)unit * F.Gg + sl) * R + row];
+            merge_pair(m, z, pc.x, pc.y);
+        }
+    sh[tid] = make_float2(m, z);
+    __syncthreads();
+    if (sub == 0) {
+        for (int c = 1; c < S; ++c) {
+            const float2 pc = sh[c * R + row];
+            merge_pair(m, z, pc.x, pc.y);
+        }
+        const int ru = row >> 4, head = ru / F.UH, i = (ru % F.UH) * 16 + (row & 15);
+        if (ru < F.RU && head < F.gs && i < G.W)
+            lse[((int64_t)unit * F.gs + head) * G.W + i] = (m + log2f(z)) * 0.6931471805599453f;
+    }
+}
+
 struct LseCall {
     const void* q;
     const void* k;
@@ -1185,13 +1272,14 @@ struct LseCall {
     const ScoreGeom* G;
     const FusedGeom* F;
     float* vote;
+    float2* stat_part;
     hipStream_t st;
 };
 
-template <typename T, int D, int RUW, int NW>
+template <typename T, int D, int RUW, int NW, bool STAT>
 static hipError_t lse_instance(const LseCall* call, int* occ) {
     constexpr int KT = kFusedSlots / RUW;
-    auto kern = score_lse<T, D, RUW, KT, NW>;
+    auto kern = score_lse<T, D, RUW, KT, NW, STAT>;
     constexpr int kQBytes = 2 * RUW * (D * (std::is_same<T, bf16_k>::value ? 2 : 4) / 64) * 64 * 16;   // Q blocks of two units
     static int cached_occ = -1;
     if (cached_occ < 0) {
@@ -1207,44 +1295,48 @@ static hipError_t lse_instance(const LseCall* call, int* occ) {
     if (!call) return hipSuccess;
     const FusedGeom& F = *call->F;
     hipLaunchKernelGGL(kern, dim3(F.NG * F.Gg), dim3(NW * 64), kQBytes, call->st, call->q, call->k,
-                       call->lse, call->vote, *call->G, F);
+                       call->lse, call->vote, call->stat_part, *call->G, F);
     return hipGetLastError();
 }
 
-template <typename T, int D>
+template <typename T, int D, bool STAT>
 static hipError_t lse_by_rows(int RUW, const LseCall* call, int* occ) {
     switch (RUW) {
-        case 1: return lse_instance<T, D, 1, kFusedWaves>(call, occ);
-        case 2: return lse_instance<T, D, 2, kFusedWaves>(call, occ);
-        case 4: return lse_instance<T, D, 4, kFusedWaves>(call, occ);
-        case 8: return lse_instance<T, D, 8, kFusedWaves>(call, occ);
+        case 1: return lse_instance<T, D, 1, kFusedWaves, STAT>(call, occ);
+        case 2: return lse_instance<T, D, 2, kFusedWaves, STAT>(call, occ);
+        case 4: return lse_instance<T, D, 4, kFusedWaves, STAT>(call, occ);
+        case 8: return lse_instance<T, D, 8, kFusedWaves, STAT>(call, occ);
     }
     return hipErrorInvalidValue;
 }
 
+template <bool STAT>
 static hipError_t lse_dispatch(int dtype, int D, int RUW, const LseCall* call, int* occ) {
     if (dtype == 0) {
-        if (D == 128) return lse_by_rows<bf16_k, 128>(RUW, call, occ);
-        if (D == 64) return lse_by_rows<bf16_k, 64>(RUW, call, occ);
+        if (D == 128) return lse_by_rows<bf16_k, 128, STAT>(RUW, call, occ);
+        if (D == 64) return lse_by_rows<bf16_k, 64, STAT>(RUW, call, occ);
     } else {
-        if (D == 128) return lse_by_rows<f32_k, 128>(RUW, call, occ);
-        if (D == 64) return lse_by_rows<f32_k, 64>(RUW, call, occ);
+        if (D == 128) return lse_by_rows<f32_k, 128, STAT>(RUW, call, occ);
+        if (D == 64) return lse_by_rows<f32_k, 64, STAT>(RUW, call, occ);
     }
     return hipErrorInvalidValue;
 }
 
-// Launch plan of score_lse.  Nothing waits across workgroups, so residency is not a condition; the
-// grid is still sized to what is resident so that every workgroup streams from start to end.
+// Launch plan of the streaming kernel (both modes share it).  Nothing waits across workgroups, so
+// residency is not a condition and the prompt length is not limited by the chip; the grid is still
+// sized to what is resident so that every workgroup streams from start to end.
 bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
     int cand[8];
     const int nc = fused_split_candidates(G, cand);
     for (int c = 0; c < nc; ++c) {
-        if (!fused_shape_nw(G, kFusedWaves, cand[c], F)) continue;
-        int occ = 0;
-        if (lse_dispatch(dtype, D, F->RUW, nullptr, &occ) != hipSuccess) {
+        if (!fused_shape_nw(G, kFusedWaves, cand[c], F, false)) continue;
+        int occ = 0, occ2 = 0;
+        if (lse_dispatch<false>(dtype, D, F->RUW, nullptr, &occ) != hipSuccess ||
+            lse_dispatch<true>(dtype, D, F->RUW, nullptr, &occ2) != hipSuccess) {
             (void)hipGetLastError();
             continue;
         }
+        if (occ2 < occ) occ = occ2;
         const int64_t slots = (int64_t)cu_count() * occ;
         if (slots <= 0) continue;
         int64_t NG = slots / F->Gg;
@@ -1258,11 +1350,38 @@ bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
     return false;
 }
 
+// Bytes of per-slice row statistics that cover whichever split lse_plan ends up choosing.
+size_t stream_stat_bytes(const ScoreGeom& G) {
+    int cand[8];
+    const int nc = fused_split_candidates(G, cand);
+    size_t most = 0;
+    for (int i = 0; i < nc; ++i) {
+        FusedGeom F;
+        if (!fused_shape_nw(G, kFusedWaves, cand[i], &F, false)) continue;
+        const size_t b = sizeof(float2) * (size_t)F.units * F.Gg * F.RUW * 16;
+        most = b > most ? b : most;
+    }
+    return (most + 255) & ~(size_t)255;
+}
+
 hipError_t launch_score_lse(int dtype, int D, const void* q, const void* k, const float* lse,
                             const ScoreGeom& G, const FusedGeom& F, float* vote, hipStream_t st) {
     if (G.n <= 0) return hipSuccess;
-    const LseCall call{q, k, lse, &G, &F, vote, st};
-    return lse_dispatch(dtype, D, F.RUW, &call, nullptr);
+    const LseCall call{q, k, lse, &G, &F, vote, nullptr, st};
+    return lse_dispatch<false>(dtype, D, F.RUW, &call, nullptr);
+}
+
+// The rows' log-sum-exp by one streaming pass over K and a small merge.
+hipError_t launch_row_lse(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
+                          const FusedGeom& F, float2* stat_part, float* lse_out, hipStream_t st) {
+    if (G.n <= 0) return hipSuccess;
+    const LseCall call{q, k, nullptr, &G, &F, nullptr, stat_part, st};
+    hipError_t e = lse_dispatch<true>(dtype, D, F.RUW, &call, nullptr);
+    if (e != hipSuccess) return e;
+    stage_done(st, kStagePass1);
+    hipLaunchKernelGGL(lse_from_parts, dim3(F.units), dim3(256), 0, st, stat_part, lse_out, G, F);
+    stage_done(st, kStageReduce);
+    return hipGetLastError();
 }
 
 }  // namespace snapkv

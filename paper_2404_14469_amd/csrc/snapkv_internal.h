@@ -75,6 +75,8 @@ struct Workspace {
     float* vote;     // [Hkv][NV][n]  (two-pass path) or [Hkv][g][n] (single-read path)
     float* score;    // [Hkv][n]
     char* fused;     // hand-off buffers of the single-read path (see fused_sync_layout)
+    float2* stat_part;   // [units][Gg][R] per-slice (row max, row sum-exp) of the streaming statistics pass
+    float* lse;          // [Hq][W] the window rows' log-sum-exp computed from them
     SelectScratch sel;
 };
 
@@ -108,6 +110,9 @@ int64_t fused_sync_pairs(const FusedGeom& F);
 bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
 hipError_t launch_score_lse(int dtype, int D, const void* q, const void* k, const float* lse,
                             const ScoreGeom& G, const FusedGeom& F, float* vote, hipStream_t st);
+size_t stream_stat_bytes(const ScoreGeom& G);
+hipError_t launch_row_lse(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
+                          const FusedGeom& F, float2* stat_part, float* lse_out, hipStream_t st);
 // Pooling and selection in one cooperative launch (reads votes, writes the kept positions).
 // pool_select_ok says whether the shape fits and the grid can be resident on the current device.
 bool pool_select_ok(const ScoreGeom& G, int pool_kind, int p, int64_t kcount);

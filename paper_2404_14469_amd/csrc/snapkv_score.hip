@@ -305,16 +305,20 @@ size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base) {
     const size_t vote = align_up(sizeof(float) * (size_t)G.Hkv * G.NV * (size_t)(G.n > 0 ? G.n : 1));
     const size_t score = align_up(sizeof(float) * (size_t)G.Hkv * (size_t)(G.n > 0 ? G.n : 1));
     const size_t fused = fused_sync_bytes(G);
+    const size_t stat = stream_stat_bytes(G);
+    const size_t lse = align_up(sizeof(float) * (size_t)G.Hkv * G.g * G.W);
     if (ws) {
         ws->part = reinterpret_cast<float2*>(b + off);
         ws->mz = reinterpret_cast<float2*>(b + off + part);
         ws->vote = reinterpret_cast<float*>(b + off + part + mz);
         ws->score = reinterpret_cast<float*>(b + off + part + mz + vote);
         ws->fused = b + off + part + mz + vote + score;
+        ws->stat_part = reinterpret_cast<float2*>(b + off + part + mz + vote + score + fused);
+        ws->lse = reinterpret_cast<float*>(b + off + part + mz + vote + score + fused + stat);
     }
     const size_t sel = select_layout(G.Hkv, G.n, ws ? &ws->sel : nullptr,
-                                     ws ? b + off + part + mz + vote + score + fused : nullptr);
-    return part + mz + vote + score + fused + sel;
+                                     ws ? b + off + part + mz + vote + score + fused + stat + lse : nullptr);
+    return part + mz + vote + score + fused + stat + lse + sel;
 }
 
 template <typename T, int D>

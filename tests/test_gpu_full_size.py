@@ -53,14 +53,25 @@ def test_varlen_batch(snapkv):
         _run(snapkv, w, 0, [i % w.Hkv, (i + 3) % w.Hkv])
 
 
-def test_two_pass_scheme_at_full_size(snapkv):
-    # the kernels that take over when a prompt's logits exceed the register files
+def test_two_streaming_passes_at_full_size(snapkv):
+    # the path that takes over when a prompt's logits exceed the register files or the grid cannot be resident
     snapkv.snapkv_set_scoring_scheme(1)
     try:
         _run(snapkv, workloads.LLAMA2_7B_16K, 1, [0, 17])
         _run(snapkv, workloads.MISTRAL_7B_GQA_32K, 2, [3])
     finally:
         snapkv.snapkv_set_scoring_scheme(0)
+
+
+def test_prompt_longer_than_the_single_read_kernel_holds(snapkv):
+    # L = 200000: one head's logits no longer fit the chip's registers, so scoring takes two streaming
+    # passes (row log-sum-exp, then probabilities); nothing about the result may change
+    w = workloads.LONG_131K.with_(name="long_200k", L=200000, Hq=4, Hkv=4, C=2048, clusters=(16, 16), seed=77)
+    case, res = _run(snapkv, w, 0, [0, 3])
+    idx = res[3]
+    for hk, pos in enumerate(case["needle_pos"]):
+        lo, hi = max(0, pos - w.p // 2), min(w.n - 1, pos + w.p // 2)
+        assert set(range(lo, hi + 1)) <= set(idx[hk].tolist())
 
 
 def test_lse_entry_at_full_size(snapkv):
