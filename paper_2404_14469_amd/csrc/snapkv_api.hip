@@ -185,15 +185,21 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     CleanJob clean;
     DeviceScratch* mine = nullptr;      // the library's own buffer: its state is tracked between calls
     uint64_t key = 0;
+    bool streaming = false;
     if (g_allow_pool_select && pool_select_ok(G, pool_kind, p, C - W)) {   // pooling and selection in one launch
         bool prepared = false;
         FusedGeom Fp;
-        if (own_scratch && (lse ? lse_plan(dtype, D, G, &Fp) : (g_allow_fused && fused_plan(dtype, D, G, &Fp)))) {
+        // which scoring path run_scores will take: 1 single-read (uses the hand-off words), 2 streaming
+        // passes (does not touch them), 0 the 32x32 two-pass kernels (state not tracked)
+        const int path = lse ? (lse_plan(dtype, D, G, &Fp) ? 2 : 0)
+                             : (g_allow_fused && fused_plan(dtype, D, G, &Fp)) ? 1 : (lse_plan(dtype, D, G, &Fp) ? 2 : 0);
+        streaming = path == 2;
+        if (own_scratch && path != 0) {
             int dev = 0;
             if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
                 key = 0x9E3779B97F4A7C15ull ^ ((uint64_t)L * 1000003ull) ^ ((uint64_t)Hq << 50) ^ ((uint64_t)Hkv << 40) ^
                       ((uint64_t)D << 32) ^ ((uint64_t)W << 20) ^ ((uint64_t)dtype << 19);
-                if (lse) key ^= 0x5555ull;   // that path leaves only the counters ready, not the hand-off words
+                if (streaming) key ^= 0x5555ull;   // that path leaves only the counters ready, not the hand-off words
                 mine = &g_scratch[dev];
                 prepared = was_clean == key;
             }
@@ -218,7 +224,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     stage_done(st, kStageSelect);
     if (launch_gather(k, v, out_idx, Hkv, L, C, C, row_bytes, out_k, out_v, clean, st) != hipSuccess)
         return SNAPKV_ERR_HIP;
-    if (mine && (clean.ones || lse) && clean.zeros) {
+    if (mine && (clean.ones || streaming) && clean.zeros) {
         std::lock_guard<std::mutex> lock(g_mu);
         mine->clean_key = key;
     }

@@ -1239,12 +1239,12 @@ hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, co
 
 // ---- the streaming kernel: probabilities from a given log-sum-exp, or the row statistics that give it
 // Per window row: merge the slices' (max, sum-exp) pairs (base-2 domain) in a fixed order and store
-// the row's natural log-sum-exp.  One workgroup per unit; 256 / R threads share a row.
-__global__ __launch_bounds__(256) void lse_from_parts(const float2* __restrict__ part, float* __restrict__ lse,
+// the row's natural log-sum-exp.  One workgroup per unit; 1024 / R threads share a row.
+__global__ __launch_bounds__(1024) void lse_from_parts(const float2* __restrict__ part, float* __restrict__ lse,
                                                       const ScoreGeom G, const FusedGeom F) {
-    __shared__ float2 sh[256];
+    __shared__ float2 sh[1024];
     const int unit = blockIdx.x, tid = threadIdx.x;
-    const int R = F.RUW * 16, S = 256 / R;
+    const int R = F.RUW * 16, S = 1024 / R;
     const int row = tid % R, sub = tid / R;
     float m = -INFINITY, z = 0.f;
     if (sub < S)
@@ -1379,7 +1379,7 @@ hipError_t launch_row_lse(int dtype, int D, const void* q, const void* k, const 
     hipError_t e = lse_dispatch<true>(dtype, D, F.RUW, &call, nullptr);
     if (e != hipSuccess) return e;
     stage_done(st, kStagePass1);
-    hipLaunchKernelGGL(lse_from_parts, dim3(F.units), dim3(256), 0, st, stat_part, lse_out, G, F);
+    hipLaunchKernelGGL(lse_from_parts, dim3(F.units), dim3(1024), 0, st, stat_part, lse_out, G, F);
     stage_done(st, kStageReduce);
     return hipGetLastError();
 }
