@@ -333,14 +333,12 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         }
     };
     auto issue_tiles = [&](auto T0, auto T1, const int64_t step) {
-#ifndef SNAPKV_EXP_NOLOAD
         constexpr int t0 = decltype(T0)::value, t1 = decltype(T1)::value;
 #pragma unroll
         for (int t = t0; t < t1; ++t) {
             kp[t] += step;
             load_frag16p<T, D>(kf[t], kp[t]);
         }
-#endif
     };
     using IC0 = std::integral_constant<int, 0>;
     using ICL = std::integral_constant<int, KL>;
@@ -363,13 +361,11 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     // point 0 comes a quarter of an iteration later (their second half, by then for the next
     // unit), points 1 and 2 re-request the halves of the upper tiles for the next unit.
     auto issue_q = [&]() {
-#ifndef SNAPKV_EXP_NOLOAD
 #pragma unroll
         for (int x = 0; x < QPW; ++x) {
             qp[x] += qstep;
             qland[x] = *reinterpret_cast<const uint4*>(qp[x]);
         }
-#endif
     };
 #define SNAPKV_ISSUE(cond_, what_)                                           \
     do {                                                                     \
@@ -440,11 +436,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         TRACE(1);
 
         float mref[RUW][4], zs[RUW][4];
-#ifdef SNAPKV_EXP_NOD
-        if (false) {
-#else
         if (has_p1) {
-#endif
             // ---- D. slice row maxima over this wave's keys (raw logits; scale is positive)
 #pragma unroll
             for (int ru = 0; ru < RUW; ++ru)
@@ -484,11 +476,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                 for (int r = 0; r < 4; ++r) mref[ru][r] = row16_max(mref[ru][r]) * G.c2;   // base-2 domain
         }
         SNAPKV_ISSUE(kNext1, issue_tiles(ICLA{}, ICL{}, kstep));   // point 0
-#ifdef SNAPKV_EXP_NOD
-        if (false) {
-#else
         if (has_p1) {
-#endif
             // exponentials relative to the wave's own row maxima, and their row sums
 #pragma unroll
             for (int ru = 0; ru < RUW; ++ru)
@@ -508,11 +496,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         TRACE(10);
         // ---- E. step P2 of the unit two back: level-1 words of a row sit in 16 neighbouring
         // lanes; merge them in a fixed tree into (max, 1/sum)
-#ifdef SNAPKV_EXP_NOP2
-        if (false) {
-#else
         if (has_p2) {
-#endif
 #pragma unroll
             for (int x = 0; x < L2PT; ++x) {
                 const int idx = tid + x * NT;
@@ -577,11 +561,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         TRACE(4);
 
         // ---- F. step L1 of the previous unit: merge 32 slices of one row per half-wave
-#ifdef SNAPKV_EXP_NOE
-        if (false) {
-#else
         if (has_l1) {
-#endif
             for (int task = task0; task < real_tasks; task += 2 * NW * F.Gg) {
                 int row = l1_row, blk = l1_blk;
                 float m = -INFINITY, z = 0.f;
@@ -607,11 +587,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         }
         SNAPKV_ISSUE(kNext1, issue_tiles(ICUA{}, ICT{}, kstep));   // point 2
         TRACE(5);
-#ifdef SNAPKV_EXP_NOP2
-        if (false) {
-#else
         if (has_p2) {
-#endif
             lds_await_all<NW>(sm_flag[2], it + 1, F.spin_limit, gave_up);
             float f[RUW][4];
 #pragma unroll
@@ -627,11 +603,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
             float* vb = vote + (int64_t)unit_p2 * F.gs * G.n;
             int jst = tile0 * 16 + n16;       // opaque for the same reason as above
             asm volatile("" : "+v"(jst));
-#ifdef SNAPKV_EXP_NOVOTE
-            const int nst = (int)G.n - (int)G.L;   // timing experiment: no lane stores its votes
-#else
             const int nst = (int)G.n;
-#endif
             float v[KT];
 #pragma unroll
             for (int t = 0; t < KT; ++t) v[t] = 0.f;

@@ -58,14 +58,13 @@ struct SelectScratch {
     unsigned* chunk_gt;    // [H][chunks] positions in bins above the threshold bin
     unsigned* chunk_off;   // [H][chunks][2] output offsets: (#greater, #equal) before the chunk
     uint2* cand;           // [H][n]      (pattern, position) of positions inside the threshold bin, by chunk
-    // scratch of the cooperative pooling + selection kernel (pool_select); the first three arrays
-    // are contiguous and must be zero when the kernel starts (ps_zero_words words from ps_arrive)
+    // scratch of the cooperative pooling + selection kernel (pool_select), which keeps its candidates
+    // in `cand` above; the first two arrays are contiguous and must be zero when the kernel starts
+    // (ps_zero_words words from ps_arrive)
     unsigned* ps_arrive;   // [H][8]        arrival counters of the group-wide rendezvous points
-    unsigned* ps_cand_n;   // [H]           entries in the head's candidate list
     unsigned* ps_hist;     // [H][3][2048]  digit histograms, one per refinement level
     unsigned* ps_range;    // [H][512][2]   per-workgroup (smallest, largest) score bit pattern
     unsigned* ps_part;     // [H][512][2]   per-workgroup (#above the threshold bin, #inside it)
-    uint2* ps_cand;        // [H][4096]     (pattern, position) of positions inside the threshold bin
     int64_t ps_zero_words;
 };
 

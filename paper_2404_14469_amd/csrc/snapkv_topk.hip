@@ -1028,9 +1028,8 @@ size_t select_layout(int H, int64_t n, SelectScratch* S, void* base) {
     const size_t cgt = up256(sizeof(unsigned) * (size_t)H * nch);
     const size_t coff = up256(sizeof(unsigned) * 2 * (size_t)H * nch);
     const size_t cand = up256(sizeof(uint2) * (size_t)H * nn);
-    const size_t ps_zero = up256(sizeof(unsigned) * (size_t)H * (kPsStages + 1 + kPsLevels * kPsBins));
+    const size_t ps_zero = up256(sizeof(unsigned) * (size_t)H * (kPsStages + kPsLevels * kPsBins));
     const size_t ps_range = up256(sizeof(unsigned) * 2 * (size_t)H * kPsMaxGroup);
-    const size_t ps_cand = up256(sizeof(uint2) * (size_t)H * kPsCandCap);
     if (S) {
         char* b = static_cast<char*>(base);
         S->minmax = reinterpret_cast<unsigned*>(b);
@@ -1042,14 +1041,12 @@ size_t select_layout(int H, int64_t n, SelectScratch* S, void* base) {
         S->cand = reinterpret_cast<uint2*>(b + minmax + hist + count + info + cgt + coff);
         char* q = b + minmax + hist + count + info + cgt + coff + cand;
         S->ps_arrive = reinterpret_cast<unsigned*>(q);
-        S->ps_cand_n = S->ps_arrive + (size_t)H * kPsStages;
-        S->ps_hist = S->ps_cand_n + H;
-        S->ps_zero_words = (int64_t)H * (kPsStages + 1 + kPsLevels * kPsBins);
+        S->ps_hist = S->ps_arrive + (size_t)H * kPsStages;
+        S->ps_zero_words = (int64_t)H * (kPsStages + kPsLevels * kPsBins);
         S->ps_range = reinterpret_cast<unsigned*>(q + ps_zero);
         S->ps_part = reinterpret_cast<unsigned*>(q + ps_zero + ps_range);
-        S->ps_cand = reinterpret_cast<uint2*>(q + ps_zero + 2 * ps_range);
     }
-    return minmax + hist + count + info + cgt + coff + cand + ps_zero + 2 * ps_range + ps_cand;
+    return minmax + hist + count + info + cgt + coff + cand + ps_zero + 2 * ps_range;
 }
 
 bool select_chunked_ok(int64_t n) { return (n + kSelChunk - 1) / kSelChunk <= kSelMaxChunks; }
