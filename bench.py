@@ -58,6 +58,8 @@ def main() -> int:
     ap.add_argument("--entry", default="compress", choices=["compress", "lse"],
                     help="compress (default): snapkv_compress, the headline path; lse: snapkv_compress_lse, "
                          "the variant that is handed the window rows' log-sum-exp (a separate measurement)")
+    ap.add_argument("--layout", default="head_major", choices=["head_major", "token_major"],
+                    help="storage order of K/V: [Hkv, L, D] (default) or [L, Hkv, D] through snapkv_compress_strided")
     ap.add_argument("--explicit-workspace", action="store_true",
                     help="time snapkv_compress_ws with a caller-provided workspace instead of snapkv_compress")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
@@ -96,6 +98,9 @@ def main() -> int:
     layers = []
     for l in range(nres):
         c = workloads.generate(w, layer=l, device=dev)
+        if args.layout == "token_major":
+            c["k"] = c["k"].permute(1, 0, 2).contiguous().permute(1, 0, 2)
+            c["v"] = c["v"].permute(1, 0, 2).contiguous().permute(1, 0, 2)
         layers.append((c["q_win"], c["k"], c["v"]))
     torch.cuda.synchronize()
     out_k = torch.empty((w.Hkv, w.C, w.D), dtype=layers[0][1].dtype, device=dev)
@@ -124,6 +129,9 @@ def main() -> int:
 
     def step(i):
         q, k, v = layers[i % nres]
+        if args.layout == "token_major":
+            snapkv.snapkv_compress_strided(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx, stream=stream)
+            return
         if lses is not None:
             snapkv.snapkv_compress_lse(q, k, v, lses[i % nres], w.pool_kind, w.p, w.C, out_k, out_v, out_idx,
                                        stream=stream)
@@ -213,7 +221,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "L": w.L, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "W": w.W,
                    "pool": ("max" if w.pool_kind == 0 else "avg"), "p": w.p, "C": w.C,
-                   "step": "one layer call", "entry": args.entry, "resident_layers": nres, "scheme": args.scheme,
+                   "step": "one layer call", "entry": args.entry, "layout": args.layout, "resident_layers": nres, "scheme": args.scheme,
                    "token_layers_per_s": round(w.L / (ms_per_step * 1e-3), 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -132,6 +132,21 @@ int snapkv_pooled_scores_lse(int dtype, const void* q_win, const void* k, const 
                              void* stream);
 
 /*
+ * snapkv_compress / snapkv_compress_f32 for K and V that are not laid out [Hkv, L, D] contiguously,
+ * e.g. the token-major [L, Hkv, D] caches of attention libraries (Listing 1 indexes the tensors by
+ * (head, position), whatever their storage order).  Row r of KV head h of k starts
+ * k_head_stride * h + k_row_stride * r ELEMENTS after `k` (likewise v); the D elements of a row are
+ * contiguous.  Strides must keep every row 16-byte aligned (multiples of 8 bf16 / 4 float32 elements),
+ * k_row_stride and v_row_stride are at least D, and distinct (head, row) pairs must not overlap.
+ * q_win, out_k, out_v and out_idx are contiguous as for snapkv_compress; `dtype` is SNAPKV_DTYPE_*.
+ * Scratch comes from the library's per-device buffer.
+ */
+int64_t snapkv_compress_strided(int dtype, const void* q_win, const void* k, const void* v, int64_t L, int Hq,
+                                int Hkv, int D, int W, int64_t k_head_stride, int64_t k_row_stride,
+                                int64_t v_head_stride, int64_t v_row_stride, int pool_kind, int p, int64_t C,
+                                void* out_k, void* out_v, int32_t* out_idx, void* stream);
+
+/*
  * Top-(kcount) selection alone (Eq. 2), exposed for testing the selector on arbitrary scores:
  *   scores [H, n] device float32, all values >= +0 (their bit patterns are compared as unsigned
  *   integers); out_idx [H, kcount] device int32: the kcount best positions per row under

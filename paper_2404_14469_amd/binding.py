@@ -22,7 +22,8 @@ SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compr
            "snapkv_pooled_scores", "snapkv_pooled_scores_f32", "snapkv_workspace_bytes",
            "snapkv_compress_ws", "snapkv_select_topk", "snapkv_release", "snapkv_profile_start",
            "snapkv_profile_stop", "snapkv_num_stages", "snapkv_stage_name", "snapkv_set_scoring_scheme",
-           "snapkv_sync_timeouts", "snapkv_compress_lse", "snapkv_pooled_scores_lse")
+           "snapkv_sync_timeouts", "snapkv_compress_lse", "snapkv_pooled_scores_lse",
+           "snapkv_compress_strided")
 
 _lib = None
 
@@ -60,6 +61,9 @@ def load():
     L.snapkv_compress_lse.argtypes = [i32, vp, vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
     L.snapkv_pooled_scores_lse.restype = i32
     L.snapkv_pooled_scores_lse.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, vp, vp]
+    L.snapkv_compress_strided.restype = i64
+    L.snapkv_compress_strided.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, i32, i64, i64, i64, i64, i32, i32,
+                                          i64, vp, vp, vp, vp]
     L.snapkv_workspace_bytes.restype = sz
     L.snapkv_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
     L.snapkv_compress_ws.restype = i64
@@ -188,6 +192,32 @@ def snapkv_compress(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, pool_
                                              workspace.numel(), _stream(stream)))
     fn = lib.snapkv_compress if code == DTYPE_BF16 else lib.snapkv_compress_f32
     return _check(fn(*ptrs, L, Hq, Hkv, D, W, pool_kind, p, C, *outs, _stream(stream)))
+
+
+def snapkv_compress_strided(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, pool_kind: int, p: int,
+                            C: int, out_k: torch.Tensor, out_v: torch.Tensor, out_idx: torch.Tensor,
+                            stream=None) -> int:
+    """snapkv_compress for k/v given as [Hkv, L, D] *views* of any storage order with contiguous rows
+    (e.g. kv_token_major.permute(1, 0, 2)); the strides of dims 0 and 1 are passed on as they are."""
+    lib = load()
+    Hq, Hkv, L, D, W = _shapes(q_win, k)
+    code = _dtype_code(k)
+    if v.shape != k.shape or v.dtype != k.dtype:
+        raise ValueError("k and v must have the same shape and dtype")
+    for t, name in ((k, "k"), (v, "v")):
+        if not t.is_cuda:
+            raise ValueError(f"{name} must be a GPU tensor")
+        if t.stride(2) != 1:
+            raise ValueError(f"the rows of {name} must be contiguous")
+    if tuple(out_k.shape) != (Hkv, C, D) or tuple(out_v.shape) != (Hkv, C, D):
+        raise ValueError("out_k/out_v must be [Hkv, C, D]")
+    if tuple(out_idx.shape) != (Hkv, C):
+        raise ValueError("out_idx must be [Hkv, C]")
+    return _check(lib.snapkv_compress_strided(
+        code, _dev(q_win, "q_win", k.dtype), k.data_ptr(), v.data_ptr(), L, Hq, Hkv, D, W,
+        k.stride(0), k.stride(1), v.stride(0), v.stride(1), pool_kind, p, C,
+        _dev(out_k, "out_k", k.dtype), _dev(out_v, "out_v", k.dtype), _dev(out_idx, "out_idx", torch.int32),
+        _stream(stream)))
 
 
 def _lse_ptr(lse: torch.Tensor, Hq: int, W: int) -> int:

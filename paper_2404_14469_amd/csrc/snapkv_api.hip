@@ -145,7 +145,8 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
 int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v, int64_t L, int Hq,
                       int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k,
                       void* out_v, int32_t* out_idx, void* workspace, size_t workspace_bytes,
-                      bool own_scratch, void* stream, const float* lse = nullptr, bool with_lse = false) {
+                      bool own_scratch, void* stream, const float* lse = nullptr, bool with_lse = false,
+                      const RowLayout* k_layout = nullptr, const RowLayout* v_layout = nullptr) {
     if (dtype != SNAPKV_DTYPE_BF16 && dtype != SNAPKV_DTYPE_F32) return SNAPKV_ERR_INVALID_ARG;
     if (with_lse && !lse) return SNAPKV_ERR_INVALID_ARG;
     if (with_lse && (reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
@@ -158,15 +159,24 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     if ((reinterpret_cast<uintptr_t>(out_idx) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int row_bytes = D * (dtype == SNAPKV_DTYPE_BF16 ? 2 : 4);
+    // byte strides of K and V: contiguous [Hkv, L, D] unless the caller says otherwise
+    const RowLayout contiguous{(int64_t)L * row_bytes, (int64_t)row_bytes};
+    const RowLayout kl = k_layout ? *k_layout : contiguous, vl = v_layout ? *v_layout : contiguous;
+    for (const RowLayout* x : {&kl, &vl}) {
+        if (x->row_stride < row_bytes || x->head_stride < 0) return SNAPKV_ERR_INVALID_ARG;
+        if (((x->row_stride | x->head_stride) & 15) != 0) return SNAPKV_ERR_MISALIGNED;
+    }
 
     if (L <= C) {   // Listing 1, first branch: the prompt already fits
         if (launch_iota(Hkv, L, C, out_idx, st) != hipSuccess) return SNAPKV_ERR_HIP;
-        if (launch_gather(k, v, out_idx, Hkv, L, L, C, row_bytes, out_k, out_v, CleanJob{}, st) != hipSuccess)
+        if (launch_gather(k, v, out_idx, Hkv, L, L, C, row_bytes, out_k, out_v, kl, vl, CleanJob{}, st) != hipSuccess)
             return SNAPKV_ERR_HIP;
         return L;
     }
 
-    const ScoreGeom G = make_geom(L, Hq, Hkv, D, W);
+    ScoreGeom G = make_geom(L, Hq, Hkv, D, W);
+    G.k_hs = kl.head_stride;
+    G.k_rs = kl.row_stride;
     const size_t need = workspace_layout(G, nullptr, nullptr);
     void* base = workspace;
     uint64_t was_clean = 0;
@@ -222,7 +232,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     }
     if (se != hipSuccess) return SNAPKV_ERR_HIP;
     stage_done(st, kStageSelect);
-    if (launch_gather(k, v, out_idx, Hkv, L, C, C, row_bytes, out_k, out_v, clean, st) != hipSuccess)
+    if (launch_gather(k, v, out_idx, Hkv, L, C, C, row_bytes, out_k, out_v, kl, vl, clean, st) != hipSuccess)
         return SNAPKV_ERR_HIP;
     if (mine && (clean.ones || streaming) && clean.zeros) {
         std::lock_guard<std::mutex> lock(g_mu);
@@ -243,7 +253,9 @@ int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, 
     if (!out_scores) return SNAPKV_ERR_INVALID_ARG;
     if ((reinterpret_cast<uintptr_t>(out_scores) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
     if (L == W) return SNAPKV_OK;   // empty prefix: nothing to score
-    const ScoreGeom G = make_geom(L, Hq, Hkv, D, W);
+    ScoreGeom G = make_geom(L, Hq, Hkv, D, W);
+    G.k_rs = (int64_t)D * (dtype == SNAPKV_DTYPE_BF16 ? 2 : 4);
+    G.k_hs = G.k_rs * L;
     void* base = nullptr;
     rc = internal_scratch(workspace_layout(G, nullptr, nullptr), &base);
     if (rc != SNAPKV_OK) return rc;
@@ -394,6 +406,20 @@ int snapkv_pooled_scores_lse(int dtype, const void* q_win, const void* k, const 
                              int Hq, int Hkv, int D, int W, int pool_kind, int p, float* out_scores,
                              void* stream) {
     return scores_impl(dtype, q_win, k, L, Hq, Hkv, D, W, pool_kind, p, out_scores, stream, lse, true);
+}
+
+int64_t snapkv_compress_strided(int dtype, const void* q_win, const void* k, const void* v, int64_t L, int Hq,
+                                int Hkv, int D, int W, int64_t k_head_stride, int64_t k_row_stride,
+                                int64_t v_head_stride, int64_t v_row_stride, int pool_kind, int p, int64_t C,
+                                void* out_k, void* out_v, int32_t* out_idx, void* stream) {
+    if (dtype != SNAPKV_DTYPE_BF16 && dtype != SNAPKV_DTYPE_F32) return SNAPKV_ERR_INVALID_ARG;
+    const int64_t es = dtype == SNAPKV_DTYPE_BF16 ? 2 : 4;
+    if (k_head_stride < 0 || v_head_stride < 0 || k_row_stride < D || v_row_stride < D) return SNAPKV_ERR_INVALID_ARG;
+    const int64_t lim = (int64_t)1 << 56;
+    if (k_head_stride > lim || v_head_stride > lim || k_row_stride > lim || v_row_stride > lim) return SNAPKV_ERR_UNSUPPORTED;
+    const RowLayout kl{k_head_stride * es, k_row_stride * es}, vl{v_head_stride * es, v_row_stride * es};
+    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
+                         nullptr, 0, true, stream, nullptr, false, &kl, &vl);
 }
 
 size_t snapkv_workspace_bytes(int64_t L, int Hq, int Hkv, int D, int W) {

@@ -274,7 +274,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     for (int t = 0; t < KT; ++t) {
         int64_t j = ((int64_t)t * TS + tile0) * 16 + n16;
         j = j < G.L ? j : G.L - 1;
-        kp[t] = static_cast<const char*>(kv) + ((int64_t)(group / F.split) * G.L + j) * D * ES + kg * 16;
+        kp[t] = static_cast<const char*>(kv) + (int64_t)(group / F.split) * G.k_hs + j * G.k_rs + kg * 16;
     }
     // Q is shared by the waves: each fetches QPW of the unit's 1 KB chunks (chunk c = row unit c / NP,
     // piece c % NP, lane l = row l % 16, contraction slice l / 16) and leaves them in LDS.
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
         i = i < G.W ? i : G.W - 1;
         qp[x] = static_cast<const char*>(qv) + ((int64_t)(group * F.gs + head) * G.W + i) * D * ES + (4 * pc + kg) * 16;
     }
-    const int64_t kstep = (int64_t)(F.NG / F.split) * G.L * D * ES;   // NG is a multiple of split
+    const int64_t kstep = (int64_t)(F.NG / F.split) * G.k_hs;   // NG is a multiple of split
     const int64_t qstep = (int64_t)F.NG * F.gs * G.W * D * ES;
 
     // K tiles are consumed in two halves so that the memory pipeline never runs dry: the lower
@@ -739,7 +739,7 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
     for (int t = 0; t < KT; ++t) {
         int64_t j = ((int64_t)t * TS + tile0) * 16 + n16;
         j = j < G.L ? j : G.L - 1;
-        kp[t] = static_cast<const char*>(kv) + ((int64_t)(group / F.split) * G.L + j) * D * ES + kg * 16;
+        kp[t] = static_cast<const char*>(kv) + (int64_t)(group / F.split) * G.k_hs + j * G.k_rs + kg * 16;
     }
     const char* qp[QPW];
 #pragma unroll
@@ -757,7 +757,7 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
     const int lru = lrow >> 4, lhead = lru / F.UH, li = (lru % F.UH) * 16 + (lrow & 15);
     const bool lreal = tid < R && lru < F.RU && lhead < F.gs && li < G.W;
     const float* lp = lse + (int64_t)(group * F.gs + (lhead < F.gs ? lhead : F.gs - 1)) * G.W + (li < G.W ? li : G.W - 1);
-    const int64_t kstep = (int64_t)(F.NG / F.split) * G.L * D * ES;
+    const int64_t kstep = (int64_t)(F.NG / F.split) * G.k_hs;
     const int64_t qstep = (int64_t)F.NG * F.gs * G.W * D * ES;
     const int64_t lstep = (int64_t)F.NG * F.gs * G.W;
     constexpr float kLog2e = 1.4426950408889634f;

@@ -31,6 +31,8 @@ struct ScoreGeom {
     int VB;          // vote rows per query head
     int nchunks;     // ceil(L / kChunkKeys)
     float c2;        // log2(e) / sqrt(D): logits are kept in the base-2 domain
+    int64_t k_hs;    // bytes between the K rows of consecutive KV heads (contiguous: L * D * element size)
+    int64_t k_rs;    // bytes between consecutive K rows of a head (contiguous: D * element size)
 };
 
 // Plan of the single-read scoring kernel (snapkv_fused.hip).  A unit is a KV head or one of
@@ -134,9 +136,13 @@ struct CleanJob {
     unsigned* zeros = nullptr;
     int64_t nzeros = 0;
 };
+// Byte strides of a [heads, rows, D] tensor whose rows are contiguous.
+struct RowLayout {
+    int64_t head_stride, row_stride;
+};
 hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H, int64_t L,
                          int64_t rows, int64_t out_stride, int row_bytes, void* out_k, void* out_v,
-                         const CleanJob& clean, hipStream_t st);
+                         const RowLayout& kl, const RowLayout& vl, const CleanJob& clean, hipStream_t st);
 
 }  // namespace snapkv
 #endif

@@ -120,13 +120,13 @@ __device__ __forceinline__ void chunk_logits(f32x16 (&acc)[kTilesPerChunk], cons
                                              const void* k, const ScoreGeom& G, const Task& t,
                                              int lane) {
     const int64_t j0 = (int64_t)t.chunk * kChunkKeys;
-    const char* kbase = static_cast<const char*>(k) + (int64_t)t.hkv * G.L * D * elem_size<T>::value;
+    const char* kbase = static_cast<const char*>(k) + (int64_t)t.hkv * G.k_hs;
     Frag<T, D> kf[kTilesPerChunk];
 #pragma unroll
     for (int tt = 0; tt < kTilesPerChunk; ++tt) {
         int64_t j = j0 + tt * kTileKeys + (lane & 31);
         j = j < G.L ? j : G.L - 1;
-        load_frag<T, D>(kf[tt], kbase + j * D * elem_size<T>::value, lane >> 5);
+        load_frag<T, D>(kf[tt], kbase + j * G.k_rs, lane >> 5);
     }
 #pragma unroll
     for (int tt = 0; tt < kTilesPerChunk; ++tt) {
@@ -292,6 +292,8 @@ ScoreGeom make_geom(int64_t L, int Hq, int Hkv, int D, int W) {
     G.NV = G.g * G.VB;
     G.nchunks = (int)((L + kChunkKeys - 1) / kChunkKeys);
     G.c2 = (float)(1.4426950408889634 / __builtin_sqrt((double)D));
+    G.k_rs = 0;   // set by the caller once the element size is known
+    G.k_hs = 0;
     return G;
 }
 

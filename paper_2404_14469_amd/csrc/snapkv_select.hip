@@ -386,15 +386,17 @@ hipError_t launch_iota(int H, int64_t rows, int64_t out_stride, int32_t* out_idx
 // threads cover consecutive pieces of a row, so a 256-byte row is one coalesced 16-lane access.
 __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
                                                    const uint4* __restrict__ v,
-                                                   const int32_t* __restrict__ idx, const int64_t L,
+                                                   const int32_t* __restrict__ idx,
                                                    const int64_t rows, const int64_t out_stride,
                                                    const int pieces /* 16-byte pieces per row */,
                                                    uint4* __restrict__ out_k,
-                                                   uint4* __restrict__ out_v, const CleanJob clean) {
+                                                   uint4* __restrict__ out_v, const RowLayout kl,
+                                                   const RowLayout vl /* strides in 16-byte pieces */,
+                                                   const CleanJob clean) {
     const int h = blockIdx.y;
     const int64_t total = rows * pieces;
-    const uint4* kb = k + (int64_t)h * L * pieces;
-    const uint4* vb = v + (int64_t)h * L * pieces;
+    const uint4* kb = k + (int64_t)h * kl.head_stride;
+    const uint4* vb = v + (int64_t)h * vl.head_stride;
     uint4* okb = out_k + (int64_t)h * out_stride * pieces;
     uint4* ovb = out_v + (int64_t)h * out_stride * pieces;
     const int32_t* ib = idx + (int64_t)h * out_stride;
@@ -402,8 +404,8 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
         const int64_t r = e / pieces;
         const int c = (int)(e - r * pieces);
         const int64_t src = ib[r];
-        okb[r * pieces + c] = kb[src * pieces + c];
-        ovb[r * pieces + c] = vb[src * pieces + c];
+        okb[r * pieces + c] = kb[src * kl.row_stride + c];
+        ovb[r * pieces + c] = vb[src * vl.row_stride + c];
     }
     // the call's scratch is no longer read by anything: leave it ready for the next call
     const int64_t gid = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
@@ -414,15 +416,17 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
 
 hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H, int64_t L,
                          int64_t rows, int64_t out_stride, int row_bytes, void* out_k, void* out_v,
-                         const CleanJob& clean, hipStream_t st) {
+                         const RowLayout& kl, const RowLayout& vl, const CleanJob& clean, hipStream_t st) {
+    (void)L;
     if (H <= 0 || rows <= 0) return hipSuccess;
     const int pieces = row_bytes / 16;
     const int64_t total = rows * pieces;
     unsigned bx = (unsigned)((total + 255) / 256);
     if (bx > 4096) bx = 4096;
+    const RowLayout kp{kl.head_stride / 16, kl.row_stride / 16}, vp{vl.head_stride / 16, vl.row_stride / 16};
     hipLaunchKernelGGL(gather_rows, dim3(bx, H), dim3(256), 0, st, static_cast<const uint4*>(k),
-                       static_cast<const uint4*>(v), idx, L, rows, out_stride, pieces,
-                       static_cast<uint4*>(out_k), static_cast<uint4*>(out_v), clean);
+                       static_cast<const uint4*>(v), idx, rows, out_stride, pieces,
+                       static_cast<uint4*>(out_k), static_cast<uint4*>(out_v), kp, vp, clean);
     return hipGetLastError();
 }
 

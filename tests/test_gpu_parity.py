@@ -260,6 +260,33 @@ def test_lse_offset_scales_rows_on_the_gpu(snapkv):
     assert np.allclose(sc.cpu().numpy(), want, rtol=1e-3, atol=1e-30)
 
 
+# ----------------------------------------------------------------------------- strided K / V
+@pytest.mark.parametrize("w", [small("tm_mha", L=2100, C=300), small("tm_gqa_f32", dtype="f32", D=64, Hq=8, Hkv=2,
+                                                                       W=16, pool_kind=1, p=5, L=900, C=120),
+                               small("tm_bypass", L=100, C=128)], ids=lambda w: w.name)
+def test_strided_layouts_match_contiguous(snapkv, w):
+    # the same logical [Hkv, L, D] tensors stored token-major and with padded rows must give what the
+    # contiguous call gives, bit for bit (which is itself checked against the oracle)
+    case = workloads.generate(w, device="cuda")
+    q, k, v = case["q_win"], case["k"], case["v"]
+    ref = run_gpu(snapkv, q, k, v, w.pool_kind, w.p, w.C)
+    if w.L > w.C:
+        check_against_oracle(q, k, v, w.pool_kind, w.p, w.C, *ref)
+    k_tm = k.permute(1, 0, 2).contiguous().permute(1, 0, 2)            # storage [L, Hkv, D]
+    v_pad = torch.zeros((w.Hkv, w.L, w.D + 8), dtype=v.dtype, device="cuda")
+    v_pad[..., : w.D] = v
+    v_view = v_pad[..., : w.D]                                          # row stride D + 8
+    assert not k_tm.is_contiguous() and not v_view.is_contiguous()
+    out_k = torch.zeros_like(ref[1])
+    out_v = torch.zeros_like(ref[2])
+    out_idx = torch.full(ref[3].shape, -1, dtype=torch.int32, device="cuda")
+    kept = snapkv.snapkv_compress_strided(q, k_tm, v_view, w.pool_kind, w.p, w.C, out_k, out_v, out_idx)
+    torch.cuda.synchronize()
+    assert kept == ref[4]
+    assert np.array_equal(out_idx.cpu().numpy()[:, :kept], ref[3][:, :kept])
+    assert torch.equal(out_k[:, :kept], ref[1][:, :kept]) and torch.equal(out_v[:, :kept], ref[2][:, :kept])
+
+
 # ----------------------------------------------------------------------------- selector alone
 def _select_case(snapkv, scores_np, kcount):
     s = torch.from_numpy(scores_np).cuda()

@@ -70,6 +70,13 @@ def test_scores_and_select_reject_bad_arguments():
     assert lib.snapkv_pooled_scores_lse(5, FAKE, FAKE, FAKE, *lse_args, FAKE, None) == -1
     assert lib.snapkv_compress_lse(0, FAKE, FAKE, FAKE, None, *lse_args, 512, FAKE, FAKE, FAKE, None) == -1
     assert lib.snapkv_compress_lse(0, FAKE, FAKE, FAKE, FAKE, 4096, 8, 8, 128, 32, 0, 6, 512, FAKE, FAKE, FAKE, None) == -1
+    # strided K / V: row stride below D, negative head stride, strides that break 16-byte alignment
+    st_args = lambda khs, krs, vhs, vrs: (0, FAKE, FAKE, FAKE, 4096, 8, 8, 128, 32, khs, krs, vhs, vrs, 0, 7, 512,
+                                          FAKE, FAKE, FAKE, None)
+    assert lib.snapkv_compress_strided(*st_args(4096 * 128, 64, 4096 * 128, 128)) == -1
+    assert lib.snapkv_compress_strided(*st_args(-128, 128, 4096 * 128, 128)) == -1
+    assert lib.snapkv_compress_strided(*st_args(4096 * 128, 132, 4096 * 128, 128)) == -3
+    assert lib.snapkv_compress_strided(*st_args(128, 8 * 128, 4096 * 128 + 4, 128)) == -3
     assert lib.snapkv_select_topk(None, 1, 10, 2, FAKE, None) == -1
     assert lib.snapkv_select_topk(FAKE, 1, 10, 11, FAKE, None) == -1
     assert lib.snapkv_select_topk(FAKE, 1, 10, 0, FAKE, None) == 0
