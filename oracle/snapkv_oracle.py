@@ -50,11 +50,12 @@ POOL_AVG = 1
 
 
 def widen(x: np.ndarray) -> np.ndarray:
-    """Exact float64 view of the stored values: float arrays as is, uint16 as bf16 bit patterns."""
+    """Exact float64 view of the stored values: float arrays (IEEE half, single, double) as is,
+    uint16 as bf16 bit patterns."""
     x = np.asarray(x)
     if x.dtype == np.uint16:
         return (x.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
-    if x.dtype in (np.float32, np.float64):
+    if x.dtype in (np.float16, np.float32, np.float64):
         return x.astype(np.float64)
     raise TypeError(f"unsupported storage dtype {x.dtype}")
 

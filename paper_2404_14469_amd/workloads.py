@@ -21,7 +21,7 @@ Recipe (per call = one prompt, one layer):
     query head in that KV group gets += sum_c u_c.
   * optional needle: one prefix row of K gets += 3*sqrt(D)*u, every window
     query of the group gets += 4*u.
-  * finally everything is rounded to the storage dtype (bf16 or fp32).
+  * finally everything is rounded to the storage dtype (bf16, fp16 or fp32).
 """
 from __future__ import annotations
 
@@ -43,7 +43,7 @@ class Workload:
     pool_kind: int  # 0 = max, 1 = avg
     p: int
     C: int
-    dtype: str  # "bf16" | "f32"
+    dtype: str  # "bf16" | "f16" | "f32"
     clusters: Tuple[int, int]  # (lo, hi) inclusive range of clusters per KV head
     radius: int
     strength: float = 3.0
@@ -134,13 +134,14 @@ def generate(w: Workload, layer: int = 0, device: str = "cpu") -> Dict[str, obje
             q[hk * g:(hk + 1) * g, :, :] += 4.0 * un
             needle_pos.append(pos)
 
-    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[w.dtype]
     return {"q_win": q.to(tdt).contiguous(), "k": k.to(tdt).contiguous(),
             "v": v.to(tdt).contiguous(), "centres": centres, "needle_pos": needle_pos}
 
 
 def to_numpy_bits(t: torch.Tensor):
-    """Host copy of a tensor as a numpy array: fp32 as float32, bf16 as its uint16 bit patterns."""
+    """Host copy of a tensor as a numpy array: fp32 as float32, fp16 as float16, bf16 as its uint16 bit
+    patterns."""
     import numpy as np
     t = t.detach().cpu().contiguous()
     if t.dtype == torch.bfloat16:

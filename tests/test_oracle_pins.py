@@ -75,6 +75,17 @@ def test_two_key_closed_form():
     assert abs(orc.vote(P)[0] - P[0, 0]) == 0.0
 
 
+def test_widen_fp16_is_exact():
+    # IEEE half values, including a subnormal and the largest finite one, written out by hand
+    x = np.array([1.0, -2.5, 2.0 ** -24, 65504.0, 0.333251953125], dtype=np.float16)
+    assert orc.widen(x).tolist() == [1.0, -2.5, 2.0 ** -24, 65504.0, 0.333251953125]
+    q, k, v = rand_case(9, 2, 2, 40, 8, 4)
+    a = orc.compress(q.astype(np.float16), k.astype(np.float16), v.astype(np.float16), 4, 0, 3, 12)
+    b = orc.compress(q.astype(np.float16).astype(np.float32), k.astype(np.float16).astype(np.float32),
+                     v.astype(np.float16).astype(np.float32), 4, 0, 3, 12)
+    assert np.array_equal(a[2], b[2]) and np.array_equal(a[4], b[4]) and a[0].dtype == np.float16
+
+
 # ----------------------------------------------------------------------------- closed form: zero queries
 def harmonic_gap(L, n):
     return float(sum(Fraction(1, t) for t in range(n + 1, L + 1)))
