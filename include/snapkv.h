@@ -41,6 +41,7 @@ extern "C" {
 
 #define SNAPKV_DTYPE_BF16 0 /* bfloat16 q/k/v */
 #define SNAPKV_DTYPE_F32 1  /* IEEE float32 q/k/v */
+#define SNAPKV_DTYPE_F16 2  /* IEEE float16 q/k/v */
 
 #define SNAPKV_OK 0
 #define SNAPKV_ERR_INVALID_ARG (-1) /* null pointer, L<1, W<1, W>L, W>C, even p, bad pool_kind, Hq%Hkv!=0 */
@@ -81,6 +82,11 @@ int64_t snapkv_compress_f32(const void* q_win, const void* k, const void* v, int
                             int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k,
                             void* out_v, int32_t* out_idx, void* stream);
 
+/* Same operation with IEEE float16 q/k/v and float16 out_k/out_v (fp32 accumulation and softmax). */
+int64_t snapkv_compress_f16(const void* q_win, const void* k, const void* v, int64_t L, int Hq,
+                            int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k,
+                            void* out_v, int32_t* out_idx, void* stream);
+
 /*
  * Steps 1-3 only (window scores, voting per Eq. 1, pooling per Sec. 4.3, group sum):
  *   out_scores [Hkv, L-W] device, float32: the pooled score of every prefix position.
@@ -89,6 +95,8 @@ int64_t snapkv_compress_f32(const void* q_win, const void* k, const void* v, int
 int snapkv_pooled_scores(const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D, int W,
                          int pool_kind, int p, float* out_scores, void* stream);
 int snapkv_pooled_scores_f32(const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D,
+                             int W, int pool_kind, int p, float* out_scores, void* stream);
+int snapkv_pooled_scores_f16(const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D,
                              int W, int pool_kind, int p, float* out_scores, void* stream);
 
 /*

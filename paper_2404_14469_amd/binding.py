@@ -16,14 +16,14 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libsnapkv.so")
 
 POOL_MAX, POOL_AVG = 0, 1
-DTYPE_BF16, DTYPE_F32 = 0, 1
+DTYPE_BF16, DTYPE_F32, DTYPE_F16 = 0, 1, 2
 
 SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compress_f32",
            "snapkv_pooled_scores", "snapkv_pooled_scores_f32", "snapkv_workspace_bytes",
            "snapkv_compress_ws", "snapkv_select_topk", "snapkv_release", "snapkv_profile_start",
            "snapkv_profile_stop", "snapkv_num_stages", "snapkv_stage_name", "snapkv_set_scoring_scheme",
            "snapkv_sync_timeouts", "snapkv_compress_lse", "snapkv_pooled_scores_lse",
-           "snapkv_compress_strided")
+           "snapkv_compress_strided", "snapkv_compress_f16", "snapkv_pooled_scores_f16")
 
 _lib = None
 
@@ -49,11 +49,11 @@ def load():
     L.snapkv_version.argtypes = []
     L.snapkv_strerror.restype = ctypes.c_char_p
     L.snapkv_strerror.argtypes = [i32]
-    for name in ("snapkv_compress", "snapkv_compress_f32"):
+    for name in ("snapkv_compress", "snapkv_compress_f32", "snapkv_compress_f16"):
         f = getattr(L, name)
         f.restype = i64
         f.argtypes = [vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
-    for name in ("snapkv_pooled_scores", "snapkv_pooled_scores_f32"):
+    for name in ("snapkv_pooled_scores", "snapkv_pooled_scores_f32", "snapkv_pooled_scores_f16"):
         f = getattr(L, name)
         f.restype = i32
         f.argtypes = [vp, vp, i64, i32, i32, i32, i32, i32, i32, vp, vp]
@@ -116,7 +116,9 @@ def _dtype_code(t: torch.Tensor) -> int:
         return DTYPE_BF16
     if t.dtype == torch.float32:
         return DTYPE_F32
-    raise ValueError(f"q/k/v must be bfloat16 or float32, got {t.dtype}")
+    if t.dtype == torch.float16:
+        return DTYPE_F16
+    raise ValueError(f"q/k/v must be bfloat16, float16 or float32, got {t.dtype}")
 
 
 def snapkv_version() -> int:
@@ -190,7 +192,7 @@ def snapkv_compress(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, pool_
         wp = _dev(workspace, "workspace", torch.uint8)
         return _check(lib.snapkv_compress_ws(code, *ptrs, L, Hq, Hkv, D, W, pool_kind, p, C, *outs, wp,
                                              workspace.numel(), _stream(stream)))
-    fn = lib.snapkv_compress if code == DTYPE_BF16 else lib.snapkv_compress_f32
+    fn = {DTYPE_BF16: lib.snapkv_compress, DTYPE_F32: lib.snapkv_compress_f32, DTYPE_F16: lib.snapkv_compress_f16}[code]
     return _check(fn(*ptrs, L, Hq, Hkv, D, W, pool_kind, p, C, *outs, _stream(stream)))
 
 
@@ -266,7 +268,8 @@ def snapkv_pooled_scores(q_win: torch.Tensor, k: torch.Tensor, pool_kind: int, p
     code = _dtype_code(k)
     if tuple(out_scores.shape) != (Hkv, L - W):
         raise ValueError("out_scores must be [Hkv, L-W]")
-    fn = lib.snapkv_pooled_scores if code == DTYPE_BF16 else lib.snapkv_pooled_scores_f32
+    fn = {DTYPE_BF16: lib.snapkv_pooled_scores, DTYPE_F32: lib.snapkv_pooled_scores_f32,
+          DTYPE_F16: lib.snapkv_pooled_scores_f16}[code]
     _check(fn(_dev(q_win, "q_win", k.dtype), _dev(k, "k"), L, Hq, Hkv, D, W, pool_kind, p,
               _dev(out_scores, "out_scores", torch.float32), _stream(stream)))
 

@@ -35,6 +35,9 @@ Profile g_prof;
 bool g_allow_fused = true;   // snapkv_set_scoring_scheme: tests can force the two-pass kernels
 bool g_allow_pool_select = true;   // ... and the separate pooling and selection kernels
 
+bool valid_dtype(int dtype) { return dtype == SNAPKV_DTYPE_BF16 || dtype == SNAPKV_DTYPE_F32 || dtype == SNAPKV_DTYPE_F16; }
+int elem_bytes(int dtype) { return dtype == SNAPKV_DTYPE_F32 ? 4 : 2; }
+
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // Shape checks shared by every entry point that scores (steps 1-3).
@@ -147,7 +150,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
                       void* out_v, int32_t* out_idx, void* workspace, size_t workspace_bytes,
                       bool own_scratch, void* stream, const float* lse = nullptr, bool with_lse = false,
                       const RowLayout* k_layout = nullptr, const RowLayout* v_layout = nullptr) {
-    if (dtype != SNAPKV_DTYPE_BF16 && dtype != SNAPKV_DTYPE_F32) return SNAPKV_ERR_INVALID_ARG;
+    if (!valid_dtype(dtype)) return SNAPKV_ERR_INVALID_ARG;
     if (with_lse && !lse) return SNAPKV_ERR_INVALID_ARG;
     if (with_lse && (reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
     int rc = check_score_args(q_win, k, L, Hq, Hkv, D, W, pool_kind, p);
@@ -158,7 +161,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     if (!aligned16(v) || !aligned16(out_k) || !aligned16(out_v)) return SNAPKV_ERR_MISALIGNED;
     if ((reinterpret_cast<uintptr_t>(out_idx) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const int row_bytes = D * (dtype == SNAPKV_DTYPE_BF16 ? 2 : 4);
+    const int row_bytes = D * elem_bytes(dtype);
     // byte strides of K and V: contiguous [Hkv, L, D] unless the caller says otherwise
     const RowLayout contiguous{(int64_t)L * row_bytes, (int64_t)row_bytes};
     const RowLayout kl = k_layout ? *k_layout : contiguous, vl = v_layout ? *v_layout : contiguous;
@@ -245,7 +248,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
 int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D, int W,
                 int pool_kind, int p, float* out_scores, void* stream, const float* lse = nullptr,
                 bool with_lse = false) {
-    if (dtype != SNAPKV_DTYPE_BF16 && dtype != SNAPKV_DTYPE_F32) return SNAPKV_ERR_INVALID_ARG;
+    if (!valid_dtype(dtype)) return SNAPKV_ERR_INVALID_ARG;
     int rc = check_score_args(q_win, k, L, Hq, Hkv, D, W, pool_kind, p);
     if (rc != SNAPKV_OK) return rc;
     if (with_lse && !lse) return SNAPKV_ERR_INVALID_ARG;
@@ -254,7 +257,7 @@ int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, 
     if ((reinterpret_cast<uintptr_t>(out_scores) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
     if (L == W) return SNAPKV_OK;   // empty prefix: nothing to score
     ScoreGeom G = make_geom(L, Hq, Hkv, D, W);
-    G.k_rs = (int64_t)D * (dtype == SNAPKV_DTYPE_BF16 ? 2 : 4);
+    G.k_rs = (int64_t)D * elem_bytes(dtype);
     G.k_hs = G.k_rs * L;
     void* base = nullptr;
     rc = internal_scratch(workspace_layout(G, nullptr, nullptr), &base);
@@ -395,6 +398,18 @@ int snapkv_pooled_scores_f32(const void* q_win, const void* k, int64_t L, int Hq
     return scores_impl(SNAPKV_DTYPE_F32, q_win, k, L, Hq, Hkv, D, W, pool_kind, p, out_scores, stream);
 }
 
+int64_t snapkv_compress_f16(const void* q_win, const void* k, const void* v, int64_t L, int Hq,
+                            int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k,
+                            void* out_v, int32_t* out_idx, void* stream) {
+    return compress_impl(SNAPKV_DTYPE_F16, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k,
+                         out_v, out_idx, nullptr, 0, true, stream);
+}
+
+int snapkv_pooled_scores_f16(const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D,
+                             int W, int pool_kind, int p, float* out_scores, void* stream) {
+    return scores_impl(SNAPKV_DTYPE_F16, q_win, k, L, Hq, Hkv, D, W, pool_kind, p, out_scores, stream);
+}
+
 int64_t snapkv_compress_lse(int dtype, const void* q_win, const void* k, const void* v, const float* lse,
                             int64_t L, int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
                             void* out_k, void* out_v, int32_t* out_idx, void* stream) {
@@ -412,8 +427,8 @@ int64_t snapkv_compress_strided(int dtype, const void* q_win, const void* k, con
                                 int Hkv, int D, int W, int64_t k_head_stride, int64_t k_row_stride,
                                 int64_t v_head_stride, int64_t v_row_stride, int pool_kind, int p, int64_t C,
                                 void* out_k, void* out_v, int32_t* out_idx, void* stream) {
-    if (dtype != SNAPKV_DTYPE_BF16 && dtype != SNAPKV_DTYPE_F32) return SNAPKV_ERR_INVALID_ARG;
-    const int64_t es = dtype == SNAPKV_DTYPE_BF16 ? 2 : 4;
+    if (!valid_dtype(dtype)) return SNAPKV_ERR_INVALID_ARG;
+    const int64_t es = elem_bytes(dtype);
     if (k_head_stride < 0 || v_head_stride < 0 || k_row_stride < D || v_row_stride < D) return SNAPKV_ERR_INVALID_ARG;
     const int64_t lim = (int64_t)1 << 56;
     if (k_head_stride > lim || v_head_stride > lim || k_row_stride > lim || v_row_stride > lim) return SNAPKV_ERR_UNSUPPORTED;

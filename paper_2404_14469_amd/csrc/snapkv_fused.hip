@@ -50,12 +50,15 @@
 namespace snapkv {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
 
 struct bf16_k {};
+struct f16_k {};
 struct f32_k {};
 template <typename T> struct esize;
 template <> struct esize<bf16_k> { static constexpr int value = 2; };
+template <> struct esize<f16_k> { static constexpr int value = 2; };
 template <> struct esize<f32_k> { static constexpr int value = 4; };
 
 template <typename T, int D> struct Frag16 {
@@ -82,6 +85,16 @@ __device__ __forceinline__ f32x4 mfma16(const Frag16<bf16_k, D>& a, const Frag16
     for (int p = 0; p < Frag16<bf16_k, D>::NP; ++p)
         acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a.v[p]),
                                                       __builtin_bit_cast(bf16x8_t, b.v[p]), acc, 0, 0, 0);
+    return acc;
+}
+
+template <int D>
+__device__ __forceinline__ f32x4 mfma16(const Frag16<f16_k, D>& a, const Frag16<f16_k, D>& b) {
+    f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int p = 0; p < Frag16<f16_k, D>::NP; ++p)
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8_t, a.v[p]),
+                                                     __builtin_bit_cast(f16x8_t, b.v[p]), acc, 0, 0, 0);
     return acc;
 }
 
@@ -1129,7 +1142,7 @@ template <typename T, int D, int RUW, int NW>
 static hipError_t fused_instance(const FusedCall* call, int* occ) {
     constexpr int KT = kFusedSlots / RUW;
     auto kern = score_fused<T, D, RUW, KT, NW>;
-    constexpr int kQueueBytes = 3 * RUW * (D * (std::is_same<T, bf16_k>::value ? 2 : 4) / 64) * 64 * 16;   // Q blocks of three units
+    constexpr int kQueueBytes = 3 * RUW * (D * esize<T>::value / 64) * 64 * 16;   // Q blocks of three units
     static int cached_occ = -1;
     if (cached_occ < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1170,6 +1183,9 @@ static hipError_t fused_dispatch(int dtype, int D, int NW, int RUW, const FusedC
     if (dtype == 0) {
         if (D == 128) return fused_by_waves<bf16_k, 128>(NW, RUW, call, occ);
         if (D == 64) return fused_by_waves<bf16_k, 64>(NW, RUW, call, occ);
+    } else if (dtype == 2) {
+        if (D == 128) return fused_by_waves<f16_k, 128>(NW, RUW, call, occ);
+        if (D == 64) return fused_by_waves<f16_k, 64>(NW, RUW, call, occ);
     } else {
         if (D == 128) return fused_by_waves<f32_k, 128>(NW, RUW, call, occ);
         if (D == 64) return fused_by_waves<f32_k, 64>(NW, RUW, call, occ);
@@ -1252,7 +1268,7 @@ template <typename T, int D, int RUW, int NW, bool STAT>
 static hipError_t lse_instance(const LseCall* call, int* occ) {
     constexpr int KT = kFusedSlots / RUW;
     auto kern = score_lse<T, D, RUW, KT, NW, STAT>;
-    constexpr int kQBytes = 2 * RUW * (D * (std::is_same<T, bf16_k>::value ? 2 : 4) / 64) * 64 * 16;   // Q blocks of two units
+    constexpr int kQBytes = 2 * RUW * (D * esize<T>::value / 64) * 64 * 16;   // Q blocks of two units
     static int cached_occ = -1;
     if (cached_occ < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1287,6 +1303,9 @@ static hipError_t lse_dispatch(int dtype, int D, int RUW, const LseCall* call, i
     if (dtype == 0) {
         if (D == 128) return lse_by_rows<bf16_k, 128, STAT>(RUW, call, occ);
         if (D == 64) return lse_by_rows<bf16_k, 64, STAT>(RUW, call, occ);
+    } else if (dtype == 2) {
+        if (D == 128) return lse_by_rows<f16_k, 128, STAT>(RUW, call, occ);
+        if (D == 64) return lse_by_rows<f16_k, 64, STAT>(RUW, call, occ);
     } else {
         if (D == 128) return lse_by_rows<f32_k, 128, STAT>(RUW, call, occ);
         if (D == 64) return lse_by_rows<f32_k, 64, STAT>(RUW, call, occ);

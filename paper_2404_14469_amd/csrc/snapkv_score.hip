@@ -21,12 +21,15 @@
 namespace snapkv {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 struct bf16_tag {};
+struct f16_tag {};
 struct f32_tag {};
 template <typename T> struct elem_size;
 template <> struct elem_size<bf16_tag> { static constexpr int value = 2; };
+template <> struct elem_size<f16_tag> { static constexpr int value = 2; };
 template <> struct elem_size<f32_tag> { static constexpr int value = 4; };
 
 // Half a row of D elements as 16-byte pieces.
@@ -56,6 +59,17 @@ __device__ __forceinline__ void mfma_rows(const Frag<bf16_tag, D>& a, const Frag
         bf16x8 av = __builtin_bit_cast(bf16x8, a.v[s]);
         bf16x8 bv = __builtin_bit_cast(bf16x8, b.v[s]);
         acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, bv, acc, 0, 0, 0);
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void mfma_rows(const Frag<f16_tag, D>& a, const Frag<f16_tag, D>& b,
+                                          f32x16& acc) {
+#pragma unroll
+    for (int s = 0; s < Frag<f16_tag, D>::N16; ++s) {
+        f16x8 av = __builtin_bit_cast(f16x8, a.v[s]);
+        f16x8 bv = __builtin_bit_cast(f16x8, b.v[s]);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(av, bv, acc, 0, 0, 0);
     }
 }
 
@@ -343,6 +357,9 @@ hipError_t launch_score(int dtype, int D, const void* q, const void* k, const Sc
     if (dtype == 0) {
         if (D == 128) return launch_score_t<bf16_tag, 128>(q, k, G, ws, st);
         if (D == 64) return launch_score_t<bf16_tag, 64>(q, k, G, ws, st);
+    } else if (dtype == 2) {
+        if (D == 128) return launch_score_t<f16_tag, 128>(q, k, G, ws, st);
+        if (D == 64) return launch_score_t<f16_tag, 64>(q, k, G, ws, st);
     } else {
         if (D == 128) return launch_score_t<f32_tag, 128>(q, k, G, ws, st);
         if (D == 64) return launch_score_t<f32_tag, 64>(q, k, G, ws, st);

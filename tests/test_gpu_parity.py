@@ -44,6 +44,9 @@ SMALL_CASES = [
     small("l_is_w_plus_1", L=33, W=32, C=32),
     small("needle", L=4096, C=256, needle=True, clusters=(8, 8)),
     small("mha_w160", W=160, L=1300, C=320, p=5),            # more window rows than a wave tracks
+    small("f16_d128", dtype="f16", L=1234, C=150),
+    small("f16_d64_gqa", dtype="f16", D=64, Hq=8, Hkv=2, W=16, pool_kind=1, p=5, L=700, C=100),
+    small("f16_w160", dtype="f16", W=160, L=900, C=200),
 ]
 
 

@@ -68,6 +68,7 @@ def test_scores_and_select_reject_bad_arguments():
     assert lib.snapkv_pooled_scores_lse(0, FAKE, FAKE, None, *lse_args, FAKE, None) == -1
     assert lib.snapkv_pooled_scores_lse(0, FAKE, FAKE, FAKE + 2, *lse_args, FAKE, None) == -3
     assert lib.snapkv_pooled_scores_lse(5, FAKE, FAKE, FAKE, *lse_args, FAKE, None) == -1
+    assert lib.snapkv_pooled_scores_f16(FAKE, FAKE, 4096, 8, 8, 96, 32, 0, 7, FAKE, None) == -2
     assert lib.snapkv_compress_lse(0, FAKE, FAKE, FAKE, None, *lse_args, 512, FAKE, FAKE, FAKE, None) == -1
     assert lib.snapkv_compress_lse(0, FAKE, FAKE, FAKE, FAKE, 4096, 8, 8, 128, 32, 0, 6, 512, FAKE, FAKE, FAKE, None) == -1
     # strided K / V: row stride below D, negative head stride, strides that break 16-byte alignment
