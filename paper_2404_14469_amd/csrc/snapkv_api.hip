@@ -11,13 +11,20 @@ namespace {
 using namespace snapkv;
 
 constexpr int kMaxDevices = 64;
+// What the last call's final kernel left ready at the start of the library's own buffer, so that
+// the next call needs no preparing launch: the selection's counters (zero) for `hkv` heads and,
+// behind them in a region of `fused_bytes` bytes, `ones` hand-off words holding the "not
+// published" pattern.  ones < 0: nothing is known.  Anything else that touches the buffer
+// resets it.
+struct CleanState {
+    int hkv = 0;
+    size_t fused_bytes = 0;
+    int64_t ones = -1;
+};
 struct DeviceScratch {
     void* ptr = nullptr;
     size_t bytes = 0;
-    // Non-zero: the last call on this buffer had this shape and its final kernel left the
-    // hand-off words and counters ready, so the next call of the same shape needs no preparing
-    // launch.  Anything else that touches the buffer resets it.
-    uint64_t clean_key = 0;
+    CleanState clean;
 };
 DeviceScratch g_scratch[kMaxDevices];
 std::mutex g_mu;
@@ -58,14 +65,14 @@ int check_score_args(const void* q_win, const void* k, int64_t L, int Hq, int Hk
 
 // Hands out the device's buffer.  Whoever takes it may leave it in any state, so the record of a
 // ready-made state is handed to the caller (*was_clean, may be null) and dropped.
-int internal_scratch(size_t need, void** out, uint64_t* was_clean = nullptr) {
+int internal_scratch(size_t need, void** out, CleanState* was_clean = nullptr) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SNAPKV_ERR_HIP;
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceScratch& s = g_scratch[dev];
-    if (s.bytes < need) s.clean_key = 0;
-    if (was_clean) *was_clean = s.clean_key;
-    s.clean_key = 0;
+    if (s.bytes < need) s.clean = CleanState{};
+    if (was_clean) *was_clean = s.clean;
+    s.clean = CleanState{};
     if (s.bytes < need) {
         if (s.ptr) {
             // hipFree waits for the device, so work still reading the old buffer has finished
@@ -182,7 +189,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     G.k_rs = kl.row_stride;
     const size_t need = workspace_layout(G, nullptr, nullptr);
     void* base = workspace;
-    uint64_t was_clean = 0;
+    CleanState was_clean;
     if (own_scratch) {
         rc = internal_scratch(need, &base, &was_clean);
         if (rc != SNAPKV_OK) return rc;
@@ -197,7 +204,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     hipError_t se;
     CleanJob clean;
     DeviceScratch* mine = nullptr;      // the library's own buffer: its state is tracked between calls
-    uint64_t key = 0;
+    CleanState now;
     bool streaming = false;
     if (g_allow_pool_select && pool_select_ok(G, pool_kind, p, C - W)) {   // pooling and selection in one launch
         bool prepared = false;
@@ -210,11 +217,15 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
         if (own_scratch && path != 0) {
             int dev = 0;
             if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
-                key = 0x9E3779B97F4A7C15ull ^ ((uint64_t)L * 1000003ull) ^ ((uint64_t)Hq << 50) ^ ((uint64_t)Hkv << 40) ^
-                      ((uint64_t)D << 32) ^ ((uint64_t)W << 20) ^ ((uint64_t)dtype << 19);
-                if (streaming) key ^= 0x5555ull;   // that path leaves only the counters ready, not the hand-off words
+                // the streaming path does not touch the hand-off words
+                const int64_t nones = streaming ? 0 : fused_sync_pairs(Fp);
+                now.hkv = Hkv;
+                now.fused_bytes = fused_sync_bytes(G);
+                const bool same = was_clean.ones >= 0 && was_clean.hkv == now.hkv &&
+                                  was_clean.fused_bytes == now.fused_bytes;
+                prepared = same && was_clean.ones >= nones;
+                now.ones = same && was_clean.ones > nones ? was_clean.ones : nones;
                 mine = &g_scratch[dev];
-                prepared = was_clean == key;
             }
         }
         ScoreGeom Gv = G;
@@ -239,7 +250,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
         return SNAPKV_ERR_HIP;
     if (mine && (clean.ones || streaming) && clean.zeros) {
         std::lock_guard<std::mutex> lock(g_mu);
-        mine->clean_key = key;
+        mine->clean = now;
     }
     stage_done(st, kStageGather);
     return C;
@@ -473,7 +484,7 @@ void snapkv_release(void) {
         if (hipSetDevice(d) == hipSuccess) (void)hipFree(g_scratch[d].ptr);
         g_scratch[d].ptr = nullptr;
         g_scratch[d].bytes = 0;
-        g_scratch[d].clean_key = 0;
+        g_scratch[d].clean = CleanState{};
     }
     if (have_cur) (void)hipSetDevice(cur);
 }

@@ -1094,14 +1094,17 @@ bool fused_shape(const ScoreGeom& G, FusedGeom* F) {
 
 size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base);
 
-// Bytes of hand-off buffers that cover whichever split the launch plan ends up choosing.
+// Bytes of hand-off buffers that cover whichever split the launch plan ends up choosing, for any
+// prompt length: the size depends on the heads and the window only, so that what follows the
+// buffers in a workspace never moves onto them when the length changes.
 size_t fused_sync_bytes(const ScoreGeom& G) {
     int cand[8];
     const int nc = fused_split_candidates(G, cand);
     size_t most = 0;
     for (int i = 0; i < nc; ++i) {
         FusedGeom F;
-        if (!fused_shape_nw(G, kFusedWaves, cand[i], &F)) continue;
+        if (!fused_shape_nw(G, kFusedWaves, cand[i], &F, false)) continue;
+        F.Gg = 32 * kL1BlocksPadded;   // the most slices a launch can have
         const size_t b = fused_sync_layout(G, F, nullptr, nullptr);
         most = b > most ? b : most;
     }

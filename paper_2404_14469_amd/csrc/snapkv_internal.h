@@ -103,7 +103,9 @@ hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, co
 unsigned read_sync_timeouts();
 hipError_t launch_pool(const ScoreGeom& G, const float* vote, int pool_kind, int p, float* score,
                        unsigned* minmax, hipStream_t st);
-size_t select_layout(int H, int64_t n, SelectScratch* S, void* base);
+size_t select_counter_bytes(int H);
+size_t select_layout(int H, int64_t n, SelectScratch* S, void* base, bool own_counters = true,
+                     void* counters = nullptr);
 bool select_chunked_ok(int64_t n);
 hipError_t launch_select_init(const SelectScratch& S, int H, hipStream_t st);
 hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, int H, hipStream_t st);

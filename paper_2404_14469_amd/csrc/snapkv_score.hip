@@ -313,28 +313,33 @@ ScoreGeom make_geom(int64_t L, int Hq, int Hkv, int D, int W) {
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// The two regions whose contents carry over between calls come first, at offsets that depend on
+// the number of KV heads only: pool_select's counters (zero when idle), then the hand-off words of
+// the single-read scoring kernel (all-ones when idle).
 size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base) {
     char* b = static_cast<char*>(base);
-    size_t off = 0;
+    const size_t counters = select_counter_bytes(G.Hkv);
+    const size_t fused = fused_sync_bytes(G);
     const size_t part = align_up(sizeof(float2) * (size_t)G.Hkv * G.nchunks * G.R32 * 32);
     const size_t mz = align_up(sizeof(float2) * (size_t)G.Hkv * G.R32 * 32);
     const size_t vote = align_up(sizeof(float) * (size_t)G.Hkv * G.NV * (size_t)(G.n > 0 ? G.n : 1));
     const size_t score = align_up(sizeof(float) * (size_t)G.Hkv * (size_t)(G.n > 0 ? G.n : 1));
-    const size_t fused = fused_sync_bytes(G);
     const size_t stat = stream_stat_bytes(G);
     const size_t lse = align_up(sizeof(float) * (size_t)G.Hkv * G.g * G.W);
+    const size_t off = counters + fused;
     if (ws) {
+        ws->fused = b + counters;
         ws->part = reinterpret_cast<float2*>(b + off);
         ws->mz = reinterpret_cast<float2*>(b + off + part);
         ws->vote = reinterpret_cast<float*>(b + off + part + mz);
         ws->score = reinterpret_cast<float*>(b + off + part + mz + vote);
-        ws->fused = b + off + part + mz + vote + score;
-        ws->stat_part = reinterpret_cast<float2*>(b + off + part + mz + vote + score + fused);
-        ws->lse = reinterpret_cast<float*>(b + off + part + mz + vote + score + fused + stat);
+        ws->stat_part = reinterpret_cast<float2*>(b + off + part + mz + vote + score);
+        ws->lse = reinterpret_cast<float*>(b + off + part + mz + vote + score + stat);
     }
     const size_t sel = select_layout(G.Hkv, G.n, ws ? &ws->sel : nullptr,
-                                     ws ? b + off + part + mz + vote + score + fused + stat + lse : nullptr);
-    return part + mz + vote + score + fused + stat + lse + sel;
+                                     ws ? b + off + part + mz + vote + score + stat + lse : nullptr, false,
+                                     ws ? b : nullptr);
+    return off + part + mz + vote + score + stat + lse + sel;
 }
 
 template <typename T, int D>

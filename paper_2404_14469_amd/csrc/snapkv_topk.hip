@@ -1018,7 +1018,15 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
 
 static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
 
-size_t select_layout(int H, int64_t n, SelectScratch* S, void* base) {
+size_t select_counter_bytes(int H) {
+    return up256(sizeof(unsigned) * (size_t)H * (kPsStages + kPsLevels * kPsBins));
+}
+
+// own_counters: the arrival counters and digit histograms of pool_select sit at the end of this
+// layout; otherwise they are not part of it and are placed at `counters`
+// (select_counter_bytes(H) bytes), so that a caller can keep them at an address that does not
+// move with n.
+size_t select_layout(int H, int64_t n, SelectScratch* S, void* base, bool own_counters, void* counters) {
     const int64_t nn = n > 0 ? n : 1;
     const int64_t nch = (nn + kSelChunk - 1) / kSelChunk;
     const size_t minmax = up256(sizeof(unsigned) * 2 * (size_t)H * (size_t)((nn + 1023) / 1024));
@@ -1028,8 +1036,8 @@ size_t select_layout(int H, int64_t n, SelectScratch* S, void* base) {
     const size_t cgt = up256(sizeof(unsigned) * (size_t)H * nch);
     const size_t coff = up256(sizeof(unsigned) * 2 * (size_t)H * nch);
     const size_t cand = up256(sizeof(uint2) * (size_t)H * nn);
-    const size_t ps_zero = up256(sizeof(unsigned) * (size_t)H * (kPsStages + kPsLevels * kPsBins));
     const size_t ps_range = up256(sizeof(unsigned) * 2 * (size_t)H * kPsMaxGroup);
+    const size_t ps_zero = select_counter_bytes(H);
     if (S) {
         char* b = static_cast<char*>(base);
         S->minmax = reinterpret_cast<unsigned*>(b);
@@ -1040,13 +1048,13 @@ size_t select_layout(int H, int64_t n, SelectScratch* S, void* base) {
         S->chunk_off = reinterpret_cast<unsigned*>(b + minmax + hist + count + info + cgt);
         S->cand = reinterpret_cast<uint2*>(b + minmax + hist + count + info + cgt + coff);
         char* q = b + minmax + hist + count + info + cgt + coff + cand;
-        S->ps_arrive = reinterpret_cast<unsigned*>(q);
+        S->ps_range = reinterpret_cast<unsigned*>(q);
+        S->ps_part = reinterpret_cast<unsigned*>(q + ps_range);
+        S->ps_arrive = reinterpret_cast<unsigned*>(own_counters ? q + 2 * ps_range : static_cast<char*>(counters));
         S->ps_hist = S->ps_arrive + (size_t)H * kPsStages;
         S->ps_zero_words = (int64_t)H * (kPsStages + kPsLevels * kPsBins);
-        S->ps_range = reinterpret_cast<unsigned*>(q + ps_zero);
-        S->ps_part = reinterpret_cast<unsigned*>(q + ps_zero + ps_range);
     }
-    return minmax + hist + count + info + cgt + coff + cand + ps_zero + 2 * ps_range;
+    return minmax + hist + count + info + cgt + coff + cand + 2 * ps_range + (own_counters ? ps_zero : 0);
 }
 
 bool select_chunked_ok(int64_t n) { return (n + kSelChunk - 1) / kSelChunk <= kSelMaxChunks; }

@@ -191,6 +191,28 @@ def test_back_to_back_calls_reuse_the_scratch_state(snapkv):
     assert snapkv.snapkv_sync_timeouts() == 0
 
 
+def test_prompts_of_differing_length_back_to_back(snapkv):
+    """A batch of prompts of one model but different lengths, compressed one after the other in
+    any order: the ready state of the scratch carries over from longer to shorter prompts and
+    back, and every call still matches the oracle."""
+    lengths = [9000, 2300, 30000, 700, 30000, 5100, 9000]
+    cases = {}
+    for L in sorted(set(lengths)):
+        w = small(f"mix_{L}", Hq=8, Hkv=2, L=L, C=min(400, L // 2), seed=L)
+        cases[L] = (w, workloads.generate(w, device="cuda"))
+    refs = {}
+    for L, (w, c) in cases.items():
+        refs[L] = run_gpu(snapkv, c["q_win"], c["k"], c["v"], w.pool_kind, w.p, w.C)
+        check_against_oracle(c["q_win"], c["k"], c["v"], w.pool_kind, w.p, w.C, *refs[L])
+    for rounds in range(2):
+        for L in lengths:
+            w, c = cases[L]
+            got = _compress_only(snapkv, c, w)
+            assert np.array_equal(got[0], refs[L][3]), L
+            assert torch.equal(got[1], refs[L][1]) and torch.equal(got[2], refs[L][2]), L
+    assert snapkv.snapkv_sync_timeouts() == 0
+
+
 def test_explicit_workspace_matches(snapkv):
     w = small("ws", Hq=8, Hkv=4, L=2500, C=300)
     case = workloads.generate(w, device="cuda")
