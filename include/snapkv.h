@@ -155,6 +155,32 @@ int64_t snapkv_compress_strided(int dtype, const void* q_win, const void* k, con
                                 void* out_k, void* out_v, int32_t* out_idx, void* stream);
 
 /*
+ * One decoding step of attention over the compacted cache (Sec. 5.1.2: after compression a
+ * generated token attends to the C kept rows plus the rows appended since, so the cost of a step no
+ * longer grows with the prompt).  For every sequence b and query head h (reading KV head h / g):
+ *     out[b, h, :] = sum_j softmax_j(q[b, h] . k[b, h/g, j] / sqrt(D)) v[b, h/g, j],  j < S_b
+ *     out_lse[b, h] = log sum_j exp(q[b, h] . k[b, h/g, j] / sqrt(D))     (natural logarithm)
+ * The new token sees every valid row; the order of the rows does not matter.
+ *
+ *   dtype   SNAPKV_DTYPE_BF16 or SNAPKV_DTYPE_F16 (float32 storage: SNAPKV_ERR_UNSUPPORTED)
+ *   q       [B, Hq, D]        device, dtype: the new token's queries
+ *   k_cache, v_cache [B, Hkv, cap, D] device, dtype: row capacity `cap` per head, finite values
+ *   lens    [B] device int32 valid rows per sequence, or NULL: every sequence has S rows.  Values
+ *           are clamped to [0, cap]; a sequence with no rows gets out = 0 and out_lse = -inf.
+ *   S       1 <= S <= cap: the valid rows when lens is NULL, otherwise a hint of the typical
+ *           length (used only to choose how finely the keys are split over workgroups)
+ *   Hq % Hkv == 0, Hq / Hkv <= 16, D in {64, 128}
+ *   out     [B, Hq, D] device float32;  out_lse [B, Hq] device float32 or NULL
+ *
+ * Partial results of split key ranges live in a per-device buffer of their own that the library
+ * allocates on first use and grows when needed (hipMalloc); concurrent calls on different streams
+ * of one device would share it and race.  Returns SNAPKV_OK or a negative SNAPKV_ERR_* code.
+ */
+int snapkv_decode_attention(int dtype, const void* q, const void* k_cache, const void* v_cache,
+                            const int32_t* lens, int B, int Hq, int Hkv, int D, int64_t S, int64_t cap,
+                            float* out, float* out_lse, void* stream);
+
+/*
  * Top-(kcount) selection alone (Eq. 2), exposed for testing the selector on arbitrary scores:
  *   scores [H, n] device float32, all values >= +0 (their bit patterns are compared as unsigned
  *   integers); out_idx [H, kcount] device int32: the kcount best positions per row under

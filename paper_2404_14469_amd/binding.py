@@ -23,7 +23,8 @@ SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compr
            "snapkv_compress_ws", "snapkv_select_topk", "snapkv_release", "snapkv_profile_start",
            "snapkv_profile_stop", "snapkv_num_stages", "snapkv_stage_name", "snapkv_set_scoring_scheme",
            "snapkv_sync_timeouts", "snapkv_compress_lse", "snapkv_pooled_scores_lse",
-           "snapkv_compress_strided", "snapkv_compress_f16", "snapkv_pooled_scores_f16")
+           "snapkv_compress_strided", "snapkv_compress_f16", "snapkv_pooled_scores_f16",
+           "snapkv_decode_attention")
 
 _lib = None
 
@@ -71,6 +72,8 @@ def load():
                                      vp, vp, sz, vp]
     L.snapkv_select_topk.restype = i32
     L.snapkv_select_topk.argtypes = [vp, i32, i64, i64, vp, vp]
+    L.snapkv_decode_attention.restype = i32
+    L.snapkv_decode_attention.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, vp, vp, vp]
     L.snapkv_release.restype = None
     L.snapkv_release.argtypes = []
     L.snapkv_profile_start.restype = i32
@@ -282,6 +285,28 @@ def snapkv_select_topk(scores: torch.Tensor, kcount: int, out_idx: torch.Tensor,
         raise ValueError("out_idx must be [H, kcount]")
     _check(lib.snapkv_select_topk(_dev(scores, "scores", torch.float32), H, n, kcount,
                                   _dev(out_idx, "out_idx", torch.int32), _stream(stream)))
+
+
+def snapkv_decode_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, S: int,
+                            out: torch.Tensor, out_lse: Optional[torch.Tensor] = None,
+                            lens: Optional[torch.Tensor] = None, stream=None) -> None:
+    """q [B,Hq,D], k_cache/v_cache [B,Hkv,cap,D] (bf16 or fp16) -> out [B,Hq,D] float32 and, if given,
+    out_lse [B,Hq] float32; S valid rows per sequence, or lens [B] int32 on the GPU."""
+    lib = load()
+    B, Hq, D = q.shape
+    Bk, Hkv, cap, Dk = k_cache.shape
+    if (Bk, Dk) != (B, D) or tuple(v_cache.shape) != tuple(k_cache.shape):
+        raise ValueError("q, k_cache and v_cache disagree on their shapes")
+    if tuple(out.shape) != (B, Hq, D) or (out_lse is not None and tuple(out_lse.shape) != (B, Hq)):
+        raise ValueError("out must be [B, Hq, D] and out_lse [B, Hq]")
+    if lens is not None and tuple(lens.shape) != (B,):
+        raise ValueError("lens must be [B]")
+    code = _dtype_code(q)
+    _check(lib.snapkv_decode_attention(
+        code, _dev(q, "q"), _dev(k_cache, "k_cache", q.dtype), _dev(v_cache, "v_cache", q.dtype),
+        _dev(lens, "lens", torch.int32) if lens is not None else None, B, Hq, Hkv, D, int(S), cap,
+        _dev(out, "out", torch.float32), _dev(out_lse, "out_lse", torch.float32) if out_lse is not None else None,
+        _stream(stream)))
 
 
 def compress(q_win, k, v, pool_kind: int, p: int, C: int, stream=None

@@ -27,6 +27,8 @@ struct DeviceScratch {
     CleanState clean;
 };
 DeviceScratch g_scratch[kMaxDevices];
+DeviceScratch g_decode_scratch[kMaxDevices];   // partial results of decode attention: kept apart so that a
+                                               // decoding step leaves the compression scratch's ready state alone
 std::mutex g_mu;
 
 // Optional per-stage timing: events recorded on the caller's stream at stage boundaries.
@@ -475,6 +477,45 @@ int snapkv_select_topk(const float* scores, int H, int64_t n, int64_t kcount, in
     return SNAPKV_OK;
 }
 
+int snapkv_decode_attention(int dtype, const void* q, const void* k_cache, const void* v_cache,
+                            const int32_t* lens, int B, int Hq, int Hkv, int D, int64_t S, int64_t cap,
+                            float* out, float* out_lse, void* stream) {
+    if (!valid_dtype(dtype)) return SNAPKV_ERR_INVALID_ARG;
+    if (!q || !k_cache || !v_cache || !out) return SNAPKV_ERR_INVALID_ARG;
+    if (B < 1 || Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || cap < 1 || S < 1 || S > cap) return SNAPKV_ERR_INVALID_ARG;
+    if (dtype == SNAPKV_DTYPE_F32 || (D != 64 && D != 128)) return SNAPKV_ERR_UNSUPPORTED;
+    if (Hq / Hkv > 16 || Hkv > 65535 || B > 65535 || cap >= (int64_t)1 << 31) return SNAPKV_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k_cache) || !aligned16(v_cache)) return SNAPKV_ERR_MISALIGNED;
+    if ((reinterpret_cast<uintptr_t>(out) & 3u) != 0 || (reinterpret_cast<uintptr_t>(out_lse) & 3u) != 0 ||
+        (reinterpret_cast<uintptr_t>(lens) & 3u) != 0)
+        return SNAPKV_ERR_MISALIGNED;
+    const int nsplit = decode_splits(B, Hkv, S);
+    const size_t need = decode_scratch_bytes(B, Hq, D, nsplit);
+    void* base = nullptr;
+    if (need > 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SNAPKV_ERR_HIP;
+        std::lock_guard<std::mutex> lock(g_mu);
+        DeviceScratch& s = g_decode_scratch[dev];
+        if (s.bytes < need) {
+            if (s.ptr && hipFree(s.ptr) != hipSuccess) return SNAPKV_ERR_HIP;   // waits for work still using it
+            s.ptr = nullptr;
+            s.bytes = 0;
+            if (hipMalloc(&s.ptr, need * 2) != hipSuccess) {
+                s.ptr = nullptr;
+                (void)hipGetLastError();
+                return SNAPKV_ERR_HIP;
+            }
+            s.bytes = need * 2;
+        }
+        base = s.ptr;
+    }
+    return launch_decode(dtype, D, q, k_cache, v_cache, lens, B, Hq, Hkv, S, cap, nsplit, base, out, out_lse,
+                         static_cast<hipStream_t>(stream)) == hipSuccess
+               ? SNAPKV_OK
+               : SNAPKV_ERR_HIP;
+}
+
 void snapkv_release(void) {
     std::lock_guard<std::mutex> lock(g_mu);
     int cur = 0;
@@ -485,6 +526,12 @@ void snapkv_release(void) {
         g_scratch[d].ptr = nullptr;
         g_scratch[d].bytes = 0;
         g_scratch[d].clean = CleanState{};
+    }
+    for (int d = 0; d < kMaxDevices; ++d) {
+        if (!g_decode_scratch[d].ptr) continue;
+        if (hipSetDevice(d) == hipSuccess) (void)hipFree(g_decode_scratch[d].ptr);
+        g_decode_scratch[d].ptr = nullptr;
+        g_decode_scratch[d].bytes = 0;
     }
     if (have_cur) (void)hipSetDevice(cur);
 }

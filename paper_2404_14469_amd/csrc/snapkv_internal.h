@@ -123,6 +123,13 @@ hipError_t launch_pool_select(const ScoreGeom& G, const float* vote, int pool_ki
                               int64_t out_stride, int W_tail, int32_t* out_idx, const SelectScratch& S,
                               hipStream_t st);
 unsigned read_select_timeouts();
+
+// One decoding step of attention over a cache of [B, Hkv, cap, D] rows (snapkv_decode.hip).
+int decode_splits(int B, int Hkv, int64_t S);
+size_t decode_scratch_bytes(int B, int Hq, int D, int nsplit);
+hipError_t launch_decode(int dtype, int D, const void* q, const void* k, const void* v, const int32_t* lens,
+                         int B, int Hq, int Hkv, int64_t S, int64_t cap, int nsplit, void* scratch,
+                         float* out, float* lse, hipStream_t st);
 hipError_t launch_select_chunked(const float* score, int H, int64_t n, int64_t kcount,
                                  int64_t out_stride, int W_tail, int32_t* out_idx,
                                  const SelectScratch& S, int minmax_parts, hipStream_t st);

@@ -139,6 +139,64 @@ def generate(w: Workload, layer: int = 0, device: str = "cpu") -> Dict[str, obje
             "v": v.to(tdt).contiguous(), "centres": centres, "needle_pos": needle_pos}
 
 
+@dataclasses.dataclass(frozen=True)
+class DecodeWorkload:
+    """One decoding step over compacted caches: B sequences whose caches hold S valid rows of a
+    capacity of cap (the kept prompt rows plus the tokens generated since)."""
+    name: str
+    B: int
+    Hq: int
+    Hkv: int
+    D: int
+    S: int
+    cap: int
+    dtype: str = "bf16"
+    ragged: bool = False   # per-sequence lengths drawn in [1, S] instead of S everywhere
+    seed: int = 0
+
+
+# Sec. 5.1.2 benchmarks decoding with the cache capped at 2048 prompt rows and 512 generated
+# tokens on a 32-head, D=128 model at batch sizes 1 to 8: the last step attends to 2560 rows.
+DECODE_CAPPED_B8 = DecodeWorkload("decode_capped_b8", B=8, Hq=32, Hkv=32, D=128, S=2560, cap=2560, seed=2001)
+# The uncompressed cache of a 16K prompt at the batch size where the paper's baseline runs out of memory.
+DECODE_FULL_16K_B2 = DecodeWorkload("decode_full_16k_b2", B=2, Hq=32, Hkv=32, D=128, S=16384 + 512,
+                                    cap=16384 + 512, seed=2002)
+DECODE_CONFIGS: Dict[str, DecodeWorkload] = {w.name: w for w in (DECODE_CAPPED_B8, DECODE_FULL_16K_B2)}
+
+
+def generate_decode(w: DecodeWorkload, device: str = "cpu") -> Dict[str, object]:
+    """Draws q [B, Hq, D], k_cache and v_cache [B, Hkv, cap, D] ~ N(0, 1) and lens [B] int32 (or
+    None).  A few cache rows per (sequence, KV head) get += 2 * u for a unit vector u that the
+    queries of that group also get (+= 3 * u), so that the attention is peaked on a few rows as
+    it is on a cache that kept the rows the queries look for.  Rows beyond a sequence's length
+    hold large values that a correct result never sees."""
+    dev = torch.device(device)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    cpu_gen = torch.Generator(device="cpu")
+    cpu_gen.manual_seed(w.seed * 7919 + 17)
+    g = w.Hq // w.Hkv
+    q = torch.randn((w.B, w.Hq, w.D), generator=gen, device=dev, dtype=torch.float32)
+    k = torch.randn((w.B, w.Hkv, w.cap, w.D), generator=gen, device=dev, dtype=torch.float32)
+    v = torch.randn((w.B, w.Hkv, w.cap, w.D), generator=gen, device=dev, dtype=torch.float32)
+    lens = None
+    if w.ragged:
+        lens = torch.randint(1, w.S + 1, (w.B,), generator=cpu_gen, dtype=torch.int32)
+        lens[0] = w.S
+    u = _unit(gen, (w.B, w.Hkv, w.D), dev)
+    for b in range(w.B):
+        S = int(lens[b]) if lens is not None else w.S
+        rows = torch.randint(0, S, (4,), generator=cpu_gen).tolist()
+        for r in rows:
+            k[b, :, r, :] += 2.0 * u[b]
+        k[b, :, S:, :] = 1.0e4
+        v[b, :, S:, :] = -3.0e4
+    q += 3.0 * u.repeat_interleave(g, dim=1)
+    tdt = {"bf16": torch.bfloat16, "f16": torch.float16}[w.dtype]
+    return {"q": q.to(tdt).contiguous(), "k_cache": k.to(tdt).contiguous(), "v_cache": v.to(tdt).contiguous(),
+            "lens": lens.to(dev) if lens is not None else None}
+
+
 def to_numpy_bits(t: torch.Tensor):
     """Host copy of a tensor as a numpy array: fp32 as float32, fp16 as float16, bf16 as its uint16 bit
     patterns."""
