@@ -103,7 +103,7 @@ struct DecodeArgs {
     float2* part_ml;      // [B, Hq, nsplit]
 };
 
-constexpr int kDecWaves = 4;
+constexpr int kDecWaves = 4;   // four or eight waves measure the same; four keeps short caches unsplit
 
 template <typename T, int D>
 __global__ __launch_bounds__(kDecWaves * 64) void decode_attn(const DecodeArgs A) {
@@ -145,43 +145,33 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_attn(const DecodeArgs A
         return r < last_row ? r : last_row;   // rows past the end are read from the last valid row and masked
     };
 
-    uint4 kx[NP], ky[NP];
-    int64_t pair = p_begin + wave;
-    if (pair < p_end) {
-        const char* rx = kbase + row_of(pair, 0) * ROW;
-        const char* ry = kbase + row_of(pair, 1) * ROW;
+    // Both operands of a pair are requested one pair ahead into the other of two register sets,
+    // so a pair's arithmetic never waits for its own loads.  Every request is unconditional (past
+    // the end it repeats an in-range pair), which lets the compiler count the loads in flight.
+    struct PairRegs {
+        uint4 kx[NP], ky[NP], vx[NP], vy[NP];
+    };
+    auto request = [&](PairRegs& P, int64_t pr) {
+        const int64_t rx = row_of(pr, 0) * ROW, ry = row_of(pr, 1) * ROW;
 #pragma unroll
         for (int c = 0; c < NP; ++c) {
-            kx[c] = *reinterpret_cast<const uint4*>(rx + (4 * c + kg) * 16);
-            ky[c] = *reinterpret_cast<const uint4*>(ry + (4 * c + kg) * 16);
+            P.kx[c] = *reinterpret_cast<const uint4*>(kbase + rx + (4 * c + kg) * 16);
+            P.ky[c] = *reinterpret_cast<const uint4*>(kbase + ry + (4 * c + kg) * 16);
         }
-    }
-    for (; pair < p_end; pair += kDecWaves) {
-        // this pair's V and the next pair's K are requested before this pair's K is used
-        uint4 vx[NP], vy[NP], nx[NP], ny[NP];
-        {
-            const char* rx = vbase + row_of(pair, 0) * ROW;
-            const char* ry = vbase + row_of(pair, 1) * ROW;
 #pragma unroll
-            for (int c = 0; c < NP; ++c) {
-                vx[c] = *reinterpret_cast<const uint4*>(rx + (4 * c + kg) * 16);
-                vy[c] = *reinterpret_cast<const uint4*>(ry + (4 * c + kg) * 16);
-            }
-            const int64_t np = pair + kDecWaves < p_end ? pair + kDecWaves : pair;   // in range either way
-            const char* nrx = kbase + row_of(np, 0) * ROW;
-            const char* nry = kbase + row_of(np, 1) * ROW;
-#pragma unroll
-            for (int c = 0; c < NP; ++c) {
-                nx[c] = *reinterpret_cast<const uint4*>(nrx + (4 * c + kg) * 16);
-                ny[c] = *reinterpret_cast<const uint4*>(nry + (4 * c + kg) * 16);
-            }
+        for (int c = 0; c < NP; ++c) {
+            P.vx[c] = *reinterpret_cast<const uint4*>(vbase + rx + (4 * c + kg) * 16);
+            P.vy[c] = *reinterpret_cast<const uint4*>(vbase + ry + (4 * c + kg) * 16);
         }
+        __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the arithmetic that follows
+    };
+    auto process = [&](const PairRegs& P, int64_t pair) {
         // logits^T: lane (query n16, key group kg) gets keys 4*kg + r of X and of Y
         dfx4 sx = {0.f, 0.f, 0.f, 0.f}, sy = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int c = 0; c < NP; ++c) {
-            sx = mma(T{}, kx[c], qf[c], sx);
-            sy = mma(T{}, ky[c], qf[c], sy);
+            sx = mma(T{}, P.kx[c], qf[c], sx);
+            sy = mma(T{}, P.ky[c], qf[c], sy);
         }
         const int64_t key0 = pair * 32 + 4 * kg;
         float e[8];
@@ -217,8 +207,8 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_attn(const DecodeArgs A
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
                 const dfx4 z = {0.f, 0.f, 0.f, 0.f};
-                const dfx4 tx = mma(T{}, vx[c], half ? sel1 : sel0, z);
-                const dfx4 ty = mma(T{}, vy[c], half ? sel1 : sel0, z);
+                const dfx4 tx = mma(T{}, P.vx[c], half ? sel1 : sel0, z);
+                const dfx4 ty = mma(T{}, P.vy[c], half ? sel1 : sel0, z);
                 uint4 vt;
                 vt.x = pack_exact(T{}, tx[0], tx[1]);
                 vt.y = pack_exact(T{}, tx[2], tx[3]);
@@ -230,10 +220,20 @@ __global__ __launch_bounds__(kDecWaves * 64) void decode_attn(const DecodeArgs A
                 acc[2 * c + half] = o;
             }
         }
-#pragma unroll
-        for (int c = 0; c < NP; ++c) {
-            kx[c] = nx[c];
-            ky[c] = ny[c];
+    };
+    PairRegs R0, R1;
+    int64_t pair = p_begin + wave;
+    if (pair < p_end) {
+        request(R0, pair);
+        for (;;) {
+            request(R1, pair + kDecWaves < p_end ? pair + kDecWaves : pair);
+            process(R0, pair);
+            pair += kDecWaves;
+            if (pair >= p_end) break;
+            request(R0, pair + kDecWaves < p_end ? pair + kDecWaves : pair);
+            process(R1, pair);
+            pair += kDecWaves;
+            if (pair >= p_end) break;
         }
     }
     lsum += __shfl_xor(lsum, 16);
@@ -316,11 +316,12 @@ int cu_count() {
 
 }  // namespace
 
-// Splits of a (sequence, KV head) pair's keys: enough workgroups to fill the device a few times
-// over, at least 128 keys per wave, and 1 when the pairs alone are plenty.
+// Splits of a (sequence, KV head) pair's keys.  Measured: long-running workgroups, about one per
+// compute unit, stream best, so the keys are split only when the pairs alone leave units idle,
+// and never below 128 keys per wave.
 int decode_splits(int B, int Hkv, int64_t S) {
     const int64_t pairs = (int64_t)B * Hkv;
-    const int64_t want = (4LL * cu_count() + pairs - 1) / pairs;
+    const int64_t want = (cu_count() + pairs / 2) / pairs;
     const int64_t most = std::max<int64_t>(1, S / (128 * kDecWaves));
     return (int)std::max<int64_t>(1, std::min<int64_t>(std::min(want, most), 64));
 }
