@@ -34,6 +34,11 @@ step 3 a single exponential.  It is pinned to a hand-worked two-key case, to a l
 log-sum-exp over the visible keys, to the softmax path (true lse changes nothing) and to the
 row-scaling law of an offset lse.
 
+A third form, compress_per_query_head, keeps one cache per query head of a grouped-query model
+(the listing's equal head counts, reached by repeating KV heads); it is pinned to single-head
+problems solved one by one, to the grouped form at g = 1 and to planted keys that only one query
+head of a group looks for.
+
 Pins (tests/test_oracle_*.py): closed forms for all-zero queries (harmonic numbers, both
 pool kinds and the tie rule), softmax rows summing to one, mass conservation, shift
 invariance, permutation equivariance, nested selections, the W=1/p=1 special case against
@@ -214,3 +219,19 @@ def compress(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, W: int, pool_kind:
         out_k[oi] = k[hk][idx]
         out_v[oi] = v[hk][idx]
     return out_k, out_v, out_idx, C, score
+
+
+def compress_per_query_head(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, W: int, pool_kind: int,
+                            p: int, C: int):
+    """The step as Listing 1 states it, with one cache per *query* head: the listing's tensors have
+    equal head counts, which a grouped-query model reaches by repeating every KV head for the g
+    query heads that read it (query head h reads KV head h // g).  Each query head then votes,
+    pools and selects alone (no sum over the group, cf. step 6) and gets its own C kept rows.
+    Returns (out_k [Hq, kept, D], out_v, out_idx [Hq, kept], kept, score [Hq, n])."""
+    Hq = q_win.shape[0]
+    Hkv = k.shape[0]
+    if Hq % Hkv != 0:
+        raise ValueError("Hq must be a multiple of Hkv")
+    g = Hq // Hkv
+    return compress(q_win, np.repeat(k, g, axis=0), np.repeat(v, g, axis=0), W, pool_kind, p, C)
+

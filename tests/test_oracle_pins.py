@@ -487,3 +487,42 @@ def test_c_oracle_bypass_and_errors():
     with pytest.raises(ValueError):
         c_oracle.pooled_scores(q, k, 8, 0, 4)
     assert c_oracle.threads() >= 1
+
+
+# ----------------------------------------------------------------------------- one cache per query head
+def test_per_query_head_form_solves_each_head_alone():
+    # catches: h % g instead of h // g in the head mapping, any leakage between query heads
+    Hq, Hkv, L, D, W, C = 6, 2, 90, 8, 4, 20
+    q, k, v = rand_case(41, Hq, Hkv, L, D, W)
+    ok, ov, oi, kept, sc = orc.compress_per_query_head(q, k, v, W, orc.POOL_MAX, 3, C)
+    assert ok.shape == (Hq, C, D) and oi.shape == (Hq, C) and kept == C
+    for h in range(Hq):
+        hk = h // (Hq // Hkv)
+        a = orc.compress(q[h:h + 1], k[hk:hk + 1], v[hk:hk + 1], W, orc.POOL_MAX, 3, C)
+        assert np.array_equal(oi[h], a[2][0]) and np.array_equal(ok[h], a[0][0]) and np.array_equal(ov[h], a[1][0])
+        assert np.array_equal(sc[h], a[4][0])
+
+
+def test_per_query_head_form_equals_the_grouped_form_without_groups():
+    q, k, v = rand_case(42, 4, 4, 70, 8, 4)
+    a = orc.compress_per_query_head(q, k, v, 4, orc.POOL_AVG, 5, 16)
+    b = orc.compress(q, k, v, 4, orc.POOL_AVG, 5, 16)
+    assert all(np.array_equal(x, y) for x, y in zip(a[:3], b[:3])) and a[3] == b[3]
+
+
+def test_per_query_head_form_keeps_what_each_head_looks_for():
+    # two query heads of one group look for different planted keys: each keeps its own, the
+    # grouped form keeps both.  catches: a sum over the group left in the per-head form
+    Hq, Hkv, L, D, W, C = 2, 1, 64, 8, 2, 3
+    q = np.zeros((Hq, W, D), dtype=np.float32)
+    k = np.zeros((Hkv, L, D), dtype=np.float32)
+    v = np.arange(Hkv * L * D, dtype=np.float32).reshape(Hkv, L, D)
+    q[0, :, 0] = 30.0
+    q[1, :, 1] = 30.0
+    k[0, 10, 0] = 1.0
+    k[0, 40, 1] = 1.0
+    _, _, oi, _, _ = orc.compress_per_query_head(q, k, v, W, orc.POOL_MAX, 1, C)
+    assert oi[0].tolist() == [10, 62, 63] and oi[1].tolist() == [40, 62, 63]
+    _, _, og, _, _ = orc.compress(q, k, v, W, orc.POOL_MAX, 1, 4)
+    assert og[0].tolist() == [10, 40, 62, 63]
+
