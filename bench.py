@@ -124,9 +124,10 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scheme", type=int, default=0,
                     help="kernel scheme bits for measurements (see snapkv_set_scoring_scheme); 0 = default")
-    ap.add_argument("--entry", default="compress", choices=["compress", "lse"],
+    ap.add_argument("--entry", default="compress", choices=["compress", "lse", "per_query_head"],
                     help="compress (default): snapkv_compress, the headline path; lse: snapkv_compress_lse, "
-                         "the variant that is handed the window rows' log-sum-exp (a separate measurement)")
+                         "the variant that is handed the window rows' log-sum-exp; per_query_head: "
+                         "snapkv_compress_per_query_head, one cache per query head (separate measurements)")
     ap.add_argument("--layout", default="head_major", choices=["head_major", "token_major"],
                     help="storage order of K/V: [Hkv, L, D] (default) or [L, Hkv, D] through snapkv_compress_strided")
     ap.add_argument("--explicit-workspace", action="store_true",
@@ -174,9 +175,10 @@ def main() -> int:
             c["v"] = c["v"].permute(1, 0, 2).contiguous().permute(1, 0, 2)
         layers.append((c["q_win"], c["k"], c["v"]))
     torch.cuda.synchronize()
-    out_k = torch.empty((w.Hkv, w.C, w.D), dtype=layers[0][1].dtype, device=dev)
+    hout = w.Hq if args.entry == "per_query_head" else w.Hkv
+    out_k = torch.empty((hout, w.C, w.D), dtype=layers[0][1].dtype, device=dev)
     out_v = torch.empty_like(out_k)
-    out_idx = torch.empty((w.Hkv, w.C), dtype=torch.int32, device=dev)
+    out_idx = torch.empty((hout, w.C), dtype=torch.int32, device=dev)
     ws = None
     if args.explicit_workspace:
         ws = torch.empty(snapkv.snapkv_workspace_bytes(w.L, w.Hq, w.Hkv, w.D, w.W), dtype=torch.uint8, device=dev)
@@ -202,6 +204,9 @@ def main() -> int:
         q, k, v = layers[i % nres]
         if args.layout == "token_major":
             snapkv.snapkv_compress_strided(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx, stream=stream)
+            return
+        if args.entry == "per_query_head":
+            snapkv.snapkv_compress_per_query_head(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx, stream=stream)
             return
         if lses is not None:
             snapkv.snapkv_compress_lse(q, k, v, lses[i % nres], w.pool_kind, w.p, w.C, out_k, out_v, out_idx,
@@ -253,7 +258,7 @@ def main() -> int:
     }
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.entry != "per_query_head":
         from oracle import c_oracle
         # bounded sample: whole resident layers until about 1.5e11 multiply-adds of the scoring
         # product have been spent (tens of core-seconds on the host's cores)

@@ -155,6 +155,21 @@ int64_t snapkv_compress_strided(int dtype, const void* q_win, const void* k, con
                                 void* out_k, void* out_v, int32_t* out_idx, void* stream);
 
 /*
+ * The compression step with one cache per QUERY head (Listing 1 as printed has equal head counts;
+ * a grouped-query model reaches them by repeating every KV head for the g = Hq / Hkv query heads that
+ * read it).  Query head h scores the keys of KV head h / g, and votes, pools and selects alone (no
+ * sum over the group); its kept rows are gathered from that KV head.  Arguments as for
+ * snapkv_compress except:
+ *   dtype   SNAPKV_DTYPE_*
+ *   out_k, out_v [Hq, C, D] device, dtype;   out_idx [Hq, C] device int32
+ * With Hq == Hkv the result equals snapkv_compress.  SNAPKV_ERR_UNSUPPORTED for windows of more than
+ * 128 rows per query head.  Scratch comes from the library's per-device buffer.
+ */
+int64_t snapkv_compress_per_query_head(int dtype, const void* q_win, const void* k, const void* v, int64_t L,
+                                       int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
+                                       void* out_k, void* out_v, int32_t* out_idx, void* stream);
+
+/*
  * One decoding step of attention over the compacted cache (Sec. 5.1.2: after compression a
  * generated token attends to the C kept rows plus the rows appended since, so the cost of a step no
  * longer grows with the prompt).  For every sequence b and query head h (reading KV head h / g):

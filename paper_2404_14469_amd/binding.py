@@ -24,7 +24,7 @@ SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compr
            "snapkv_profile_stop", "snapkv_num_stages", "snapkv_stage_name", "snapkv_set_scoring_scheme",
            "snapkv_sync_timeouts", "snapkv_compress_lse", "snapkv_pooled_scores_lse",
            "snapkv_compress_strided", "snapkv_compress_f16", "snapkv_pooled_scores_f16",
-           "snapkv_decode_attention")
+           "snapkv_decode_attention", "snapkv_compress_per_query_head")
 
 _lib = None
 
@@ -72,6 +72,8 @@ def load():
                                      vp, vp, sz, vp]
     L.snapkv_select_topk.restype = i32
     L.snapkv_select_topk.argtypes = [vp, i32, i64, i64, vp, vp]
+    L.snapkv_compress_per_query_head.restype = i64
+    L.snapkv_compress_per_query_head.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
     L.snapkv_decode_attention.restype = i32
     L.snapkv_decode_attention.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, vp, vp, vp]
     L.snapkv_release.restype = None
@@ -285,6 +287,22 @@ def snapkv_select_topk(scores: torch.Tensor, kcount: int, out_idx: torch.Tensor,
         raise ValueError("out_idx must be [H, kcount]")
     _check(lib.snapkv_select_topk(_dev(scores, "scores", torch.float32), H, n, kcount,
                                   _dev(out_idx, "out_idx", torch.int32), _stream(stream)))
+
+
+def snapkv_compress_per_query_head(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, pool_kind: int, p: int,
+                                   C: int, out_k: torch.Tensor, out_v: torch.Tensor, out_idx: torch.Tensor,
+                                   stream=None) -> int:
+    """One cache per query head: q_win [Hq,W,D], k/v [Hkv,L,D] -> out_k/out_v [Hq,C,D], out_idx [Hq,C]."""
+    lib = load()
+    Hq, Hkv, L, D, W = _shapes(q_win, k)
+    if tuple(out_k.shape) != (Hq, C, D) or tuple(out_v.shape) != (Hq, C, D) or tuple(out_idx.shape) != (Hq, C):
+        raise ValueError("out_k/out_v must be [Hq, C, D] and out_idx [Hq, C]")
+    code = _dtype_code(q_win)
+    kept = lib.snapkv_compress_per_query_head(
+        code, _dev(q_win, "q_win"), _dev(k, "k", q_win.dtype), _dev(v, "v", q_win.dtype), L, Hq, Hkv, D, W,
+        int(pool_kind), int(p), int(C), _dev(out_k, "out_k", q_win.dtype), _dev(out_v, "out_v", q_win.dtype),
+        _dev(out_idx, "out_idx", torch.int32), _stream(stream))
+    return _check(kept)
 
 
 def snapkv_decode_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, S: int,

@@ -17,7 +17,7 @@ constexpr int kMaxDevices = 64;
 // published" pattern.  ones < 0: nothing is known.  Anything else that touches the buffer
 // resets it.
 struct CleanState {
-    int hkv = 0;
+    int hkv = 0, hq = 0;
     size_t fused_bytes = 0;
     int64_t ones = -1;
 };
@@ -105,7 +105,7 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
     if (lse) {   // the rows' normalisers are given: one streaming pass, nothing handed between workgroups
         if (!lse_plan(dtype, D, G, &F)) return SNAPKV_ERR_UNSUPPORTED;
         if (!already_prepared && prepare_select) {
-            if (launch_prepare(nullptr, 0, &ws.sel, G.Hkv, st) != hipSuccess) return SNAPKV_ERR_HIP;
+            if (launch_prepare(nullptr, 0, &ws.sel, G.Hkv * G.g, st) != hipSuccess) return SNAPKV_ERR_HIP;
             stage_done(st, kStagePrepare);
         }
         if (launch_score_lse(dtype, D, q_win, k, lse, G, F, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
@@ -123,7 +123,7 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
     if (fused) fused_sync_layout(G, F, &S, ws.fused);
     if (!already_prepared) {
         if (launch_prepare(fused ? S.part : nullptr, fused ? fused_sync_pairs(F) : 0,
-                           prepare_select ? &ws.sel : nullptr, G.Hkv, st) != hipSuccess)
+                           prepare_select ? &ws.sel : nullptr, G.Hkv * G.g, st) != hipSuccess)   // scratch is laid out per query head
             return SNAPKV_ERR_HIP;
         stage_done(st, kStagePrepare);
     }
@@ -158,7 +158,8 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
                       int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k,
                       void* out_v, int32_t* out_idx, void* workspace, size_t workspace_bytes,
                       bool own_scratch, void* stream, const float* lse = nullptr, bool with_lse = false,
-                      const RowLayout* k_layout = nullptr, const RowLayout* v_layout = nullptr) {
+                      const RowLayout* k_layout = nullptr, const RowLayout* v_layout = nullptr,
+                      bool per_query_head = false) {
     if (!valid_dtype(dtype)) return SNAPKV_ERR_INVALID_ARG;
     if (with_lse && !lse) return SNAPKV_ERR_INVALID_ARG;
     if (with_lse && (reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
@@ -179,9 +180,12 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
         if (((x->row_stride | x->head_stride) & 15) != 0) return SNAPKV_ERR_MISALIGNED;
     }
 
+    // heads that select and keep rows: the KV heads, or every query head for itself
+    const int Hout = per_query_head ? Hq : Hkv;
+    const int head_div = per_query_head ? Hq / Hkv : 1;
     if (L <= C) {   // Listing 1, first branch: the prompt already fits
-        if (launch_iota(Hkv, L, C, out_idx, st) != hipSuccess) return SNAPKV_ERR_HIP;
-        if (launch_gather(k, v, out_idx, Hkv, L, L, C, row_bytes, out_k, out_v, kl, vl, CleanJob{}, st) != hipSuccess)
+        if (launch_iota(Hout, L, C, out_idx, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        if (launch_gather(k, v, out_idx, Hout, L, L, C, row_bytes, out_k, out_v, kl, vl, CleanJob{}, st, head_div) != hipSuccess)
             return SNAPKV_ERR_HIP;
         return L;
     }
@@ -208,7 +212,18 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     DeviceScratch* mine = nullptr;      // the library's own buffer: its state is tracked between calls
     CleanState now;
     bool streaming = false;
-    if (g_allow_pool_select && pool_select_ok(G, pool_kind, p, C - W)) {   // pooling and selection in one launch
+    // Per-query-head form: the votes are laid out [Hq][n] (one row per query head, which the
+    // single-read and streaming kernels produce), so pooling and selection see Hq heads of one.
+    ScoreGeom Gsel = G;
+    if (per_query_head) {
+        FusedGeom Ft;
+        if (!lse_plan(dtype, D, G, &Ft)) return SNAPKV_ERR_UNSUPPORTED;   // more window rows than those kernels take
+        Gsel.Hkv = Hq;
+        Gsel.g = 1;
+        Gsel.NV = 1;
+        Gsel.VB = 1;
+    }
+    if (g_allow_pool_select && pool_select_ok(Gsel, pool_kind, p, C - W)) {   // pooling and selection in one launch
         bool prepared = false;
         FusedGeom Fp;
         // which scoring path run_scores will take: 1 single-read (uses the hand-off words), 2 streaming
@@ -222,8 +237,9 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
                 // the streaming path does not touch the hand-off words
                 const int64_t nones = streaming ? 0 : fused_sync_pairs(Fp);
                 now.hkv = Hkv;
+                now.hq = Hq;
                 now.fused_bytes = fused_sync_bytes(G);
-                const bool same = was_clean.ones >= 0 && was_clean.hkv == now.hkv &&
+                const bool same = was_clean.ones >= 0 && was_clean.hkv == now.hkv && was_clean.hq == now.hq &&
                                   was_clean.fused_bytes == now.fused_bytes;
                 prepared = same && was_clean.ones >= nones;
                 now.ones = same && was_clean.ones > nones ? was_clean.ones : nones;
@@ -234,21 +250,32 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
         rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, true, &Gv, st, prepared,
                         mine ? &clean : nullptr, lse);
         if (rc != SNAPKV_OK) return rc;
+        if (per_query_head) Gv = Gsel;
         se = launch_pool_select(Gv, ws.vote, pool_kind, p, C - W, C, W, out_idx, ws.sel, st);
         if (mine) {
             clean.zeros = ws.sel.ps_arrive;
             clean.nzeros = ws.sel.ps_zero_words;
         }
     } else {
-        rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr,
-                        chunked, nullptr, st, false, nullptr, lse);
-        if (rc != SNAPKV_OK) return rc;
-        se = chunked ? launch_select_chunked(ws.score, Hkv, G.n, C - W, C, W, out_idx, ws.sel, pool_tiles(G.n), st)
-                     : launch_select(ws.score, Hkv, G.n, C - W, C, W, out_idx, st);
+        if (per_query_head) {   // votes first, then pooled per query head
+            ScoreGeom Gv = G;
+            rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, chunked, &Gv, st, false, nullptr, lse);
+            if (rc != SNAPKV_OK) return rc;
+            if (Gv.VB != 1 || Gv.NV != G.g) return SNAPKV_ERR_UNSUPPORTED;
+            if (launch_pool(Gsel, ws.vote, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr, st) != hipSuccess)
+                return SNAPKV_ERR_HIP;
+            stage_done(st, kStagePool);
+        } else {
+            rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr,
+                            chunked, nullptr, st, false, nullptr, lse);
+            if (rc != SNAPKV_OK) return rc;
+        }
+        se = chunked ? launch_select_chunked(ws.score, Hout, G.n, C - W, C, W, out_idx, ws.sel, pool_tiles(G.n), st)
+                     : launch_select(ws.score, Hout, G.n, C - W, C, W, out_idx, st);
     }
     if (se != hipSuccess) return SNAPKV_ERR_HIP;
     stage_done(st, kStageSelect);
-    if (launch_gather(k, v, out_idx, Hkv, L, C, C, row_bytes, out_k, out_v, kl, vl, clean, st) != hipSuccess)
+    if (launch_gather(k, v, out_idx, Hout, L, C, C, row_bytes, out_k, out_v, kl, vl, clean, st, head_div) != hipSuccess)
         return SNAPKV_ERR_HIP;
     if (mine && (clean.ones || streaming) && clean.zeros) {
         std::lock_guard<std::mutex> lock(g_mu);
@@ -448,6 +475,13 @@ int64_t snapkv_compress_strided(int dtype, const void* q_win, const void* k, con
     const RowLayout kl{k_head_stride * es, k_row_stride * es}, vl{v_head_stride * es, v_row_stride * es};
     return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
                          nullptr, 0, true, stream, nullptr, false, &kl, &vl);
+}
+
+int64_t snapkv_compress_per_query_head(int dtype, const void* q_win, const void* k, const void* v, int64_t L,
+                                       int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
+                                       void* out_k, void* out_v, int32_t* out_idx, void* stream) {
+    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
+                         nullptr, 0, true, stream, nullptr, false, nullptr, nullptr, true);
 }
 
 size_t snapkv_workspace_bytes(int64_t L, int Hq, int Hkv, int D, int W) {

@@ -145,13 +145,15 @@ struct CleanJob {
     unsigned* zeros = nullptr;
     int64_t nzeros = 0;
 };
-// Byte strides of a [heads, rows, D] tensor whose rows are contiguous.
+// Byte strides of a [heads, rows, D] tensor whose rows are contiguous.  launch_gather writes H
+// output heads; output head h reads source head h / head_div.
 struct RowLayout {
     int64_t head_stride, row_stride;
 };
 hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H, int64_t L,
                          int64_t rows, int64_t out_stride, int row_bytes, void* out_k, void* out_v,
-                         const RowLayout& kl, const RowLayout& vl, const CleanJob& clean, hipStream_t st);
+                         const RowLayout& kl, const RowLayout& vl, const CleanJob& clean, hipStream_t st,
+                         int head_div = 1);
 
 }  // namespace snapkv
 #endif

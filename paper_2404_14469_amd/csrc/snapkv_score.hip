@@ -315,15 +315,17 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 // The two regions whose contents carry over between calls come first, at offsets that depend on
 // the number of KV heads only: pool_select's counters (zero when idle), then the hand-off words of
-// the single-read scoring kernel (all-ones when idle).
+// the single-read scoring kernel (all-ones when idle).  The selection's scratch and the scores are
+// sized for one selection per query head, which the per-query-head form of the step runs.
 size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base) {
     char* b = static_cast<char*>(base);
-    const size_t counters = select_counter_bytes(G.Hkv);
+    const int Hsel = G.Hkv * G.g;
+    const size_t counters = select_counter_bytes(Hsel);
     const size_t fused = fused_sync_bytes(G);
     const size_t part = align_up(sizeof(float2) * (size_t)G.Hkv * G.nchunks * G.R32 * 32);
     const size_t mz = align_up(sizeof(float2) * (size_t)G.Hkv * G.R32 * 32);
     const size_t vote = align_up(sizeof(float) * (size_t)G.Hkv * G.NV * (size_t)(G.n > 0 ? G.n : 1));
-    const size_t score = align_up(sizeof(float) * (size_t)G.Hkv * (size_t)(G.n > 0 ? G.n : 1));
+    const size_t score = align_up(sizeof(float) * (size_t)Hsel * (size_t)(G.n > 0 ? G.n : 1));
     const size_t stat = stream_stat_bytes(G);
     const size_t lse = align_up(sizeof(float) * (size_t)G.Hkv * G.g * G.W);
     const size_t off = counters + fused;
@@ -336,7 +338,7 @@ size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base) {
         ws->stat_part = reinterpret_cast<float2*>(b + off + part + mz + vote + score);
         ws->lse = reinterpret_cast<float*>(b + off + part + mz + vote + score + stat);
     }
-    const size_t sel = select_layout(G.Hkv, G.n, ws ? &ws->sel : nullptr,
+    const size_t sel = select_layout(Hsel, G.n, ws ? &ws->sel : nullptr,
                                      ws ? b + off + part + mz + vote + score + stat + lse : nullptr, false,
                                      ws ? b : nullptr);
     return off + part + mz + vote + score + stat + lse + sel;

@@ -213,6 +213,54 @@ def test_prompts_of_differing_length_back_to_back(snapkv):
     assert snapkv.snapkv_sync_timeouts() == 0
 
 
+def _per_query_head(snapkv, w, case):
+    q, k, v = case["q_win"], case["k"], case["v"]
+    out_k = torch.zeros((w.Hq, w.C, w.D), dtype=k.dtype, device="cuda")
+    out_v = torch.zeros_like(out_k)
+    out_idx = torch.full((w.Hq, w.C), -1, dtype=torch.int32, device="cuda")
+    kept = snapkv.snapkv_compress_per_query_head(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx)
+    torch.cuda.synchronize()
+    return out_k, out_v, out_idx.cpu().numpy(), kept
+
+
+PER_HEAD_CASES = [
+    (small("pqh_gqa4_w32", Hq=16, Hkv=4, L=2200, C=300), True),      # same launch shape as the repeated-head run
+    (small("pqh_gqa2_w16", Hq=8, Hkv=4, L=1500, W=16, C=200, pool_kind=1, p=5), False),
+    (small("pqh_gqa8_d64", Hq=16, Hkv=2, D=64, L=3000, W=32, C=256, p=13), False),
+    (small("pqh_mha", Hq=4, Hkv=4, L=1300, C=160), True),
+    (small("pqh_f16", Hq=8, Hkv=2, L=1800, C=256, dtype="f16"), False),
+    (small("pqh_bypass", Hq=8, Hkv=2, L=120, C=160), True),
+    (small("pqh_two_pass_select", Hq=8, Hkv=2, L=40000, C=1024), False),
+]
+
+
+@pytest.mark.parametrize("w,exact", PER_HEAD_CASES, ids=lambda x: x.name if hasattr(x, "name") else str(x))
+def test_one_cache_per_query_head(snapkv, scheme, w, exact):
+    """snapkv_compress_per_query_head against the oracle's per-query-head form, which is the
+    equal-head-count step on KV heads repeated g times: the checker gets the repeated tensors."""
+    case = workloads.generate(w, device="cuda")
+    out_k, out_v, out_idx, kept = _per_query_head(snapkv, w, case)
+    g = w.Hq // w.Hkv
+    k_rep = case["k"].repeat_interleave(g, dim=0).contiguous()
+    v_rep = case["v"].repeat_interleave(g, dim=0).contiguous()
+    scores = None
+    if w.L > w.C:
+        sc = torch.empty((w.Hq, w.n), dtype=torch.float32, device="cuda")
+        snapkv.snapkv_pooled_scores(case["q_win"], k_rep, w.pool_kind, w.p, sc)
+        scores = sc.cpu().numpy()
+    check_against_oracle(case["q_win"], k_rep, v_rep, w.pool_kind, w.p, w.C, scores, out_k, out_v, out_idx, kept,
+                         own_topk_exact=exact and scheme != 1)
+    assert snapkv.snapkv_sync_timeouts() == 0
+
+
+def test_per_query_head_equals_grouped_call_without_groups(snapkv):
+    w = small("pqh_eq", Hq=4, Hkv=4, L=2100, C=256)
+    case = workloads.generate(w, device="cuda")
+    a = _per_query_head(snapkv, w, case)
+    b = _compress_only(snapkv, case, w)
+    assert np.array_equal(a[2], b[0]) and torch.equal(a[0], b[1]) and torch.equal(a[1], b[2])
+
+
 def test_explicit_workspace_matches(snapkv):
     w = small("ws", Hq=8, Hkv=4, L=2500, C=300)
     case = workloads.generate(w, device="cuda")
