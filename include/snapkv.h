@@ -170,6 +170,14 @@ int64_t snapkv_compress_per_query_head(int dtype, const void* q_win, const void*
                                        void* out_k, void* out_v, int32_t* out_idx, void* stream);
 
 /*
+ * Capacity for the rate form of the selection size (Sec. 4, "Voting": k = floor(rate * L_prefix) prefix
+ * positions are kept, L_prefix = L - W): returns C = W + floor(rate * (L - W)), the value to pass as `C`
+ * to the compress entry points.  The product is taken in IEEE double.  Host-only arithmetic; returns
+ * SNAPKV_ERR_INVALID_ARG unless 0 <= rate <= 1 and 1 <= W <= L.
+ */
+int64_t snapkv_capacity_for_rate(int64_t L, int W, double rate);
+
+/*
  * One decoding step of attention over the compacted cache (Sec. 5.1.2: after compression a
  * generated token attends to the C kept rows plus the rows appended since, so the cost of a step no
  * longer grows with the prompt).  For every sequence b and query head h (reading KV head h / g):

@@ -235,3 +235,13 @@ def compress_per_query_head(q_win: np.ndarray, k: np.ndarray, v: np.ndarray, W: 
     g = Hq // Hkv
     return compress(q_win, np.repeat(k, g, axis=0), np.repeat(v, g, axis=0), W, pool_kind, p, C)
 
+
+def capacity_for_rate(L: int, W: int, rate: float) -> int:
+    """Capacity C = W + k for the rate form of Sec. 4 ("Voting"): k = floor(rate * L_prefix) prefix
+    positions are kept, L_prefix = L - W.  The product is taken in IEEE double, as printed (no
+    rational arithmetic): 0.29 * 100 is 28.999999999999996 and gives 28."""
+    if not (0.0 <= rate <= 1.0) or W < 1 or W > L:
+        raise ValueError("rate must be in [0, 1] and 1 <= W <= L")
+    import math
+    return W + int(math.floor(float(rate) * float(L - W)))
+

@@ -24,7 +24,8 @@ SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compr
            "snapkv_profile_stop", "snapkv_num_stages", "snapkv_stage_name", "snapkv_set_scoring_scheme",
            "snapkv_sync_timeouts", "snapkv_compress_lse", "snapkv_pooled_scores_lse",
            "snapkv_compress_strided", "snapkv_compress_f16", "snapkv_pooled_scores_f16",
-           "snapkv_decode_attention", "snapkv_compress_per_query_head")
+           "snapkv_decode_attention", "snapkv_compress_per_query_head",
+           "snapkv_capacity_for_rate")
 
 _lib = None
 
@@ -74,6 +75,8 @@ def load():
     L.snapkv_select_topk.argtypes = [vp, i32, i64, i64, vp, vp]
     L.snapkv_compress_per_query_head.restype = i64
     L.snapkv_compress_per_query_head.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
+    L.snapkv_capacity_for_rate.restype = i64
+    L.snapkv_capacity_for_rate.argtypes = [i64, i32, ctypes.c_double]
     L.snapkv_decode_attention.restype = i32
     L.snapkv_decode_attention.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, vp, vp, vp]
     L.snapkv_release.restype = None
@@ -303,6 +306,11 @@ def snapkv_compress_per_query_head(q_win: torch.Tensor, k: torch.Tensor, v: torc
         int(pool_kind), int(p), int(C), _dev(out_k, "out_k", q_win.dtype), _dev(out_v, "out_v", q_win.dtype),
         _dev(out_idx, "out_idx", torch.int32), _stream(stream))
     return _check(kept)
+
+
+def snapkv_capacity_for_rate(L: int, W: int, rate: float) -> int:
+    """C = W + floor(rate * (L - W)): the capacity that keeps the given share of the prefix."""
+    return _check(load().snapkv_capacity_for_rate(int(L), int(W), float(rate)))
 
 
 def snapkv_decode_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, S: int,

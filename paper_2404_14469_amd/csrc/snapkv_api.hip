@@ -3,6 +3,7 @@
 #include "../../include/snapkv.h"
 #include "snapkv_internal.h"
 
+#include <cmath>
 #include <mutex>
 #include <vector>
 
@@ -482,6 +483,11 @@ int64_t snapkv_compress_per_query_head(int dtype, const void* q_win, const void*
                                        void* out_k, void* out_v, int32_t* out_idx, void* stream) {
     return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
                          nullptr, 0, true, stream, nullptr, false, nullptr, nullptr, true);
+}
+
+int64_t snapkv_capacity_for_rate(int64_t L, int W, double rate) {
+    if (!(rate >= 0.0 && rate <= 1.0) || W < 1 || W > L) return SNAPKV_ERR_INVALID_ARG;
+    return (int64_t)W + (int64_t)std::floor(rate * (double)(L - W));
 }
 
 size_t snapkv_workspace_bytes(int64_t L, int Hq, int Hkv, int D, int W) {

@@ -91,6 +91,21 @@ def test_scores_and_select_reject_bad_arguments():
     assert lib.snapkv_compress_ws(*args, 0x10010, need, None) == -3
 
 
+def test_capacity_for_rate_matches_the_oracle():
+    """Host arithmetic, so it runs without a GPU: both sides floor the same IEEE-double product."""
+    import random
+    from oracle import snapkv_oracle as orc
+    rnd = random.Random(5)
+    cases = [(100 + 32, 32, 0.29), (1000, 32, 0.0), (1000, 32, 1.0), (35, 32, 0.999), (131072, 32, 0.03125)]
+    cases += [(rnd.randint(40, 200000), rnd.choice([1, 16, 32, 64]), rnd.random()) for _ in range(200)]
+    for L, W, rate in cases:
+        assert pkg.snapkv_capacity_for_rate(L, W, rate) == orc.capacity_for_rate(L, W, rate), (L, W, rate)
+    assert pkg.snapkv_capacity_for_rate(132, 32, 0.29) == 32 + 28      # 0.29 * 100 is just under 29 in double
+    for bad in ((100, 32, -0.1), (100, 32, 1.01), (100, 0, 0.5), (10, 32, 0.5), (100, 32, float("nan"))):
+        with pytest.raises(pkg.SnapKVError):
+            pkg.snapkv_capacity_for_rate(*bad)
+
+
 def test_workspace_bytes():
     assert pkg.snapkv_workspace_bytes(0, 8, 8, 128, 32) == 0
     assert pkg.snapkv_workspace_bytes(4096, 8, 3, 128, 32) == 0

@@ -526,3 +526,19 @@ def test_per_query_head_form_keeps_what_each_head_looks_for():
     _, _, og, _, _ = orc.compress(q, k, v, W, orc.POOL_MAX, 1, 4)
     assert og[0].tolist() == [10, 40, 62, 63]
 
+
+# ----------------------------------------------------------------------------- rate-form capacity
+def test_capacity_for_rate_closed_cases():
+    # catches: rounding up or to nearest instead of down, the rate applied to L instead of L - W
+    assert orc.capacity_for_rate(1000, 32, 0.0) == 32
+    assert orc.capacity_for_rate(1000, 32, 1.0) == 1000
+    assert orc.capacity_for_rate(1032, 32, 0.5) == 32 + 500
+    assert orc.capacity_for_rate(1033, 32, 0.5) == 32 + 500          # floor(500.5)
+    assert orc.capacity_for_rate(132, 32, 0.25) == 32 + 25
+    assert orc.capacity_for_rate(35, 32, 0.999) == 32 + 2            # floor(2.997)
+    for n in (1, 7, 100, 4096):
+        for num, den in ((1, 2), (1, 4), (3, 8), (5, 16)):           # dyadic rates: the product is exact
+            assert orc.capacity_for_rate(n + 16, 16, num / den) == 16 + (n * num) // den
+    with pytest.raises(ValueError):
+        orc.capacity_for_rate(100, 32, 1.5)
+
