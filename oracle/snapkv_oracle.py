@@ -39,6 +39,11 @@ A third form, compress_per_query_head, keeps one cache per query head of a group
 problems solved one by one, to the grouped form at g = 1 and to planted keys that only one query
 head of a group looks for.
 
+The hit rate of Sec. 4 (Eq. 3-7; current_attention, hit_rate_counts, hit_rate) is a quality probe:
+how many of the positions the generated token attends to above a threshold the voting had kept.
+Pinned to a uniform field (zero query), to planted keys with a hand-counted overlap and to a loop
+over Python sets on tiny inputs.
+
 Pins (tests/test_oracle_*.py): closed forms for all-zero queries (harmonic numbers, both
 pool kinds and the tie rule), softmax rows summing to one, mass conservation, shift
 invariance, permutation equivariance, nested selections, the W=1/p=1 special case against
@@ -244,4 +249,44 @@ def capacity_for_rate(L: int, W: int, rate: float) -> int:
         raise ValueError("rate must be in [0, 1] and 1 <= W <= L")
     import math
     return W + int(math.floor(float(rate) * float(L - W)))
+
+
+def current_attention(q_cur: np.ndarray, k: np.ndarray) -> np.ndarray:
+    """A_cur of Sec. 4 ("Hit Rate") before it is cut to the prefix: the softmax-normalised attention
+    of the query of the token being generated, q_cur [Hq, D], over all Lk keys it sees, k [Hkv, Lk, D]
+    (query head h reads KV head h // g; scale 1/sqrt(D) as everywhere).  Returns [Hq, Lk] float64."""
+    q_cur = widen(q_cur)
+    k = widen(k)
+    Hq, D = q_cur.shape
+    Hkv = k.shape[0]
+    g = Hq // Hkv
+    A = np.empty((Hq, k.shape[1]), dtype=np.float64)
+    for h in range(Hq):
+        s = k[h // g] @ q_cur[h] / np.sqrt(float(D))
+        e = np.exp(s - s.max())
+        A[h] = e / e.sum()
+    return A
+
+
+def hit_rate_counts(A_cur: np.ndarray, idx: np.ndarray, theta: float):
+    """Eq. 3-7 as counts.  A_cur [Hq, n]: current attention over the n prefix positions; idx
+    [Hidx, kc]: the prefix positions voting selected, per KV head (Hidx = Hkv: query head h is checked
+    against the selection of its KV head) or per query head (Hidx = Hq).  Per query head:
+    important = number of positions with A_cur > theta (the threshold mask), hits = number of those
+    that are selected (the overlap O).  The hit rate is H = sum(hits) / sum(important)."""
+    Hq, n = A_cur.shape
+    Hidx = idx.shape[0]
+    div = Hq // Hidx
+    M_vote = np.zeros((Hq, n), dtype=bool)
+    for h in range(Hq):
+        M_vote[h, idx[h // div]] = True
+    M_thr = A_cur > theta
+    O = np.logical_and(M_thr, M_vote)
+    return M_thr.sum(axis=1).astype(np.int64), O.sum(axis=1).astype(np.int64)
+
+
+def hit_rate(important: np.ndarray, hits: np.ndarray) -> float:
+    """H of Eq. 7 from the counts; nan when nothing is above the threshold."""
+    tot = int(np.sum(important))
+    return float(np.sum(hits)) / tot if tot > 0 else float("nan")
 

@@ -542,3 +542,69 @@ def test_capacity_for_rate_closed_cases():
     with pytest.raises(ValueError):
         orc.capacity_for_rate(100, 32, 1.5)
 
+
+# ----------------------------------------------------------------------------- hit rate (Eq. 3-7)
+def test_hit_rate_uniform_attention():
+    # zero query: A_cur = 1/Lk everywhere.  Below that value every prefix position is important and
+    # the hits are the selected ones; above it nothing is.  catches: >= instead of >, a wrong denominator
+    Hq, Hkv, Lk, n, D = 4, 2, 50, 40, 8
+    q = np.zeros((Hq, D), dtype=np.float32)
+    k = np.random.default_rng(3).standard_normal((Hkv, Lk, D)).astype(np.float32)
+    A = orc.current_attention(q, k)
+    assert np.allclose(A, 1.0 / Lk, rtol=0, atol=1e-16) and A.shape == (Hq, Lk)
+    idx = np.array([[1, 5, 9], [0, 2, 39]])
+    imp, hits = orc.hit_rate_counts(A[:, :n], idx, 0.5 / Lk)
+    assert imp.tolist() == [n] * Hq and hits.tolist() == [3] * Hq
+    assert orc.hit_rate(imp, hits) == 3 / n
+    imp, hits = orc.hit_rate_counts(A[:, :n], idx, 1.0 / Lk + 1e-12)
+    assert imp.sum() == 0 and hits.sum() == 0 and np.isnan(orc.hit_rate(imp, hits))
+    imp, hits = orc.hit_rate_counts(np.full((Hq, n), 0.25), idx, 0.25)      # equality is not above
+    assert imp.sum() == 0
+
+
+def test_hit_rate_planted_keys_hand_counted():
+    # head 0 looks at keys 3 and 20, head 1 at key 7 and at key 45, which lies outside the prefix
+    Hq, Hkv, Lk, n, D = 2, 2, 48, 40, 4
+    q = np.zeros((Hq, D), dtype=np.float32)
+    k = np.zeros((Hkv, Lk, D), dtype=np.float32)
+    q[0, 0] = 20.0
+    q[1, 1] = 20.0
+    k[0, 3, 0] = k[0, 20, 0] = 1.0
+    k[1, 7, 1] = k[1, 45, 1] = 1.0
+    A = orc.current_attention(q, k)
+    assert abs(A[0, 3] - 0.5) < 1e-3 and abs(A[1, 45] - 0.5) < 1e-3 and np.allclose(A.sum(axis=1), 1.0)
+    idx = np.array([[3, 4], [8, 9]])                 # head 0 kept one of its two keys, head 1 none
+    imp, hits = orc.hit_rate_counts(A[:, :n], idx, 0.1)
+    assert imp.tolist() == [2, 1] and hits.tolist() == [1, 0]
+    assert orc.hit_rate(imp, hits) == 1 / 3
+
+
+def test_hit_rate_counts_against_python_sets():
+    # catches: a group mapping that is not h // g, masks built on the wrong axis
+    rng = np.random.default_rng(8)
+    Hq, Hkv, n = 6, 3, 30
+    A = rng.random((Hq, n)) * 0.1
+    idx = np.stack([np.sort(rng.choice(n, size=7, replace=False)) for _ in range(Hkv)])
+    imp, hits = orc.hit_rate_counts(A, idx, 0.05)
+    for h in range(Hq):
+        important = {j for j in range(n) if A[h, j] > 0.05}
+        assert imp[h] == len(important) and hits[h] == len(important & set(idx[h // 2].tolist()))
+    idx_q = np.stack([np.sort(rng.choice(n, size=5, replace=False)) for _ in range(Hq)])
+    imp2, hits2 = orc.hit_rate_counts(A, idx_q, 0.05)
+    for h in range(Hq):
+        assert hits2[h] == len({j for j in range(n) if A[h, j] > 0.05} & set(idx_q[h].tolist()))
+    assert np.array_equal(imp, imp2)
+
+
+def test_current_attention_is_the_decoding_softmax():
+    # the same weights the decoding oracle (pinned on its own) applies to the value rows
+    from oracle import decode_oracle as dec
+    rng = np.random.default_rng(9)
+    Hq, Hkv, Lk, D = 4, 2, 33, 8
+    q = rng.standard_normal((Hq, D)).astype(np.float32)
+    k = rng.standard_normal((Hkv, Lk, D)).astype(np.float32)
+    A = orc.current_attention(q, k)
+    eye = np.broadcast_to(np.eye(Lk, dtype=np.float32), (1, Hkv, Lk, Lk)).copy()   # values = one-hot rows
+    out, _ = dec.decode_attention(q[None], k[None], eye)
+    assert np.allclose(A, out[0], rtol=0, atol=1e-14)
+
