@@ -600,7 +600,7 @@ def test_current_attention_is_the_decoding_softmax():
     # the same weights the decoding oracle (pinned on its own) applies to the value rows
     from oracle import decode_oracle as dec
     rng = np.random.default_rng(9)
-    Hq, Hkv, Lk, D = 4, 2, 33, 8
+    Hq, Hkv, Lk, D = 4, 2, 16, 16            # Lk = D so that one-hot rows fit the value tensor
     q = rng.standard_normal((Hq, D)).astype(np.float32)
     k = rng.standard_normal((Hkv, Lk, D)).astype(np.float32)
     A = orc.current_attention(q, k)
