@@ -178,6 +178,28 @@ int64_t snapkv_compress_per_query_head(int dtype, const void* q_win, const void*
 int64_t snapkv_capacity_for_rate(int64_t L, int W, double rate);
 
 /*
+ * Hit rate of the voting (Sec. 4, "Hit Rate", Eq. 3-7), as counts: a quality probe.  A_cur is the
+ * softmax-normalised attention of the query of a token being generated over all Lk keys it sees, cut to
+ * the n prefix positions; a position is important when A_cur > theta; a hit is an important position
+ * that the voting selected.  The hit rate is H = sum(hits) / sum(important).
+ *
+ *   dtype   SNAPKV_DTYPE_BF16 or SNAPKV_DTYPE_F16 (float32 storage: SNAPKV_ERR_UNSUPPORTED)
+ *   q_cur   [Hq, D] device, dtype;  k [Hkv, Lk, D] device, dtype (query head h reads KV head h / g, g <= 16)
+ *   n       0 <= n <= Lk prefix positions
+ *   idx     [Hidx, idx_stride] device int32: the first kcount entries of a row are the selected prefix
+ *           positions in ascending order (the out_idx of a compress call with kcount = C - W and
+ *           idx_stride = C).  Hidx divides Hq: Hkv rows for snapkv_compress (query head h is checked
+ *           against row h / g), Hq rows for snapkv_compress_per_query_head.
+ *   out_counts [Hq, 2] device int32: per query head (important, hits); overwritten.
+ *
+ * The logits of the call live in the per-device auxiliary buffer the decoding step also uses (hipMalloc
+ * on first use and on growth; concurrent calls on one device would race).
+ */
+int snapkv_hit_rate(int dtype, const void* q_cur, const void* k, int64_t Lk, int64_t n, int Hq, int Hkv, int D,
+                    const int32_t* idx, int Hidx, int64_t kcount, int64_t idx_stride, float theta,
+                    int32_t* out_counts, void* stream);
+
+/*
  * One decoding step of attention over the compacted cache (Sec. 5.1.2: after compression a
  * generated token attends to the C kept rows plus the rows appended since, so the cost of a step no
  * longer grows with the prompt).  For every sequence b and query head h (reading KV head h / g):

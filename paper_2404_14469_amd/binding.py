@@ -25,7 +25,7 @@ SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compr
            "snapkv_sync_timeouts", "snapkv_compress_lse", "snapkv_pooled_scores_lse",
            "snapkv_compress_strided", "snapkv_compress_f16", "snapkv_pooled_scores_f16",
            "snapkv_decode_attention", "snapkv_compress_per_query_head",
-           "snapkv_capacity_for_rate")
+           "snapkv_capacity_for_rate", "snapkv_hit_rate")
 
 _lib = None
 
@@ -77,6 +77,8 @@ def load():
     L.snapkv_compress_per_query_head.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
     L.snapkv_capacity_for_rate.restype = i64
     L.snapkv_capacity_for_rate.argtypes = [i64, i32, ctypes.c_double]
+    L.snapkv_hit_rate.restype = i32
+    L.snapkv_hit_rate.argtypes = [i32, vp, vp, i64, i64, i32, i32, i32, vp, i32, i64, i64, ctypes.c_float, vp, vp]
     L.snapkv_decode_attention.restype = i32
     L.snapkv_decode_attention.argtypes = [i32, vp, vp, vp, vp, i32, i32, i32, i32, i64, i64, vp, vp, vp]
     L.snapkv_release.restype = None
@@ -311,6 +313,22 @@ def snapkv_compress_per_query_head(q_win: torch.Tensor, k: torch.Tensor, v: torc
 def snapkv_capacity_for_rate(L: int, W: int, rate: float) -> int:
     """C = W + floor(rate * (L - W)): the capacity that keeps the given share of the prefix."""
     return _check(load().snapkv_capacity_for_rate(int(L), int(W), float(rate)))
+
+
+def snapkv_hit_rate(q_cur: torch.Tensor, k: torch.Tensor, n: int, idx: torch.Tensor, kcount: int, theta: float,
+                    out_counts: torch.Tensor, stream=None) -> None:
+    """q_cur [Hq,D], k [Hkv,Lk,D] (bf16 or fp16), idx [Hidx, stride] int32 whose first kcount entries per row
+    are the selected prefix positions (ascending) -> out_counts [Hq,2] int32: (important, hits) per query head."""
+    lib = load()
+    Hq, D = q_cur.shape
+    Hkv, Lk, D2 = k.shape
+    if D != D2:
+        raise ValueError("q_cur and k disagree on head dim")
+    if idx.dim() != 2 or tuple(out_counts.shape) != (Hq, 2):
+        raise ValueError("idx must be [Hidx, stride] and out_counts [Hq, 2]")
+    _check(lib.snapkv_hit_rate(_dtype_code(q_cur), _dev(q_cur, "q_cur"), _dev(k, "k", q_cur.dtype), Lk, int(n), Hq, Hkv, D,
+                               _dev(idx, "idx", torch.int32), idx.shape[0], int(kcount), idx.shape[1], float(theta),
+                               _dev(out_counts, "out_counts", torch.int32), _stream(stream)))
 
 
 def snapkv_decode_attention(q: torch.Tensor, k_cache: torch.Tensor, v_cache: torch.Tensor, S: int,

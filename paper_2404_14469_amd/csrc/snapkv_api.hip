@@ -28,9 +28,30 @@ struct DeviceScratch {
     CleanState clean;
 };
 DeviceScratch g_scratch[kMaxDevices];
-DeviceScratch g_decode_scratch[kMaxDevices];   // partial results of decode attention: kept apart so that a
-                                               // decoding step leaves the compression scratch's ready state alone
 std::mutex g_mu;
+DeviceScratch g_decode_scratch[kMaxDevices];   // partial results of decode attention and the hit-rate probe's logits:
+                                               // kept apart so that they leave the compression scratch's ready state alone
+
+// The auxiliary buffer of the current device, grown when needed (need > 0).
+int aux_scratch(size_t need, void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SNAPKV_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_mu);
+    DeviceScratch& s = g_decode_scratch[dev];
+    if (s.bytes < need) {
+        if (s.ptr && hipFree(s.ptr) != hipSuccess) return SNAPKV_ERR_HIP;   // waits for work still using it
+        s.ptr = nullptr;
+        s.bytes = 0;
+        if (hipMalloc(&s.ptr, need * 2) != hipSuccess) {
+            s.ptr = nullptr;
+            (void)hipGetLastError();
+            return SNAPKV_ERR_HIP;
+        }
+        s.bytes = need * 2;
+    }
+    *out = s.ptr;
+    return SNAPKV_OK;
+}
 
 // Optional per-stage timing: events recorded on the caller's stream at stage boundaries.
 struct Profile {
@@ -533,25 +554,33 @@ int snapkv_decode_attention(int dtype, const void* q, const void* k_cache, const
     const size_t need = decode_scratch_bytes(B, Hq, D, nsplit);
     void* base = nullptr;
     if (need > 0) {
-        int dev = 0;
-        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SNAPKV_ERR_HIP;
-        std::lock_guard<std::mutex> lock(g_mu);
-        DeviceScratch& s = g_decode_scratch[dev];
-        if (s.bytes < need) {
-            if (s.ptr && hipFree(s.ptr) != hipSuccess) return SNAPKV_ERR_HIP;   // waits for work still using it
-            s.ptr = nullptr;
-            s.bytes = 0;
-            if (hipMalloc(&s.ptr, need * 2) != hipSuccess) {
-                s.ptr = nullptr;
-                (void)hipGetLastError();
-                return SNAPKV_ERR_HIP;
-            }
-            s.bytes = need * 2;
-        }
-        base = s.ptr;
+        const int rc = aux_scratch(need, &base);
+        if (rc != SNAPKV_OK) return rc;
     }
     return launch_decode(dtype, D, q, k_cache, v_cache, lens, B, Hq, Hkv, S, cap, nsplit, base, out, out_lse,
                          static_cast<hipStream_t>(stream)) == hipSuccess
+               ? SNAPKV_OK
+               : SNAPKV_ERR_HIP;
+}
+
+int snapkv_hit_rate(int dtype, const void* q_cur, const void* k, int64_t Lk, int64_t n, int Hq, int Hkv, int D,
+                    const int32_t* idx, int Hidx, int64_t kcount, int64_t idx_stride, float theta,
+                    int32_t* out_counts, void* stream) {
+    if (!valid_dtype(dtype)) return SNAPKV_ERR_INVALID_ARG;
+    if (!q_cur || !k || !out_counts) return SNAPKV_ERR_INVALID_ARG;
+    if (Hq < 1 || Hkv < 1 || Hq % Hkv != 0 || Lk < 1 || n < 0 || n > Lk) return SNAPKV_ERR_INVALID_ARG;
+    if (Hidx < 1 || Hq % Hidx != 0 || kcount < 0 || kcount > idx_stride || (kcount > 0 && !idx)) return SNAPKV_ERR_INVALID_ARG;
+    if (!(theta == theta)) return SNAPKV_ERR_INVALID_ARG;
+    if (dtype == SNAPKV_DTYPE_F32 || (D != 64 && D != 128)) return SNAPKV_ERR_UNSUPPORTED;
+    if (Hq / Hkv > 16 || Hkv > 65535 || Hq > 65535 || Lk >= (int64_t)1 << 31) return SNAPKV_ERR_UNSUPPORTED;
+    if (!aligned16(q_cur) || !aligned16(k)) return SNAPKV_ERR_MISALIGNED;
+    if ((reinterpret_cast<uintptr_t>(idx) & 3u) != 0 || (reinterpret_cast<uintptr_t>(out_counts) & 3u) != 0)
+        return SNAPKV_ERR_MISALIGNED;
+    void* base = nullptr;
+    const int rc = aux_scratch(hit_rate_scratch_bytes(Hq, Lk), &base);
+    if (rc != SNAPKV_OK) return rc;
+    return launch_hit_rate(dtype, D, q_cur, k, Lk, n, Hq, Hkv, idx, Hidx, kcount, idx_stride, theta, base, out_counts,
+                           static_cast<hipStream_t>(stream)) == hipSuccess
                ? SNAPKV_OK
                : SNAPKV_ERR_HIP;
 }

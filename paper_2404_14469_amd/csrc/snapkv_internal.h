@@ -124,6 +124,12 @@ hipError_t launch_pool_select(const ScoreGeom& G, const float* vote, int pool_ki
                               hipStream_t st);
 unsigned read_select_timeouts();
 
+// Hit rate of the voting (snapkv_hitrate.hip).
+size_t hit_rate_scratch_bytes(int Hq, int64_t Lk);
+hipError_t launch_hit_rate(int dtype, int D, const void* q, const void* k, int64_t Lk, int64_t n, int Hq, int Hkv,
+                           const int32_t* idx, int Hidx, int64_t kcount, int64_t idx_stride, float theta,
+                           void* scratch, int32_t* counts, hipStream_t st);
+
 // One decoding step of attention over a cache of [B, Hkv, cap, D] rows (snapkv_decode.hip).
 int decode_splits(int B, int Hkv, int64_t S);
 size_t decode_scratch_bytes(int B, int Hq, int D, int nsplit);
