@@ -290,3 +290,14 @@ def hit_rate(important: np.ndarray, hits: np.ndarray) -> float:
     tot = int(np.sum(important))
     return float(np.sum(hits)) / tot if tot > 0 else float("nan")
 
+
+def rows_from_pages(pages: np.ndarray, block_table: np.ndarray, L: int) -> np.ndarray:
+    """Logical [H, L, D] view of a paged cache: pages [num_pages, page_size, H, D] (the rows of a page
+    are token-major), block_table[i] = physical page of logical page i.  Listing 1 indexes K and V by
+    (head, position) whatever their storage, so the step on a paged cache is the step on this view."""
+    num_pages, ps, H, D = pages.shape
+    out = np.empty((H, L, D), dtype=pages.dtype)
+    for j in range(L):
+        out[:, j, :] = pages[int(block_table[j // ps]), j % ps]
+    return out
+

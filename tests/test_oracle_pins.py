@@ -608,3 +608,21 @@ def test_current_attention_is_the_decoding_softmax():
     out, _ = dec.decode_attention(q[None], k[None], eye)
     assert np.allclose(A, out[0], rtol=0, atol=1e-14)
 
+
+# ----------------------------------------------------------------------------- paged storage
+def test_rows_from_pages_inverts_a_scattering_into_pages():
+    # catches: page and in-page index swapped, head and row axes swapped, a table read by physical page
+    rng = np.random.default_rng(12)
+    H, L, D, ps = 3, 37, 4, 8
+    x = rng.standard_normal((H, L, D)).astype(np.float32)
+    npages = 9
+    table = rng.permutation(npages)[: (L + ps - 1) // ps]
+    pages = np.full((npages, ps, H, D), np.nan, dtype=np.float32)
+    for j in range(L):                                   # scatter by the definition of the layout
+        for h in range(H):
+            pages[table[j // ps], j % ps, h] = x[h, j]
+    assert np.array_equal(orc.rows_from_pages(pages, table, L), x)
+    ident = np.arange(npages)
+    flat = pages.reshape(npages * ps, H, D)              # identity table: the view is a plain reshape
+    assert np.array_equal(orc.rows_from_pages(pages, ident, L), np.transpose(flat[:L], (1, 0, 2)), equal_nan=True)
+
