@@ -155,6 +155,24 @@ int64_t snapkv_compress_strided(int dtype, const void* q_win, const void* k, con
                                 void* out_k, void* out_v, int32_t* out_idx, void* stream);
 
 /*
+ * The compression step on a paged cache (Listing 1 indexes K and V by (head, position), whatever their
+ * storage): k_pages and v_pages are [num_pages, page_size, Hkv, D] (the rows of a page are token-major)
+ * and logical position j of every head lives in physical page block_table[j / page_size], row
+ * j % page_size.  One table serves K and V.
+ *
+ *   block_table  [ceil(L / page_size)] device int32, entries in [0, num_pages) (entries outside are
+ *                clamped to that range, so a bad table gives wrong results, not a wild access)
+ *   page_size >= 1 (16 or more for coalesced reads), ceil(L / page_size) <= num_pages
+ * Other arguments, outputs (contiguous out_k/out_v [Hkv, C, D], out_idx [Hkv, C] in logical positions)
+ * and the return value as for snapkv_compress; `dtype` is SNAPKV_DTYPE_*.  Scratch comes from the
+ * library's per-device buffer.
+ */
+int64_t snapkv_compress_paged(int dtype, const void* q_win, const void* k_pages, const void* v_pages,
+                              const int32_t* block_table, int64_t num_pages, int page_size, int64_t L, int Hq,
+                              int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k, void* out_v,
+                              int32_t* out_idx, void* stream);
+
+/*
  * The compression step with one cache per QUERY head (Listing 1 as printed has equal head counts;
  * a grouped-query model reaches them by repeating every KV head for the g = Hq / Hkv query heads that
  * read it).  Query head h scores the keys of KV head h / g, and votes, pools and selects alone (no

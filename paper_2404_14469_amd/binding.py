@@ -25,7 +25,7 @@ SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compr
            "snapkv_sync_timeouts", "snapkv_compress_lse", "snapkv_pooled_scores_lse",
            "snapkv_compress_strided", "snapkv_compress_f16", "snapkv_pooled_scores_f16",
            "snapkv_decode_attention", "snapkv_compress_per_query_head",
-           "snapkv_capacity_for_rate", "snapkv_hit_rate")
+           "snapkv_capacity_for_rate", "snapkv_hit_rate", "snapkv_compress_paged")
 
 _lib = None
 
@@ -77,6 +77,8 @@ def load():
     L.snapkv_compress_per_query_head.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
     L.snapkv_capacity_for_rate.restype = i64
     L.snapkv_capacity_for_rate.argtypes = [i64, i32, ctypes.c_double]
+    L.snapkv_compress_paged.restype = i64
+    L.snapkv_compress_paged.argtypes = [i32, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
     L.snapkv_hit_rate.restype = i32
     L.snapkv_hit_rate.argtypes = [i32, vp, vp, i64, i64, i32, i32, i32, vp, i32, i64, i64, ctypes.c_float, vp, vp]
     L.snapkv_decode_attention.restype = i32
@@ -308,6 +310,27 @@ def snapkv_compress_per_query_head(q_win: torch.Tensor, k: torch.Tensor, v: torc
         int(pool_kind), int(p), int(C), _dev(out_k, "out_k", q_win.dtype), _dev(out_v, "out_v", q_win.dtype),
         _dev(out_idx, "out_idx", torch.int32), _stream(stream))
     return _check(kept)
+
+
+def snapkv_compress_paged(q_win: torch.Tensor, k_pages: torch.Tensor, v_pages: torch.Tensor, block_table: torch.Tensor,
+                          L: int, pool_kind: int, p: int, C: int, out_k: torch.Tensor, out_v: torch.Tensor,
+                          out_idx: torch.Tensor, stream=None) -> int:
+    """q_win [Hq,W,D]; k_pages/v_pages [num_pages, page_size, Hkv, D]; block_table [ceil(L/page_size)] int32
+    -> out_k/out_v [Hkv,C,D], out_idx [Hkv,C] (logical positions); returns rows kept."""
+    lib = load()
+    Hq, W, D = q_win.shape
+    num_pages, page_size, Hkv, D2 = k_pages.shape
+    if D != D2 or tuple(v_pages.shape) != tuple(k_pages.shape):
+        raise ValueError("q_win, k_pages and v_pages disagree on their shapes")
+    if block_table.dim() != 1 or block_table.numel() < (L + page_size - 1) // page_size:
+        raise ValueError("block_table must hold ceil(L / page_size) entries")
+    if tuple(out_k.shape) != (Hkv, C, D) or tuple(out_v.shape) != (Hkv, C, D) or tuple(out_idx.shape) != (Hkv, C):
+        raise ValueError("out_k/out_v must be [Hkv, C, D] and out_idx [Hkv, C]")
+    return _check(lib.snapkv_compress_paged(
+        _dtype_code(q_win), _dev(q_win, "q_win"), _dev(k_pages, "k_pages", q_win.dtype),
+        _dev(v_pages, "v_pages", q_win.dtype), _dev(block_table, "block_table", torch.int32), num_pages, page_size,
+        int(L), Hq, Hkv, D, W, int(pool_kind), int(p), int(C), _dev(out_k, "out_k", q_win.dtype),
+        _dev(out_v, "out_v", q_win.dtype), _dev(out_idx, "out_idx", torch.int32), _stream(stream)))
 
 
 def snapkv_capacity_for_rate(L: int, W: int, rate: float) -> int:

@@ -181,7 +181,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
                       void* out_v, int32_t* out_idx, void* workspace, size_t workspace_bytes,
                       bool own_scratch, void* stream, const float* lse = nullptr, bool with_lse = false,
                       const RowLayout* k_layout = nullptr, const RowLayout* v_layout = nullptr,
-                      bool per_query_head = false) {
+                      bool per_query_head = false, const PageMap& pm = PageMap{}) {
     if (!valid_dtype(dtype)) return SNAPKV_ERR_INVALID_ARG;
     if (with_lse && !lse) return SNAPKV_ERR_INVALID_ARG;
     if (with_lse && (reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
@@ -207,7 +207,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     const int head_div = per_query_head ? Hq / Hkv : 1;
     if (L <= C) {   // Listing 1, first branch: the prompt already fits
         if (launch_iota(Hout, L, C, out_idx, st) != hipSuccess) return SNAPKV_ERR_HIP;
-        if (launch_gather(k, v, out_idx, Hout, L, L, C, row_bytes, out_k, out_v, kl, vl, CleanJob{}, st, head_div) != hipSuccess)
+        if (launch_gather(k, v, out_idx, Hout, L, L, C, row_bytes, out_k, out_v, kl, vl, CleanJob{}, st, head_div, pm) != hipSuccess)
             return SNAPKV_ERR_HIP;
         return L;
     }
@@ -215,6 +215,9 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     ScoreGeom G = make_geom(L, Hq, Hkv, D, W);
     G.k_hs = kl.head_stride;
     G.k_rs = kl.row_stride;
+    G.k_table = pm.table;
+    G.k_page = pm.page;
+    G.k_pages = pm.pages;
     const size_t need = workspace_layout(G, nullptr, nullptr);
     void* base = workspace;
     CleanState was_clean;
@@ -297,7 +300,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     }
     if (se != hipSuccess) return SNAPKV_ERR_HIP;
     stage_done(st, kStageSelect);
-    if (launch_gather(k, v, out_idx, Hout, L, C, C, row_bytes, out_k, out_v, kl, vl, clean, st, head_div) != hipSuccess)
+    if (launch_gather(k, v, out_idx, Hout, L, C, C, row_bytes, out_k, out_v, kl, vl, clean, st, head_div, pm) != hipSuccess)
         return SNAPKV_ERR_HIP;
     if (mine && (clean.ones || streaming) && clean.zeros) {
         std::lock_guard<std::mutex> lock(g_mu);
@@ -497,6 +500,25 @@ int64_t snapkv_compress_strided(int dtype, const void* q_win, const void* k, con
     const RowLayout kl{k_head_stride * es, k_row_stride * es}, vl{v_head_stride * es, v_row_stride * es};
     return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
                          nullptr, 0, true, stream, nullptr, false, &kl, &vl);
+}
+
+int64_t snapkv_compress_paged(int dtype, const void* q_win, const void* k_pages, const void* v_pages,
+                              const int32_t* block_table, int64_t num_pages, int page_size, int64_t L, int Hq,
+                              int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k, void* out_v,
+                              int32_t* out_idx, void* stream) {
+    if (!valid_dtype(dtype) || !block_table) return SNAPKV_ERR_INVALID_ARG;
+    if (page_size < 1 || num_pages < 1 || L < 1 || (L + page_size - 1) / page_size > num_pages) return SNAPKV_ERR_INVALID_ARG;
+    if ((reinterpret_cast<uintptr_t>(block_table) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
+    if (num_pages >= (int64_t)1 << 31 || Hkv < 1) return SNAPKV_ERR_UNSUPPORTED;
+    // rows of a page are token-major: [num_pages, page_size, Hkv, D]
+    const int64_t row = (int64_t)D * elem_bytes(dtype);
+    const RowLayout lay{row, row * Hkv};
+    PageMap pm;
+    pm.table = block_table;
+    pm.page = page_size;
+    pm.pages = num_pages;
+    return compress_impl(dtype, q_win, k_pages, v_pages, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
+                         nullptr, 0, true, stream, nullptr, false, &lay, &lay, false, pm);
 }
 
 int64_t snapkv_compress_per_query_head(int dtype, const void* q_win, const void* k, const void* v, int64_t L,

@@ -287,6 +287,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     for (int t = 0; t < KT; ++t) {
         int64_t j = ((int64_t)t * TS + tile0) * 16 + n16;
         j = j < G.L ? j : G.L - 1;
+        j = physical_row(G.k_table, G.k_page, G.k_pages, j);
         kp[t] = static_cast<const char*>(kv) + (int64_t)(group / F.split) * G.k_hs + j * G.k_rs + kg * 16;
     }
     // Q is shared by the waves: each fetches QPW of the unit's 1 KB chunks (chunk c = row unit c / NP,
@@ -752,6 +753,7 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
     for (int t = 0; t < KT; ++t) {
         int64_t j = ((int64_t)t * TS + tile0) * 16 + n16;
         j = j < G.L ? j : G.L - 1;
+        j = physical_row(G.k_table, G.k_page, G.k_pages, j);
         kp[t] = static_cast<const char*>(kv) + (int64_t)(group / F.split) * G.k_hs + j * G.k_rs + kg * 16;
     }
     const char* qp[QPW];

@@ -33,7 +33,20 @@ struct ScoreGeom {
     float c2;        // log2(e) / sqrt(D): logits are kept in the base-2 domain
     int64_t k_hs;    // bytes between the K rows of consecutive KV heads (contiguous: L * D * element size)
     int64_t k_rs;    // bytes between consecutive K rows of a head (contiguous: D * element size)
+    // paged K: logical row j lives at physical row k_table[j / k_page] * k_page + j % k_page (null: j itself)
+    const int32_t* k_table;
+    int k_page;
+    int64_t k_pages;
 };
+
+// Physical row of logical row j of a possibly paged tensor; page ids outside [0, pages) are clamped
+// so that a bad table cannot send a load outside the allocation.
+__device__ __forceinline__ int64_t physical_row(const int32_t* table, int page, int64_t pages, int64_t j) {
+    if (!table) return j;
+    int64_t pg = table[j / page];
+    pg = pg < 0 ? 0 : (pg >= pages ? pages - 1 : pg);
+    return pg * page + j % page;
+}
 
 // Plan of the single-read scoring kernel (snapkv_fused.hip).  A unit is a KV head or one of
 // `split` equal parts of its query heads; its window
@@ -156,10 +169,16 @@ struct CleanJob {
 struct RowLayout {
     int64_t head_stride, row_stride;
 };
+// Paging of K and V (one table for both); table == nullptr: rows are not paged.
+struct PageMap {
+    const int32_t* table = nullptr;
+    int page = 1;
+    int64_t pages = 0;
+};
 hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H, int64_t L,
                          int64_t rows, int64_t out_stride, int row_bytes, void* out_k, void* out_v,
                          const RowLayout& kl, const RowLayout& vl, const CleanJob& clean, hipStream_t st,
-                         int head_div = 1);
+                         int head_div = 1, const PageMap& pm = PageMap{});
 
 }  // namespace snapkv
 #endif

@@ -140,6 +140,7 @@ __device__ __forceinline__ void chunk_logits(f32x16 (&acc)[kTilesPerChunk], cons
     for (int tt = 0; tt < kTilesPerChunk; ++tt) {
         int64_t j = j0 + tt * kTileKeys + (lane & 31);
         j = j < G.L ? j : G.L - 1;
+        j = physical_row(G.k_table, G.k_page, G.k_pages, j);
         load_frag<T, D>(kf[tt], kbase + j * G.k_rs, lane >> 5);
     }
 #pragma unroll
@@ -308,6 +309,9 @@ ScoreGeom make_geom(int64_t L, int Hq, int Hkv, int D, int W) {
     G.c2 = (float)(1.4426950408889634 / __builtin_sqrt((double)D));
     G.k_rs = 0;   // set by the caller once the element size is known
     G.k_hs = 0;
+    G.k_table = nullptr;
+    G.k_page = 1;
+    G.k_pages = 0;
     return G;
 }
 

@@ -393,7 +393,7 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
                                                    uint4* __restrict__ out_v, const RowLayout kl,
                                                    const RowLayout vl /* strides in 16-byte pieces */,
                                                    const int head_div /* output heads per source head */,
-                                                   const CleanJob clean) {
+                                                   const PageMap pm, const CleanJob clean) {
     const int h = blockIdx.y;
     const int64_t total = rows * pieces;
     const uint4* kb = k + (int64_t)(h / head_div) * kl.head_stride;
@@ -404,7 +404,7 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
         const int64_t r = e / pieces;
         const int c = (int)(e - r * pieces);
-        const int64_t src = ib[r];
+        const int64_t src = physical_row(pm.table, pm.page, pm.pages, ib[r]);
         okb[r * pieces + c] = kb[src * kl.row_stride + c];
         ovb[r * pieces + c] = vb[src * vl.row_stride + c];
     }
@@ -418,7 +418,7 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
 hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H, int64_t L,
                          int64_t rows, int64_t out_stride, int row_bytes, void* out_k, void* out_v,
                          const RowLayout& kl, const RowLayout& vl, const CleanJob& clean, hipStream_t st,
-                         int head_div) {
+                         int head_div, const PageMap& pm) {
     (void)L;
     if (head_div < 1) return hipErrorInvalidValue;
     if (H <= 0 || rows <= 0) return hipSuccess;
@@ -429,7 +429,7 @@ hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H
     const RowLayout kp{kl.head_stride / 16, kl.row_stride / 16}, vp{vl.head_stride / 16, vl.row_stride / 16};
     hipLaunchKernelGGL(gather_rows, dim3(bx, H), dim3(256), 0, st, static_cast<const uint4*>(k),
                        static_cast<const uint4*>(v), idx, rows, out_stride, pieces,
-                       static_cast<uint4*>(out_k), static_cast<uint4*>(out_v), kp, vp, head_div, clean);
+                       static_cast<uint4*>(out_k), static_cast<uint4*>(out_v), kp, vp, head_div, pm, clean);
     return hipGetLastError();
 }
 

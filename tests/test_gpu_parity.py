@@ -261,6 +261,74 @@ def test_per_query_head_equals_grouped_call_without_groups(snapkv):
     assert np.array_equal(a[2], b[0]) and torch.equal(a[0], b[1]) and torch.equal(a[1], b[2])
 
 
+def _paged(case, w, page_size, seed):
+    """Scatters the contiguous K/V of a case into pages [num_pages, page_size, Hkv, D] behind a random table
+    (torch indexing only: input preparation); unused pages and the tail of the last page hold large values."""
+    k, v = case["k"], case["v"]
+    nlog = (w.L + page_size - 1) // page_size
+    num_pages = nlog + 3
+    g = torch.Generator().manual_seed(seed)
+    table = torch.randperm(num_pages, generator=g)[:nlog].to(torch.int32)
+    kp = torch.full((num_pages, page_size, w.Hkv, w.D), 3.0e4, dtype=k.dtype, device="cuda")
+    vp = torch.full_like(kp, -3.0e4)
+    pos = torch.arange(w.L)
+    phys_page = table.long()[pos // page_size].cuda()
+    in_page = (pos % page_size).cuda()
+    kp[phys_page, in_page] = k.permute(1, 0, 2)
+    vp[phys_page, in_page] = v.permute(1, 0, 2)
+    return kp, vp, table.cuda()
+
+
+PAGED_CASES = [
+    (small("paged_16", L=1500, C=200), 16),
+    (small("paged_64_gqa", Hq=16, Hkv=4, L=3000, C=300), 64),
+    (small("paged_48_ragged", L=1111, C=140), 48),                   # not a power of two, L not a multiple
+    (small("paged_1", L=300, C=64), 1),                              # every row its own page
+    (small("paged_256_d64_f16", D=64, dtype="f16", L=2500, C=256), 256),
+    (small("paged_w160", W=160, L=1300, C=320, p=5), 32),            # the wide-window kernels
+    (small("paged_bypass", L=100, C=128), 16),
+    (small("paged_one_page", L=200, C=64), 512),                     # the whole prompt inside one page
+]
+
+
+@pytest.mark.parametrize("w,page_size", PAGED_CASES, ids=lambda x: x.name if hasattr(x, "name") else str(x))
+def test_paged_cache_matches_contiguous_and_oracle(snapkv, scheme, w, page_size):
+    from oracle import snapkv_oracle as orc_
+    case = workloads.generate(w, device="cuda")
+    kp, vp, table = _paged(case, w, page_size, seed=w.L)
+    out_k = torch.zeros((w.Hkv, w.C, w.D), dtype=kp.dtype, device="cuda")
+    out_v = torch.zeros_like(out_k)
+    out_idx = torch.full((w.Hkv, w.C), -1, dtype=torch.int32, device="cuda")
+    kept = snapkv.snapkv_compress_paged(case["q_win"], kp, vp, table, w.L, w.pool_kind, w.p, w.C, out_k, out_v, out_idx)
+    torch.cuda.synchronize()
+    ref = run_gpu(snapkv, case["q_win"], case["k"], case["v"], w.pool_kind, w.p, w.C)
+    rows = min(w.C, w.L)
+    assert kept == ref[4]
+    assert np.array_equal(out_idx.cpu().numpy()[:, :rows], ref[3][:, :rows])
+    assert torch.equal(out_k[:, :rows], ref[1][:, :rows]) and torch.equal(out_v[:, :rows], ref[2][:, :rows])
+    # against the oracle on its own logical view of the pages
+    kl = orc_.rows_from_pages(workloads.to_numpy_bits(kp), table.cpu().numpy(), w.L)
+    vl = orc_.rows_from_pages(workloads.to_numpy_bits(vp), table.cpu().numpy(), w.L)
+    assert np.array_equal(kl, workloads.to_numpy_bits(case["k"])) and np.array_equal(vl, workloads.to_numpy_bits(case["v"]))
+    check_against_oracle(case["q_win"], case["k"], case["v"], w.pool_kind, w.p, w.C, ref[0], out_k, out_v,
+                         out_idx.cpu().numpy(), kept)
+
+
+def test_paged_rejects_bad_arguments(snapkv):
+    w = small("paged_bad", L=500, C=64)
+    case = workloads.generate(w, device="cuda")
+    kp, vp, table = _paged(case, w, 16, seed=1)
+    out_k = torch.zeros((w.Hkv, w.C, w.D), dtype=kp.dtype, device="cuda")
+    out_v = torch.zeros_like(out_k)
+    out_idx = torch.zeros((w.Hkv, w.C), dtype=torch.int32, device="cuda")
+    lib = snapkv.load()
+    args = lambda npages, ps: (0, case["q_win"].data_ptr(), kp.data_ptr(), vp.data_ptr(), table.data_ptr(), npages, ps,
+                               w.L, w.Hq, w.Hkv, w.D, w.W, 0, 7, w.C, out_k.data_ptr(), out_v.data_ptr(),
+                               out_idx.data_ptr(), None)
+    assert lib.snapkv_compress_paged(*args(10, 16)) == -1      # the prompt needs 32 pages
+    assert lib.snapkv_compress_paged(*args(40, 0)) == -1
+
+
 def test_explicit_workspace_matches(snapkv):
     w = small("ws", Hq=8, Hkv=4, L=2500, C=300)
     case = workloads.generate(w, device="cuda")
