@@ -128,8 +128,9 @@ def main() -> int:
                     help="compress (default): snapkv_compress, the headline path; lse: snapkv_compress_lse, "
                          "the variant that is handed the window rows' log-sum-exp; per_query_head: "
                          "snapkv_compress_per_query_head, one cache per query head (separate measurements)")
-    ap.add_argument("--layout", default="head_major", choices=["head_major", "token_major"],
-                    help="storage order of K/V: [Hkv, L, D] (default) or [L, Hkv, D] through snapkv_compress_strided")
+    ap.add_argument("--layout", default="head_major", choices=["head_major", "token_major", "paged"],
+                    help="storage order of K/V: [Hkv, L, D] (default), [L, Hkv, D] through snapkv_compress_strided, or pages "
+                         "[num_pages, 16, Hkv, D] behind a shuffled block table through snapkv_compress_paged")
     ap.add_argument("--explicit-workspace", action="store_true",
                     help="time snapkv_compress_ws with a caller-provided workspace instead of snapkv_compress")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
@@ -173,6 +174,20 @@ def main() -> int:
         if args.layout == "token_major":
             c["k"] = c["k"].permute(1, 0, 2).contiguous().permute(1, 0, 2)
             c["v"] = c["v"].permute(1, 0, 2).contiguous().permute(1, 0, 2)
+        if args.layout == "paged":      # scatter into 16-row pages in a shuffled order (input preparation)
+            ps = 16
+            npg = (w.L + ps - 1) // ps
+            gen = torch.Generator().manual_seed(l)
+            table = torch.randperm(npg, generator=gen).to(torch.int32).to(dev)
+            pos = torch.arange(w.L, device=dev)
+            pages = []
+            for name in ("k", "v"):
+                pg = torch.zeros((npg, ps, w.Hkv, w.D), dtype=c[name].dtype, device=dev)
+                pg[table.long()[pos // ps], pos % ps] = c[name].permute(1, 0, 2)
+                pages.append(pg)
+            c["k"], c["v"], c["table"] = pages[0], pages[1], table
+            layers.append((c["q_win"], c["k"], c["v"], c["table"]))
+            continue
         layers.append((c["q_win"], c["k"], c["v"]))
     torch.cuda.synchronize()
     hout = w.Hq if args.entry == "per_query_head" else w.Hkv
@@ -201,6 +216,10 @@ def main() -> int:
         torch.cuda.synchronize()
 
     def step(i):
+        if args.layout == "paged":
+            q, kp, vp, table = layers[i % nres]
+            snapkv.snapkv_compress_paged(q, kp, vp, table, w.L, w.pool_kind, w.p, w.C, out_k, out_v, out_idx, stream=stream)
+            return
         q, k, v = layers[i % nres]
         if args.layout == "token_major":
             snapkv.snapkv_compress_strided(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx, stream=stream)
@@ -258,7 +277,7 @@ def main() -> int:
     }
 
     cpu = None
-    if not args.no_cpu_baseline and args.entry != "per_query_head":
+    if not args.no_cpu_baseline and args.entry != "per_query_head" and args.layout != "paged":
         from oracle import c_oracle
         # bounded sample: whole resident layers until about 1.5e11 multiply-adds of the scoring
         # product have been spent (tens of core-seconds on the host's cores)
