@@ -1,0 +1,80 @@
+"""The compression step and the decoding step recorded into a HIP graph and replayed.
+
+Callers with launch-bound inner loops capture the calls once and replay them.  The entry point with a
+caller-provided workspace allocates nothing and clears its scratch with a fill kernel (no memset
+nodes), so it can be captured; each replay is checked against an eager call on the same inputs, with
+eager work and synchronisations between the replays.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2404_14469_amd import workloads
+from paper_2404_14469_amd.workloads import DecodeWorkload, Workload
+
+pytestmark = pytest.mark.gpu
+
+
+def test_compress_ws_replays_in_a_graph(snapkv):
+    w = Workload("graph", Hq=8, Hkv=4, D=128, L=6000, W=32, pool_kind=0, p=7, C=512, dtype="bf16",
+                 clusters=(6, 6), radius=6, seed=70)
+    cases = [workloads.generate(w, layer=l, device="cuda") for l in range(3)]
+    q = torch.empty_like(cases[0]["q_win"])
+    k = torch.empty_like(cases[0]["k"])
+    v = torch.empty_like(cases[0]["v"])
+    ws = torch.empty(snapkv.snapkv_workspace_bytes(w.L, w.Hq, w.Hkv, w.D, w.W), dtype=torch.uint8, device="cuda")
+    out_k = torch.zeros((w.Hkv, w.C, w.D), dtype=k.dtype, device="cuda")
+    out_v = torch.zeros_like(out_k)
+    out_idx = torch.zeros((w.Hkv, w.C), dtype=torch.int32, device="cuda")
+
+    def load(c):
+        q.copy_(c["q_win"]); k.copy_(c["k"]); v.copy_(c["v"])
+
+    load(cases[0])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up outside the capture: launch plans are cached
+        snapkv.snapkv_compress(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        snapkv.snapkv_compress(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx, workspace=ws)
+    for rep in range(6):
+        c = cases[rep % 3]
+        load(c)
+        out_idx.fill_(-1); out_k.zero_(); out_v.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        got = (out_idx.cpu().numpy().copy(), out_k.clone(), out_v.clone())
+        # eager call on the same inputs, own outputs, the library's own scratch
+        ek = torch.zeros_like(out_k); ev = torch.zeros_like(out_v); ei = torch.zeros_like(out_idx)
+        snapkv.snapkv_compress(c["q_win"], c["k"], c["v"], w.pool_kind, w.p, w.C, ek, ev, ei)
+        torch.cuda.synchronize()
+        assert np.array_equal(got[0], ei.cpu().numpy()), f"replay {rep}"
+        assert torch.equal(got[1], ek) and torch.equal(got[2], ev), f"replay {rep}"
+    assert snapkv.snapkv_sync_timeouts() == 0
+
+
+def test_decode_replays_in_a_graph(snapkv):
+    w = DecodeWorkload("graph_decode", B=2, Hq=8, Hkv=4, D=128, S=5000, cap=5000, seed=71)   # keys split: merge kernel too
+    cases = [workloads.generate_decode(DecodeWorkload(**{**w.__dict__, "seed": 71 + i}), device="cuda") for i in range(2)]
+    q = torch.empty_like(cases[0]["q"]); k = torch.empty_like(cases[0]["k_cache"]); v = torch.empty_like(cases[0]["v_cache"])
+    out = torch.zeros((w.B, w.Hq, w.D), dtype=torch.float32, device="cuda")
+    lse = torch.zeros((w.B, w.Hq), dtype=torch.float32, device="cuda")
+    q.copy_(cases[0]["q"]); k.copy_(cases[0]["k_cache"]); v.copy_(cases[0]["v_cache"])
+    snapkv.snapkv_decode_attention(q, k, v, w.S, out, lse)      # allocates the partials' buffer before the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        snapkv.snapkv_decode_attention(q, k, v, w.S, out, lse)
+    for rep in range(4):
+        c = cases[rep % 2]
+        q.copy_(c["q"]); k.copy_(c["k_cache"]); v.copy_(c["v_cache"])
+        out.fill_(float("nan")); lse.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        eo = torch.empty_like(out); el = torch.empty_like(lse)
+        snapkv.snapkv_decode_attention(c["q"], c["k_cache"], c["v_cache"], w.S, eo, el)
+        torch.cuda.synchronize()
+        assert torch.equal(out, eo) and torch.equal(lse, el), f"replay {rep}"
