@@ -155,6 +155,29 @@ int64_t snapkv_compress_strided(int dtype, const void* q_win, const void* k, con
                                 void* out_k, void* out_v, int32_t* out_idx, void* stream);
 
 /*
+ * The compression step for a batch of prompts of one model (same heads, window, pooling and capacity,
+ * different lengths), e.g. the prompts of one serving step.  Every prompt gets exactly the result of its
+ * own snapkv_compress call; the batch only saves launches: scoring still runs once per prompt, pooling
+ * with selection and the gather run once for up to 32 prompts.
+ *
+ *   n_prompts >= 0
+ *   q_win, k, v, out_k, out_v, out_idx   HOST arrays of n_prompts DEVICE pointers, each as the argument of
+ *           the same name of snapkv_compress for that prompt (k[i], v[i] are [Hkv, L[i], D], ...)
+ *   L       HOST array of n_prompts prompt lengths
+ *   kept    HOST array of n_prompts, or NULL: rows kept per head of each prompt, min(C, L[i])
+ *   dtype   SNAPKV_DTYPE_*; the other arguments as for snapkv_compress
+ *
+ * The host arrays are read before the call returns.  All prompts are validated before anything is enqueued;
+ * returns SNAPKV_OK or a negative SNAPKV_ERR_* code.  Shapes the joint kernels do not take (windows of more
+ * than 128 rows per query head, a batch that is not resident at once) run prompt by prompt inside the call.
+ * Scratch comes from the library's per-device buffer.
+ */
+int snapkv_compress_varlen(int dtype, int n_prompts, const void* const* q_win, const void* const* k,
+                           const void* const* v, const int64_t* L, int Hq, int Hkv, int D, int W, int pool_kind,
+                           int p, int64_t C, void* const* out_k, void* const* out_v, int32_t* const* out_idx,
+                           int64_t* kept, void* stream);
+
+/*
  * The compression step on a paged cache (Listing 1 indexes K and V by (head, position), whatever their
  * storage): k_pages and v_pages are [num_pages, page_size, Hkv, D] (the rows of a page are token-major)
  * and logical position j of every head lives in physical page block_table[j / page_size], row

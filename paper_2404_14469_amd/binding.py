@@ -25,7 +25,8 @@ SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compr
            "snapkv_sync_timeouts", "snapkv_compress_lse", "snapkv_pooled_scores_lse",
            "snapkv_compress_strided", "snapkv_compress_f16", "snapkv_pooled_scores_f16",
            "snapkv_decode_attention", "snapkv_compress_per_query_head",
-           "snapkv_capacity_for_rate", "snapkv_hit_rate", "snapkv_compress_paged")
+           "snapkv_capacity_for_rate", "snapkv_hit_rate", "snapkv_compress_paged",
+           "snapkv_compress_varlen")
 
 _lib = None
 
@@ -79,6 +80,8 @@ def load():
     L.snapkv_capacity_for_rate.argtypes = [i64, i32, ctypes.c_double]
     L.snapkv_compress_paged.restype = i64
     L.snapkv_compress_paged.argtypes = [i32, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
+    L.snapkv_compress_varlen.restype = i32
+    L.snapkv_compress_varlen.argtypes = [i32, i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp, vp]
     L.snapkv_hit_rate.restype = i32
     L.snapkv_hit_rate.argtypes = [i32, vp, vp, i64, i64, i32, i32, i32, vp, i32, i64, i64, ctypes.c_float, vp, vp]
     L.snapkv_decode_attention.restype = i32
@@ -331,6 +334,38 @@ def snapkv_compress_paged(q_win: torch.Tensor, k_pages: torch.Tensor, v_pages: t
         _dev(v_pages, "v_pages", q_win.dtype), _dev(block_table, "block_table", torch.int32), num_pages, page_size,
         int(L), Hq, Hkv, D, W, int(pool_kind), int(p), int(C), _dev(out_k, "out_k", q_win.dtype),
         _dev(out_v, "out_v", q_win.dtype), _dev(out_idx, "out_idx", torch.int32), _stream(stream)))
+
+
+def snapkv_compress_varlen(q_wins, ks, vs, pool_kind: int, p: int, C: int, out_ks, out_vs, out_idxs, stream=None):
+    """A batch of prompts of one model: lists of tensors shaped as for snapkv_compress (k [Hkv, L_i, D], ...).
+    Returns the rows kept per head of every prompt."""
+    lib = load()
+    n = len(q_wins)
+    if not (len(ks) == len(vs) == len(out_ks) == len(out_vs) == len(out_idxs) == n):
+        raise ValueError("all lists must have one entry per prompt")
+    if n == 0:
+        return []
+    Hq, Hkv, _, D, W = _shapes(q_wins[0], ks[0])
+    code = _dtype_code(q_wins[0])
+    Ls = []
+    for i in range(n):
+        hq, hkv, L, d, w = _shapes(q_wins[i], ks[i])
+        if (hq, hkv, d, w) != (Hq, Hkv, D, W) or _dtype_code(q_wins[i]) != code:
+            raise ValueError("the prompts of a batch share heads, head dim, window and dtype")
+        if tuple(vs[i].shape) != tuple(ks[i].shape):
+            raise ValueError("k and v must have the same shape")
+        if tuple(out_ks[i].shape) != (Hkv, C, D) or tuple(out_vs[i].shape) != (Hkv, C, D) or \
+                tuple(out_idxs[i].shape) != (Hkv, C):
+            raise ValueError("out_k/out_v must be [Hkv, C, D] and out_idx [Hkv, C]")
+        Ls.append(L)
+    dt = q_wins[0].dtype
+    arr = lambda ts, name, dtype: (ctypes.c_void_p * n)(*[_dev(t, name, dtype) for t in ts])
+    kept = (ctypes.c_int64 * n)()
+    _check(lib.snapkv_compress_varlen(
+        code, n, arr(q_wins, "q_win", dt), arr(ks, "k", dt), arr(vs, "v", dt), (ctypes.c_int64 * n)(*Ls), Hq, Hkv, D, W,
+        int(pool_kind), int(p), int(C), arr(out_ks, "out_k", dt), arr(out_vs, "out_v", dt),
+        arr(out_idxs, "out_idx", torch.int32), kept, _stream(stream)))
+    return [int(x) for x in kept]
 
 
 def snapkv_capacity_for_rate(L: int, W: int, rate: float) -> int:

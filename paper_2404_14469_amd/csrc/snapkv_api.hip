@@ -336,6 +336,106 @@ int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, 
 }  // namespace
 
 namespace snapkv {
+void stage_done(hipStream_t st, int stage);
+}
+
+namespace {
+
+// Selection and gather of several prompts of one model in one launch each (the scoring kernel still
+// runs once per prompt, into vote rows padded to the longest prefix).  Returns SNAPKV_OK, a negative
+// error, or 1 when this batch has to be done prompt by prompt (shapes the joint kernels do not take).
+int compress_batch(int dtype, int count, const void* const* q_win, const void* const* k, const void* const* v,
+                   const int64_t* L, int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
+                   void* const* out_k, void* const* out_v, int32_t* const* out_idx, hipStream_t st) {
+    if (count < 2 || count > kMaxBatch || !g_allow_pool_select) return 1;
+    const int g = Hq / Hkv;
+    const int row_bytes = D * elem_bytes(dtype);
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    ScoreGeom G[kMaxBatch];
+    int64_t nmax = 0;
+    size_t per_prompt[kMaxBatch], stats = 0, handoff = 0;   // handoff: bytes of hand-off words per prompt
+    for (int i = 0; i < count; ++i) {
+        G[i] = make_geom(L[i], Hq, Hkv, D, W);
+        G[i].k_rs = row_bytes;
+        G[i].k_hs = (int64_t)row_bytes * L[i];
+        FusedGeom F;
+        if (!lse_plan(dtype, D, G[i], &F)) return 1;   // more window rows than the one-row-per-head kernels take
+        if (g_allow_fused && fused_plan(dtype, D, G[i], &F)) {   // hand-off words this prompt's launch will use
+            const size_t words = (size_t)fused_sync_pairs(F) * sizeof(unsigned long long);
+            handoff = words > handoff ? words : handoff;
+        }
+        nmax = G[i].n > nmax ? G[i].n : nmax;
+        per_prompt[i] = up(stream_stat_bytes(G[i])) + up(sizeof(float) * (size_t)Hq * W);
+        stats += per_prompt[i];
+    }
+    const int64_t npad = (nmax + 3) & ~(int64_t)3;
+    const int Htot = Hkv * count;
+    ScoreGeom Gb = make_geom(npad + W, Hq * count, Htot, D, W);   // the batch as one prompt of count * Hkv heads
+    Gb.NV = g;
+    Gb.VB = 1;
+    if (!pool_select_ok(Gb, pool_kind, p, C - W)) return 1;
+
+    const size_t counters = select_counter_bytes(Htot);
+    handoff = up(handoff);
+    const size_t votes = up(sizeof(float) * (size_t)Hq * count * (size_t)npad);
+    const size_t idx_tmp = up(sizeof(int32_t) * (size_t)Htot * (size_t)C);
+    const size_t nvalid = up(sizeof(int32_t) * (size_t)Htot);
+    const size_t sel = select_layout(Htot, npad, nullptr, nullptr, false, nullptr);
+    const size_t need = counters + handoff * count + votes + stats + idx_tmp + nvalid + sel;
+    void* base = nullptr;
+    int rc = internal_scratch(need, &base);
+    if (rc != SNAPKV_OK) return rc;
+    char* b = static_cast<char*>(base);
+    char* handoff_p = b + counters;
+    float* votes_p = reinterpret_cast<float*>(handoff_p + handoff * count);
+    char* stats_p = reinterpret_cast<char*>(votes_p) + votes;
+    int32_t* idx_p = reinterpret_cast<int32_t*>(stats_p + stats);
+    int32_t* nvalid_p = reinterpret_cast<int32_t*>(reinterpret_cast<char*>(idx_p) + idx_tmp);
+    SelectScratch Sb;
+    select_layout(Htot, npad, &Sb, reinterpret_cast<char*>(nvalid_p) + nvalid, false, b);
+
+    BatchDesc B;
+    B.count = count;
+    B.Hkv = Hkv;
+    for (int i = 0; i < count; ++i) {
+        B.L[i] = L[i];
+        B.n[i] = G[i].n;
+        B.k[i] = k[i];
+        B.v[i] = v[i];
+        B.out_k[i] = out_k[i];
+        B.out_v[i] = out_v[i];
+        B.out_idx[i] = out_idx[i];
+    }
+    stage_done(st, kStageBegin);
+    if (launch_prepare(handoff_p, (int64_t)(handoff * count / sizeof(unsigned long long)), &Sb, Htot, st) != hipSuccess)
+        return SNAPKV_ERR_HIP;
+    if (launch_batch_lengths(B, nvalid_p, st) != hipSuccess) return SNAPKV_ERR_HIP;
+    stage_done(st, kStagePrepare);
+    char* sp = stats_p;
+    for (int i = 0; i < count; ++i) {
+        Workspace ws{};
+        ws.fused = handoff_p + handoff * i;
+        ws.vote = votes_p + (size_t)i * Hq * (size_t)npad;
+        ws.stat_part = reinterpret_cast<float2*>(sp);
+        ws.lse = reinterpret_cast<float*>(sp + up(stream_stat_bytes(G[i])));
+        sp += per_prompt[i];
+        G[i].vpitch = npad;
+        ScoreGeom Gv = G[i];
+        rc = run_scores(dtype, q_win[i], k[i], D, G[i], ws, pool_kind, p, nullptr, nullptr, false, &Gv, st, true);
+        if (rc != SNAPKV_OK) return rc;
+        if (Gv.VB != 1 || Gv.NV != g) return SNAPKV_ERR_UNSUPPORTED;   // not reached: lse_plan held above
+    }
+    if (launch_pool_select(Gb, votes_p, pool_kind, p, C - W, C, W, idx_p, Sb, st, nvalid_p) != hipSuccess)
+        return SNAPKV_ERR_HIP;
+    stage_done(st, kStageSelect);
+    if (launch_gather_batch(B, idx_p, C, row_bytes, CleanJob{}, st) != hipSuccess) return SNAPKV_ERR_HIP;
+    stage_done(st, kStageGather);
+    return SNAPKV_OK;
+}
+
+}  // namespace
+
+namespace snapkv {
 void stage_done(hipStream_t st, int stage) {
     if (!g_prof.active) return;
     if (stage == kStageBegin) {
@@ -519,6 +619,63 @@ int64_t snapkv_compress_paged(int dtype, const void* q_win, const void* k_pages,
     pm.pages = num_pages;
     return compress_impl(dtype, q_win, k_pages, v_pages, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
                          nullptr, 0, true, stream, nullptr, false, &lay, &lay, false, pm);
+}
+
+int snapkv_compress_varlen(int dtype, int n_prompts, const void* const* q_win, const void* const* k,
+                           const void* const* v, const int64_t* L, int Hq, int Hkv, int D, int W, int pool_kind,
+                           int p, int64_t C, void* const* out_k, void* const* out_v, int32_t* const* out_idx,
+                           int64_t* kept, void* stream) {
+    if (n_prompts < 0 || (n_prompts > 0 && (!q_win || !k || !v || !L || !out_k || !out_v || !out_idx)))
+        return SNAPKV_ERR_INVALID_ARG;
+    if (!valid_dtype(dtype)) return SNAPKV_ERR_INVALID_ARG;
+    // every prompt is checked before anything is enqueued
+    for (int i = 0; i < n_prompts; ++i) {
+        int rc = check_score_args(q_win[i], k[i], L[i], Hq, Hkv, D, W, pool_kind, p);
+        if (rc != SNAPKV_OK) return rc;
+        if (!v[i] || !out_k[i] || !out_v[i] || !out_idx[i]) return SNAPKV_ERR_INVALID_ARG;
+        if (C < 1 || W > C) return SNAPKV_ERR_INVALID_ARG;
+        if (C >= (int64_t)1 << 31) return SNAPKV_ERR_UNSUPPORTED;
+        if (!aligned16(v[i]) || !aligned16(out_k[i]) || !aligned16(out_v[i])) return SNAPKV_ERR_MISALIGNED;
+        if ((reinterpret_cast<uintptr_t>(out_idx[i]) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int order[kMaxBatch];
+    int i = 0;
+    while (i < n_prompts) {
+        // the next run of prompts that need compressing (L > C), at most kMaxBatch of them
+        int cnt = 0, j = i;
+        for (; j < n_prompts && cnt < kMaxBatch; ++j) {
+            if (L[j] > C) order[cnt++] = j;
+            else {   // Listing 1, first branch: returned unchanged
+                const int64_t r = compress_impl(dtype, q_win[j], k[j], v[j], L[j], Hq, Hkv, D, W, pool_kind, p, C,
+                                                out_k[j], out_v[j], out_idx[j], nullptr, 0, true, stream);
+                if (r < 0) return (int)r;
+                if (kept) kept[j] = r;
+            }
+        }
+        const void *bq[kMaxBatch], *bk[kMaxBatch], *bv[kMaxBatch];
+        void *bok[kMaxBatch], *bov[kMaxBatch];
+        int32_t* boi[kMaxBatch];
+        int64_t bl[kMaxBatch];
+        for (int c = 0; c < cnt; ++c) {
+            const int s = order[c];
+            bq[c] = q_win[s]; bk[c] = k[s]; bv[c] = v[s]; bok[c] = out_k[s]; bov[c] = out_v[s]; boi[c] = out_idx[s];
+            bl[c] = L[s];
+        }
+        int rc = cnt > 0 ? compress_batch(dtype, cnt, bq, bk, bv, bl, Hq, Hkv, D, W, pool_kind, p, C, bok, bov, boi, st) : SNAPKV_OK;
+        if (rc < 0) return rc;
+        for (int c = 0; c < cnt; ++c) {
+            const int s = order[c];
+            if (rc == 1) {   // prompt by prompt
+                const int64_t r = compress_impl(dtype, bq[c], bk[c], bv[c], bl[c], Hq, Hkv, D, W, pool_kind, p, C,
+                                                bok[c], bov[c], boi[c], nullptr, 0, true, stream);
+                if (r < 0) return (int)r;
+            }
+            if (kept) kept[s] = C;
+        }
+        i = j;
+    }
+    return SNAPKV_OK;
 }
 
 int64_t snapkv_compress_per_query_head(int dtype, const void* q_win, const void* k, const void* v, int64_t L,

@@ -614,7 +614,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                 f[ru][2] = (ms.z == -INFINITY || b.y == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.z - b.x) * b.y;
                 f[ru][3] = (ms.w == -INFINITY || b.w == 0.f) ? 0.f : __builtin_amdgcn_exp2f(ms.w - b.z) * b.w;
             }
-            float* vb = vote + (int64_t)unit_p2 * F.gs * G.n;
+            float* vb = vote + (int64_t)unit_p2 * F.gs * G.vpitch;
             int jst = tile0 * 16 + n16;       // opaque for the same reason as above
             asm volatile("" : "+v"(jst));
             const int nst = (int)G.n;
@@ -633,7 +633,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                 }
                 if ((ru + 1) % F.UH == 0) {   // last row unit of a query head: finish its votes
                     const int head = ru / F.UH;
-                    float* vh = vb + (int64_t)head * G.n;
+                    float* vh = vb + (int64_t)head * G.vpitch;
                     // sum over the four contraction-slice lanes of a column; with several tiles
                     // the lanes split the tiles between them so that each stores its own share
                     if constexpr (KT >= 4) {
@@ -913,7 +913,7 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
 
         // votes: sum over the window rows of each query head, then over the four lanes of a column
         if constexpr (!STAT) {
-            float* vb = vote + (int64_t)unit * F.gs * G.n;
+            float* vb = vote + (int64_t)unit * F.gs * G.vpitch;
             int jst = tile0 * 16 + n16;
             asm volatile("" : "+v"(jst));
             const int nst = (int)G.n;
@@ -929,7 +929,7 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
                 }
                 if ((ru + 1) % F.UH == 0) {
                     const int head = ru / F.UH;
-                    float* vh = vb + (int64_t)head * G.n;
+                    float* vh = vb + (int64_t)head * G.vpitch;
                     if constexpr (KT >= 4) {
                         float a[KT / 2], b[KT / 4];
 #pragma unroll

@@ -33,6 +33,7 @@ struct ScoreGeom {
     float c2;        // log2(e) / sqrt(D): logits are kept in the base-2 domain
     int64_t k_hs;    // bytes between the K rows of consecutive KV heads (contiguous: L * D * element size)
     int64_t k_rs;    // bytes between consecutive K rows of a head (contiguous: D * element size)
+    int64_t vpitch;  // floats between the vote rows of consecutive query heads (n unless a batch pads them)
     // paged K: logical row j lives at physical row k_table[j / k_page] * k_page + j % k_page (null: j itself)
     const int32_t* k_table;
     int k_page;
@@ -132,9 +133,11 @@ hipError_t launch_row_lse(int dtype, int D, const void* q, const void* k, const 
 // Pooling and selection in one cooperative launch (reads votes, writes the kept positions).
 // pool_select_ok says whether the shape fits and the grid can be resident on the current device.
 bool pool_select_ok(const ScoreGeom& G, int pool_kind, int p, int64_t kcount);
+// nvalid (may be null): per head the number of valid positions, at most G.n, which is then only the
+// pitch of the vote rows and of the candidate lists.
 hipError_t launch_pool_select(const ScoreGeom& G, const float* vote, int pool_kind, int p, int64_t kcount,
                               int64_t out_stride, int W_tail, int32_t* out_idx, const SelectScratch& S,
-                              hipStream_t st);
+                              hipStream_t st, const int32_t* nvalid = nullptr);
 unsigned read_select_timeouts();
 
 // Hit rate of the voting (snapkv_hitrate.hip).
@@ -175,6 +178,22 @@ struct PageMap {
     int page = 1;
     int64_t pages = 0;
 };
+// A batch of prompts of one model (same heads, window and capacity, different lengths) whose
+// selection and gather run as one launch each.  Passed by value to the kernels.
+constexpr int kMaxBatch = 32;
+struct BatchDesc {
+    int count, Hkv;
+    int64_t L[kMaxBatch], n[kMaxBatch];
+    const void* k[kMaxBatch];
+    const void* v[kMaxBatch];
+    void* out_k[kMaxBatch];
+    void* out_v[kMaxBatch];
+    int32_t* out_idx[kMaxBatch];
+};
+hipError_t launch_batch_lengths(const BatchDesc& B, int32_t* nvalid, hipStream_t st);
+hipError_t launch_gather_batch(const BatchDesc& B, const int32_t* idx, int64_t C, int row_bytes,
+                               const CleanJob& clean, hipStream_t st);
+
 hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H, int64_t L,
                          int64_t rows, int64_t out_stride, int row_bytes, void* out_k, void* out_v,
                          const RowLayout& kl, const RowLayout& vl, const CleanJob& clean, hipStream_t st,

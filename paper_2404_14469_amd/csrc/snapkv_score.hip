@@ -309,6 +309,7 @@ ScoreGeom make_geom(int64_t L, int Hq, int Hkv, int D, int W) {
     G.c2 = (float)(1.4426950408889634 / __builtin_sqrt((double)D));
     G.k_rs = 0;   // set by the caller once the element size is known
     G.k_hs = 0;
+    G.vpitch = G.n;
     G.k_table = nullptr;
     G.k_page = 1;
     G.k_pages = 0;

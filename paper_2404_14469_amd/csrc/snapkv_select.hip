@@ -415,6 +415,57 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
     for (int64_t j = gid; j < clean.nzeros; j += gsz) clean.zeros[j] = 0u;
 }
 
+// Per-head valid prefix lengths of a batch: head h of the batch belongs to prompt h / Hkv.
+__global__ __launch_bounds__(256) void batch_lengths(const BatchDesc B, int32_t* __restrict__ nvalid) {
+    const int i = blockIdx.x * 256 + threadIdx.x;
+    if (i < B.count * B.Hkv) nvalid[i] = (int32_t)B.n[i / B.Hkv];
+}
+
+hipError_t launch_batch_lengths(const BatchDesc& B, int32_t* nvalid, hipStream_t st) {
+    const int items = B.count * B.Hkv;
+    hipLaunchKernelGGL(batch_lengths, dim3((items + 255) / 256), dim3(256), 0, st, B, nvalid);
+    return hipGetLastError();
+}
+
+// gather_rows for a batch: head h of the grid is KV head h % Hkv of prompt h / Hkv; the kept
+// positions come from one [heads, C] array and are also copied to the prompt's own out_idx.
+__global__ __launch_bounds__(256) void gather_rows_batch(const BatchDesc B, const int32_t* __restrict__ idx,
+                                                         const int64_t C, const int pieces, const CleanJob clean) {
+    const int h = blockIdx.y, pr = h / B.Hkv, head = h % B.Hkv;
+    const int64_t L = B.L[pr];
+    const uint4* kb = static_cast<const uint4*>(B.k[pr]) + (int64_t)head * L * pieces;
+    const uint4* vb = static_cast<const uint4*>(B.v[pr]) + (int64_t)head * L * pieces;
+    uint4* okb = static_cast<uint4*>(B.out_k[pr]) + (int64_t)head * C * pieces;
+    uint4* ovb = static_cast<uint4*>(B.out_v[pr]) + (int64_t)head * C * pieces;
+    const int32_t* ib = idx + (int64_t)h * C;
+    int32_t* ob = B.out_idx[pr] + (int64_t)head * C;
+    const int64_t total = C * pieces;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+        const int64_t r = e / pieces;
+        const int c = (int)(e - r * pieces);
+        int64_t src = ib[r];
+        src = src < 0 ? 0 : (src < L ? src : L - 1);   // a failed selection cannot send a read outside the prompt
+        okb[r * pieces + c] = kb[src * pieces + c];
+        ovb[r * pieces + c] = vb[src * pieces + c];
+        if (c == 0) ob[r] = ib[r];
+    }
+    const int64_t gid = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
+    const int64_t gsz = (int64_t)gridDim.y * gridDim.x * 256;
+    for (int64_t j = gid; j < clean.nones; j += gsz) clean.ones[j] = ~0ull;
+    for (int64_t j = gid; j < clean.nzeros; j += gsz) clean.zeros[j] = 0u;
+}
+
+hipError_t launch_gather_batch(const BatchDesc& B, const int32_t* idx, int64_t C, int row_bytes,
+                               const CleanJob& clean, hipStream_t st) {
+    if (B.count <= 0 || C <= 0) return hipSuccess;
+    const int pieces = row_bytes / 16;
+    const int64_t total = C * pieces;
+    unsigned bx = (unsigned)((total + 255) / 256);
+    if (bx > 1024) bx = 1024;
+    hipLaunchKernelGGL(gather_rows_batch, dim3(bx, B.count * B.Hkv), dim3(256), 0, st, B, idx, C, pieces, clean);
+    return hipGetLastError();
+}
+
 hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H, int64_t L,
                          int64_t rows, int64_t out_stride, int row_bytes, void* out_k, void* out_v,
                          const RowLayout& kl, const RowLayout& vl, const CleanJob& clean, hipStream_t st,

@@ -581,7 +581,8 @@ template <int EPT, int P, int KIND>   // KIND: 0 max pooling, 1 average pooling
 __global__ __launch_bounds__(kPsThreads) void pool_select(
     const float* __restrict__ vote, const ScoreGeom G, const int p_arg,
     const int64_t kcount, const int64_t out_stride, const int W_tail, int32_t* __restrict__ out_idx,
-    const SelectScratch S, const int Wh, const int chunk, const unsigned spin_limit) {
+    const SelectScratch S, const int Wh, const int chunk, const unsigned spin_limit,
+    const int32_t* __restrict__ nvalid) {
     constexpr int NT = kPsThreads;
     constexpr int NWV = NT / 64;
     // One dynamic LDS block, used in turn as the staging area of the votes (chunk plus a halo of
@@ -596,7 +597,14 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
     __shared__ unsigned sh_off[kPsMaxGroup + 1];    // start of each workgroup's candidates in the merged list
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int h = blockIdx.x / Wh, c = blockIdx.x % Wh;
-    const int64_t n = G.n;
+    // rows of votes and candidate lists are G.n apart; a head may have fewer valid positions (a
+    // batch of prompts of different lengths shares one launch)
+    const int64_t pitch = G.n;
+    int64_t n = pitch;
+    if (nvalid) {
+        n = nvalid[h];
+        n = n < 0 ? 0 : (n > pitch ? pitch : n);
+    }
     const int64_t chunk0 = (int64_t)c * chunk;
     const int64_t chunk1 = chunk0 + chunk < n ? chunk0 + chunk : n;
     const int len = chunk1 > chunk0 ? (int)(chunk1 - chunk0) : 0;
@@ -621,7 +629,7 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
     constexpr int pool_kind = KIND;
     const float pad = KIND == 0 ? -INFINITY : 0.f;
     const int nf4 = ((len + 3) / 4) + 2 * (HQ / 4);   // 16-byte pieces to stage
-    const bool rows_aligned = (n & 3) == 0 && (reinterpret_cast<uintptr_t>(vote) & 15u) == 0;
+    const bool rows_aligned = ((n | pitch) & 3) == 0 && (reinterpret_cast<uintptr_t>(vote) & 15u) == 0;
     auto pos_local = [&](int e) { return (e >> 2) * (4 * NT) + 4 * tid + (e & 3); };
     const int nn = (int)n, kc = (int)kcount;
     unsigned x[EPT];
@@ -630,7 +638,7 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
 #pragma unroll
         for (int e = 0; e < EPT; ++e) acc[e] = 0.f;
         for (int hq = 0; hq < G.g; ++hq) {
-            const float* vb = vote + ((int64_t)h * G.NV + (int64_t)hq * G.VB) * n;
+            const float* vb = vote + ((int64_t)h * G.NV + (int64_t)hq * G.VB) * pitch;
             if (hq > 0) __syncthreads();          // the previous head's taps have been read
             float4 land[E4 + 1];                  // all loads are in flight before the first LDS write
 #pragma unroll
@@ -650,7 +658,7 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
                             if (q >= 0 && q < nn) {
                                 t[k] = vb[q];
                                 if (P == 0)   // several vote rows per query head only reach the loop form
-                                    for (int b = 1; b < G.VB; ++b) t[k] += vb[(int64_t)b * n + q];
+                                    for (int b = 1; b < G.VB; ++b) t[k] += vb[(int64_t)b * pitch + q];
                             }
                         }
                         t4 = make_float4(t[0], t[1], t[2], t[3]);
@@ -826,7 +834,7 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
     block_sum3<NT>(above_total, z1, z2, sh_red);
     if (!exact) {   // this workgroup's candidates go to the start of its own stretch of the head's list
         unsigned slot = in_before;
-        unsigned long long* const my_cand = reinterpret_cast<unsigned long long*>(S.cand + (int64_t)h * n + chunk0);
+        unsigned long long* const my_cand = reinterpret_cast<unsigned long long*>(S.cand + (int64_t)h * pitch + chunk0);
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
             if (active >> e & 1u) {
@@ -890,9 +898,9 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
                 if (sh_off[mid] <= i) a2 = mid; else b2 = mid;
             }
             int64_t at = (int64_t)a2 * chunk + (i - sh_off[a2]);
-            at = at < n ? at : n - 1;       // only counts that a failed rendezvous left inconsistent get here
+            at = at < pitch ? at : pitch - 1;       // only counts that a failed rendezvous left inconsistent get here
             const unsigned long long both = __hip_atomic_load(
-                reinterpret_cast<const unsigned long long*>(&S.cand[(int64_t)h * n + at]),
+                reinterpret_cast<const unsigned long long*>(&S.cand[(int64_t)h * pitch + at]),
                 __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             sh_cand[i] = make_uint2((unsigned)(both & 0xffffffffull), (unsigned)(both >> 32));
         }
@@ -1098,6 +1106,7 @@ struct PoolSelCall {
     const SelectScratch* S;
     int Wh, chunk;
     hipStream_t st;
+    const int32_t* nvalid;
 };
 
 constexpr unsigned kPsSpinLimit = 1u << 14;    // polls before a rendezvous gives up (tens of ms)
@@ -1131,7 +1140,7 @@ static hipError_t pool_select_instance(const PoolSelCall* call, int* occ) {
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(call->G->Hkv * call->Wh)), dim3(kPsThreads), kLds, call->st,
                        call->vote, *call->G, call->p, call->kcount, call->out_stride,
-                       call->W_tail, call->out_idx, *call->S, call->Wh, call->chunk, kPsSpinLimit);
+                       call->W_tail, call->out_idx, *call->S, call->Wh, call->chunk, kPsSpinLimit, call->nvalid);
     return hipGetLastError();
 }
 
@@ -1200,10 +1209,10 @@ bool pool_select_ok(const ScoreGeom& G, int pool_kind, int p, int64_t kcount) {
 
 hipError_t launch_pool_select(const ScoreGeom& G, const float* vote, int pool_kind, int p, int64_t kcount,
                               int64_t out_stride, int W_tail, int32_t* out_idx, const SelectScratch& S,
-                              hipStream_t st) {
+                              hipStream_t st, const int32_t* nvalid) {
     int Wh = 0, chunk = 0, ept = 0;
     if (!pool_select_plan(G, pool_kind, p, kcount, &Wh, &chunk, &ept)) return hipErrorInvalidValue;
-    const PoolSelCall call{vote, &G, pool_kind, p, kcount, out_stride, W_tail, out_idx, &S, Wh, chunk, st};
+    const PoolSelCall call{vote, &G, pool_kind, p, kcount, out_stride, W_tail, out_idx, &S, Wh, chunk, st, nvalid};
     int occ = 0;
     return pool_select_dispatch(ept, ps_width(G, p), pool_kind, &call, &occ);
 }
