@@ -176,12 +176,28 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
     return SNAPKV_OK;
 }
 
+// What the entry points vary on top of the plain step.
+struct CompressOptions {
+    void* workspace = nullptr;          // caller's workspace; null: the library's own per-device buffer
+    size_t workspace_bytes = 0;
+    bool own_scratch = true;
+    const float* lse = nullptr;         // the window rows' log-sum-exp, when the caller hands it in
+    bool with_lse = false;
+    const RowLayout* k_layout = nullptr;   // null: contiguous [Hkv, L, D]
+    const RowLayout* v_layout = nullptr;
+    bool per_query_head = false;        // one selection and one cache per query head
+    PageMap pm;                         // paged K and V
+};
+
 int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v, int64_t L, int Hq,
                       int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k,
-                      void* out_v, int32_t* out_idx, void* workspace, size_t workspace_bytes,
-                      bool own_scratch, void* stream, const float* lse = nullptr, bool with_lse = false,
-                      const RowLayout* k_layout = nullptr, const RowLayout* v_layout = nullptr,
-                      bool per_query_head = false, const PageMap& pm = PageMap{}) {
+                      void* out_v, int32_t* out_idx, void* stream, const CompressOptions& opt = CompressOptions{}) {
+    void* const workspace = opt.workspace;
+    const size_t workspace_bytes = opt.workspace_bytes;
+    const bool own_scratch = opt.own_scratch, with_lse = opt.with_lse, per_query_head = opt.per_query_head;
+    const float* const lse = opt.lse;
+    const RowLayout *const k_layout = opt.k_layout, *const v_layout = opt.v_layout;
+    const PageMap& pm = opt.pm;
     if (!valid_dtype(dtype)) return SNAPKV_ERR_INVALID_ARG;
     if (with_lse && !lse) return SNAPKV_ERR_INVALID_ARG;
     if (with_lse && (reinterpret_cast<uintptr_t>(lse) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
@@ -535,22 +551,25 @@ int64_t snapkv_compress(const void* q_win, const void* k, const void* v, int64_t
                         int D, int W, int pool_kind, int p, int64_t C, void* out_k, void* out_v,
                         int32_t* out_idx, void* stream) {
     return compress_impl(SNAPKV_DTYPE_BF16, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k,
-                         out_v, out_idx, nullptr, 0, true, stream);
+                         out_v, out_idx, stream);
 }
 
 int64_t snapkv_compress_f32(const void* q_win, const void* k, const void* v, int64_t L, int Hq,
                             int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k,
                             void* out_v, int32_t* out_idx, void* stream) {
     return compress_impl(SNAPKV_DTYPE_F32, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k,
-                         out_v, out_idx, nullptr, 0, true, stream);
+                         out_v, out_idx, stream);
 }
 
 int64_t snapkv_compress_ws(int dtype, const void* q_win, const void* k, const void* v, int64_t L,
                            int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
                            void* out_k, void* out_v, int32_t* out_idx, void* workspace,
                            size_t workspace_bytes, void* stream) {
-    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
-                         workspace, workspace_bytes, false, stream);
+    CompressOptions opt;
+    opt.workspace = workspace;
+    opt.workspace_bytes = workspace_bytes;
+    opt.own_scratch = false;
+    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx, stream, opt);
 }
 
 int snapkv_pooled_scores(const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D, int W,
@@ -567,7 +586,7 @@ int64_t snapkv_compress_f16(const void* q_win, const void* k, const void* v, int
                             int Hkv, int D, int W, int pool_kind, int p, int64_t C, void* out_k,
                             void* out_v, int32_t* out_idx, void* stream) {
     return compress_impl(SNAPKV_DTYPE_F16, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k,
-                         out_v, out_idx, nullptr, 0, true, stream);
+                         out_v, out_idx, stream);
 }
 
 int snapkv_pooled_scores_f16(const void* q_win, const void* k, int64_t L, int Hq, int Hkv, int D,
@@ -578,8 +597,10 @@ int snapkv_pooled_scores_f16(const void* q_win, const void* k, int64_t L, int Hq
 int64_t snapkv_compress_lse(int dtype, const void* q_win, const void* k, const void* v, const float* lse,
                             int64_t L, int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
                             void* out_k, void* out_v, int32_t* out_idx, void* stream) {
-    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
-                         nullptr, 0, true, stream, lse, true);
+    CompressOptions opt;
+    opt.lse = lse;
+    opt.with_lse = true;
+    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx, stream, opt);
 }
 
 int snapkv_pooled_scores_lse(int dtype, const void* q_win, const void* k, const float* lse, int64_t L,
@@ -598,8 +619,10 @@ int64_t snapkv_compress_strided(int dtype, const void* q_win, const void* k, con
     const int64_t lim = (int64_t)1 << 56;
     if (k_head_stride > lim || v_head_stride > lim || k_row_stride > lim || v_row_stride > lim) return SNAPKV_ERR_UNSUPPORTED;
     const RowLayout kl{k_head_stride * es, k_row_stride * es}, vl{v_head_stride * es, v_row_stride * es};
-    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
-                         nullptr, 0, true, stream, nullptr, false, &kl, &vl);
+    CompressOptions opt;
+    opt.k_layout = &kl;
+    opt.v_layout = &vl;
+    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx, stream, opt);
 }
 
 int64_t snapkv_compress_paged(int dtype, const void* q_win, const void* k_pages, const void* v_pages,
@@ -617,8 +640,11 @@ int64_t snapkv_compress_paged(int dtype, const void* q_win, const void* k_pages,
     pm.table = block_table;
     pm.page = page_size;
     pm.pages = num_pages;
-    return compress_impl(dtype, q_win, k_pages, v_pages, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
-                         nullptr, 0, true, stream, nullptr, false, &lay, &lay, false, pm);
+    CompressOptions opt;
+    opt.k_layout = &lay;
+    opt.v_layout = &lay;
+    opt.pm = pm;
+    return compress_impl(dtype, q_win, k_pages, v_pages, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx, stream, opt);
 }
 
 int snapkv_compress_varlen(int dtype, int n_prompts, const void* const* q_win, const void* const* k,
@@ -648,7 +674,7 @@ int snapkv_compress_varlen(int dtype, int n_prompts, const void* const* q_win, c
             if (L[j] > C) order[cnt++] = j;
             else {   // Listing 1, first branch: returned unchanged
                 const int64_t r = compress_impl(dtype, q_win[j], k[j], v[j], L[j], Hq, Hkv, D, W, pool_kind, p, C,
-                                                out_k[j], out_v[j], out_idx[j], nullptr, 0, true, stream);
+                                                out_k[j], out_v[j], out_idx[j], stream);
                 if (r < 0) return (int)r;
                 if (kept) kept[j] = r;
             }
@@ -668,7 +694,7 @@ int snapkv_compress_varlen(int dtype, int n_prompts, const void* const* q_win, c
             const int s = order[c];
             if (rc == 1) {   // prompt by prompt
                 const int64_t r = compress_impl(dtype, bq[c], bk[c], bv[c], bl[c], Hq, Hkv, D, W, pool_kind, p, C,
-                                                bok[c], bov[c], boi[c], nullptr, 0, true, stream);
+                                                bok[c], bov[c], boi[c], stream);
                 if (r < 0) return (int)r;
             }
             if (kept) kept[s] = C;
@@ -681,8 +707,9 @@ int snapkv_compress_varlen(int dtype, int n_prompts, const void* const* q_win, c
 int64_t snapkv_compress_per_query_head(int dtype, const void* q_win, const void* k, const void* v, int64_t L,
                                        int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
                                        void* out_k, void* out_v, int32_t* out_idx, void* stream) {
-    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx,
-                         nullptr, 0, true, stream, nullptr, false, nullptr, nullptr, true);
+    CompressOptions opt;
+    opt.per_query_head = true;
+    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx, stream, opt);
 }
 
 int64_t snapkv_capacity_for_rate(int64_t L, int W, double rate) {
