@@ -161,7 +161,9 @@ DECODE_CAPPED_B8 = DecodeWorkload("decode_capped_b8", B=8, Hq=32, Hkv=32, D=128,
 # The uncompressed cache of a 16K prompt at the batch size where the paper's baseline runs out of memory.
 DECODE_FULL_16K_B2 = DecodeWorkload("decode_full_16k_b2", B=2, Hq=32, Hkv=32, D=128, S=16384 + 512,
                                     cap=16384 + 512, seed=2002)
-DECODE_CONFIGS: Dict[str, DecodeWorkload] = {w.name: w for w in (DECODE_CAPPED_B8, DECODE_FULL_16K_B2)}
+# The capped cache at the same batch size, for the ratio between the two.
+DECODE_CAPPED_B2 = DecodeWorkload("decode_capped_b2", B=2, Hq=32, Hkv=32, D=128, S=2560, cap=2560, seed=2003)
+DECODE_CONFIGS: Dict[str, DecodeWorkload] = {w.name: w for w in (DECODE_CAPPED_B8, DECODE_FULL_16K_B2, DECODE_CAPPED_B2)}
 
 
 def generate_decode(w: DecodeWorkload, device: str = "cpu") -> Dict[str, object]:
