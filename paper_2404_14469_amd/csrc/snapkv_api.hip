@@ -3,6 +3,7 @@
 #include "../../include/snapkv.h"
 #include "snapkv_internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <mutex>
 #include <vector>
@@ -427,19 +428,61 @@ int compress_batch(int dtype, int count, const void* const* q_win, const void* c
         return SNAPKV_ERR_HIP;
     if (launch_batch_lengths(B, nvalid_p, st) != hipSuccess) return SNAPKV_ERR_HIP;
     stage_done(st, kStagePrepare);
+    // scoring: the prompts, longest first, share launches of the single-read kernel as far as they fit
+    // the chip together; a prompt that kernel does not take is scored by a launch sequence of its own
+    Workspace wsp[kMaxBatch];
     char* sp = stats_p;
     for (int i = 0; i < count; ++i) {
-        Workspace ws{};
-        ws.fused = handoff_p + handoff * i;
-        ws.vote = votes_p + (size_t)i * Hq * (size_t)npad;
-        ws.stat_part = reinterpret_cast<float2*>(sp);
-        ws.lse = reinterpret_cast<float*>(sp + up(stream_stat_bytes(G[i])));
+        wsp[i] = Workspace{};
+        wsp[i].fused = handoff_p + handoff * i;
+        wsp[i].vote = votes_p + (size_t)i * Hq * (size_t)npad;
+        wsp[i].stat_part = reinterpret_cast<float2*>(sp);
+        wsp[i].lse = reinterpret_cast<float*>(sp + up(stream_stat_bytes(G[i])));
         sp += per_prompt[i];
         G[i].vpitch = npad;
-        ScoreGeom Gv = G[i];
-        rc = run_scores(dtype, q_win[i], k[i], D, G[i], ws, pool_kind, p, nullptr, nullptr, false, &Gv, st, true);
-        if (rc != SNAPKV_OK) return rc;
-        if (Gv.VB != 1 || Gv.NV != g) return SNAPKV_ERR_UNSUPPORTED;   // not reached: lse_plan held above
+    }
+    int rest[kMaxBatch], nrest = count;
+    for (int i = 0; i < count; ++i) rest[i] = i;
+    std::sort(rest, rest + count, [&](int a, int b) { return L[a] != L[b] ? L[a] > L[b] : a < b; });
+    while (nrest > 0) {
+        ScoreGeom Gr[kMaxBatch];
+        FusedGeom Fr[kMaxBatch];
+        for (int r = 0; r < nrest; ++r) Gr[r] = G[rest[r]];
+        int take[kMaxJointPrompts], wg_begin[kMaxJointPrompts], grid = 0;
+        const int taken = g_allow_fused ? fused_joint_plan(dtype, D, nrest, Gr, Fr, take, wg_begin, &grid) : 0;
+        if (taken == 0) {   // the longest of the rest goes alone
+            const int i = rest[0];
+            ScoreGeom Gv = G[i];
+            rc = run_scores(dtype, q_win[i], k[i], D, G[i], wsp[i], pool_kind, p, nullptr, nullptr, false, &Gv, st, true);
+            if (rc != SNAPKV_OK) return rc;
+            if (Gv.VB != 1 || Gv.NV != g) return SNAPKV_ERR_UNSUPPORTED;   // not reached: lse_plan held above
+            for (int r = 1; r < nrest; ++r) rest[r - 1] = rest[r];
+            --nrest;
+            continue;
+        }
+        const void *jq[kMaxJointPrompts], *jk[kMaxJointPrompts];
+        float* jv[kMaxJointPrompts];
+        ScoreGeom jG[kMaxJointPrompts];
+        FusedGeom jF[kMaxJointPrompts];
+        FusedSync jS[kMaxJointPrompts];
+        for (int t = 0; t < taken; ++t) {
+            const int i = rest[take[t]];
+            jq[t] = q_win[i];
+            jk[t] = k[i];
+            jv[t] = wsp[i].vote;
+            jG[t] = G[i];
+            jF[t] = Fr[take[t]];
+            fused_sync_layout(jG[t], jF[t], &jS[t], wsp[i].fused);
+        }
+        if (launch_score_fused_joint(dtype, D, taken, jq, jk, jG, jF, jS, jv, wg_begin, grid, st) != hipSuccess)
+            return SNAPKV_ERR_HIP;
+        stage_done(st, kStageFused);
+        int keep = 0;
+        for (int r = 0, t = 0; r < nrest; ++r) {
+            if (t < taken && take[t] == r) ++t;
+            else rest[keep++] = rest[r];
+        }
+        nrest = keep;
     }
     if (launch_pool_select(Gb, votes_p, pool_kind, p, C - W, C, W, idx_p, Sb, st, nvalid_p) != hipSuccess)
         return SNAPKV_ERR_HIP;

@@ -227,11 +227,12 @@ __device__ __forceinline__ void load_frag16p(Frag16<T, D>& f, const char* p) {
     for (int x = 0; x < Frag16<T, D>::NP; ++x) f.v[x] = *reinterpret_cast<const uint4*>(p + 64 * x);
 }
 
+// The kernel's body; `bid` is the workgroup's index inside its own launch plan (the block index,
+// or the block index less the first block of the prompt when several prompts share a launch).
 template <typename T, int D, int RUW, int KT, int NW>
-__global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ qv,
-                                                       const void* __restrict__ kv,
-                                                       float* __restrict__ vote, const FusedSync S,
-                                                       const ScoreGeom G, const FusedGeom F) {
+__device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, const void* __restrict__ kv,
+                                                 float* __restrict__ vote, const FusedSync& S,
+                                                 const ScoreGeom& G, const FusedGeom& F, const int bid) {
     constexpr int R = RUW * 16;          // window rows a workgroup tracks per unit
     constexpr int NT = NW * 64;
     constexpr int NSLOT = RUW * KT;      // accumulator tiles per lane per unit
@@ -258,7 +259,7 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
 
     const int tid = threadIdx.x, lane = tid & 63, n16 = lane & 15, kg = lane >> 4;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wg = (int)(blockIdx.x % F.Gg), group = (int)(blockIdx.x / F.Gg);
+    const int wg = bid % F.Gg, group = bid / F.Gg;
     // Tile t of this wave is key tile tile0 + t * TS: the waves of the whole group work on the same
     // t at about the same time, and this way what they request together is one contiguous stretch
     // of K instead of one 4 KB piece out of every wave's 16 KB (which loads only part of the memory
@@ -702,6 +703,44 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
     for (; it < nu + 2; ++it) iteration(std::integral_constant<int, 0>{}, it);   // last unit, two drain steps
     if (gave_up) atomicAdd(&g_sync_timeouts, 1u);
 }
+
+template <typename T, int D, int RUW, int KT, int NW>
+__global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ qv,
+                                                       const void* __restrict__ kv,
+                                                       float* __restrict__ vote, const FusedSync S,
+                                                       const ScoreGeom G, const FusedGeom F) {
+    score_fused_body<T, D, RUW, KT, NW>(qv, kv, vote, S, G, F, (int)blockIdx.x);
+}
+
+// Several prompts of one model in one launch: every prompt has its own groups of workgroups
+// (blocks wg_begin .. of the grid), its own hand-off words and vote rows, and runs exactly as in
+// a launch of its own; together the prompts fill the chip that one short prompt leaves idle.
+constexpr int kMaxJoint = kMaxJointPrompts;
+struct FusedPrompt {
+    const void* q;
+    const void* k;
+    float* vote;
+    FusedSync S;
+    ScoreGeom G;
+    FusedGeom F;
+    int wg_begin;
+};
+struct FusedJoint {
+    int count;
+    FusedPrompt p[kMaxJoint];
+};
+
+template <typename T, int D, int RUW, int KT, int NW>
+__global__ __launch_bounds__(NW * 64) void score_fused_joint(const FusedJoint J) {
+    int pi = 0;
+    for (int i = 1; i < J.count; ++i)
+        if ((int)blockIdx.x >= J.p[i].wg_begin) pi = i;
+    const FusedPrompt& P = J.p[pi];
+    const int bid = (int)blockIdx.x - P.wg_begin;
+    if (bid >= P.F.NG * P.F.Gg) return;   // padding between two prompts' blocks
+    score_fused_body<T, D, RUW, KT, NW>(P.q, P.k, P.vote, P.S, P.G, P.F, bid);
+}
+
 
 // ---------------------------------------------------------------------------------------------
 // Scoring and voting when the window rows' log-sum-exp is handed in (the normalisers a block-wise
@@ -1221,6 +1260,131 @@ bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
         return true;
     }
     return false;
+}
+
+// ---- several prompts in one launch
+template <typename T, int D, int RUW, int NW>
+static hipError_t joint_instance(const FusedJoint* J, int grid, hipStream_t st, int* occ) {
+    constexpr int KT = kFusedSlots / RUW;
+    auto kern = score_fused_joint<T, D, RUW, KT, NW>;
+    constexpr int kQueueBytes = 3 * RUW * (D * esize<T>::value / 64) * 64 * 16;
+    static int cached_occ = -1;
+    if (cached_occ < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kQueueBytes);
+        if (e != hipSuccess) return e;
+        int n = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, NW * 64, kQueueBytes);
+        if (e != hipSuccess) return e;
+        cached_occ = n;
+    }
+    if (occ) *occ = cached_occ;
+    if (!J) return hipSuccess;
+    if ((int64_t)grid > (int64_t)cached_occ * cu_count()) return hipErrorCooperativeLaunchTooLarge;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(NW * 64), kQueueBytes, st, *J);
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t joint_by_rows(int RUW, const FusedJoint* J, int grid, hipStream_t st, int* occ) {
+    switch (RUW) {
+        case 1: return joint_instance<T, D, 1, kFusedWaves>(J, grid, st, occ);
+        case 2: return joint_instance<T, D, 2, kFusedWaves>(J, grid, st, occ);
+        case 4: return joint_instance<T, D, 4, kFusedWaves>(J, grid, st, occ);
+        case 8: return joint_instance<T, D, 8, kFusedWaves>(J, grid, st, occ);
+    }
+    return hipErrorInvalidValue;
+}
+
+// Two-byte storage types only: the joint launch serves batches of short prompts.
+static hipError_t joint_dispatch(int dtype, int D, int RUW, const FusedJoint* J, int grid, hipStream_t st, int* occ) {
+    if (dtype == 0) {
+        if (D == 128) return joint_by_rows<bf16_k, 128>(RUW, J, grid, st, occ);
+        if (D == 64) return joint_by_rows<bf16_k, 64>(RUW, J, grid, st, occ);
+    } else if (dtype == 2) {
+        if (D == 128) return joint_by_rows<f16_k, 128>(RUW, J, grid, st, occ);
+        if (D == 64) return joint_by_rows<f16_k, 64>(RUW, J, grid, st, occ);
+    }
+    return hipErrorInvalidValue;
+}
+
+static int up8(int x) { return (x + 7) & ~7; }
+
+// Plans one joint launch over some of the prompts G[0..count), scanned in the order given (the
+// caller puts the longest first): take[] gets the indices taken (at most kMaxJoint), F[i] of a taken
+// prompt its shape and its number of groups, wg_begin[t] the first block of the t-th taken prompt (a
+// multiple of eight, so that the die of a workgroup is the same as in a launch of its own), *grid
+// the blocks of the launch.  Returns how many prompts the launch takes; 0 when G[0] cannot use the
+// kernel at all.  Every prompt gets at least one group per part of a KV head; what the chip has
+// left over goes, a step at a time, to the prompt with the most iterations still to run.
+int fused_joint_plan(int dtype, int D, int count, const ScoreGeom* G, FusedGeom* F, int* take, int* wg_begin,
+                     int* grid) {
+    if (count < 1 || (dtype != 0 && dtype != 2)) return 0;
+    if (!fused_plan(dtype, D, G[0], &F[0])) return 0;
+    int occ = 0;
+    if (joint_dispatch(dtype, D, F[0].RUW, nullptr, 0, nullptr, &occ) != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    const int slots = cu_count() * occ;
+    int taken = 0, total = 0;
+    for (int i = 0; i < count && taken < kMaxJoint; ++i) {
+        if (i > 0 && (!fused_plan(dtype, D, G[i], &F[i]) || F[i].RUW != F[0].RUW || F[i].split != F[0].split ||
+                      F[i].NW != F[0].NW))
+            continue;
+        const int least = up8(F[i].split * F[i].Gg);
+        if (total + least > slots) {
+            if (i == 0) return 0;
+            continue;
+        }
+        F[i].NG = F[i].split;
+        total += least;
+        take[taken++] = i;
+    }
+    for (;;) {   // hand the spare blocks out
+        int best = -1, best_iters = 0;
+        for (int t = 0; t < taken; ++t) {
+            const FusedGeom& f = F[take[t]];
+            if (f.NG + f.split > f.units) continue;
+            const int more = up8((f.NG + f.split) * f.Gg) - up8(f.NG * f.Gg);
+            const int iters = (f.units + f.NG - 1) / f.NG;
+            if (total + more <= slots && iters > best_iters) {
+                best = t;
+                best_iters = iters;
+            }
+        }
+        if (best < 0 || best_iters <= 1) break;
+        FusedGeom& f = F[take[best]];
+        total += up8((f.NG + f.split) * f.Gg) - up8(f.NG * f.Gg);
+        f.NG += f.split;
+    }
+    int at = 0;
+    for (int t = 0; t < taken; ++t) {
+        wg_begin[t] = at;
+        at += up8(F[take[t]].NG * F[take[t]].Gg);
+    }
+    *grid = at;
+    return taken;
+}
+
+hipError_t launch_score_fused_joint(int dtype, int D, int count, const void* const* q, const void* const* k,
+                                    const ScoreGeom* G, const FusedGeom* F, const FusedSync* S, float* const* vote,
+                                    const int* wg_begin, int grid, hipStream_t st) {
+    if (count < 1 || count > kMaxJoint) return hipErrorInvalidValue;
+    FusedJoint J;
+    J.count = count;
+    for (int i = 0; i < count; ++i) {
+        if (G[i].n <= 0) return hipErrorInvalidValue;
+        J.p[i].q = q[i];
+        J.p[i].k = k[i];
+        J.p[i].vote = vote[i];
+        J.p[i].S = S[i];
+        J.p[i].G = G[i];
+        J.p[i].F = F[i];
+        J.p[i].wg_begin = wg_begin[i];
+    }
+    for (int i = count; i < kMaxJoint; ++i) J.p[i] = J.p[0];
+    return joint_dispatch(dtype, D, F[0].RUW, &J, grid, st, nullptr);
 }
 
 hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,

@@ -112,6 +112,13 @@ bool fused_shape(const ScoreGeom& G, FusedGeom* F);
 size_t fused_sync_bytes(const ScoreGeom& G);
 bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
 size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base);
+// Several prompts of one model in one launch of the single-read kernel (snapkv_fused.hip).
+constexpr int kMaxJointPrompts = 8;
+int fused_joint_plan(int dtype, int D, int count, const ScoreGeom* G, FusedGeom* F, int* take, int* wg_begin,
+                     int* grid);
+hipError_t launch_score_fused_joint(int dtype, int D, int count, const void* const* q, const void* const* k,
+                                    const ScoreGeom* G, const FusedGeom* F, const FusedSync* S, float* const* vote,
+                                    const int* wg_begin, int grid, hipStream_t st);
 hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                               const FusedGeom& F, const FusedSync& S, float* vote, hipStream_t st);
 unsigned read_sync_timeouts();
