@@ -157,8 +157,9 @@ int64_t snapkv_compress_strided(int dtype, const void* q_win, const void* k, con
 /*
  * The compression step for a batch of prompts of one model (same heads, window, pooling and capacity,
  * different lengths), e.g. the prompts of one serving step.  Every prompt gets exactly the result of its
- * own snapkv_compress call; the batch only saves launches: scoring still runs once per prompt, pooling
- * with selection and the gather run once for up to 32 prompts.
+ * own snapkv_compress call; the batch only saves launches and idle compute units: prompts share scoring
+ * launches as far as they fit the chip together, and pooling with selection and the gather run once for
+ * up to 32 prompts.
  *
  *   n_prompts >= 0
  *   q_win, k, v, out_k, out_v, out_idx   HOST arrays of n_prompts DEVICE pointers, each as the argument of
