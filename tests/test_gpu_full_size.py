@@ -53,6 +53,96 @@ def test_varlen_batch(snapkv):
         _run(snapkv, w, 0, [i % w.Hkv, (i + 3) % w.Hkv])
 
 
+def test_varlen_batch_through_the_batch_entry(snapkv):
+    """The batched-varlen configuration as bench.py times it: every prompt of the batch gets, bit for bit,
+    what its own call gives (which test_varlen_batch checks against the oracle)."""
+    import numpy as np
+    ws = workloads.varlen_prompts()
+    cases = [workloads.generate(w, device="cuda") for w in ws]
+    w0 = ws[0]
+    oks = [torch.zeros((w0.Hkv, w0.C, w0.D), dtype=torch.bfloat16, device="cuda") for _ in ws]
+    ovs = [torch.zeros_like(t) for t in oks]
+    ois = [torch.full((w0.Hkv, w0.C), -1, dtype=torch.int32, device="cuda") for _ in ws]
+    kept = snapkv.snapkv_compress_varlen([c["q_win"] for c in cases], [c["k"] for c in cases], [c["v"] for c in cases],
+                                         w0.pool_kind, w0.p, w0.C, oks, ovs, ois)
+    torch.cuda.synchronize()
+    for i, (w, c) in enumerate(zip(ws, cases)):
+        print(f"[full-size] varlen batch prompt {i} L={w.L}", flush=True)
+        ref = run_gpu(snapkv, c["q_win"], c["k"], c["v"], w.pool_kind, w.p, w.C)
+        assert kept[i] == ref[4] == w.C
+        assert np.array_equal(ois[i].cpu().numpy(), ref[3])
+        assert torch.equal(oks[i], ref[1]) and torch.equal(ovs[i], ref[2])
+    assert snapkv.snapkv_sync_timeouts() == 0
+
+
+def test_one_cache_per_query_head_at_full_size(snapkv):
+    """The GQA configuration with one cache per query head: all properties that hold at any size on every
+    query head, the oracle's per-query-head form (the step on repeated KV heads) on sampled ones."""
+    w = workloads.MISTRAL_7B_GQA_32K
+    case = workloads.generate(w, layer=3, device="cuda")
+    q, k, v = case["q_win"], case["k"], case["v"]
+    g = w.Hq // w.Hkv
+    out_k = torch.zeros((w.Hq, w.C, w.D), dtype=k.dtype, device="cuda")
+    out_v = torch.zeros_like(out_k)
+    out_idx = torch.full((w.Hq, w.C), -1, dtype=torch.int32, device="cuda")
+    kept = snapkv.snapkv_compress_per_query_head(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx)
+    k_rep, v_rep = k.repeat_interleave(g, dim=0).contiguous(), v.repeat_interleave(g, dim=0).contiguous()
+    sc = torch.empty((w.Hq, w.n), dtype=torch.float32, device="cuda")
+    snapkv.snapkv_pooled_scores(q, k_rep, w.pool_kind, w.p, sc)
+    torch.cuda.synchronize()
+    idx = out_idx.cpu().numpy()
+    check_self_consistency(q, k_rep, v_rep, w.C, sc.cpu().numpy(), out_k, out_v, idx, kept)
+    check_against_oracle(q, k_rep, v_rep, w.pool_kind, w.p, w.C, sc.cpu().numpy(), out_k, out_v, idx, kept,
+                         heads=[0, 9, 31])
+
+
+def test_paged_cache_at_full_size(snapkv):
+    """The long-context configuration from 16-row pages in shuffled order: identical to the contiguous call."""
+    import numpy as np
+    w = workloads.LONG_131K
+    case = workloads.generate(w, layer=1, device="cuda")
+    q, k, v = case["q_win"], case["k"], case["v"]
+    ref = run_gpu(snapkv, q, k, v, w.pool_kind, w.p, w.C)
+    ps = 16
+    npg = (w.L + ps - 1) // ps
+    table = torch.randperm(npg, generator=torch.Generator().manual_seed(4)).to(torch.int32).cuda()
+    pos = torch.arange(w.L, device="cuda")
+    kp = torch.zeros((npg, ps, w.Hkv, w.D), dtype=k.dtype, device="cuda")
+    vp = torch.zeros_like(kp)
+    kp[table.long()[pos // ps], pos % ps] = k.permute(1, 0, 2)
+    vp[table.long()[pos // ps], pos % ps] = v.permute(1, 0, 2)
+    del case, k, v
+    out_k = torch.zeros((w.Hkv, w.C, w.D), dtype=kp.dtype, device="cuda")
+    out_v = torch.zeros_like(out_k)
+    out_idx = torch.full((w.Hkv, w.C), -1, dtype=torch.int32, device="cuda")
+    kept = snapkv.snapkv_compress_paged(q, kp, vp, table, w.L, w.pool_kind, w.p, w.C, out_k, out_v, out_idx)
+    torch.cuda.synchronize()
+    assert kept == ref[4]
+    assert np.array_equal(out_idx.cpu().numpy(), ref[3])
+    assert torch.equal(out_k, ref[1]) and torch.equal(out_v, ref[2])
+    assert snapkv.snapkv_sync_timeouts() == 0
+
+
+def test_decode_at_full_size(snapkv):
+    """The decoding workload bench.py times (batch 8, 2560 rows per head), against the oracle on two sequences."""
+    import numpy as np
+    from oracle import decode_oracle as dec
+    w = workloads.DECODE_CAPPED_B8
+    c = workloads.generate_decode(w, device="cuda")
+    out = torch.empty((w.B, w.Hq, w.D), dtype=torch.float32, device="cuda")
+    lse = torch.empty((w.B, w.Hq), dtype=torch.float32, device="cuda")
+    snapkv.snapkv_decode_attention(c["q"], c["k_cache"], c["v_cache"], w.S, out, lse)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all() and torch.isfinite(lse).all()
+    for b in (0, 7):
+        want, want_lse = dec.decode_attention(workloads.to_numpy_bits(c["q"][b:b + 1]),
+                                              workloads.to_numpy_bits(c["k_cache"][b:b + 1]),
+                                              workloads.to_numpy_bits(c["v_cache"][b:b + 1]))
+        vmax = float(c["v_cache"][b].float().abs().max())
+        assert np.abs(out[b].cpu().numpy() - want[0]).max() <= 1e-4 * vmax
+        assert np.abs(lse[b].cpu().numpy() - want_lse[0]).max() <= 1e-4
+
+
 def test_two_streaming_passes_at_full_size(snapkv):
     # the path that takes over when a prompt's logits exceed the register files or the grid cannot be resident
     snapkv.snapkv_set_scoring_scheme(1)
