@@ -344,6 +344,23 @@ def main() -> int:
         "path_frac": round((scan_b + gather_b) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
     }
 
+    # the planted needle of the long-context workload and its neighbours within the pooling reach must be kept
+    needle_kept = None
+    if w.needle and args.entry == "compress" and args.layout == "head_major":
+        c0 = workloads.generate(w, layer=0, device=dev)
+        snapkv.snapkv_compress(c0["q_win"], c0["k"], c0["v"], w.pool_kind, w.p, w.C, out_k, out_v, out_idx, stream=stream)
+        torch.cuda.synchronize()
+        kept_idx = out_idx.cpu().numpy()
+        needle_kept = True
+        for hk, pos in enumerate(c0["needle_pos"]):
+            lo, hi = max(0, pos - w.p // 2), min(w.n - 1, pos + w.p // 2)
+            have = set(kept_idx[hk].tolist())
+            needle_kept = needle_kept and all(j in have for j in range(lo, hi + 1))
+        del c0
+        if not needle_kept:
+            print("bench.py: the planted needle was not kept", file=sys.stderr)
+            return 1
+
     cpu = None
     if not args.no_cpu_baseline and args.entry != "per_query_head" and args.layout != "paged":
         from oracle import c_oracle
@@ -384,7 +401,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": w.name, "L": w.L, "Hq": w.Hq, "Hkv": w.Hkv, "D": w.D, "W": w.W,
                    "pool": ("max" if w.pool_kind == 0 else "avg"), "p": w.p, "C": w.C,
-                   "step": "one layer call", "entry": args.entry, "layout": args.layout, "resident_layers": nres, "scheme": args.scheme,
+                   "step": "one layer call", "entry": args.entry, "layout": args.layout, "resident_layers": nres, "scheme": args.scheme, "needle_kept": needle_kept,
                    "token_layers_per_s": round(w.L / (ms_per_step * 1e-3), 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,
