@@ -340,6 +340,9 @@ def main() -> int:
         "algorithmic_bytes_per_launch": scan_b,
         "kernel_ms": round(score_ms, 4),
         "stage_ms": {k: round(v, 4) for k, v in stage_ms.items()},
+        # evidence beside the bound: the scoring product's MFMA rate and the exponentials per second
+        "mfma_tflops": round(2.0 * w.Hq * w.W * w.L * w.D / (score_ms * 1e-3) / 1e12, 1) if score_ms > 0 else None,
+        "exp_per_s": round(float(w.Hq) * w.W * w.L / (score_ms * 1e-3), 1) if score_ms > 0 else None,
         "path_algorithmic_bytes": scan_b + gather_b,
         "path_frac": round((scan_b + gather_b) / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
     }
