@@ -365,6 +365,7 @@ int compress_batch(int dtype, int count, const void* const* q_win, const void* c
                    const int64_t* L, int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
                    void* const* out_k, void* const* out_v, int32_t* const* out_idx, hipStream_t st) {
     if (count < 2 || count > kMaxBatch || !g_allow_pool_select) return 1;
+    if ((int64_t)Hkv * count > 65535) return 1;   // the joint gather has one grid row per head of the batch
     const int g = Hq / Hkv;
     const int row_bytes = D * elem_bytes(dtype);
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
