@@ -1129,15 +1129,6 @@ static int fused_split_candidates(const ScoreGeom& G, int* out) {
     return nc;
 }
 
-// Whether any split fits; *F gets the first candidate's shape.
-bool fused_shape(const ScoreGeom& G, FusedGeom* F) {
-    int cand[8];
-    const int nc = fused_split_candidates(G, cand);
-    for (int i = 0; i < nc; ++i)
-        if (fused_shape_nw(G, kFusedWaves, cand[i], F)) return true;
-    return false;
-}
-
 size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base);
 
 // Bytes of hand-off buffers that cover whichever split the launch plan ends up choosing, for any

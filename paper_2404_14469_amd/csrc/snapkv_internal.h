@@ -108,7 +108,6 @@ void stage_done(hipStream_t st, int stage);
 // All launchers enqueue on `st` and return the launch status.
 hipError_t launch_score(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                         const Workspace& ws, hipStream_t st);
-bool fused_shape(const ScoreGeom& G, FusedGeom* F);
 size_t fused_sync_bytes(const ScoreGeom& G);
 bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
 size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base);
