@@ -110,7 +110,15 @@ def check_self_consistency(q, k, v, C, scores, out_k, out_v, out_idx, kept):
         if kc > 0:
             s = scores[hk]
             order = np.argsort(-s.astype(np.float64), kind="stable")[:kc]
-            assert np.array_equal(idx[:kc], np.sort(order)), f"head {hk}: not the exact top-k"
+            want = np.sort(order)
+            if not np.array_equal(idx[:kc], want):
+                extra = np.setdiff1d(idx[:kc], want)
+                missing = np.setdiff1d(want, idx[:kc])
+                raise AssertionError(
+                    f"head {hk}: not the exact top-k of the GPU's scores: {len(extra)} kept beyond it "
+                    f"(first {extra[:4].tolist()}, scores {s[extra[:4]].tolist()}), {len(missing)} missing "
+                    f"(first {missing[:4].tolist()}, scores {s[missing[:4]].tolist()}), "
+                    f"k-th score {float(np.sort(s)[::-1][kc - 1])!r}")
         assert torch.equal(out_k[hk].view(torch.uint8), k[hk][idx_dev[hk]].view(torch.uint8))
         assert torch.equal(out_v[hk].view(torch.uint8), v[hk][idx_dev[hk]].view(torch.uint8))
 
