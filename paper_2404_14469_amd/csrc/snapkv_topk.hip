@@ -522,18 +522,36 @@ __device__ __forceinline__ unsigned coherent_load(const unsigned* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__device__ __forceinline__ void coherent_store(unsigned* p, unsigned v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+// Hand-over stores and additions are issued as atomics WITH a return value, and the wave waits for
+// all of them before the rendezvous below.  A store, or an addition whose result nobody asks for,
+// only has to be on its way when the wave's memory counter lets go of it; the returning form
+// completes when it has been performed where all dies see it.  The callers fold the returned
+// values into a dummy so that several can be in flight, and hand the dummy to hand_over_done().
+__device__ __forceinline__ unsigned coherent_store(unsigned* p, unsigned v) {
+    return __hip_atomic_exchange(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned coherent_store64(unsigned long long* p, unsigned long long v) {
+    return (unsigned)__hip_atomic_exchange(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned coherent_add(unsigned* p, unsigned v) {
+    return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// Every hand-over of this thread has been performed once this returns.
+__device__ __forceinline__ void hand_over_done(unsigned folded) {
+    asm volatile("" ::"v"(folded));            // the returned values are needed here: the wave waits for them
+    __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): and for anything else it has outstanding
 }
 
 // Rendezvous of the `expect` workgroups that share `ctr` (zero before the first arrival).  What a
-// workgroup handed over before the call with coherent_store / device-scope atomics can be read
-// by all of them after it with coherent_load.  No cache write-back or invalidate is involved: those
-// accesses are performed at the device's coherence point, and a wave's memory counter only
-// reaches zero once they have been acknowledged, which is what the workgroup-scope fence waits for
-// before thread 0 counts the workgroup in.
+// workgroup handed over before the call with coherent_store / coherent_add (and waited for with
+// hand_over_done) can be read by all of them after it with coherent_load.  No cache write-back or
+// invalidate is involved: those accesses are performed at the device's coherence point.  Every wave
+// waits for its own outstanding memory operations before the barrier (a workgroup-scope fence does
+// not: inside a compute unit it has nothing to wait for), and only then does thread 0 count the
+// workgroup in.
 __device__ __forceinline__ void group_rendezvous(unsigned* ctr, unsigned expect, unsigned limit,
                                                  unsigned* gave_up) {
+    __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0)
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (threadIdx.x == 0 && !*gave_up) {
@@ -749,8 +767,9 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
     block_range();
     PS_TRACE(14);
     if (tid == 0) {
-        coherent_store(&S.ps_range[2 * ((int64_t)h * kPsMaxGroup + c)], lo);
-        coherent_store(&S.ps_range[2 * ((int64_t)h * kPsMaxGroup + c) + 1], hi);
+        unsigned done = coherent_store(&S.ps_range[2 * ((int64_t)h * kPsMaxGroup + c)], lo);
+        done ^= coherent_store(&S.ps_range[2 * ((int64_t)h * kPsMaxGroup + c) + 1], hi);
+        hand_over_done(done);
     }
     unsigned* arrive = S.ps_arrive + (int64_t)h * kPsStages;
     PS_TRACE(2);
@@ -791,10 +810,12 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
         __syncthreads();
         PS_TRACE(15);
         unsigned* gh = S.ps_hist + ((int64_t)h * kPsLevels + lvl) * kPsBins;
+        unsigned done = 0;
         for (int b = tid; b < kPsBins; b += NT) {
             const unsigned cnt = sh_hist[b];
-            if (cnt) atomicAdd(&gh[b], cnt);
+            if (cnt) done ^= coherent_add(&gh[b], cnt);
         }
+        hand_over_done(done);
         PS_TRACE(4 + 2 * (lvl < 2 ? lvl : 1));
         group_rendezvous(arrive + 1 + lvl, (unsigned)Wh, spin_limit, &sh_gave_up);
         PS_TRACE(5 + 2 * (lvl < 2 ? lvl : 1));
@@ -833,21 +854,22 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
     unsigned above_total = above, z1 = 0, z2 = 0;
     block_sum3<NT>(above_total, z1, z2, sh_red);
     if (!exact) {   // this workgroup's candidates go to the start of its own stretch of the head's list
-        unsigned slot = in_before;
+        unsigned slot = in_before, done = 0;
         unsigned long long* const my_cand = reinterpret_cast<unsigned long long*>(S.cand + (int64_t)h * pitch + chunk0);
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
             if (active >> e & 1u) {
                 if (slot < (unsigned)len)
-                    __hip_atomic_store(my_cand + slot,
-                                       ((unsigned long long)(unsigned)((int)chunk0 + pos_local(e)) << 32) | x[e],
-                                       __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    done ^= coherent_store64(my_cand + slot,
+                                             ((unsigned long long)(unsigned)((int)chunk0 + pos_local(e)) << 32) | x[e]);
                 ++slot;
             }
+        hand_over_done(done);
     }
     if (tid == 0) {
-        coherent_store(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + c)], above_total);
-        coherent_store(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + c) + 1], in_total);
+        unsigned done = coherent_store(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + c)], above_total);
+        done ^= coherent_store(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + c) + 1], in_total);
+        hand_over_done(done);
     }
     PS_TRACE(9);
     group_rendezvous(arrive + 1 + kPsLevels, (unsigned)Wh, spin_limit, &sh_gave_up);
