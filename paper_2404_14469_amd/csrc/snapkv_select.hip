@@ -382,8 +382,12 @@ hipError_t launch_iota(int H, int64_t rows, int64_t out_stride, int32_t* out_idx
     return hipGetLastError();
 }
 
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4_nt;
+
 // Each thread moves 16 bytes of a K row and the matching 16 bytes of the V row; consecutive
 // threads cover consecutive pieces of a row, so a 256-byte row is one coalesced 16-lane access.
+// Every row is read once and written once: the non-temporal policy keeps both out of the way of
+// the next call's K stream.
 __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
                                                    const uint4* __restrict__ v,
                                                    const int32_t* __restrict__ idx,
@@ -408,8 +412,10 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
         int64_t pos = ib[r];
         pos = pos < 0 ? 0 : (pos < L ? pos : L - 1);   // whatever idx holds, the read stays inside the prompt
         const int64_t src = physical_row(pm.table, pm.page, pm.pages, pos);
-        okb[r * pieces + c] = kb[src * kl.row_stride + c];
-        ovb[r * pieces + c] = vb[src * vl.row_stride + c];
+        const u32x4_nt a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(&kb[src * kl.row_stride + c]));
+        const u32x4_nt b = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(&vb[src * vl.row_stride + c]));
+        __builtin_nontemporal_store(a, reinterpret_cast<u32x4_nt*>(&okb[r * pieces + c]));
+        __builtin_nontemporal_store(b, reinterpret_cast<u32x4_nt*>(&ovb[r * pieces + c]));
     }
     // the call's scratch is no longer read by anything: leave it ready for the next call
     const int64_t gid = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
@@ -448,8 +454,10 @@ __global__ __launch_bounds__(256) void gather_rows_batch(const BatchDesc B, cons
         const int c = (int)(e - r * pieces);
         int64_t src = ib[r];
         src = src < 0 ? 0 : (src < L ? src : L - 1);   // a failed selection cannot send a read outside the prompt
-        okb[r * pieces + c] = kb[src * pieces + c];
-        ovb[r * pieces + c] = vb[src * pieces + c];
+        const u32x4_nt a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(&kb[src * pieces + c]));
+        const u32x4_nt b = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(&vb[src * pieces + c]));
+        __builtin_nontemporal_store(a, reinterpret_cast<u32x4_nt*>(&okb[r * pieces + c]));
+        __builtin_nontemporal_store(b, reinterpret_cast<u32x4_nt*>(&ovb[r * pieces + c]));
         if (c == 0) ob[r] = ib[r];
     }
     const int64_t gid = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
