@@ -202,5 +202,35 @@ def test_separate_pool_and_select_kernels_at_full_size(snapkv):
         snapkv.snapkv_set_scoring_scheme(0)
 
 
+def test_many_calls_in_a_row_select_what_their_own_scores_say(snapkv):
+    """The cooperative selection hands data between workgroups on different dies; a hand-over that
+    a reader can overtake shows as a wrong position in a few calls out of a hundred, not in one.
+    150 calls on fresh inputs (own scratch and caller's workspace alternating), each checked for
+    every head against the oracle's selection from the library's own pooled scores: integer work
+    on identical scores, so the comparison is exact."""
+    import numpy as np
+    from oracle import snapkv_oracle as orc
+    w = workloads.LLAMA2_7B_16K
+    ws = torch.empty(snapkv.snapkv_workspace_bytes(w.L, w.Hq, w.Hkv, w.D, w.W), dtype=torch.uint8, device="cuda")
+    kc = w.C - w.W
+    for rep in range(50):
+        c = workloads.generate(w, layer=rep, device="cuda")
+        q, k, v = c["q_win"], c["k"], c["v"]
+        sc = torch.empty((w.Hkv, w.n), dtype=torch.float32, device="cuda")
+        snapkv.snapkv_pooled_scores(q, k, w.pool_kind, w.p, sc)
+        got = []
+        for call in range(3):
+            ok = torch.zeros((w.Hkv, w.C, w.D), dtype=k.dtype, device="cuda")
+            ov = torch.zeros_like(ok)
+            oi = torch.full((w.Hkv, w.C), -1, dtype=torch.int32, device="cuda")
+            snapkv.snapkv_compress(q, k, v, w.pool_kind, w.p, w.C, ok, ov, oi, workspace=ws if call == 2 else None)
+            got.append(oi)
+        torch.cuda.synchronize()
+        s0 = sc.cpu().numpy().astype(np.float64)
+        want = np.stack([orc.select(s0[h], kc) for h in range(w.Hkv)])
+        for call, oi in enumerate(got):
+            assert np.array_equal(oi.cpu().numpy()[:, :kc], want), (rep, call)
+
+
 def test_no_handoff_wait_gave_up(snapkv):
     assert snapkv.snapkv_sync_timeouts() == 0
