@@ -3,7 +3,8 @@
 //
 // The softmax normaliser of a window row needs all L logits of that row before any probability
 // can be summed down a column.  Instead of reading K twice, this kernel keeps the exponentials
-// of the logits in registers across a device-wide hand-off of the row normalisers:
+// of the logits on the compute unit (registers, then the wave's own piece of LDS) across a
+// device-wide hand-off of the row normalisers:
 //
 //   * a "unit" is a KV head, or, when the query heads of a KV head have more window rows than a
 //     wave tracks well, one of `split` equal parts of its query heads (units of one KV head then
@@ -13,7 +14,7 @@
 //     workgroup stays resident (the grid never exceeds what the device keeps resident at once).
 //   * step P1 of a unit: the slice of K, loaded once, meets the window queries on MFMA
 //     (16x16x32 bf16 or 16x16x4 fp32, fp32 accumulate); the slice's row maxima m_s are taken,
-//     e = 2^(s - m_s) stays in the wave's registers and (m_s, sum e) per row is published.
+//     e = 2^(s - m_s) stays with the wave (registers, LDS) and (m_s, sum e) per row is published.
 //   * step L1, one unit later: the Gg slices of a row are merged 32 at a time by half-waves
 //     spread evenly over the workgroups of the group, and the merged pairs published.
 //   * step P2, another unit later: every workgroup merges the few level-1 pairs of each row
