@@ -3,8 +3,7 @@
 //
 // The softmax normaliser of a window row needs all L logits of that row before any probability
 // can be summed down a column.  Instead of reading K twice, this kernel keeps the exponentials
-// of the logits on the compute unit (registers, then the wave's own piece of LDS) across a
-// device-wide hand-off of the row normalisers:
+// of the logits in registers across a device-wide hand-off of the row normalisers:
 //
 //   * a "unit" is a KV head, or, when the query heads of a KV head have more window rows than a
 //     wave tracks well, one of `split` equal parts of its query heads (units of one KV head then
@@ -14,7 +13,7 @@
 //     workgroup stays resident (the grid never exceeds what the device keeps resident at once).
 //   * step P1 of a unit: the slice of K, loaded once, meets the window queries on MFMA
 //     (16x16x32 bf16 or 16x16x4 fp32, fp32 accumulate); the slice's row maxima m_s are taken,
-//     e = 2^(s - m_s) stays with the wave (registers, LDS) and (m_s, sum e) per row is published.
+//     e = 2^(s - m_s) stays in the wave's registers and (m_s, sum e) per row is published.
 //   * step L1, one unit later: the Gg slices of a row are merged 32 at a time by half-waves
 //     spread evenly over the workgroups of the group, and the merged pairs published.
 //   * step P2, another unit later: every workgroup merges the few level-1 pairs of each row
@@ -55,7 +54,6 @@ namespace snapkv {
 // about 10 us per call at 131072 keys x 32 heads, together with the gather's policy).
 #define VOTE_STORE(p_, v_) __builtin_nontemporal_store((v_), (p_))
 
-constexpr int kFusedSlots = 8;          // RUW * KT: accumulator tiles a wave keeps per unit (8 waves)
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
 typedef __attribute__((ext_vector_type(8))) _Float16 f16x8_t;
 typedef __attribute__((ext_vector_type(4))) float f32x4;
@@ -234,16 +232,6 @@ __device__ __forceinline__ void load_frag16p(Frag16<T, D>& f, const char* p) {
     for (int x = 0; x < Frag16<T, D>::NP; ++x) f.v[x] = *reinterpret_cast<const uint4*>(p + 64 * x);
 }
 
-// Dynamic LDS of the kernel: the Q blocks of three units and, where it fits the 160 KB of a compute
-// unit beside them, two parked sets of exponentials per wave (see score_fused_body).
-template <typename T, int D, int RUW>
-struct FusedLds {
-    static constexpr int kQueueBytes = 3 * RUW * (D * esize<T>::value / 64) * 64 * 16;
-    static constexpr int kParkBytesPerWave = 2 * kFusedSlots * 64 * 16;
-    static constexpr bool kPark = kQueueBytes <= 24 * 1024;
-    static constexpr int bytes(int NW) { return kQueueBytes + (kPark ? NW * kParkBytesPerWave : 0); }
-};
-
 // The kernel's body; `bid` is the workgroup's index inside its own launch plan (the block index,
 // or the block index less the first block of the prompt when several prompts share a launch).
 template <typename T, int D, int RUW, int KT, int NW>
@@ -343,19 +331,12 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
         if (w + x * NW < QCH) qbuf[(w + x * NW) * 64 + lane] = qland[x];
     if (tid < 3 * NW) sm_flag[tid / NW][tid % NW] = tid < NW ? 1 : 0;   // Q of unit 0 is in place
     __syncthreads();
-    // The exponentials of the two previous units wait for their votes: in LDS where the compute
-    // unit has room for them (a region of the wave's own, lane-interleaved 16-byte pieces: no
-    // bank conflicts, no synchronisation), otherwise in registers.
-    constexpr bool kPark = FusedLds<T, D, RUW>::kPark;
-    f32x4* const park = reinterpret_cast<f32x4*>(qbuf + 3 * QCH * 64) + (size_t)w * 2 * NSLOT * 64 + lane;
-    f32x4 e1[kPark ? 1 : RUW][kPark ? 1 : KT], e2[kPark ? 1 : RUW][kPark ? 1 : KT];
+    // exponentials of the two previous units stay in registers until their votes are taken
+    f32x4 e1[RUW][KT], e2[RUW][KT];
 #pragma unroll
     for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
-        for (int t = 0; t < KT; ++t) {
-            e[ru][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-            if constexpr (!kPark) e1[ru][t] = e2[ru][t] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
+        for (int t = 0; t < KT; ++t) e[ru][t] = e1[ru][t] = e2[ru][t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     // logits of tiles [T0, T1) of the unit whose Q block sits in half `par` of qbuf
     auto mfma_tiles = [&](auto T0, auto T1, const int par) {
@@ -650,9 +631,7 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
             for (int ru = 0; ru < RUW; ++ru) {
 #pragma unroll
                 for (int t = 0; t < KT; ++t) {
-                    f32x4 ev;
-                    if constexpr (kPark) ev = park[((it & 1) * NSLOT + ru * KT + t) * 64];   // parked two units ago
-                    else ev = e2[ru][t];
+                    const f32x4 ev = e2[ru][t];
                     v[t] = fmaf(ev[0], f[ru][0], v[t]);
                     v[t] = fmaf(ev[1], f[ru][1], v[t]);
                     v[t] = fmaf(ev[2], f[ru][2], v[t]);
@@ -702,12 +681,8 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
         for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
             for (int t = 0; t < KT; ++t) {
-                if constexpr (kPark) {
-                    park[((it & 1) * NSLOT + ru * KT + t) * 64] = e[ru][t];   // read again two iterations on
-                } else {
-                    e2[ru][t] = e1[ru][t];
-                    e1[ru][t] = e[ru][t];
-                }
+                e2[ru][t] = e1[ru][t];
+                e1[ru][t] = e[ru][t];
             }
         TRACE(6);
         // ---- H. the next unit's lower tiles meet its Q (in LDS since the barrier) and their
@@ -1083,6 +1058,7 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
 // ---------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------
+constexpr int kFusedSlots = 8;          // RUW * KT: accumulator tiles a wave keeps per unit (8 waves)
 constexpr unsigned kSpinLimit = 1u << 15;   // polls before a hand-off wait gives up (tens of ms)
 
 static int g_cu_count[64] = {0};
@@ -1206,7 +1182,7 @@ template <typename T, int D, int RUW, int NW>
 static hipError_t fused_instance(const FusedCall* call, int* occ) {
     constexpr int KT = kFusedSlots / RUW;
     auto kern = score_fused<T, D, RUW, KT, NW>;
-    constexpr int kQueueBytes = FusedLds<T, D, RUW>::bytes(NW);   // Q blocks of three units, parked exponentials
+    constexpr int kQueueBytes = 3 * RUW * (D * esize<T>::value / 64) * 64 * 16;   // Q blocks of three units
     static int cached_occ = -1;
     if (cached_occ < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1287,7 +1263,7 @@ template <typename T, int D, int RUW, int NW>
 static hipError_t joint_instance(const FusedJoint* J, int grid, hipStream_t st, int* occ) {
     constexpr int KT = kFusedSlots / RUW;
     auto kern = score_fused_joint<T, D, RUW, KT, NW>;
-    constexpr int kQueueBytes = FusedLds<T, D, RUW>::bytes(NW);
+    constexpr int kQueueBytes = 3 * RUW * (D * esize<T>::value / 64) * 64 * 16;
     static int cached_occ = -1;
     if (cached_occ < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
