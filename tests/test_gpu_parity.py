@@ -466,3 +466,29 @@ def test_select_wide_dynamic_range(snapkv):
     x[0, 5] = np.float32(1e-45)                                           # a denormal
     _select_case(snapkv, x, 3000)
     _select_case(snapkv, x, n - 5)
+
+
+def _random_shapes(seed, count):
+    import random
+    rng = random.Random(seed)
+    out = []
+    for it in range(count):
+        g = rng.choice([1, 1, 2, 4, 8])
+        Hkv = rng.choice([1, 2, 3, 4, 8])
+        W = rng.choice([1, 2, 7, 8, 15, 16, 17, 31, 32, 33, 48, 64])
+        n = rng.choice([1, 2, 5, 17, 63, 64, 65, 255, 300, 511, 512, 513, 1000, 2047, 2048, 2049, 3000, 4100, 5000,
+                        7001, 9000])
+        C = W + rng.choice([0, 1, 2, max(1, n // 7), max(1, n // 2), max(0, n - 1), n, n + 5])
+        out.append(Workload(f"random{seed}_{it}", Hq=Hkv * g, Hkv=Hkv, D=rng.choice([64, 128]), L=W + n, W=W,
+                            pool_kind=rng.choice([0, 1]), p=rng.choice([1, 3, 5, 7, 13, 21, 129]), C=C,
+                            dtype=rng.choice(["bf16", "bf16", "f16", "f32"]), clusters=(1, 4),
+                            radius=rng.choice([1, 4, 9]), seed=1000 + it))
+    return out
+
+
+@pytest.mark.parametrize("w", _random_shapes(7, 64), ids=lambda w: w.name)
+def test_random_shapes(snapkv, w):
+    """Shapes nobody picked by hand: head counts, windows, prefix lengths, pooling widths, capacities and
+    storage types drawn from lists that straddle the kernels' tile, chunk and wave sizes (capacity 0, 1,
+    all but one, all, and more than all of the prefix included), each against the oracle."""
+    gpu_vs_oracle(snapkv, w)
