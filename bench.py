@@ -196,6 +196,12 @@ def main() -> int:
     ap.add_argument("--layout", default="head_major", choices=["head_major", "token_major", "paged"],
                     help="storage order of K/V: [Hkv, L, D] (default), [L, Hkv, D] through snapkv_compress_strided, or pages "
                          "[num_pages, 16, Hkv, D] behind a shuffled block table through snapkv_compress_paged")
+    ap.add_argument("--window", type=int, default=0, metavar="W",
+                    help="override the workload's observation window (e.g. 64 with --pool-width 13: the setting the "
+                         "paper uses for Command-R; a separate measurement, named in config)")
+    ap.add_argument("--pool-width", type=int, default=0, metavar="P", help="override the workload's pooling kernel size")
+    ap.add_argument("--length", type=int, default=0, metavar="L",
+                    help="override the workload's prompt length (e.g. the grouped-query configuration at 131072 tokens)")
     ap.add_argument("--explicit-workspace", action="store_true",
                     help="time snapkv_compress_ws with a caller-provided workspace instead of snapkv_compress")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
@@ -233,6 +239,8 @@ def main() -> int:
     if args.workload in workloads.DECODE_CONFIGS:
         return bench_decode(args, snapkv, workloads, workloads.DECODE_CONFIGS[args.workload], dev)
     w = workloads.CONFIGS[args.workload]
+    if args.window or args.pool_width or args.length:
+        w = w.with_(W=args.window or w.W, p=args.pool_width or w.p, L=args.length or w.L)
 
     nres = max(1, min(args.resident_layers, max(w.layers, 1) if w.layers > 1 else args.resident_layers))
     layers = []

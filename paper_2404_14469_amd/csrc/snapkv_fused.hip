@@ -8,7 +8,8 @@
 //   * a "unit" is a KV head, or, when the query heads of a KV head have more window rows than a
 //     wave tracks well, one of `split` equal parts of its query heads (units of one KV head then
 //     run side by side in neighbouring groups, so that its keys are fetched from memory once and
-//     found in the cache by the others).  The keys of a unit are cut into slices, one per workgroup of a
+//     found in the cache by the others; where the prompt is too long for that, they follow one
+//     another on the same workgroups).  The keys of a unit are cut into slices, one per workgroup of a
 //     group of Gg workgroups; NG groups work on different units at the same time.  Every
 //     workgroup stays resident (the grid never exceeds what the device keeps resident at once).
 //   * step P1 of a unit: the slice of K, loaded once, meets the window queries on MFMA
@@ -309,7 +310,17 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
         i = i < G.W ? i : G.W - 1;
         qp[x] = static_cast<const char*>(qv) + ((int64_t)(group * F.gs + head) * G.W + i) * D * ES + (4 * pc + kg) * 16;
     }
-    const int64_t kstep = (int64_t)(F.NG / F.split) * G.k_hs;   // NG is a multiple of split
+    // The KV head of unit u is u / split, and a group's units are NG apart.  Where whole KV heads run
+    // side by side (NG a multiple of split) the K pointers move by the same amount every iteration;
+    // where a prompt is so long that fewer groups than a KV head has parts fit the chip, the parts of a
+    // KV head follow one another on the same workgroups (its keys then come from the cache the second
+    // time) and the step from one unit to the next is zero or one head.
+    const bool even_steps = F.NG % F.split == 0;
+    const int64_t kstep_even = (int64_t)(F.NG / F.split) * G.k_hs;
+    auto kstep_to = [&](const int itn) -> int64_t {   // from the K of the group's unit itn - 1 to that of unit itn
+        if (even_steps) return kstep_even;
+        return (int64_t)((group + itn * F.NG) / F.split - (group + (itn - 1) * F.NG) / F.split) * G.k_hs;
+    };
     const int64_t qstep = (int64_t)F.NG * F.gs * G.W * D * ES;
 
     // K tiles are consumed in two halves so that the memory pipeline never runs dry: the lower
@@ -370,7 +381,7 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
     // Unconditional (a group with a single unit re-reads it): the compiler derives how long a wait
     // for older loads must be from the loads that certainly follow them on every path, so no load
     // of the steady state may sit behind a branch.
-    issue_tiles(IC0{}, ICLA{}, nu > 1 ? kstep : 0);
+    issue_tiles(IC0{}, ICLA{}, nu > 1 ? kstep_to(1) : 0);
     __builtin_amdgcn_sched_barrier(0);
 
     // K requests are paced: the tile buffers are requested again at four points spread evenly
@@ -426,6 +437,7 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
         const int unit = group + it * F.NG;
         const int unit_l1 = unit - F.NG;
         const int unit_p2 = unit - 2 * F.NG;
+        const int64_t kstep = kNext1 ? kstep_to(it + 1) : 0;   // to the next unit's keys
         TRACE(0);
 
         // ---- A. request this iteration's hand-off words at the very top: they are needed after
@@ -693,7 +705,7 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
             mfma_tiles(IC0{}, ICL{}, (it + 1) % 3);
         }
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (kNext2) issue_tiles(IC0{}, ICLA{}, kstep);   // point 3
+        if constexpr (kNext2) issue_tiles(IC0{}, ICLA{}, kstep_to(it + 2));   // point 3
         __builtin_amdgcn_sched_barrier(0);
         TRACE(7);
 #ifdef SNAPKV_FUSED_TRACE
@@ -1250,8 +1262,12 @@ bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
         if (slots <= 0 || F->Gg > slots) continue;          // one unit's logits do not fit on the chip
         int64_t NG = slots / F->Gg;
         if (NG > F->units) NG = F->units;
-        NG -= NG % F->split;      // the parts of a KV head run side by side, in neighbouring groups
-        if (NG < F->split) continue;
+        if (NG >= F->split) {
+            NG -= NG % F->split;  // the parts of a KV head run side by side, in neighbouring groups
+        } else {                  // or, when the prompt leaves no room for that, one after another on the same groups
+            while (NG > 1 && F->split % NG != 0) --NG;
+        }
+        if (NG < 1) continue;
         F->NG = (int)NG;
         return true;
     }

@@ -47,6 +47,27 @@ def test_long_131k_sampled_heads_and_needle(snapkv, layer, heads):
     torch.cuda.empty_cache()
 
 
+def test_window_64_pool_13_at_full_size(snapkv):
+    """The wider window and pooling kernel the paper uses for one of its models (Sec. 5.2's
+    Command-R setting: W = 64, p = 13), on the grouped-query and on the long configuration."""
+    _run(snapkv, workloads.MISTRAL_7B_GQA_32K.with_(name="gqa_32k_w64_p13", W=64, p=13), 2, [0, 7])
+    _run(snapkv, workloads.LONG_131K.with_(name="long_131k_w64_p13", W=64, p=13), 5, [11])
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("L,heads", [(65536, [3]), (131072, [6]), (100003, [0])])
+def test_grouped_query_prompts_whose_parts_follow_one_another(snapkv, L, heads):
+    """Grouped-query prompts so long that the parts of a KV head (one query head each) no longer fit
+    the chip side by side: they follow one another on the same workgroups, and the single-read kernel
+    still takes the prompt (two groups of two parts at 65536 tokens, one group at 131072)."""
+    w = workloads.MISTRAL_7B_GQA_32K.with_(name=f"gqa_{L}", L=L, C=4096)
+    snapkv.snapkv_profile_start(4)
+    _run(snapkv, w, 1, heads)
+    ms, calls = snapkv.snapkv_profile_stop()
+    assert ms.get("score_fused", 0.0) > 0.0 and ms.get("score_pass2", 0.0) == 0.0, ms
+    torch.cuda.empty_cache()
+
+
 def test_varlen_batch(snapkv):
     prompts = workloads.varlen_prompts()
     for i, w in enumerate(prompts):
