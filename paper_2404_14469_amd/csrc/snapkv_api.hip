@@ -122,7 +122,7 @@ int internal_scratch(size_t need, void** out, CleanState* was_clean = nullptr) {
 int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGeom& G,
                const Workspace& ws, int pool_kind, int p, float* score, unsigned* minmax,
                bool prepare_select, ScoreGeom* Gv, hipStream_t st, bool already_prepared = false,
-               CleanJob* clean = nullptr, const float* lse = nullptr) {
+               CleanJob* clean = nullptr, const float* lse = nullptr, bool allow_blocks = false) {
     FusedGeom F;
     ScoreGeom Gp = G;
     if (lse) {   // the rows' normalisers are given: one streaming pass, nothing handed between workgroups
@@ -141,7 +141,7 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
         stage_done(st, kStagePool);
         return SNAPKV_OK;
     }
-    const bool fused = g_allow_fused && fused_plan(dtype, D, G, &F);
+    const bool fused = g_allow_fused && fused_plan(dtype, D, G, &F, allow_blocks);
     FusedSync S;
     if (fused) fused_sync_layout(G, F, &S, ws.fused);
     if (!already_prepared) {
@@ -157,8 +157,8 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
     if (fused) {   // K is read once; otherwise two passes over K
         if (launch_score_fused(dtype, D, q_win, k, G, F, S, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
         stage_done(st, kStageFused);
-        Gp.NV = G.g;
-        Gp.VB = 1;
+        Gp.NV = G.g * F.BH;   // one vote row per query head, or per 32-row block of its window
+        Gp.VB = F.BH;
     } else if (lse_plan(dtype, D, G, &F)) {
         // two streaming passes over K with nothing handed between workgroups: the rows'
         // log-sum-exp first, then the probabilities from it
@@ -256,6 +256,9 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     bool streaming = false;
     // Per-query-head form: the votes are laid out [Hq][n] (one row per query head, which the
     // single-read and streaming kernels produce), so pooling and selection see Hq heads of one.
+    // a window of 64, 96, ... rows may be scored block by block (one vote row per 32-row block); the
+    // per-query-head form and the handed-in log-sum-exp keep one vote row per query head
+    const bool blocks_ok = !per_query_head && !lse;
     ScoreGeom Gsel = G;
     if (per_query_head) {
         FusedGeom Ft;
@@ -271,7 +274,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
         // which scoring path run_scores will take: 1 single-read (uses the hand-off words), 2 streaming
         // passes (does not touch them), 0 the 32x32 two-pass kernels (state not tracked)
         const int path = lse ? (lse_plan(dtype, D, G, &Fp) ? 2 : 0)
-                             : (g_allow_fused && fused_plan(dtype, D, G, &Fp)) ? 1 : (lse_plan(dtype, D, G, &Fp) ? 2 : 0);
+                             : (g_allow_fused && fused_plan(dtype, D, G, &Fp, blocks_ok)) ? 1 : (lse_plan(dtype, D, G, &Fp) ? 2 : 0);
         streaming = path == 2;
         if (own_scratch && path != 0) {
             int dev = 0;
@@ -290,7 +293,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
         }
         ScoreGeom Gv = G;
         rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, true, &Gv, st, prepared,
-                        mine ? &clean : nullptr, lse);
+                        mine ? &clean : nullptr, lse, blocks_ok);
         if (rc != SNAPKV_OK) return rc;
         if (per_query_head) Gv = Gsel;
         se = launch_pool_select(Gv, ws.vote, pool_kind, p, C - W, C, W, out_idx, ws.sel, st);
@@ -309,7 +312,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
             stage_done(st, kStagePool);
         } else {
             rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr,
-                            chunked, nullptr, st, false, nullptr, lse);
+                            chunked, nullptr, st, false, nullptr, lse, blocks_ok);
             if (rc != SNAPKV_OK) return rc;
         }
         se = chunked ? launch_select_chunked(ws.score, Hout, G.n, C - W, C, W, out_idx, ws.sel, pool_tiles(G.n), st)
@@ -347,7 +350,7 @@ int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, 
     Workspace ws;
     workspace_layout(G, &ws, base);
     return run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, out_scores, nullptr, false, nullptr,
-                      static_cast<hipStream_t>(stream), false, nullptr, lse);
+                      static_cast<hipStream_t>(stream), false, nullptr, lse, !lse);
 }
 
 }  // namespace

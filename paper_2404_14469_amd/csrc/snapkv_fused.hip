@@ -495,7 +495,8 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
                     for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            const int i = (ru % F.UH) * 16 + kg * 4 + r;
+                            // the row's place in the window (blocks of a longer window are heads to this kernel)
+                            const int i = (ru % F.UH) * 16 + kg * 4 + r + ((unit * F.gs + ru / F.UH) % F.BH) * 32;
                             // prompt-phase causal mask; keys past the end of the prompt
                             if (j > nn + i || j >= LL) e[ru][t][r] = -INFINITY;
                             mref[ru][r] = fmaxf(mref[ru][r], e[ru][t][r]);
@@ -1116,7 +1117,24 @@ static bool fused_shape_nw(const ScoreGeom& G, int NW, int split, FusedGeom* F, 
     F->units = G.Hkv * split;
     F->split = split;
     F->gs = gs;
+    F->BH = 1;
     F->spin_limit = kSpinLimit;
+    return true;
+}
+
+// The geometry in which every 32-row block of the window counts as a query head (windows of 64, 96,
+// ... rows): the rows of a block keep their softmax to themselves, so a block is to the kernel what
+// a query head is, except that its rows' causal mask starts 32 * (block index) rows later.
+static bool block_geom(const ScoreGeom& G, ScoreGeom* Gs) {
+    if (G.W <= 32 || G.W % 32 != 0) return false;
+    *Gs = G;
+    Gs->g = G.g * G.BH;
+    Gs->W = 32;
+    Gs->mode16 = 0;
+    Gs->BH = 1;
+    Gs->R32 = Gs->g;
+    Gs->VB = 1;
+    Gs->NV = Gs->g;
     return true;
 }
 
@@ -1147,15 +1165,20 @@ size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, v
 // prompt length: the size depends on the heads and the window only, so that what follows the
 // buffers in a workspace never moves onto them when the length changes.
 size_t fused_sync_bytes(const ScoreGeom& G) {
-    int cand[8];
-    const int nc = fused_split_candidates(G, cand);
     size_t most = 0;
-    for (int i = 0; i < nc; ++i) {
-        FusedGeom F;
-        if (!fused_shape_nw(G, kFusedWaves, cand[i], &F, false)) continue;
-        F.Gg = 32 * kL1BlocksPadded;   // the most slices a launch can have
-        const size_t b = fused_sync_layout(G, F, nullptr, nullptr);
-        most = b > most ? b : most;
+    ScoreGeom Gs;
+    const ScoreGeom* geoms[2] = {&G, block_geom(G, &Gs) ? &Gs : nullptr};
+    for (const ScoreGeom* g : geoms) {
+        if (!g) continue;
+        int cand[8];
+        const int nc = fused_split_candidates(*g, cand);
+        for (int i = 0; i < nc; ++i) {
+            FusedGeom F;
+            if (!fused_shape_nw(*g, kFusedWaves, cand[i], &F, false)) continue;
+            F.Gg = 32 * kL1BlocksPadded;   // the most slices a launch can have
+            const size_t b = fused_sync_layout(*g, F, nullptr, nullptr);
+            most = b > most ? b : most;
+        }
     }
     return most;
 }
@@ -1248,7 +1271,18 @@ static hipError_t fused_dispatch(int dtype, int D, int NW, int RUW, const FusedC
 // Whether the current device can keep a whole group of workgroups resident, and how many groups
 // run side by side.  The number of resident workgroups comes from the runtime's occupancy
 // answer for the exact kernel instance, never from an assumption.
-bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
+static bool fused_plan_for(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
+
+bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F, bool allow_blocks) {
+    ScoreGeom Gs;
+    if (allow_blocks && block_geom(G, &Gs) && fused_plan_for(dtype, D, Gs, F)) {
+        F->BH = G.BH;
+        return true;
+    }
+    return fused_plan_for(dtype, D, G, F);
+}
+
+static bool fused_plan_for(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
     int cand[8];
     const int nc = fused_split_candidates(G, cand);
     for (int c = 0; c < nc; ++c) {
@@ -1402,7 +1436,9 @@ hipError_t launch_score_fused_joint(int dtype, int D, int count, const void* con
 hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                               const FusedGeom& F, const FusedSync& S, float* vote, hipStream_t st) {
     if (G.n <= 0) return hipSuccess;
-    const FusedCall call{q, k, &G, &F, &S, vote, st};
+    ScoreGeom Gl = G;
+    if (F.BH > 1 && !block_geom(G, &Gl)) return hipErrorInvalidValue;
+    const FusedCall call{q, k, &Gl, &F, &S, vote, st};
     return fused_dispatch(dtype, D, F.NW, F.RUW, &call, nullptr);
 }
 

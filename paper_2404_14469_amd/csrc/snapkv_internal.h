@@ -56,6 +56,8 @@ __device__ __forceinline__ int64_t physical_row(const int32_t* table, int page, 
 struct FusedGeom {
     int RU, UH, RUW, KT, NW, Gg, NG, NB, units;   // NW waves per workgroup; NB blocks of 32 slices per row
     int split, gs;           // units per KV head; query heads per unit (g = split * gs)
+    int BH;                  // 1, or: every 32-row block of the window is a query head of its own to the
+                             // kernel (BH blocks per real head; g, split and gs then count such blocks)
     int64_t ntiles;          // ceil(L / 16)
     unsigned spin_limit;     // bound on the hand-off wait, in polls
 };
@@ -109,7 +111,9 @@ void stage_done(hipStream_t st, int stage);
 hipError_t launch_score(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                         const Workspace& ws, hipStream_t st);
 size_t fused_sync_bytes(const ScoreGeom& G);
-bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
+// allow_blocks: the plan may treat the 32-row blocks of a window longer than 32 rows as query heads
+// of their own (F->BH > 1); the votes then have one row per block (NV = g * BH, VB = BH).
+bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F, bool allow_blocks = false);
 size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base);
 // Several prompts of one model in one launch of the single-read kernel (snapkv_fused.hip).
 constexpr int kMaxJointPrompts = 8;
