@@ -468,14 +468,14 @@ def test_select_wide_dynamic_range(snapkv):
     _select_case(snapkv, x, n - 5)
 
 
-def _random_shapes(seed, count):
+def _random_shapes(seed, count, windows=(1, 2, 7, 8, 15, 16, 17, 31, 32, 33, 48, 64)):
     import random
     rng = random.Random(seed)
     out = []
     for it in range(count):
         g = rng.choice([1, 1, 2, 4, 8])
         Hkv = rng.choice([1, 2, 3, 4, 8])
-        W = rng.choice([1, 2, 7, 8, 15, 16, 17, 31, 32, 33, 48, 64])
+        W = rng.choice(list(windows))
         n = rng.choice([1, 2, 5, 17, 63, 64, 65, 255, 300, 511, 512, 513, 1000, 2047, 2048, 2049, 3000, 4100, 5000,
                         7001, 9000])
         C = W + rng.choice([0, 1, 2, max(1, n // 7), max(1, n // 2), max(0, n - 1), n, n + 5])
@@ -491,4 +491,11 @@ def test_random_shapes(snapkv, w):
     """Shapes nobody picked by hand: head counts, windows, prefix lengths, pooling widths, capacities and
     storage types drawn from lists that straddle the kernels' tile, chunk and wave sizes (capacity 0, 1,
     all but one, all, and more than all of the prefix included), each against the oracle."""
+    gpu_vs_oracle(snapkv, w)
+
+
+@pytest.mark.parametrize("w", _random_shapes(21, 48, windows=(64, 64, 96, 128)), ids=lambda w: w.name)
+def test_random_shapes_with_long_windows(snapkv, w):
+    """Windows of two, three and four 32-row blocks: the single-read kernel scores them block by block
+    (one vote row per block, summed before pooling); head counts, lengths, pooling and capacities as above."""
     gpu_vs_oracle(snapkv, w)
