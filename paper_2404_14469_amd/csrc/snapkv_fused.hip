@@ -1378,21 +1378,31 @@ int fused_joint_plan(int dtype, int D, int count, const ScoreGeom* G, FusedGeom*
         if (i > 0 && (!fused_plan(dtype, D, G[i], &F[i]) || F[i].RUW != F[0].RUW || F[i].split != F[0].split ||
                       F[i].NW != F[0].NW))
             continue;
-        const int least = up8(F[i].split * F[i].Gg);
+        // a prompt joins with one group (the parts of its KV heads then follow one another); the
+        // spare blocks go to whoever has most iterations left
+        const int least = up8(F[i].Gg);
         if (total + least > slots) {
             if (i == 0) return 0;
             continue;
         }
-        F[i].NG = F[i].split;
+        F[i].NG = 1;
         total += least;
         take[taken++] = i;
     }
+    // the next number of groups a prompt can have: a divisor of split below it, a multiple of it above
+    auto next_groups = [](const FusedGeom& f) {
+        if (f.NG >= f.split) return f.NG + f.split;
+        int n = f.NG + 1;
+        while (f.split % n != 0) ++n;
+        return n;
+    };
     for (;;) {   // hand the spare blocks out
         int best = -1, best_iters = 0;
         for (int t = 0; t < taken; ++t) {
             const FusedGeom& f = F[take[t]];
-            if (f.NG + f.split > f.units) continue;
-            const int more = up8((f.NG + f.split) * f.Gg) - up8(f.NG * f.Gg);
+            const int nx = next_groups(f);
+            if (nx > f.units) continue;
+            const int more = up8(nx * f.Gg) - up8(f.NG * f.Gg);
             const int iters = (f.units + f.NG - 1) / f.NG;
             if (total + more <= slots && iters > best_iters) {
                 best = t;
@@ -1401,8 +1411,9 @@ int fused_joint_plan(int dtype, int D, int count, const ScoreGeom* G, FusedGeom*
         }
         if (best < 0 || best_iters <= 1) break;
         FusedGeom& f = F[take[best]];
-        total += up8((f.NG + f.split) * f.Gg) - up8(f.NG * f.Gg);
-        f.NG += f.split;
+        const int nx = next_groups(f);
+        total += up8(nx * f.Gg) - up8(f.NG * f.Gg);
+        f.NG = nx;
     }
     int at = 0;
     for (int t = 0; t < taken; ++t) {
