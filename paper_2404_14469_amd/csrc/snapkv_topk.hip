@@ -666,7 +666,18 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
                 float4 t4 = make_float4(pad, pad, pad, pad);
                 if (f < nf4) {
                     if (P > 0 && rows_aligned) {
-                        if (q0 >= 0 && q0 < nn) t4 = *reinterpret_cast<const float4*>(vb + q0);
+                        if (q0 >= 0 && q0 < nn) {
+                            t4 = *reinterpret_cast<const float4*>(vb + q0);
+                            if constexpr (EPT <= 4) {   // (at 16 positions per thread this sum costs registers the kernel does not have)
+                                for (int b = 1; b < G.VB; ++b) {   // the vote rows of a query head, in order
+                                    const float4 u = *reinterpret_cast<const float4*>(vb + (int64_t)b * pitch + q0);
+                                    t4.x += u.x;
+                                    t4.y += u.y;
+                                    t4.z += u.z;
+                                    t4.w += u.w;
+                                }
+                            }
+                        }
                     } else {
                         float t[4];
 #pragma unroll
@@ -675,7 +686,7 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
                             t[k] = pad;
                             if (q >= 0 && q < nn) {
                                 t[k] = vb[q];
-                                if (P == 0)   // several vote rows per query head only reach the loop form
+                                if (P == 0 || EPT <= 4)   // several vote rows per query head: the loop form, or the light kernel
                                     for (int b = 1; b < G.VB; ++b) t[k] += vb[(int64_t)b * pitch + q];
                             }
                         }
@@ -1195,8 +1206,11 @@ static int ps_cu_count() {
     return cached[dev];
 }
 
-// Width the kernel is instantiated for: the unrolled taps need one vote row per query head.
-static int ps_width(const ScoreGeom& G, int p) { return (G.VB == 1 && (p == 5 || p == 7 || p == 13)) ? p : 0; }
+// Width the kernel is instantiated for (unrolled taps), or 0 for the loop form.  With several vote rows
+// per query head only the kernel for 4 positions per thread has the unrolled form.
+static int ps_width(const ScoreGeom& G, int p, int ept) {
+    return ((G.VB == 1 || ept <= 4) && (p == 5 || p == 7 || p == 13)) ? p : 0;
+}
 
 static bool pool_select_plan(const ScoreGeom& G, int pool_kind, int p, int64_t kcount, int* Wh, int* chunk, int* ept) {
     if (G.n < 1 || kcount < 0 || kcount > G.n || G.Hkv < 1) return false;
@@ -1204,7 +1218,7 @@ static bool pool_select_plan(const ScoreGeom& G, int pool_kind, int p, int64_t k
     if (cus <= 0) return false;
     for (int e : {4, 16}) {   // positions per thread: the lighter variant when the chunks allow it
         int occ = 0;
-        if (pool_select_dispatch(e, ps_width(G, p), pool_kind, nullptr, &occ) != hipSuccess) {
+        if (pool_select_dispatch(e, ps_width(G, p, e), pool_kind, nullptr, &occ) != hipSuccess) {
             (void)hipGetLastError();
             continue;
         }
@@ -1236,7 +1250,7 @@ hipError_t launch_pool_select(const ScoreGeom& G, const float* vote, int pool_ki
     if (!pool_select_plan(G, pool_kind, p, kcount, &Wh, &chunk, &ept)) return hipErrorInvalidValue;
     const PoolSelCall call{vote, &G, pool_kind, p, kcount, out_stride, W_tail, out_idx, &S, Wh, chunk, st, nvalid};
     int occ = 0;
-    return pool_select_dispatch(ept, ps_width(G, p), pool_kind, &call, &occ);
+    return pool_select_dispatch(ept, ps_width(G, p, ept), pool_kind, &call, &occ);
 }
 
 hipError_t launch_select_init(const SelectScratch& S, int H, hipStream_t st) {
