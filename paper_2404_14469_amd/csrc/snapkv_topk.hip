@@ -726,6 +726,44 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
                         if (pool_kind != 0) val = val / (float)P;
                         acc[4 * e4 + k] += val;
                     }
+                } else if (p >= 5) {
+                    // The four positions share all but three of their taps: every staged value is read
+                    // once and goes to the positions whose window holds it, each position taking its
+                    // taps in increasing order (the order of the plain loop below, so sums agree bit for bit).
+                    const int s0 = i0 + HQ - r;
+                    auto op = [](float a, float b) { return KIND == 0 ? fmaxf(a, b) : a + b; };
+                    const float t0 = stage[s0], t1 = stage[s0 + 1], t2 = stage[s0 + 2];
+                    float v0 = op(op(t0, t1), t2), v1 = op(t1, t2), v2 = t2;
+                    float t = stage[s0 + 3];
+                    v0 = op(v0, t);
+                    v1 = op(v1, t);
+                    v2 = op(v2, t);
+                    float v3 = t;
+                    for (int d = 4; d < p; ++d) {
+                        t = stage[s0 + d];
+                        v0 = op(v0, t);
+                        v1 = op(v1, t);
+                        v2 = op(v2, t);
+                        v3 = op(v3, t);
+                    }
+                    t = stage[s0 + p];
+                    v1 = op(v1, t);
+                    v2 = op(v2, t);
+                    v3 = op(v3, t);
+                    t = stage[s0 + p + 1];
+                    v2 = op(v2, t);
+                    v3 = op(v3, t);
+                    v3 = op(v3, stage[s0 + p + 2]);
+                    if (pool_kind != 0) {
+                        v0 = v0 / (float)p;
+                        v1 = v1 / (float)p;
+                        v2 = v2 / (float)p;
+                        v3 = v3 / (float)p;
+                    }
+                    acc[4 * e4] += v0;
+                    acc[4 * e4 + 1] += v1;
+                    acc[4 * e4 + 2] += v2;
+                    acc[4 * e4 + 3] += v3;
                 } else {
 #pragma unroll
                     for (int k = 0; k < 4; ++k) {
