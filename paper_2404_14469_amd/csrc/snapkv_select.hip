@@ -406,16 +406,38 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
     uint4* okb = out_k + (int64_t)h * out_stride * pieces;
     uint4* ovb = out_v + (int64_t)h * out_stride * pieces;
     const int32_t* ib = idx + (int64_t)h * out_stride;
-    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-        const int64_t r = e / pieces;
-        const int c = (int)(e - r * pieces);
-        int64_t pos = ib[r];
-        pos = pos < 0 ? 0 : (pos < L ? pos : L - 1);   // whatever idx holds, the read stays inside the prompt
-        const int64_t src = physical_row(pm.table, pm.page, pm.pages, pos);
-        const u32x4_nt a = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(&kb[src * kl.row_stride + c]));
-        const u32x4_nt b = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(&vb[src * vl.row_stride + c]));
-        __builtin_nontemporal_store(a, reinterpret_cast<u32x4_nt*>(&okb[r * pieces + c]));
-        __builtin_nontemporal_store(b, reinterpret_cast<u32x4_nt*>(&ovb[r * pieces + c]));
+    // Four pieces per thread and pass, a grid stride apart: the positions are fetched first, then all
+    // eight loads are in flight together, then the stores; a thread's two dependent memory latencies
+    // (position, then row) are so paid once per four pieces.
+    constexpr int U = 4;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t e0 = (int64_t)blockIdx.x * 256 + threadIdx.x; e0 < total; e0 += U * stride) {
+        int64_t r[U], src[U];
+        int c[U];
+        bool on[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t e = e0 + u * stride;
+            on[u] = e < total;
+            r[u] = on[u] ? e / pieces : 0;
+            c[u] = on[u] ? (int)(e - r[u] * pieces) : 0;
+            int64_t pos = ib[r[u]];
+            pos = pos < 0 ? 0 : (pos < L ? pos : L - 1);   // whatever idx holds, the read stays inside the prompt
+            src[u] = pos;
+        }
+        u32x4_nt a[U], b[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t row = physical_row(pm.table, pm.page, pm.pages, src[u]);
+            a[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(&kb[row * kl.row_stride + c[u]]));
+            b[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4_nt*>(&vb[row * vl.row_stride + c[u]]));
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (on[u]) {
+                __builtin_nontemporal_store(a[u], reinterpret_cast<u32x4_nt*>(&okb[r[u] * pieces + c[u]]));
+                __builtin_nontemporal_store(b[u], reinterpret_cast<u32x4_nt*>(&ovb[r[u] * pieces + c[u]]));
+            }
     }
     // the call's scratch is no longer read by anything: leave it ready for the next call
     const int64_t gid = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * 256 + threadIdx.x;
@@ -485,7 +507,7 @@ hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H
     if (H <= 0 || rows <= 0) return hipSuccess;
     const int pieces = row_bytes / 16;
     const int64_t total = rows * pieces;
-    unsigned bx = (unsigned)((total + 255) / 256);
+    unsigned bx = (unsigned)((total + 1023) / 1024);   // four pieces per thread
     if (bx > 4096) bx = 4096;
     const RowLayout kp{kl.head_stride / 16, kl.row_stride / 16}, vp{vl.head_stride / 16, vl.row_stride / 16};
     hipLaunchKernelGGL(gather_rows, dim3(bx, H), dim3(256), 0, st, static_cast<const uint4*>(k),
