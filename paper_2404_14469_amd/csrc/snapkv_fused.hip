@@ -154,14 +154,6 @@ unsigned read_sync_timeouts() {
     return v;
 }
 
-// Optional timestamp trace for tuning builds (-DSNAPKV_FUSED_TRACE): wave 0 of every workgroup
-// writes wall-clock stamps at fixed points of each unit into g_trace.  Not compiled by default.
-#ifdef SNAPKV_FUSED_TRACE
-__device__ long long g_trace[512 * 64 * 12];
-#define TRACE(slot_) do { if (tid == 0) g_trace[((int64_t)blockIdx.x * 64 + trace_ui) * 12 + (slot_)] = wall_clock64(); } while (0)
-#else
-#define TRACE(slot_) do { } while (0)
-#endif
 
 constexpr unsigned long long kInvalidPair = ~0ull;   // a sum-exp is never NaN: no real pair looks like this
 constexpr int kSlicesPerBlock = 32;                  // slices merged by one half-wave in step L1
@@ -282,9 +274,6 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
     const int hw = tid >> 5, l32 = tid & 31;
     const int real_tasks = R * F.NB;
     bool gave_up = false;
-#ifdef SNAPKV_FUSED_TRACE
-    int trace_ui = 0;
-#endif
 
     // Per-lane row addresses; they advance by one group stride per iteration.  Loads are
     // unconditional (out-of-range tiles and padding rows re-read a valid row and are masked or
@@ -438,7 +427,6 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
         const int unit_l1 = unit - F.NG;
         const int unit_p2 = unit - 2 * F.NG;
         const int64_t kstep = kNext1 ? kstep_to(it + 1) : 0;   // to the next unit's keys
-        TRACE(0);
 
         // ---- A. request this iteration's hand-off words at the very top: they are needed after
         // the arithmetic of step D, about one memory latency from now.  A wave's loads retire in
@@ -456,16 +444,11 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
 
         // ---- B. logits of the upper tiles of the slice (waits for their K; the lower tiles were
         // done at the end of the previous iteration)
-#ifdef SNAPKV_FUSED_TRACE
-        TRACE(8);
-#endif
         if (has_p1) mfma_tiles(ICL{}, ICT{}, it % 3);
         __builtin_amdgcn_sched_barrier(0);
-        TRACE(9);
 
         // ---- C. the next unit's Q and upper K tiles follow in portions between the steps below
         SNAPKV_ISSUE(kNext1, issue_q());
-        TRACE(1);
 
         float mref[RUW][4], zs[RUW][4];
         if (has_p1) {
@@ -526,7 +509,6 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
                     zs[ru][r] = row16_sum(z);
                 }
         }
-        TRACE(10);
         // ---- E. step P2 of the unit two back: level-1 words of a row sit in 16 neighbouring
         // lanes; merge them in a fixed tree into (max, 1/sum)
         if (has_p2) {
@@ -564,9 +546,7 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
         // what this wave has written up to here is complete: stamp its three flags
         lds_release();
         if (lane < 3) lds_stamp(&sm_flag[lane][w], lane == 0 ? it + 2 : it + 1);
-        TRACE(2);
         SNAPKV_ISSUE(kNext1, issue_tiles(ICL{}, ICUA{}, kstep));   // point 1
-        TRACE(3);
         if (has_p1 && tid >= NT - R) {   // the last R threads merge the waves (in wave order) and publish
             const int row = tid - (NT - R);
             lds_await_all<NW>(sm_flag[1], it + 1, F.spin_limit, gave_up);
@@ -591,7 +571,6 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
                 for (int w2 = 0; w2 + d < NW; w2 += 2 * d) zz[w2] += zz[w2 + d];
             publish_pair(&S.part[((int64_t)unit * F.Gg + wg) * R + row], m, zz[0]);
         }
-        TRACE(4);
 
         // ---- F. step L1 of the previous unit: merge 32 slices of one row per half-wave
         if (has_l1) {
@@ -619,7 +598,6 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
             }
         }
         SNAPKV_ISSUE(kNext1, issue_tiles(ICUA{}, ICT{}, kstep));   // point 2
-        TRACE(5);
         if (has_p2) {
             lds_await_all<NW>(sm_flag[2], it + 1, F.spin_limit, gave_up);
             float f[RUW][4];
@@ -697,7 +675,6 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
                 e2[ru][t] = e1[ru][t];
                 e1[ru][t] = e[ru][t];
             }
-        TRACE(6);
         // ---- H. the next unit's lower tiles meet its Q (in LDS since the barrier) and their
         // buffers are requested again for the unit after it
         __builtin_amdgcn_sched_barrier(0);
@@ -708,10 +685,6 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (kNext2) issue_tiles(IC0{}, ICLA{}, kstep_to(it + 2));   // point 3
         __builtin_amdgcn_sched_barrier(0);
-        TRACE(7);
-#ifdef SNAPKV_FUSED_TRACE
-        ++trace_ui;
-#endif
     };
 
 #undef SNAPKV_ISSUE
@@ -1605,9 +1578,3 @@ hipError_t launch_row_lse(int dtype, int D, const void* q, const void* k, const 
 
 }  // namespace snapkv
 
-#ifdef SNAPKV_FUSED_TRACE
-extern "C" int snapkv_debug_trace(long long* out, int n) {
-    if (n > 512 * 64 * 12) n = 512 * 64 * 12;
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(snapkv::g_trace), sizeof(long long) * n);
-}
-#endif

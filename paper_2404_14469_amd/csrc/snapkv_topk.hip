@@ -504,13 +504,6 @@ __global__ __launch_bounds__(256) void sel_emit(const float* __restrict__ score,
 // ------------------------------------------------------------------------------------------------
 __device__ unsigned g_select_timeouts = 0;
 
-// Optional timestamps for tuning builds (-DSNAPKV_FUSED_TRACE); not compiled by default.
-#ifdef SNAPKV_FUSED_TRACE
-__device__ long long g_ps_trace[1024 * 16];
-#define PS_TRACE(slot_) do { if (threadIdx.x == 0 && blockIdx.x < 1024) g_ps_trace[blockIdx.x * 16 + (slot_)] = wall_clock64(); } while (0)
-#else
-#define PS_TRACE(slot_) do { } while (0)
-#endif
 
 unsigned read_select_timeouts() {
     unsigned v = 0;
@@ -631,7 +624,6 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
         for (int t = tid; t < W_tail; t += NT) out[kcount + t] = (int32_t)(n + t);
     if (kcount <= 0) return;
     if (tid == 0) sh_gave_up = 0u;
-    PS_TRACE(0);
 
     // ---- pooled, group-summed scores of this thread's positions, in the arithmetic and order of
     // pool_group.  A thread owns EPT / 4 runs of four consecutive positions: element e = 4 * e4 + k
@@ -701,7 +693,6 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
                 if (f < nf4) reinterpret_cast<float4*>(stage)[f] = land[e4];
             }
             __syncthreads();
-            PS_TRACE(13);
 #pragma unroll
             for (int e4 = 0; e4 < E4; ++e4) {
                 const int i0 = e4 * (4 * NT) + 4 * tid;      // first of the four positions; its taps
@@ -784,7 +775,6 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
     for (int e = 0; e < EPT; ++e)
         if (pos_local(e) < len) active |= 1u << e;
     const unsigned valid = active;
-    PS_TRACE(1);
 
     // ---- the head's range of bit patterns
     unsigned lo = 0xFFFFFFFFu, hi = 0u;
@@ -814,16 +804,13 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
         }
     };
     block_range();
-    PS_TRACE(14);
     if (tid == 0) {
         unsigned done = coherent_store(&S.ps_range[2 * ((int64_t)h * kPsMaxGroup + c)], lo);
         done ^= coherent_store(&S.ps_range[2 * ((int64_t)h * kPsMaxGroup + c) + 1], hi);
         hand_over_done(done);
     }
     unsigned* arrive = S.ps_arrive + (int64_t)h * kPsStages;
-    PS_TRACE(2);
     group_rendezvous(arrive + 0, (unsigned)Wh, spin_limit, &sh_gave_up);
-    PS_TRACE(3);
     lo = 0xFFFFFFFFu;
     hi = 0u;
     for (int i = lane; i < Wh; i += 64) {     // every wave reads all of them: no barrier needed
@@ -857,7 +844,6 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
         for (int e = 0; e < EPT; ++e)
             if (active >> e & 1u) atomicAdd(&sh_hist[((x[e] - cur_lo) >> cur_sh) & (kPsBins - 1)], 1u);
         __syncthreads();
-        PS_TRACE(15);
         unsigned* gh = S.ps_hist + ((int64_t)h * kPsLevels + lvl) * kPsBins;
         unsigned done = 0;
         for (int b = tid; b < kPsBins; b += NT) {
@@ -865,9 +851,7 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
             if (cnt) done ^= coherent_add(&gh[b], cnt);
         }
         hand_over_done(done);
-        PS_TRACE(4 + 2 * (lvl < 2 ? lvl : 1));
         group_rendezvous(arrive + 1 + lvl, (unsigned)Wh, spin_limit, &sh_gave_up);
-        PS_TRACE(5 + 2 * (lvl < 2 ? lvl : 1));
         unsigned bins[kPsBins / NT];
 #pragma unroll
         for (int e = 0; e < kPsBins / NT; ++e)
@@ -894,7 +878,6 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
             cur_sh = range_shift_bits((1u << cur_sh) - 1u, kPsBinBits);
         }
     }
-    PS_TRACE(8);
 
     // ---- final exchange: counts per workgroup, and the candidates unless T is already exact
     const unsigned mine_in = (unsigned)__popc(active);
@@ -920,9 +903,7 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
         done ^= coherent_store(&S.ps_part[2 * ((int64_t)h * kPsMaxGroup + c) + 1], in_total);
         hand_over_done(done);
     }
-    PS_TRACE(9);
     group_rendezvous(arrive + 1 + kPsLevels, (unsigned)Wh, spin_limit, &sh_gave_up);
-    PS_TRACE(10);
 
     // kept positions of the head before this chunk.  Every wave sums the per-workgroup counts
     // itself (no barrier); without an exact T the candidates are fetched, workgroup by workgroup.
@@ -1013,7 +994,6 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
         gt_before += g2;
         eq_before = q2;
     }
-    PS_TRACE(11);
 
     // ---- ordered emission: position order is (run e4, wave, lane, k).  Every wave leaves the
     // counts of its part of each run row in a table; lane e4 of a wave then turns row e4 of the
@@ -1091,7 +1071,6 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
             qb += eq;
         }
     }
-    PS_TRACE(12);
     if (tid == 0 && sh_gave_up) atomicAdd(&g_select_timeouts, 1u);
 }
 
@@ -1321,9 +1300,3 @@ hipError_t launch_select_chunked(const float* score, int H, int64_t n, int64_t k
 
 }  // namespace snapkv
 
-#ifdef SNAPKV_FUSED_TRACE
-extern "C" int snapkv_debug_ps_trace(long long* out, int n) {
-    if (n > 1024 * 16) n = 1024 * 16;
-    return (int)hipMemcpyFromSymbol(out, HIP_SYMBOL(snapkv::g_ps_trace), sizeof(long long) * n);
-}
-#endif
