@@ -179,6 +179,30 @@ int snapkv_compress_varlen(int dtype, int n_prompts, const void* const* q_win, c
                            int64_t* kept, void* stream);
 
 /*
+ * The compression step for several layers of one prompt in one call (Listing 1 runs once per layer; the
+ * layers of a prompt have the same shape and are independent of each other, Sec. 4.1).  Every layer gets
+ * exactly the result of its own snapkv_compress call.  What the call saves: layers whose tensors lie one
+ * directly behind the other in memory (slices of stacked [layers, heads, ...] tensors, for q_win, k, v,
+ * out_k, out_v and out_idx alike) go through the kernels as ONE layer with that many more heads, so the
+ * scoring kernel streams all their keys in a single launch and pays its start-up and drain once, and
+ * pooling, selection and gather run as a few large launches instead of three per layer.  With the whole
+ * uncompressed prompt cache resident (68.7 GB at 32 layers x 32 heads x 131072 tokens: this is what 288 GB
+ * of HBM are for) that is the fastest form of the step.  Layers that do not lie that way are done one by one.
+ *
+ *   n_layers >= 0
+ *   q_win, k, v, out_k, out_v, out_idx   HOST arrays of n_layers DEVICE pointers, each as the argument of the
+ *           same name of snapkv_compress for that layer
+ *   dtype   SNAPKV_DTYPE_*; the other arguments as for snapkv_compress
+ *
+ * The host arrays are read before the call returns.  All layers are validated before anything is enqueued;
+ * returns SNAPKV_OK or a negative SNAPKV_ERR_* code.  Scratch comes from the library's per-device buffer
+ * and grows with the number of layers that run together (at most 6 GiB; longer runs are cut).
+ */
+int snapkv_compress_layers(int dtype, int n_layers, const void* const* q_win, const void* const* k,
+                           const void* const* v, int64_t L, int Hq, int Hkv, int D, int W, int pool_kind, int p,
+                           int64_t C, void* const* out_k, void* const* out_v, int32_t* const* out_idx, void* stream);
+
+/*
  * The compression step on a paged cache (Listing 1 indexes K and V by (head, position), whatever their
  * storage): k_pages and v_pages are [num_pages, page_size, Hkv, D] (the rows of a page are token-major)
  * and logical position j of every head lives in physical page block_table[j / page_size], row

@@ -26,7 +26,7 @@ SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compr
            "snapkv_compress_strided", "snapkv_compress_f16", "snapkv_pooled_scores_f16",
            "snapkv_decode_attention", "snapkv_compress_per_query_head",
            "snapkv_capacity_for_rate", "snapkv_hit_rate", "snapkv_compress_paged",
-           "snapkv_compress_varlen")
+           "snapkv_compress_varlen", "snapkv_compress_layers")
 
 _lib = None
 
@@ -80,6 +80,8 @@ def load():
     L.snapkv_capacity_for_rate.argtypes = [i64, i32, ctypes.c_double]
     L.snapkv_compress_paged.restype = i64
     L.snapkv_compress_paged.argtypes = [i32, vp, vp, vp, vp, i64, i32, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
+    L.snapkv_compress_layers.restype = i32
+    L.snapkv_compress_layers.argtypes = [i32, i32, vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
     L.snapkv_compress_varlen.restype = i32
     L.snapkv_compress_varlen.argtypes = [i32, i32, vp, vp, vp, vp, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp, vp]
     L.snapkv_hit_rate.restype = i32
@@ -366,6 +368,32 @@ def snapkv_compress_varlen(q_wins, ks, vs, pool_kind: int, p: int, C: int, out_k
         int(pool_kind), int(p), int(C), arr(out_ks, "out_k", dt), arr(out_vs, "out_v", dt),
         arr(out_idxs, "out_idx", torch.int32), kept, _stream(stream)))
     return [int(x) for x in kept]
+
+
+def snapkv_compress_layers(q_wins, ks, vs, pool_kind: int, p: int, C: int, out_ks, out_vs, out_idxs, stream=None) -> None:
+    """Several layers of one prompt: lists of tensors shaped as for snapkv_compress, all of one shape.  Slices of
+    stacked [layers, heads, ...] tensors (for all six lists) take the fast form of the step."""
+    lib = load()
+    n = len(q_wins)
+    if not (len(ks) == len(vs) == len(out_ks) == len(out_vs) == len(out_idxs) == n):
+        raise ValueError("all lists must have one entry per layer")
+    if n == 0:
+        return
+    Hq, Hkv, L, D, W = _shapes(q_wins[0], ks[0])
+    code = _dtype_code(q_wins[0])
+    for i in range(n):
+        if _shapes(q_wins[i], ks[i]) != (Hq, Hkv, L, D, W) or _dtype_code(q_wins[i]) != code:
+            raise ValueError("the layers of a call share heads, length, head dim, window and dtype")
+        if tuple(vs[i].shape) != tuple(ks[i].shape):
+            raise ValueError("k and v must have the same shape")
+        if tuple(out_ks[i].shape) != (Hkv, C, D) or tuple(out_vs[i].shape) != (Hkv, C, D) or \
+                tuple(out_idxs[i].shape) != (Hkv, C):
+            raise ValueError("out_k/out_v must be [Hkv, C, D] and out_idx [Hkv, C]")
+    dt = q_wins[0].dtype
+    arr = lambda ts, name, dtype: (ctypes.c_void_p * n)(*[_dev(t, name, dtype) for t in ts])
+    _check(lib.snapkv_compress_layers(
+        code, n, arr(q_wins, "q_win", dt), arr(ks, "k", dt), arr(vs, "v", dt), L, Hq, Hkv, D, W, int(pool_kind), int(p),
+        int(C), arr(out_ks, "out_k", dt), arr(out_vs, "out_v", dt), arr(out_idxs, "out_idx", torch.int32), _stream(stream)))
 
 
 def snapkv_capacity_for_rate(L: int, W: int, rate: float) -> int:

@@ -13,6 +13,7 @@ namespace {
 using namespace snapkv;
 
 constexpr int kMaxDevices = 64;
+constexpr size_t kLayersScratchCap = (size_t)6 << 30;   // snapkv_compress_layers: most scratch one run of layers may take
 // What the last call's final kernel left ready at the start of the library's own buffer, so that
 // the next call needs no preparing launch: the selection's counters (zero) for `hkv` heads and,
 // behind them in a region of `fused_bytes` bytes, `ones` hand-off words holding the "not
@@ -22,6 +23,7 @@ struct CleanState {
     int hkv = 0, hq = 0;
     size_t fused_bytes = 0;
     int64_t ones = -1;
+    hipStream_t stream = nullptr;   // the stream the call that left this state was enqueued on
 };
 struct DeviceScratch {
     void* ptr = nullptr;
@@ -284,8 +286,10 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
                 now.hkv = Hkv;
                 now.hq = Hq;
                 now.fused_bytes = fused_sync_bytes(G);
+                now.stream = st;
+                // (a call on another stream is not ordered behind the kernel that left the state)
                 const bool same = was_clean.ones >= 0 && was_clean.hkv == now.hkv && was_clean.hq == now.hq &&
-                                  was_clean.fused_bytes == now.fused_bytes;
+                                  was_clean.fused_bytes == now.fused_bytes && was_clean.stream == st;
                 prepared = same && was_clean.ones >= nones;
                 now.ones = same && was_clean.ones > nones ? was_clean.ones : nones;
                 mine = &g_scratch[dev];
@@ -747,6 +751,52 @@ int snapkv_compress_varlen(int dtype, int n_prompts, const void* const* q_win, c
             if (kept) kept[s] = C;
         }
         i = j;
+    }
+    return SNAPKV_OK;
+}
+
+int snapkv_compress_layers(int dtype, int n_layers, const void* const* q_win, const void* const* k,
+                           const void* const* v, int64_t L, int Hq, int Hkv, int D, int W, int pool_kind, int p,
+                           int64_t C, void* const* out_k, void* const* out_v, int32_t* const* out_idx, void* stream) {
+    if (n_layers < 0 || (n_layers > 0 && (!q_win || !k || !v || !out_k || !out_v || !out_idx))) return SNAPKV_ERR_INVALID_ARG;
+    if (!valid_dtype(dtype)) return SNAPKV_ERR_INVALID_ARG;
+    for (int i = 0; i < n_layers; ++i) {   // every layer is checked before anything is enqueued
+        const int rc = check_score_args(q_win[i], k[i], L, Hq, Hkv, D, W, pool_kind, p);
+        if (rc != SNAPKV_OK) return rc;
+        if (!v[i] || !out_k[i] || !out_v[i] || !out_idx[i]) return SNAPKV_ERR_INVALID_ARG;
+        if (C < 1 || W > C) return SNAPKV_ERR_INVALID_ARG;
+        if (C >= (int64_t)1 << 31) return SNAPKV_ERR_UNSUPPORTED;
+        if (!aligned16(v[i]) || !aligned16(out_k[i]) || !aligned16(out_v[i])) return SNAPKV_ERR_MISALIGNED;
+        if ((reinterpret_cast<uintptr_t>(out_idx[i]) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
+    }
+    // Layers that lie one behind the other in memory (a stacked [layers, heads, ...] tensor for each of the
+    // seven arguments) are to the kernels one layer with that many more heads: heads are independent, and
+    // a head's result does not depend on how many others the call has.
+    const int64_t e = elem_bytes(dtype);
+    const int64_t rows = L <= C ? L : C;   // rows a head writes
+    (void)rows;
+    const int64_t dq = (int64_t)Hq * W * D * e, dk = (int64_t)Hkv * L * D * e, dok = (int64_t)Hkv * C * D * e,
+                  di = (int64_t)Hkv * C * (int64_t)sizeof(int32_t);
+    auto follows = [&](int i) {   // layer i + 1 lies directly behind layer i in all seven tensors
+        auto gap = [](const void* a, const void* b) { return static_cast<const char*>(b) - static_cast<const char*>(a); };
+        return gap(q_win[i], q_win[i + 1]) == dq && gap(k[i], k[i + 1]) == dk && gap(v[i], v[i + 1]) == dk &&
+               gap(out_k[i], out_k[i + 1]) == dok && gap(out_v[i], out_v[i + 1]) == dok &&
+               gap(out_idx[i], out_idx[i + 1]) == di;
+    };
+    // the scratch of a run grows with its heads: runs are cut so that it stays under kLayersScratchCap
+    const size_t per_layer = L > C ? workspace_layout(make_geom(L, Hq, Hkv, D, W), nullptr, nullptr) : 0;
+    int most = (int)(kLayersScratchCap / (per_layer > 0 ? per_layer : 1));
+    most = most < 1 ? 1 : most;
+    if ((int64_t)most * Hkv > 65535) most = 65535 / Hkv;
+    if (L <= C) most = 1;                  // prompts that fit are copied layer by layer (out rows [L, C) stay untouched)
+    int i = 0;
+    while (i < n_layers) {
+        int r = 1;
+        while (i + r < n_layers && r < most && follows(i + r - 1)) ++r;
+        const int64_t got = compress_impl(dtype, q_win[i], k[i], v[i], L, Hq * r, Hkv * r, D, W, pool_kind, p, C, out_k[i],
+                                          out_v[i], out_idx[i], stream);
+        if (got < 0) return (int)got;
+        i += r;
     }
     return SNAPKV_OK;
 }
