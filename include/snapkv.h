@@ -118,6 +118,22 @@ int64_t snapkv_compress_ws(int dtype, const void* q_win, const void* k, const vo
                            size_t workspace_bytes, void* stream);
 
 /*
+ * snapkv_compress_ws for callers that cannot allocate and have no workspace to hand in: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch is a fixed array of
+ * SNAPKV_STATIC_SCRATCH_BYTES inside the library's device image (every GPU the library runs on holds it
+ * until the process ends); the call allocates nothing and frees nothing.  Shapes whose
+ * snapkv_workspace_bytes(L, Hq, Hkv, D, W) exceeds SNAPKV_STATIC_SCRATCH_BYTES are refused with
+ * SNAPKV_ERR_WORKSPACE before anything is enqueued (32 heads x 16384 tokens and 32/8 heads x 32768 tokens
+ * fit; 32 heads x 131072 tokens do not).  Arguments, outputs and results are those of snapkv_compress_ws.
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents (the call's first kernel
+ * clears what must start at zero): calls that overlap on one GPU, on whatever streams, race.
+ */
+#define SNAPKV_STATIC_SCRATCH_BYTES (32u << 20)
+int64_t snapkv_compress_static(int dtype, const void* q_win, const void* k, const void* v, int64_t L,
+                               int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
+                               void* out_k, void* out_v, int32_t* out_idx, void* stream);
+
+/*
  * The same step when the softmax normalisers of the window rows are already known (an attention
  * prefill that works block by block keeps, for every query row, the log of its softmax
  * denominator; Sec. 4.1 runs the compression at the end of prompt encoding, so they exist).

@@ -8,6 +8,12 @@
 #include <mutex>
 #include <vector>
 
+// Scratch of snapkv_compress_static: a fixed array in the library's own device image, so that entry point
+// neither allocates nor takes a workspace.  In host code this name is only a stand-in for the symbol:
+// the array's device address is looked up once per device (static_scratch below) and that address is
+// what the kernels get.
+static __device__ __align__(256) unsigned char scratch[SNAPKV_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 using namespace snapkv;
@@ -116,6 +122,26 @@ int internal_scratch(size_t need, void** out, CleanState* was_clean = nullptr) {
         s.bytes = want;
     }
     *out = s.ptr;
+    return SNAPKV_OK;
+}
+
+// Device address of `scratch` on the current device.  Every GPU holds its own copy of the array at its
+// own address, so the address is asked for with that device current, the first time the device is seen.
+void* g_static_scratch[kMaxDevices] = {nullptr};
+
+int static_scratch(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SNAPKV_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_mu);
+    if (!g_static_scratch[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return SNAPKV_ERR_HIP;
+        }
+        g_static_scratch[dev] = ptr;
+    }
+    *out = g_static_scratch[dev];
     return SNAPKV_OK;
 }
 
@@ -620,6 +646,24 @@ int64_t snapkv_compress_ws(int dtype, const void* q_win, const void* k, const vo
     opt.workspace = workspace;
     opt.workspace_bytes = workspace_bytes;
     opt.own_scratch = false;
+    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx, stream, opt);
+}
+
+int64_t snapkv_compress_static(int dtype, const void* q_win, const void* k, const void* v, int64_t L,
+                               int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
+                               void* out_k, void* out_v, int32_t* out_idx, void* stream) {
+    // the size is checked first: a shape that does not fit is refused before anything else happens
+    if (L >= 1 && W >= 1 && W <= L && Hq >= 1 && Hkv >= 1 && Hq % Hkv == 0 && (D == 64 || D == 128) &&
+        L < ((int64_t)1 << 31) && L > C &&
+        workspace_layout(make_geom(L, Hq, Hkv, D, W), nullptr, nullptr) > (size_t)SNAPKV_STATIC_SCRATCH_BYTES)
+        return SNAPKV_ERR_WORKSPACE;
+    void* ptr = nullptr;
+    const int rc = static_scratch(&ptr);
+    if (rc != SNAPKV_OK) return rc;
+    CompressOptions opt;
+    opt.workspace = ptr;                   // the looked-up device address, never the array's name
+    opt.workspace_bytes = SNAPKV_STATIC_SCRATCH_BYTES;
+    opt.own_scratch = false;               // everything that must start at zero is cleared by the call's first kernel
     return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx, stream, opt);
 }
 
