@@ -30,7 +30,7 @@ def run_gpu(pkg, q, k, v, pool_kind, p, C):
 
 
 def check_against_oracle(q, k, v, pool_kind, p, C, scores, out_k, out_v, out_idx, kept, heads=None,
-                         own_topk_exact=True):
+                         own_topk_exact=True, oracle_scores=None):
     """The parity bar, per KV head in `heads` (default: all).
 
     - pooled scores within REL_TOL relative of the oracle's;
@@ -39,6 +39,8 @@ def check_against_oracle(q, k, v, pool_kind, p, C, scores, out_k, out_v, out_idx
     - sharp self-consistency: the kept set is exactly the top-(C-W) of the GPU's own scores under
       (score descending, position ascending);
     - positions unique, ascending, window last; gathered K/V rows bit-identical to the inputs'.
+    `oracle_scores` [Hkv, L-W] (fp64), when given, are the oracle's pooled scores computed beforehand (the
+    plain-C oracle does a whole full-size layer at once); otherwise the numpy oracle is run head by head.
     Returns the number of band (near-tie) positions seen, for information.
     """
     Hkv, L, D = k.shape
@@ -59,7 +61,8 @@ def check_against_oracle(q, k, v, pool_kind, p, C, scores, out_k, out_v, out_idx
     kc = C - W
     qb = workloads.to_numpy_bits(q)
     for oi, hk in enumerate(heads):
-        s_orc = orc.pooled_scores(qb[hk * g:(hk + 1) * g], kb[oi:oi + 1], W, pool_kind, p)[0]
+        s_orc = (oracle_scores[hk] if oracle_scores is not None
+                 else orc.pooled_scores(qb[hk * g:(hk + 1) * g], kb[oi:oi + 1], W, pool_kind, p)[0])
         s_gpu = scores[hk].astype(np.float64)
         assert np.all(np.isfinite(s_gpu)), f"head {hk}: non-finite GPU score"
         err = np.abs(s_gpu - s_orc)

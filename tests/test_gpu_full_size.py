@@ -1,7 +1,8 @@
-"""The named configurations at full size, in the launch configuration bench.py times.
+"""The named configurations at full size, in the launch configurations bench.py times.
 
-The oracle is evaluated on sampled KV heads (one head of the longest configuration is ~1 GFLOP of
-fp64); properties that hold at any size are checked on every head."""
+The numpy oracle is evaluated on sampled KV heads (one head of the longest configuration is ~1 GFLOP of
+fp64), the plain-C oracle on every head of a layer; properties that hold at any size are checked on
+every head."""
 import pytest
 import torch
 
@@ -47,8 +48,59 @@ def test_long_131k_sampled_heads_and_needle(snapkv, layer, heads):
     torch.cuda.empty_cache()
 
 
+def test_long_131k_every_head_of_a_layer_against_the_c_oracle(snapkv):
+    """All 32 heads of one layer of the long-context configuration: pooled scores within 1e-3 relative of
+    the plain-C fp64 oracle's, kept positions by the band rule, the kept set the exact top-k of the GPU's
+    own scores, gathered rows bit-identical (the sampled heads above are the numpy oracle's second opinion)."""
+    from oracle import c_oracle
+    w = workloads.LONG_131K
+    layer = 9
+    print(f"[full-size] {w.name} layer {layer}: all {w.Hkv} heads against the plain-C oracle", flush=True)
+    case = workloads.generate(w, layer=layer, device="cuda")
+    q, k, v = case["q_win"], case["k"], case["v"]
+    res = run_gpu(snapkv, q, k, v, w.pool_kind, w.p, w.C)
+    _, _, _, kept, score = c_oracle.compress(*(workloads.to_numpy_bits(x) for x in (q, k, v)), w.W, w.pool_kind, w.p, w.C)
+    assert kept == w.C and score.shape == (w.Hkv, w.n)
+    band = check_against_oracle(q, k, v, w.pool_kind, w.p, w.C, *res, oracle_scores=score)
+    print(f"[full-size] {w.name}: positions inside the +-1e-3 band around the threshold, all heads: {band}", flush=True)
+    del case, res
+    torch.cuda.empty_cache()
+
+
+def test_layers_entry_at_full_size(snapkv):
+    """Three layers of the long-context configuration through snapkv_compress_layers (stacked, so they run
+    as one layer of 96 heads, on the kernels the 32-layer call of bench.py uses): bit for bit what single
+    calls give, and one head against the oracle."""
+    import numpy as np
+    w = workloads.LONG_131K
+    nl = 3
+    print(f"[full-size] {w.name}: {nl} stacked layers through snapkv_compress_layers", flush=True)
+    K = torch.empty((nl, w.Hkv, w.L, w.D), dtype=torch.bfloat16, device="cuda")
+    V = torch.empty_like(K)
+    Q = torch.empty((nl, w.Hq, w.W, w.D), dtype=torch.bfloat16, device="cuda")
+    for l in range(nl):
+        c = workloads.generate(w, layer=20 + l, device="cuda")
+        K[l].copy_(c["k"]), V[l].copy_(c["v"]), Q[l].copy_(c["q_win"])
+        del c
+    ok = torch.zeros((nl, w.Hkv, w.C, w.D), dtype=torch.bfloat16, device="cuda")
+    ov = torch.zeros_like(ok)
+    oi = torch.full((nl, w.Hkv, w.C), -1, dtype=torch.int32, device="cuda")
+    snapkv.snapkv_compress_layers(list(Q), list(K), list(V), w.pool_kind, w.p, w.C, list(ok), list(ov), list(oi))
+    torch.cuda.synchronize()
+    for l in range(nl):
+        ref = run_gpu(snapkv, Q[l], K[l], V[l], w.pool_kind, w.p, w.C)
+        assert np.array_equal(oi[l].cpu().numpy(), ref[3]), f"layer {l}: kept positions"
+        assert torch.equal(ok[l], ref[1]) and torch.equal(ov[l], ref[2]), f"layer {l}: rows"
+        if l == 1:
+            check_against_oracle(Q[l], K[l], V[l], w.pool_kind, w.p, w.C, ref[0], ok[l], ov[l], oi[l].cpu().numpy(), w.C,
+                                 heads=[17])
+    assert snapkv.snapkv_sync_timeouts() == 0
+    del K, V, Q, ok, ov, oi
+    torch.cuda.empty_cache()
+
+
 def test_window_64_pool_13_at_full_size(snapkv):
-    """The wider window and pooling kernel the paper uses for one of its models (Sec. 5.2's
+    """The wider window and pooling kernel the paper uses for one of its models (Sec. 5.4's
     Command-R setting: W = 64, p = 13), on the grouped-query and on the long configuration."""
     _run(snapkv, workloads.MISTRAL_7B_GQA_32K.with_(name="gqa_32k_w64_p13", W=64, p=13), 2, [0, 7])
     _run(snapkv, workloads.LONG_131K.with_(name="long_131k_w64_p13", W=64, p=13), 5, [11])
