@@ -49,6 +49,7 @@ extern "C" {
 #define SNAPKV_ERR_MISALIGNED (-3)  /* a q/k/v/out_k/out_v pointer is not 16-byte aligned */
 #define SNAPKV_ERR_WORKSPACE (-4)   /* workspace missing or smaller than snapkv_workspace_bytes() */
 #define SNAPKV_ERR_HIP (-5)         /* a HIP call (allocation or launch) failed */
+#define SNAPKV_ERR_TIMEOUT (-6)     /* a bounded wait inside a kernel gave up: the results of that call are invalid */
 
 /* Library version: major*10000 + minor*100 + patch. */
 int snapkv_version(void);
@@ -72,6 +73,11 @@ const char* snapkv_strerror(int code);
  * written.  Scratch memory comes from a per-device buffer the library allocates on first use
  * and grows when a larger problem arrives (hipMalloc; see snapkv_compress_ws for a variant that
  * never allocates); concurrent calls on different streams of one device would share it and race.
+ * Calls that use this buffer (this entry and every entry below that says so) must come from one host
+ * thread at a time and be ordered by the stream(s) they are enqueued on; on a stream that is being
+ * captured into a graph they return SNAPKV_ERR_UNSUPPORTED (the library keeps a host-side record of the
+ * state the buffer is left in, which a replay would bypass): capture snapkv_compress_ws or
+ * snapkv_compress_static instead.
  */
 int64_t snapkv_compress(const void* q_win, const void* k, const void* v, int64_t L, int Hq, int Hkv,
                         int D, int W, int pool_kind, int p, int64_t C, void* out_k, void* out_v,
@@ -116,6 +122,29 @@ int64_t snapkv_compress_ws(int dtype, const void* q_win, const void* k, const vo
                            int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
                            void* out_k, void* out_v, int32_t* out_idx, void* workspace,
                            size_t workspace_bytes, void* stream);
+
+/*
+ * snapkv_compress_ws that also leaves the call's verdict in device memory.  The single-read scoring
+ * kernel and the cooperative pooling + selection kernel hand data between workgroups that must all be
+ * resident at the same time; the host checks that the device CAN keep them resident, but cannot know
+ * what else occupies it, so every such wait is bounded, and a wait that gives up leaves the call's
+ * outputs invalid (memory-safe, but not the kept rows).  Once the stream has reached the end of the call,
+ *   *status = rows kept per head (min(C, L)), or SNAPKV_ERR_TIMEOUT if a wait gave up in this call.
+ *   status  device int32 of the caller's (4-byte aligned), written by the call's last kernel
+ * The caller reads it where it synchronises anyway; the library never synchronises for it.  The other
+ * arguments and the return value are those of snapkv_compress_ws.
+ *
+ * The entries that use the library's own scratch (snapkv_compress and its variants) report the same
+ * condition one call late: the device records it in pinned host memory when it happens, and the next
+ * such call on that device that finds the record returns SNAPKV_ERR_TIMEOUT (once) instead of enqueuing
+ * anything: a call before it, already returned, produced invalid results.  They must be used from one
+ * stream at a time per device (calls on different streams are not ordered against each other and share
+ * the scratch) and not from several host threads at once.
+ */
+int64_t snapkv_compress_ws_status(int dtype, const void* q_win, const void* k, const void* v, int64_t L,
+                                  int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
+                                  void* out_k, void* out_v, int32_t* out_idx, void* workspace,
+                                  size_t workspace_bytes, int32_t* status, void* stream);
 
 /*
  * snapkv_compress_ws for callers that cannot allocate and have no workspace to hand in: code under HIP
@@ -350,6 +379,15 @@ int snapkv_set_scoring_scheme(int scheme);
  * device.  Returns the count since the library was loaded, or a negative SNAPKV_ERR_* code.
  */
 int64_t snapkv_sync_timeouts(void);
+
+/*
+ * Test hook, not for production: bounds every wait inside the kernels to `polls` polls (0: every wait gives
+ * up at once; negative: the kernels' own bounds, tens of milliseconds).  With a bound of 0 all kernels
+ * still run to their end and stay inside their buffers, the results are invalid and the condition is
+ * reported as described at snapkv_compress_ws_status.  Process-wide.  -2 also sets the count of
+ * snapkv_sync_timeouts back to zero (and synchronises the device for it).
+ */
+int snapkv_debug_set_wait_limit(long long polls);
 
 /* Frees the library's per-device scratch buffers (synchronises each device that has one). */
 void snapkv_release(void);

@@ -26,7 +26,8 @@ SYMBOLS = ("snapkv_version", "snapkv_strerror", "snapkv_compress", "snapkv_compr
            "snapkv_compress_strided", "snapkv_compress_f16", "snapkv_pooled_scores_f16",
            "snapkv_decode_attention", "snapkv_compress_per_query_head",
            "snapkv_capacity_for_rate", "snapkv_hit_rate", "snapkv_compress_paged",
-           "snapkv_compress_varlen", "snapkv_compress_layers", "snapkv_compress_static")
+           "snapkv_compress_varlen", "snapkv_compress_layers", "snapkv_compress_static",
+           "snapkv_compress_ws_status", "snapkv_debug_set_wait_limit")
 
 _lib = None
 
@@ -74,6 +75,11 @@ def load():
                                      vp, vp, sz, vp]
     L.snapkv_compress_static.restype = i64
     L.snapkv_compress_static.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp, vp, vp]
+    L.snapkv_compress_ws_status.restype = i64
+    L.snapkv_compress_ws_status.argtypes = [i32, vp, vp, vp, i64, i32, i32, i32, i32, i32, i32, i64, vp, vp,
+                                            vp, vp, sz, vp, vp]
+    L.snapkv_debug_set_wait_limit.restype = i32
+    L.snapkv_debug_set_wait_limit.argtypes = [ctypes.c_longlong]
     L.snapkv_select_topk.restype = i32
     L.snapkv_select_topk.argtypes = [vp, i32, i64, i64, vp, vp]
     L.snapkv_compress_per_query_head.restype = i64
@@ -216,6 +222,29 @@ def snapkv_compress(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, pool_
 
 
 STATIC_SCRATCH_BYTES = 32 << 20
+ERR_TIMEOUT = -6
+
+
+def snapkv_compress_ws_status(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, pool_kind: int, p: int, C: int,
+                              out_k: torch.Tensor, out_v: torch.Tensor, out_idx: torch.Tensor, workspace: torch.Tensor,
+                              status: torch.Tensor, stream=None) -> int:
+    """snapkv_compress_ws plus `status` (an int32 GPU tensor of one element): rows kept, or ERR_TIMEOUT."""
+    lib = load()
+    Hq, Hkv, L, D, W = _shapes(q_win, k)
+    if v.shape != k.shape:
+        raise ValueError("k and v must have the same shape")
+    if tuple(out_k.shape) != (Hkv, C, D) or tuple(out_v.shape) != (Hkv, C, D) or tuple(out_idx.shape) != (Hkv, C):
+        raise ValueError("out_k/out_v must be [Hkv, C, D] and out_idx [Hkv, C]")
+    return _check(lib.snapkv_compress_ws_status(
+        _dtype_code(k), _dev(q_win, "q_win", k.dtype), _dev(k, "k"), _dev(v, "v", k.dtype), L, Hq, Hkv, D, W, pool_kind, p, C,
+        _dev(out_k, "out_k", k.dtype), _dev(out_v, "out_v", k.dtype), _dev(out_idx, "out_idx", torch.int32),
+        _dev(workspace, "workspace", torch.uint8), workspace.numel(), _dev(status, "status", torch.int32), _stream(stream)))
+
+
+def snapkv_debug_set_wait_limit(polls: int) -> None:
+    """Test hook: bound of every wait inside the kernels, in polls (negative = the kernels' own bounds)."""
+    _check(load().snapkv_debug_set_wait_limit(int(polls)))
+
 
 
 def snapkv_compress_static(q_win: torch.Tensor, k: torch.Tensor, v: torch.Tensor, pool_kind: int, p: int,

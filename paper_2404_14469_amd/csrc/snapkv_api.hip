@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <atomic>
 #include <mutex>
 #include <vector>
 
@@ -35,6 +36,7 @@ struct DeviceScratch {
     void* ptr = nullptr;
     size_t bytes = 0;
     CleanState clean;
+    unsigned* sticky = nullptr;   // pinned host word the device sets when a call on this scratch had a wait give up
 };
 DeviceScratch g_scratch[kMaxDevices];
 std::mutex g_mu;
@@ -75,6 +77,8 @@ Profile g_prof;
 bool g_allow_fused = true;   // snapkv_set_scoring_scheme: tests can force the two-pass kernels
 bool g_allow_pool_select = true;   // ... and the separate pooling and selection kernels
 
+std::atomic<long long> g_wait_limit{-1};   // snapkv_debug_set_wait_limit: < 0 = the kernels' own bounds
+
 bool valid_dtype(int dtype) { return dtype == SNAPKV_DTYPE_BF16 || dtype == SNAPKV_DTYPE_F32 || dtype == SNAPKV_DTYPE_F16; }
 int elem_bytes(int dtype) { return dtype == SNAPKV_DTYPE_F32 ? 4 : 2; }
 
@@ -96,13 +100,35 @@ int check_score_args(const void* q_win, const void* k, int64_t L, int Hq, int Hk
     return SNAPKV_OK;
 }
 
+// The entries that use the library's own scratch keep a host-side record of the state their last kernel
+// leaves it in, and may allocate; neither survives being recorded into a graph and replayed later, so
+// they refuse a stream that is capturing (snapkv_compress_ws and snapkv_compress_static are the forms to capture).
+bool capturing(hipStream_t st) {
+    hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(st, &cs) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return cs != hipStreamCaptureStatusNone;
+}
+
 // Hands out the device's buffer.  Whoever takes it may leave it in any state, so the record of a
 // ready-made state is handed to the caller (*was_clean, may be null) and dropped.
-int internal_scratch(size_t need, void** out, CleanState* was_clean = nullptr) {
+int internal_scratch(size_t need, void** out, CleanState* was_clean = nullptr, unsigned** sticky = nullptr) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return SNAPKV_ERR_HIP;
     std::lock_guard<std::mutex> lock(g_mu);
     DeviceScratch& s = g_scratch[dev];
+    if (!s.sticky) {   // allocated, not registered: a few bytes of pinned host memory the kernels can write
+        void* p = nullptr;
+        if (hipHostMalloc(&p, 64, hipHostMallocDefault) != hipSuccess) {
+            (void)hipGetLastError();
+            return SNAPKV_ERR_HIP;
+        }
+        s.sticky = static_cast<unsigned*>(p);
+        *s.sticky = 0u;
+    }
+    if (sticky) *sticky = s.sticky;
     if (s.bytes < need) s.clean = CleanState{};
     if (was_clean) *was_clean = s.clean;
     s.clean = CleanState{};
@@ -155,8 +181,9 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
     ScoreGeom Gp = G;
     if (lse) {   // the rows' normalisers are given: one streaming pass, nothing handed between workgroups
         if (!lse_plan(dtype, D, G, &F)) return SNAPKV_ERR_UNSUPPORTED;
-        if (!already_prepared && prepare_select) {
-            if (launch_prepare(nullptr, 0, &ws.sel, G.Hkv * G.g, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        if (!already_prepared) {
+            if (launch_prepare(nullptr, 0, prepare_select ? &ws.sel : nullptr, G.Hkv * G.g, st, ws.status_flag) != hipSuccess)
+                return SNAPKV_ERR_HIP;
             stage_done(st, kStagePrepare);
         }
         if (launch_score_lse(dtype, D, q_win, k, lse, G, F, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
@@ -171,10 +198,13 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
     }
     const bool fused = g_allow_fused && fused_plan(dtype, D, G, &F, allow_blocks);
     FusedSync S;
-    if (fused) fused_sync_layout(G, F, &S, ws.fused);
+    if (fused) {
+        fused_sync_layout(G, F, &S, ws.fused);
+        S.gave_up_flag = ws.status_flag;
+    }
     if (!already_prepared) {
         if (launch_prepare(fused ? S.part : nullptr, fused ? fused_sync_pairs(F) : 0,
-                           prepare_select ? &ws.sel : nullptr, G.Hkv * G.g, st) != hipSuccess)   // scratch is laid out per query head
+                           prepare_select ? &ws.sel : nullptr, G.Hkv * G.g, st, ws.status_flag) != hipSuccess)   // scratch is laid out per query head
             return SNAPKV_ERR_HIP;
         stage_done(st, kStagePrepare);
     }
@@ -216,6 +246,7 @@ struct CompressOptions {
     const RowLayout* v_layout = nullptr;
     bool per_query_head = false;        // one selection and one cache per query head
     PageMap pm;                         // paged K and V
+    int32_t* status = nullptr;          // device word of the caller's that receives the call's verdict
 };
 
 int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v, int64_t L, int Hq,
@@ -250,9 +281,13 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     // heads that select and keep rows: the KV heads, or every query head for itself
     const int Hout = per_query_head ? Hq : Hkv;
     const int head_div = per_query_head ? Hq / Hkv : 1;
+    if (opt.status && (reinterpret_cast<uintptr_t>(opt.status) & 3u) != 0) return SNAPKV_ERR_MISALIGNED;
     if (L <= C) {   // Listing 1, first branch: the prompt already fits
         if (launch_iota(Hout, L, C, out_idx, st) != hipSuccess) return SNAPKV_ERR_HIP;
-        if (launch_gather(k, v, out_idx, Hout, L, L, C, row_bytes, out_k, out_v, kl, vl, CleanJob{}, st, head_div, pm) != hipSuccess)
+        CleanJob verdict;
+        verdict.status = opt.status;
+        verdict.rows = (int32_t)L;
+        if (launch_gather(k, v, out_idx, Hout, L, L, C, row_bytes, out_k, out_v, kl, vl, verdict, st, head_div, pm) != hipSuccess)
             return SNAPKV_ERR_HIP;
         return L;
     }
@@ -266,9 +301,17 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     const size_t need = workspace_layout(G, nullptr, nullptr);
     void* base = workspace;
     CleanState was_clean;
+    unsigned* sticky = nullptr;
     if (own_scratch) {
-        rc = internal_scratch(need, &base, &was_clean);
+        if (capturing(st)) return SNAPKV_ERR_UNSUPPORTED;
+        rc = internal_scratch(need, &base, &was_clean, &sticky);
         if (rc != SNAPKV_OK) return rc;
+        // An earlier call on this scratch whose kernels have finished by now had a bounded wait give up: its
+        // results were invalid.  Said once, here, since that call had already returned when it happened.
+        if (__hip_atomic_load(sticky, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM) != 0u) {
+            __hip_atomic_store(sticky, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+            return SNAPKV_ERR_TIMEOUT;
+        }
     } else {
         if (!workspace || workspace_bytes < need) return SNAPKV_ERR_WORKSPACE;
         if ((reinterpret_cast<uintptr_t>(workspace) & 255u) != 0) return SNAPKV_ERR_MISALIGNED;
@@ -279,6 +322,10 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     const bool chunked = select_chunked_ok(G.n);
     hipError_t se;
     CleanJob clean;
+    clean.flag = ws.status_flag;
+    clean.status = opt.status;
+    clean.sticky = sticky;
+    clean.rows = (int32_t)C;
     DeviceScratch* mine = nullptr;      // the library's own buffer: its state is tracked between calls
     CleanState now;
     bool streaming = false;
@@ -375,6 +422,7 @@ int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, 
     G.k_rs = (int64_t)D * elem_bytes(dtype);
     G.k_hs = G.k_rs * L;
     void* base = nullptr;
+    if (capturing(static_cast<hipStream_t>(stream))) return SNAPKV_ERR_UNSUPPORTED;
     rc = internal_scratch(workspace_layout(G, nullptr, nullptr), &base);
     if (rc != SNAPKV_OK) return rc;
     Workspace ws;
@@ -398,6 +446,7 @@ int compress_batch(int dtype, int count, const void* const* q_win, const void* c
                    const int64_t* L, int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
                    void* const* out_k, void* const* out_v, int32_t* const* out_idx, hipStream_t st) {
     if (count < 2 || count > kMaxBatch || !g_allow_pool_select) return 1;
+    if (capturing(st)) return SNAPKV_ERR_UNSUPPORTED;
     if ((int64_t)Hkv * count > 65535) return 1;   // the joint gather has one grid row per head of the batch
     const int g = Hq / Hkv;
     const int row_bytes = D * elem_bytes(dtype);
@@ -529,6 +578,11 @@ int compress_batch(int dtype, int count, const void* const* q_win, const void* c
 }  // namespace
 
 namespace snapkv {
+unsigned wait_limit(unsigned dflt) {
+    const long long v = g_wait_limit.load();
+    return v < 0 ? dflt : (unsigned)v;
+}
+
 void stage_done(hipStream_t st, int stage) {
     if (!g_prof.active) return;
     if (stage == kStageBegin) {
@@ -590,6 +644,12 @@ int snapkv_profile_stop(double* stage_ms, int* calls) {
     return rc;
 }
 
+int snapkv_debug_set_wait_limit(long long polls) {
+    g_wait_limit.store(polls < 0 ? -1 : (polls > 0x7fffffffLL ? 0x7fffffffLL : polls));
+    if (polls == -2 && (!reset_sync_timeouts() || !reset_select_timeouts())) return SNAPKV_ERR_HIP;
+    return SNAPKV_OK;
+}
+
 int snapkv_set_scoring_scheme(int scheme) {
     if (scheme < 0 || scheme > 3) return SNAPKV_ERR_INVALID_ARG;
     g_allow_fused = (scheme & 1) == 0;
@@ -620,6 +680,7 @@ const char* snapkv_strerror(int code) {
         case SNAPKV_ERR_MISALIGNED: return "pointer not sufficiently aligned";
         case SNAPKV_ERR_WORKSPACE: return "workspace missing or too small";
         case SNAPKV_ERR_HIP: return "HIP call failed";
+        case SNAPKV_ERR_TIMEOUT: return "a bounded wait inside a kernel gave up";
         default: return code > 0 ? "ok" : "unknown error";
     }
 }
@@ -664,6 +725,19 @@ int64_t snapkv_compress_static(int dtype, const void* q_win, const void* k, cons
     opt.workspace = ptr;                   // the looked-up device address, never the array's name
     opt.workspace_bytes = SNAPKV_STATIC_SCRATCH_BYTES;
     opt.own_scratch = false;               // everything that must start at zero is cleared by the call's first kernel
+    return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx, stream, opt);
+}
+
+int64_t snapkv_compress_ws_status(int dtype, const void* q_win, const void* k, const void* v, int64_t L,
+                                  int Hq, int Hkv, int D, int W, int pool_kind, int p, int64_t C,
+                                  void* out_k, void* out_v, int32_t* out_idx, void* workspace,
+                                  size_t workspace_bytes, int32_t* status, void* stream) {
+    if (!status) return SNAPKV_ERR_INVALID_ARG;
+    CompressOptions opt;
+    opt.workspace = workspace;
+    opt.workspace_bytes = workspace_bytes;
+    opt.own_scratch = false;
+    opt.status = status;
     return compress_impl(dtype, q_win, k, v, L, Hq, Hkv, D, W, pool_kind, p, C, out_k, out_v, out_idx, stream, opt);
 }
 
@@ -942,6 +1016,11 @@ void snapkv_release(void) {
         g_scratch[d].ptr = nullptr;
         g_scratch[d].bytes = 0;
         g_scratch[d].clean = CleanState{};
+    }
+    for (int d = 0; d < kMaxDevices; ++d) {
+        if (!g_scratch[d].sticky) continue;
+        if (hipSetDevice(d) == hipSuccess) (void)hipHostFree(g_scratch[d].sticky);
+        g_scratch[d].sticky = nullptr;
     }
     for (int d = 0; d < kMaxDevices; ++d) {
         if (!g_decode_scratch[d].ptr) continue;

@@ -150,6 +150,11 @@ __device__ __forceinline__ void merge_pair(float& m, float& z, float pm, float p
 // Number of hand-off waits that gave up (never expected; read by snapkv_sync_timeouts()).
 __device__ unsigned g_sync_timeouts = 0;
 
+bool reset_sync_timeouts() {
+    const unsigned zero = 0;
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_sync_timeouts), &zero, sizeof zero) == hipSuccess;
+}
+
 unsigned read_sync_timeouts() {
     unsigned v = 0;
     if (hipMemcpyFromSymbol(&v, HIP_SYMBOL(g_sync_timeouts), sizeof v) != hipSuccess) return ~0u;
@@ -694,7 +699,10 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
     for (; it + 2 < nu; ++it) iteration(std::integral_constant<int, 3>{}, it);
     for (; it + 1 < nu; ++it) iteration(std::integral_constant<int, 1>{}, it);   // last but one unit
     for (; it < nu + 2; ++it) iteration(std::integral_constant<int, 0>{}, it);   // last unit, two drain steps
-    if (gave_up) atomicAdd(&g_sync_timeouts, 1u);
+    if (gave_up) {
+        atomicAdd(&g_sync_timeouts, 1u);
+        if (S.gave_up_flag) __hip_atomic_store(S.gave_up_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 template <typename T, int D, int RUW, int KT, int NW>
@@ -1093,7 +1101,7 @@ static bool fused_shape_nw(const ScoreGeom& G, int NW, int split, FusedGeom* F, 
     F->split = split;
     F->gs = gs;
     F->BH = 1;
-    F->spin_limit = kSpinLimit;
+    F->spin_limit = wait_limit(kSpinLimit);
     return true;
 }
 
@@ -1167,6 +1175,7 @@ size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, v
         char* b = static_cast<char*>(base);
         S->part = reinterpret_cast<float2*>(b);
         S->l1 = reinterpret_cast<float2*>(b + part);
+        S->gave_up_flag = nullptr;
     }
     return up(part + l1);
 }

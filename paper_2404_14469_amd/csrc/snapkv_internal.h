@@ -65,6 +65,7 @@ struct FusedGeom {
 struct FusedSync {
     float2* part;            // [units][Gg][RUW*16] per-slice (row max, row sum-exp), base-2 domain
     float2* l1;              // [units][RUW*16][NB] the same merged over blocks of 32 slices
+    unsigned* gave_up_flag;  // null, or a word of the call's scratch that is set when a bounded wait gives up
 };
 
 // Scratch of the chunked top-k selection (snapkv_topk.hip), per head h of H heads.
@@ -84,9 +85,12 @@ struct SelectScratch {
     unsigned* ps_range;    // [H][512][2]   per-workgroup (smallest, largest) score bit pattern
     unsigned* ps_part;     // [H][512][2]   per-workgroup (#above the threshold bin, #inside it)
     int64_t ps_zero_words;
+    unsigned* ps_flag;     // null, or a word of the call's scratch that is set when a bounded wait gives up
 };
 
 struct Workspace {
+    unsigned* status_flag;   // first word of the block: set by a kernel whose bounded wait gave up, read and cleared by
+                             // the call's last kernel
     float2* part;    // [Hkv][nchunks][R32][32] per-chunk (row max, row sum-exp) in base-2 domain
     float2* mz;      // [Hkv][R32][32]          (row max, 1 / row sum-exp); (0, 0) for padding rows
     float* vote;     // [Hkv][NV][n]  (two-pass path) or [Hkv][g][n] (single-read path)
@@ -125,6 +129,8 @@ hipError_t launch_score_fused_joint(int dtype, int D, int count, const void* con
 hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                               const FusedGeom& F, const FusedSync& S, float* vote, hipStream_t st);
 unsigned read_sync_timeouts();
+bool reset_sync_timeouts();     // (test hook) both synchronise the device
+bool reset_select_timeouts();
 hipError_t launch_pool(const ScoreGeom& G, const float* vote, int pool_kind, int p, float* score,
                        unsigned* minmax, hipStream_t st);
 size_t select_counter_bytes(int H);
@@ -132,7 +138,9 @@ size_t select_layout(int H, int64_t n, SelectScratch* S, void* base, bool own_co
                      void* counters = nullptr);
 bool select_chunked_ok(int64_t n);
 hipError_t launch_select_init(const SelectScratch& S, int H, hipStream_t st);
-hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, int H, hipStream_t st);
+// flag (may be null): the status word of the call's scratch, cleared too (default: S->ps_flag).
+hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, int H, hipStream_t st,
+                          unsigned* flag = nullptr);
 int64_t fused_sync_pairs(const FusedGeom& F);
 bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
 hipError_t launch_score_lse(int dtype, int D, const void* q, const void* k, const float* lse,
@@ -176,7 +184,19 @@ struct CleanJob {
     int64_t nones = 0;
     unsigned* zeros = nullptr;
     int64_t nzeros = 0;
+    // The call's verdict: if *flag is set (a bounded wait gave up in one of the call's kernels) the
+    // last kernel writes SNAPKV_ERR_TIMEOUT to *status (device memory of the caller's, may be null) and 1
+    // to *sticky (pinned host memory of the library's, may be null), otherwise `rows` to *status; then it
+    // clears *flag.  flag == nullptr: nothing of this.
+    unsigned* flag = nullptr;
+    int32_t* status = nullptr;
+    unsigned* sticky = nullptr;
+    int32_t rows = 0;
 };
+constexpr int32_t kStatusTimeout = -6;   // SNAPKV_ERR_TIMEOUT
+// Polls a bounded wait makes before it gives up: `dflt`, unless a test has set another bound
+// (snapkv_debug_set_wait_limit).
+unsigned wait_limit(unsigned dflt);
 // Byte strides of a [heads, rows, D] tensor whose rows are contiguous.  launch_gather writes H
 // output heads; output head h reads source head h / head_div.
 struct RowLayout {

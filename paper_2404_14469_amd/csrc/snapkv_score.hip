@@ -323,7 +323,8 @@ static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 // the single-read scoring kernel (all-ones when idle).  The selection's scratch and the scores are
 // sized for one selection per query head, which the per-query-head form of the step runs.
 size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base) {
-    char* b = static_cast<char*>(base);
+    constexpr size_t kHeader = 256;      // the status word (see Workspace::status_flag)
+    char* b = static_cast<char*>(base) + (base ? kHeader : 0);
     const int Hsel = G.Hkv * G.g;
     const size_t counters = select_counter_bytes(Hsel);
     const size_t fused = fused_sync_bytes(G);
@@ -335,6 +336,7 @@ size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base) {
     const size_t lse = align_up(sizeof(float) * (size_t)G.Hkv * G.g * G.W);
     const size_t off = counters + fused;
     if (ws) {
+        ws->status_flag = reinterpret_cast<unsigned*>(base);
         ws->fused = b + counters;
         ws->part = reinterpret_cast<float2*>(b + off);
         ws->mz = reinterpret_cast<float2*>(b + off + part);
@@ -346,7 +348,8 @@ size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base) {
     const size_t sel = select_layout(Hsel, G.n, ws ? &ws->sel : nullptr,
                                      ws ? b + off + part + mz + vote + score + stat + lse : nullptr, false,
                                      ws ? b : nullptr);
-    return off + part + mz + vote + score + stat + lse + sel;
+    if (ws) ws->sel.ps_flag = ws->status_flag;
+    return kHeader + off + part + mz + vote + score + stat + lse + sel;
 }
 
 template <typename T, int D>

@@ -444,6 +444,12 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
     const int64_t gsz = (int64_t)gridDim.y * gridDim.x * 256;
     for (int64_t j = gid; j < clean.nones; j += gsz) clean.ones[j] = ~0ull;
     for (int64_t j = gid; j < clean.nzeros; j += gsz) clean.zeros[j] = 0u;
+    if (gid == 0 && (clean.flag || clean.status)) {   // the call's verdict (see CleanJob)
+        const unsigned gave_up = clean.flag ? *clean.flag : 0u;
+        if (clean.status) *clean.status = gave_up ? kStatusTimeout : clean.rows;
+        if (gave_up && clean.sticky) __hip_atomic_store(clean.sticky, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (clean.flag) *clean.flag = 0u;
+    }
 }
 
 // Per-head valid prefix lengths of a batch: head h of the batch belongs to prompt h / Hkv.

@@ -505,6 +505,11 @@ __global__ __launch_bounds__(256) void sel_emit(const float* __restrict__ score,
 __device__ unsigned g_select_timeouts = 0;
 
 
+bool reset_select_timeouts() {
+    const unsigned zero = 0;
+    return hipMemcpyToSymbol(HIP_SYMBOL(g_select_timeouts), &zero, sizeof zero) == hipSuccess;
+}
+
 unsigned read_select_timeouts() {
     unsigned v = 0;
     if (hipMemcpyFromSymbol(&v, HIP_SYMBOL(g_select_timeouts), sizeof v) != hipSuccess) return ~0u;
@@ -1071,7 +1076,10 @@ __global__ __launch_bounds__(kPsThreads) void pool_select(
             qb += eq;
         }
     }
-    if (tid == 0 && sh_gave_up) atomicAdd(&g_select_timeouts, 1u);
+    if (tid == 0 && sh_gave_up) {
+        atomicAdd(&g_select_timeouts, 1u);
+        if (S.ps_flag) __hip_atomic_store(S.ps_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 static size_t up256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -1111,6 +1119,7 @@ size_t select_layout(int H, int64_t n, SelectScratch* S, void* base, bool own_co
         S->ps_arrive = reinterpret_cast<unsigned*>(own_counters ? q + 2 * ps_range : static_cast<char*>(counters));
         S->ps_hist = S->ps_arrive + (size_t)H * kPsStages;
         S->ps_zero_words = (int64_t)H * (kPsStages + kPsLevels * kPsBins);
+        S->ps_flag = nullptr;
     }
     return minmax + hist + count + info + cgt + coff + cand + 2 * ps_range + (own_counters ? ps_zero : 0);
 }
@@ -1121,8 +1130,9 @@ bool select_chunked_ok(int64_t n) { return (n + kSelChunk - 1) / kSelChunk <= kS
 // kernel (all-ones = "not published yet") and the selection's histogram and list counters (zero).
 __global__ __launch_bounds__(256) void prepare_scratch(unsigned long long* pairs, int64_t npairs,
                                                       unsigned* hist, int nhist, unsigned* cand_count,
-                                                      int H, unsigned* ps_zero, int64_t ps_words) {
+                                                      int H, unsigned* ps_zero, int64_t ps_words, unsigned* flag) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i == 0 && flag) *flag = 0u;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t j = i; j < npairs; j += stride) pairs[j] = ~0ull;
     for (int64_t j = i; j < nhist; j += stride) hist[j] = 0u;
@@ -1130,18 +1140,20 @@ __global__ __launch_bounds__(256) void prepare_scratch(unsigned long long* pairs
     if (i < H) cand_count[i] = 0u;
 }
 
-hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, int H, hipStream_t st) {
+hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, int H, hipStream_t st, unsigned* flag) {
     const int nhist = S ? H * kSelBins1 : 0;
     int64_t work = npairs > nhist ? npairs : nhist;
     if (S && work < S->ps_zero_words) work = S->ps_zero_words;
     if (work < H) work = H;
+    if (!flag && S) flag = S->ps_flag;
+    if (work <= 0 && flag) work = 1;
     if (work <= 0) return hipSuccess;
     int64_t blocks = (work + 255) / 256;
     if (blocks > 2048) blocks = 2048;
     hipLaunchKernelGGL(prepare_scratch, dim3((unsigned)blocks), dim3(256), 0, st,
                        static_cast<unsigned long long*>(pairs), npairs, S ? S->hist : nullptr, nhist,
                        S ? S->cand_count : nullptr, S ? H : 0, S ? S->ps_arrive : nullptr,
-                       S ? S->ps_zero_words : 0);
+                       S ? S->ps_zero_words : 0, flag);
     return hipGetLastError();
 }
 
@@ -1190,7 +1202,7 @@ static hipError_t pool_select_instance(const PoolSelCall* call, int* occ) {
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(call->G->Hkv * call->Wh)), dim3(kPsThreads), kLds, call->st,
                        call->vote, *call->G, call->p, call->kcount, call->out_stride,
-                       call->W_tail, call->out_idx, *call->S, call->Wh, call->chunk, kPsSpinLimit, call->nvalid);
+                       call->W_tail, call->out_idx, *call->S, call->Wh, call->chunk, wait_limit(kPsSpinLimit), call->nvalid);
     return hipGetLastError();
 }
 

@@ -78,3 +78,79 @@ def test_decode_replays_in_a_graph(snapkv):
         snapkv.snapkv_decode_attention(c["q"], c["k_cache"], c["v_cache"], w.S, eo, el)
         torch.cuda.synchronize()
         assert torch.equal(out, eo) and torch.equal(lse, el), f"replay {rep}"
+
+
+def test_static_scratch_entry_replays_in_a_graph(snapkv):
+    """The entry point for callers that cannot allocate is the other form to capture."""
+    w = Workload("graph_static", Hq=8, Hkv=4, D=128, L=5000, W=32, pool_kind=1, p=5, C=384, dtype="bf16",
+                 clusters=(6, 6), radius=6, seed=72)
+    cases = [workloads.generate(w, layer=l, device="cuda") for l in range(2)]
+    q = cases[0]["q_win"].clone(); k = cases[0]["k"].clone(); v = cases[0]["v"].clone()
+    out_k = torch.zeros((w.Hkv, w.C, w.D), dtype=k.dtype, device="cuda")
+    out_v = torch.zeros_like(out_k)
+    out_idx = torch.zeros((w.Hkv, w.C), dtype=torch.int32, device="cuda")
+    snapkv.snapkv_compress_static(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx)   # launch plans are cached
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        snapkv.snapkv_compress_static(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx)
+    for rep in range(4):
+        c = cases[rep % 2]
+        q.copy_(c["q_win"]); k.copy_(c["k"]); v.copy_(c["v"])
+        out_idx.fill_(-1); out_k.zero_(); out_v.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        ek = torch.zeros_like(out_k); ev = torch.zeros_like(out_v); ei = torch.zeros_like(out_idx)
+        snapkv.snapkv_compress(c["q_win"], c["k"], c["v"], w.pool_kind, w.p, w.C, ek, ev, ei)
+        torch.cuda.synchronize()
+        assert np.array_equal(out_idx.cpu().numpy(), ei.cpu().numpy()), f"replay {rep}"
+        assert torch.equal(out_k, ek) and torch.equal(out_v, ev), f"replay {rep}"
+    assert snapkv.snapkv_sync_timeouts() == 0
+
+
+def test_own_scratch_entries_refuse_a_capturing_stream(snapkv):
+    w = Workload("graph_refused", Hq=4, Hkv=4, D=64, L=2000, W=32, pool_kind=0, p=7, C=256, dtype="bf16",
+                 clusters=(3, 3), radius=4, seed=73)
+    c = workloads.generate(w, device="cuda")
+    out_k = torch.zeros((w.Hkv, w.C, w.D), dtype=c["k"].dtype, device="cuda")
+    out_v = torch.zeros_like(out_k)
+    out_idx = torch.full((w.Hkv, w.C), -5, dtype=torch.int32, device="cuda")
+    marker = torch.zeros(8, device="cuda")
+    graph = torch.cuda.CUDAGraph()
+    codes = []
+    with torch.cuda.graph(graph):
+        marker.add_(1.0)                         # something to record
+        try:
+            snapkv.snapkv_compress(c["q_win"], c["k"], c["v"], w.pool_kind, w.p, w.C, out_k, out_v, out_idx)
+        except snapkv.SnapKVError as e:
+            codes.append(e.code)
+    graph.replay()
+    torch.cuda.synchronize()
+    assert codes == [-2]
+    assert int(out_idx.min()) == -5 and int(out_idx.max()) == -5     # nothing of the call was recorded
+
+
+def test_a_call_on_another_stream_prepares_the_scratch_again(snapkv):
+    """The record of the state a call leaves the library's scratch in holds for the stream it was left on: a
+    call on another stream is not ordered behind the kernel that left it, so the preparing launch runs."""
+    w = Workload("two_streams", Hq=8, Hkv=4, D=128, L=6000, W=32, pool_kind=0, p=7, C=512, dtype="bf16",
+                 clusters=(6, 6), radius=6, seed=74)
+    c = workloads.generate(w, device="cuda")
+    outs = [(torch.zeros((w.Hkv, w.C, w.D), dtype=c["k"].dtype, device="cuda"),
+             torch.zeros((w.Hkv, w.C, w.D), dtype=c["k"].dtype, device="cuda"),
+             torch.zeros((w.Hkv, w.C), dtype=torch.int32, device="cuda")) for _ in range(3)]
+    a, b = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+
+    def call(i, stream):
+        snapkv.snapkv_profile_start(1)
+        snapkv.snapkv_compress(c["q_win"], c["k"], c["v"], w.pool_kind, w.p, w.C, *outs[i], stream=stream)
+        ms, _ = snapkv.snapkv_profile_stop()      # waits for the device: the calls below never overlap
+        return ms.get("prepare_scratch", 0.0) > 0.0
+
+    call(0, a)
+    assert not call(1, a)        # same stream, same shape: the last kernel left the scratch ready
+    assert call(2, b)            # another stream: prepared again
+    torch.cuda.synchronize()
+    for i in (1, 2):
+        assert torch.equal(outs[i][2], outs[0][2]) and torch.equal(outs[i][0], outs[0][0]) and torch.equal(outs[i][1], outs[0][1])
