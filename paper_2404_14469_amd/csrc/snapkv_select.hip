@@ -100,8 +100,7 @@ __global__ __launch_bounds__(256) void pool_group(const float* __restrict__ vote
     }
 }
 
-// Variant for rows whose length is a multiple of four (so that every row is 16-byte aligned) and
-// one vote row per query head: a thread owns four consecutive positions and reads them and their
+// Variant for rows whose length is a multiple of four (so that every row is 16-byte aligned): a thread owns four consecutive positions and reads them and their
 // taps as float4, an order of magnitude fewer instructions per position.  The first and last
 // tiles of a row take the element-wise path.
 template <int P>
@@ -119,7 +118,9 @@ __global__ __launch_bounds__(256) void pool_group4(const float* __restrict__ vot
     const float pad = pool_kind == 0 ? -INFINITY : 0.f;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
     for (int h = 0; h < G.g; ++h) {
-        const float* vb = vote + ((int64_t)hkv * G.NV + h) * G.n;
+        // (a query head whose window was scored in blocks has one vote row per block: they are added,
+        // in order, before pooling)
+        const float* vb = vote + ((int64_t)hkv * G.NV + (int64_t)h * G.VB) * G.n;
         float v[NV4 * 4];
         if (interior) {
 #pragma unroll
@@ -130,11 +131,25 @@ __global__ __launch_bounds__(256) void pool_group4(const float* __restrict__ vot
                 v[4 * x + 2] = q.z;
                 v[4 * x + 3] = q.w;
             }
+            for (int b = 1; b < G.VB; ++b) {
+#pragma unroll
+                for (int x = 0; x < NV4; ++x) {
+                    const float4 q = *reinterpret_cast<const float4*>(vb + (int64_t)b * G.n + j0 + 4 * (x - RQ));
+                    v[4 * x] += q.x;
+                    v[4 * x + 1] += q.y;
+                    v[4 * x + 2] += q.z;
+                    v[4 * x + 3] += q.w;
+                }
+            }
         } else {
 #pragma unroll
             for (int x = 0; x < NV4 * 4; ++x) {
                 const int64_t j = j0 + x - 4 * RQ;
-                v[x] = (j >= 0 && j < G.n) ? vb[j] : pad;
+                v[x] = pad;
+                if (j >= 0 && j < G.n) {
+                    v[x] = vb[j];
+                    for (int b = 1; b < G.VB; ++b) v[x] += vb[(int64_t)b * G.n + j];
+                }
             }
         }
 #pragma unroll
@@ -193,7 +208,7 @@ hipError_t launch_pool(const ScoreGeom& G, const float* vote, int pool_kind, int
     if (G.n <= 0) return hipSuccess;
     const unsigned tiles = (unsigned)((G.n + kPoolTile - 1) / kPoolTile);
     const dim3 grid(tiles, G.Hkv);
-    if (G.n % 4 == 0 && G.VB == 1 && (reinterpret_cast<uintptr_t>(vote) & 15u) == 0 &&
+    if (G.n % 4 == 0 && (reinterpret_cast<uintptr_t>(vote) & 15u) == 0 &&
         (reinterpret_cast<uintptr_t>(score) & 15u) == 0) {
         switch (p) {
             case 1: hipLaunchKernelGGL(pool_group4<1>, grid, dim3(256), 0, st, vote, score, G, pool_kind, minmax); return hipGetLastError();
