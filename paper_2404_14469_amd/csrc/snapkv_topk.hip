@@ -534,10 +534,20 @@ __device__ __forceinline__ unsigned coherent_store64(unsigned long long* p, unsi
 __device__ __forceinline__ unsigned coherent_add(unsigned* p, unsigned v) {
     return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-// Every hand-over of this thread has been performed once this returns.
+// Operand of s_waitcnt that waits for ALL of the wave's outstanding vector-memory operations and for
+// nothing else.  gfx9-family layout of the 16-bit operand (gfx950 included): vmcnt is split over bits
+// [3:0] (low four bits) and [15:14] (high two), expcnt is bits [6:4], lgkmcnt bits [11:8]; a counter field
+// at its maximum means "do not wait for this counter".  vmcnt = 0 (all six bits clear), expcnt = 7,
+// lgkmcnt = 15:
+constexpr int kWaitVmcnt0 = (0 << 0) | (7 << 4) | (15 << 8) | (0 << 14);
+static_assert(kWaitVmcnt0 == 0x0F70, "s_waitcnt vmcnt(0) on the gfx9 family");
+
+// Every hand-over of this thread has been performed once this returns: a hand-over is an atomic WITH a
+// return value, and the value can only come back from the place where the device's dies agree on the
+// word's contents (the atomic has been carried out there by then).
 __device__ __forceinline__ void hand_over_done(unsigned folded) {
     asm volatile("" ::"v"(folded));            // the returned values are needed here: the wave waits for them
-    __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0): and for anything else it has outstanding
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);   // and for anything else it has outstanding
 }
 
 // Rendezvous of the `expect` workgroups that share `ctr` (zero before the first arrival).  What a
@@ -549,7 +559,7 @@ __device__ __forceinline__ void hand_over_done(unsigned folded) {
 // workgroup in.
 __device__ __forceinline__ void group_rendezvous(unsigned* ctr, unsigned expect, unsigned limit,
                                                  unsigned* gave_up) {
-    __builtin_amdgcn_s_waitcnt(0x0F70);        // vmcnt(0)
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (threadIdx.x == 0 && !*gave_up) {
