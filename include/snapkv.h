@@ -20,8 +20,12 @@
  *
  * All pointers named "device" are GPU global memory owned by the caller, row-major and
  * contiguous, 16-byte aligned.  Inputs are read-only and must not alias outputs.  Calls only
- * enqueue work on `stream` (a hipStream_t passed as void*, NULL = the default stream) and
- * never synchronise; outputs are valid once the stream reaches the end of the enqueued work.
+ * enqueue work on `stream` (a hipStream_t passed as void*, NULL = the default stream); outputs are
+ * valid once the stream reaches the end of the enqueued work.  They do not synchronise, with one
+ * exception: an entry that uses a scratch buffer of the library's and finds it too small frees it and
+ * allocates a larger one, and hipFree waits for the device (the first calls of a process, or the first
+ * call of a larger shape; snapkv_compress_ws, snapkv_compress_ws_status and snapkv_compress_static never
+ * do).  snapkv_sync_timeouts, snapkv_profile_stop, snapkv_release and the test hook say so themselves.
  * Every entry point validates its arguments on the host before touching the GPU and returns
  * a negative SNAPKV_ERR_* code on failure; nothing has been enqueued in that case unless the
  * code is SNAPKV_ERR_HIP.
