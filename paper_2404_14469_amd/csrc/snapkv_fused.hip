@@ -234,6 +234,19 @@ __device__ __forceinline__ void load_frag16p(Frag16<T, D>& f, const char* p) {
 
 // The kernel's body; `bid` is the workgroup's index inside its own launch plan (the block index,
 // or the block index less the first block of the prompt when several prompts share a launch).
+constexpr int kFusedSlots = 8;          // RUW * KT: accumulator tiles a wave keeps per unit (8 waves)
+
+// The instance with one row unit per workgroup (a window of at most 16 rows, one query head per
+// unit) holds eight K tile buffers per wave, twice what the others hold, and has no registers left
+// for the exponentials of the two previous units: those wait for their vote in LDS instead (two
+// generations of RUW * KT accumulator tiles per thread, behind the Q blocks).
+template <int RUW> struct fused_parks { static constexpr bool value = RUW == 1; };
+
+// Bytes of dynamic LDS of score_fused: the Q blocks of three units, then the parked exponentials.
+template <typename T, int D, int RUW, int NW> constexpr int fused_lds_bytes() {
+    return 3 * RUW * (D * esize<T>::value / 64) * 64 * 16 + (fused_parks<RUW>::value ? 2 * kFusedSlots * NW * 64 * 16 : 0);
+}
+
 template <typename T, int D, int RUW, int KT, int NW>
 __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, const void* __restrict__ kv,
                                                  float* __restrict__ vote, const FusedSync& S,
@@ -250,6 +263,9 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
     constexpr int QCH = RUW * NP;        // 1 KB chunks of a unit's Q block, in the order the MFMAs read them
     constexpr int QPW = (QCH + NW - 1) / NW;   // chunks a wave fetches per unit
     extern __shared__ uint4 qbuf[];      // [3][QCH][64]: Q blocks of three consecutive units
+    constexpr bool PARK = fused_parks<RUW>::value;
+    // [2][NSLOT][NT] exponentials of the units one and two back, each thread's own (PARK only)
+    f32x4* const park = reinterpret_cast<f32x4*>(qbuf + 3 * QCH * 64);
     // No barrier inside the loop.  Why the buffers may be reused when they are: a wave writes
     // them only after step E of an iteration, which has waited for level-1 words of the unit two
     // back; those exist only once every workgroup, this one included, has published that unit's
@@ -338,12 +354,15 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
         if (w + x * NW < QCH) qbuf[(w + x * NW) * 64 + lane] = qland[x];
     if (tid < 3 * NW) sm_flag[tid / NW][tid % NW] = tid < NW ? 1 : 0;   // Q of unit 0 is in place
     __syncthreads();
-    // exponentials of the two previous units stay in registers until their votes are taken
-    f32x4 e1[RUW][KT], e2[RUW][KT];
+    // exponentials of the two previous units stay in registers (or, PARK, in LDS) until their votes are taken
+    f32x4 e1[PARK ? 1 : RUW][PARK ? 1 : KT], e2[PARK ? 1 : RUW][PARK ? 1 : KT];
 #pragma unroll
     for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
-        for (int t = 0; t < KT; ++t) e[ru][t] = e1[ru][t] = e2[ru][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int t = 0; t < KT; ++t) {
+            e[ru][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if constexpr (!PARK) e1[ru][t] = e2[ru][t] = e[ru][t];
+        }
 
     // logits of tiles [T0, T1) of the unit whose Q block sits in half `par` of qbuf
     auto mfma_tiles = [&](auto T0, auto T1, const int par) {
@@ -629,7 +648,9 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
             for (int ru = 0; ru < RUW; ++ru) {
 #pragma unroll
                 for (int t = 0; t < KT; ++t) {
-                    const f32x4 ev = e2[ru][t];
+                    f32x4 ev;
+                    if constexpr (PARK) ev = park[((it & 1) * NSLOT + ru * KT + t) * NT + tid];   // left there at it - 2
+                    else ev = e2[ru][t];
                     v[t] = fmaf(ev[0], f[ru][0], v[t]);
                     v[t] = fmaf(ev[1], f[ru][1], v[t]);
                     v[t] = fmaf(ev[2], f[ru][2], v[t]);
@@ -674,13 +695,18 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
                 }
             }
         }
-        // ---- G. age the kept exponentials by one unit
+        // ---- G. age the kept exponentials by one unit (PARK: this unit's take the place of the ones just voted on;
+        // a thread reads back only what it wrote itself, in program order)
 #pragma unroll
         for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
             for (int t = 0; t < KT; ++t) {
-                e2[ru][t] = e1[ru][t];
-                e1[ru][t] = e[ru][t];
+                if constexpr (PARK) {
+                    if (has_p1) park[((it & 1) * NSLOT + ru * KT + t) * NT + tid] = e[ru][t];
+                } else {
+                    e2[ru][t] = e1[ru][t];
+                    e1[ru][t] = e[ru][t];
+                }
             }
         // ---- H. the next unit's lower tiles meet its Q (in LDS since the barrier) and their
         // buffers are requested again for the unit after it
@@ -1054,7 +1080,6 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
 // ---------------------------------------------------------------------------------------------
 // Host side
 // ---------------------------------------------------------------------------------------------
-constexpr int kFusedSlots = 8;          // RUW * KT: accumulator tiles a wave keeps per unit (8 waves)
 constexpr unsigned kSpinLimit = 1u << 15;   // polls before a hand-off wait gives up (tens of ms)
 
 static int g_cu_count[64] = {0};
@@ -1201,7 +1226,7 @@ template <typename T, int D, int RUW, int NW>
 static hipError_t fused_instance(const FusedCall* call, int* occ) {
     constexpr int KT = kFusedSlots / RUW;
     auto kern = score_fused<T, D, RUW, KT, NW>;
-    constexpr int kQueueBytes = 3 * RUW * (D * esize<T>::value / 64) * 64 * 16;   // Q blocks of three units
+    constexpr int kQueueBytes = fused_lds_bytes<T, D, RUW, NW>();
     static int cached_occ = -1;
     if (cached_occ < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
@@ -1297,7 +1322,7 @@ template <typename T, int D, int RUW, int NW>
 static hipError_t joint_instance(const FusedJoint* J, int grid, hipStream_t st, int* occ) {
     constexpr int KT = kFusedSlots / RUW;
     auto kern = score_fused_joint<T, D, RUW, KT, NW>;
-    constexpr int kQueueBytes = 3 * RUW * (D * esize<T>::value / 64) * 64 * 16;
+    constexpr int kQueueBytes = fused_lds_bytes<T, D, RUW, NW>();
     static int cached_occ = -1;
     if (cached_occ < 0) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
