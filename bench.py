@@ -430,6 +430,9 @@ def main() -> int:
     ap.add_argument("--pool-width", type=int, default=0, metavar="P", help="override the workload's pooling kernel size")
     ap.add_argument("--length", type=int, default=0, metavar="L",
                     help="override the workload's prompt length (e.g. the grouped-query configuration at 131072 tokens)")
+    ap.add_argument("--capacity", type=int, default=0, metavar="C",
+                    help="override the workload's cache capacity (e.g. --length 380000 --window 16 --pool-width 5 --capacity "
+                         "1024: the 380K-token setting of Sec. 5.1.1)")
     ap.add_argument("--explicit-workspace", action="store_true",
                     help="time snapkv_compress_ws with a caller-provided workspace instead of snapkv_compress")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
@@ -468,8 +471,8 @@ def main() -> int:
     if args.workload in workloads.DECODE_CONFIGS:
         return bench_decode(args, snapkv, workloads, workloads.DECODE_CONFIGS[args.workload], dev)
     w = workloads.CONFIGS[args.workload]
-    if args.window or args.pool_width or args.length:
-        w = w.with_(W=args.window or w.W, p=args.pool_width or w.p, L=args.length or w.L)
+    if args.window or args.pool_width or args.length or args.capacity:
+        w = w.with_(W=args.window or w.W, p=args.pool_width or w.p, L=args.length or w.L, C=args.capacity or w.C)
     plain = args.entry == "compress" and args.layout == "head_major" and not args.explicit_workspace
     mode = args.mode
     if mode == "auto":

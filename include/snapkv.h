@@ -366,9 +366,11 @@ const char* snapkv_stage_name(int stage);
 
 /*
  * Kernel scheme, a bit set (default 0).  Bit 0 clear: prompts whose window logits fit the chip's
- * register files are scored by the single-read kernel (K is streamed once), longer ones in two
- * streaming passes (K is streamed twice; no workgroup waits for another); bit 0 set: always two
- * passes.  Bit 1 clear:
+ * register files are scored by the single-read kernel (K is streamed once); of a longer prompt that
+ * kernel takes the keys that fit and two streaming passes the rest (those keys are streamed twice; the
+ * streaming passes hand nothing between workgroups); bit 0 set: always two streaming passes over
+ * all keys.  Bit 2 set (test hook): plans of the single-read kernel count 16 workgroups as resident, so
+ * that prompts of a few thousand tokens already take the path of the long ones.  Bit 1 clear:
  * pooling and top-k selection run as one cooperative launch where a head's scores fit the
  * resident workgroups, otherwise as separate kernels; bit 1 set: always the separate kernels.
  * All schemes give the scores of Eq. 1 to within rounding, and the selection of Eq. 2 exactly

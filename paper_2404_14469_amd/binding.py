@@ -163,7 +163,8 @@ def snapkv_release() -> None:
 
 
 def snapkv_set_scoring_scheme(scheme: int) -> None:
-    """Bit 0: always the two-pass scoring kernels; bit 1: always separate pooling and selection kernels."""
+    """Bit 0: always the two-pass scoring kernels; bit 1: always separate pooling and selection kernels;
+    bit 2 (test hook): the single-read kernel plans with 16 resident workgroups."""
     _check(load().snapkv_set_scoring_scheme(int(scheme)))
 
 

@@ -173,10 +173,28 @@ int static_scratch(void** out) {
 
 // Steps 1-3.  With score == nullptr the pooling kernel is left out (the caller pools and selects
 // in one launch) and *Gv tells how the votes are laid out.
+// Which kernels score a prompt: the single-read kernel (its hand-off words are in use; *F is its plan), the
+// single-read kernel on the front part of a prompt too long for it and streaming passes on the rest (the
+// same, *F = LP->Ff), two streaming passes (the hand-off words stay untouched; *F is their plan), or the
+// 32x32 two-pass kernels.
+enum { kPathOld = 0, kPathFused = 1, kPathStream = 2, kPathLong = 3 };
+int scoring_path(int dtype, int D, const ScoreGeom& G, bool lse_given, bool allow_blocks, bool allow_long,
+                 FusedGeom* F, LongPlan* LP) {
+    if (!lse_given && g_allow_fused) {
+        if (fused_plan(dtype, D, G, F, allow_blocks)) return kPathFused;
+        if (allow_long && long_plan(dtype, D, G, LP)) {
+            *F = LP->Ff;
+            return kPathLong;
+        }
+    }
+    return lse_plan(dtype, D, G, F) ? kPathStream : kPathOld;
+}
+
 int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGeom& G,
                const Workspace& ws, int pool_kind, int p, float* score, unsigned* minmax,
                bool prepare_select, ScoreGeom* Gv, hipStream_t st, bool already_prepared = false,
-               CleanJob* clean = nullptr, const float* lse = nullptr, bool allow_blocks = false) {
+               CleanJob* clean = nullptr, const float* lse = nullptr, bool allow_blocks = false,
+               bool allow_long = false) {
     FusedGeom F;
     ScoreGeom Gp = G;
     if (lse) {   // the rows' normalisers are given: one streaming pass, nothing handed between workgroups
@@ -196,27 +214,42 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
         stage_done(st, kStagePool);
         return SNAPKV_OK;
     }
-    const bool fused = g_allow_fused && fused_plan(dtype, D, G, &F, allow_blocks);
+    LongPlan LP;
+    const int path = scoring_path(dtype, D, G, false, allow_blocks, allow_long, &F, &LP);
+    const bool fused = path == kPathFused, split_read = path == kPathLong;
     FusedSync S;
-    if (fused) {
-        fused_sync_layout(G, F, &S, ws.fused);
-        S.gave_up_flag = ws.status_flag;
-    }
+    if (fused) fused_sync_layout(G, F, &S, ws.fused);
+    if (split_read) fused_sync_layout(LP.Gf, F, &S, ws.fused);   // F is the front part's plan
+    const bool handoff = fused || split_read;
+    if (handoff) S.gave_up_flag = ws.status_flag;
     if (!already_prepared) {
-        if (launch_prepare(fused ? S.part : nullptr, fused ? fused_sync_pairs(F) : 0,
+        if (launch_prepare(handoff ? S.part : nullptr, handoff ? fused_sync_pairs(F) : 0,
                            prepare_select ? &ws.sel : nullptr, G.Hkv * G.g, st, ws.status_flag) != hipSuccess)   // scratch is laid out per query head
             return SNAPKV_ERR_HIP;
         stage_done(st, kStagePrepare);
     }
-    if (clean && fused) {
+    if (clean && handoff) {
         clean->ones = reinterpret_cast<unsigned long long*>(S.part);
         clean->nones = fused_sync_pairs(F);
     }
-    if (fused) {   // K is read once; otherwise two passes over K
+    if (fused) {   // K is read once; otherwise two passes over K, or over the part of it the chip cannot hold
         if (launch_score_fused(dtype, D, q_win, k, G, F, S, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
         stage_done(st, kStageFused);
         Gp.NV = G.g * F.BH;   // one vote row per query head, or per 32-row block of its window
         Gp.VB = F.BH;
+    } else if (split_read) {
+        const char* k_rest = static_cast<const char*>(k) + LP.front * G.k_rs;
+        if (launch_row_lse(dtype, D, q_win, k_rest, LP.Gr, LP.Fr, ws.stat_part, nullptr, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        if (launch_publish_rest(ws.stat_part, S, LP, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        stage_done(st, kStageReduce);
+        S.lse_out = ws.lse;
+        if (launch_score_fused(dtype, D, q_win, k, LP.Gf, LP.Ff, S, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        stage_done(st, kStageFused);
+        if (launch_score_lse(dtype, D, q_win, k_rest, ws.lse, LP.Gr, LP.Fr, ws.vote + LP.front, st) != hipSuccess)
+            return SNAPKV_ERR_HIP;
+        stage_done(st, kStagePass2);
+        Gp.NV = G.g;
+        Gp.VB = 1;
     } else if (lse_plan(dtype, D, G, &F)) {
         // two streaming passes over K with nothing handed between workgroups: the rows'
         // log-sum-exp first, then the probabilities from it
@@ -346,12 +379,11 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     if (g_allow_pool_select && pool_select_ok(Gsel, pool_kind, p, C - W)) {   // pooling and selection in one launch
         bool prepared = false;
         FusedGeom Fp;
-        // which scoring path run_scores will take: 1 single-read (uses the hand-off words), 2 streaming
-        // passes (does not touch them), 0 the 32x32 two-pass kernels (state not tracked)
-        const int path = lse ? (lse_plan(dtype, D, G, &Fp) ? 2 : 0)
-                             : (g_allow_fused && fused_plan(dtype, D, G, &Fp, blocks_ok)) ? 1 : (lse_plan(dtype, D, G, &Fp) ? 2 : 0);
-        streaming = path == 2;
-        if (own_scratch && path != 0) {
+        // which scoring path run_scores will take (the state of the 32x32 two-pass kernels is not tracked)
+        LongPlan LPp;
+        const int path = scoring_path(dtype, D, G, lse != nullptr, blocks_ok, true, &Fp, &LPp);
+        streaming = path == kPathStream;
+        if (own_scratch && path != kPathOld) {
             int dev = 0;
             if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
                 // the streaming path does not touch the hand-off words
@@ -370,7 +402,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
         }
         ScoreGeom Gv = G;
         rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, true, &Gv, st, prepared,
-                        mine ? &clean : nullptr, lse, blocks_ok);
+                        mine ? &clean : nullptr, lse, blocks_ok, true);
         if (rc != SNAPKV_OK) return rc;
         if (per_query_head) Gv = Gsel;
         se = launch_pool_select(Gv, ws.vote, pool_kind, p, C - W, C, W, out_idx, ws.sel, st);
@@ -381,7 +413,8 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     } else {
         if (per_query_head) {   // votes first, then pooled per query head
             ScoreGeom Gv = G;
-            rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, chunked, &Gv, st, false, nullptr, lse);
+            rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, chunked, &Gv, st, false, nullptr, lse,
+                            false, true);
             if (rc != SNAPKV_OK) return rc;
             if (Gv.VB != 1 || Gv.NV != G.g) return SNAPKV_ERR_UNSUPPORTED;
             if (launch_pool(Gsel, ws.vote, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr, st) != hipSuccess)
@@ -389,7 +422,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
             stage_done(st, kStagePool);
         } else {
             rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr,
-                            chunked, nullptr, st, false, nullptr, lse, blocks_ok);
+                            chunked, nullptr, st, false, nullptr, lse, blocks_ok, true);
             if (rc != SNAPKV_OK) return rc;
         }
         se = chunked ? launch_select_chunked(ws.score, Hout, G.n, C - W, C, W, out_idx, ws.sel, pool_tiles(G.n), st)
@@ -428,7 +461,7 @@ int scores_impl(int dtype, const void* q_win, const void* k, int64_t L, int Hq, 
     Workspace ws;
     workspace_layout(G, &ws, base);
     return run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, out_scores, nullptr, false, nullptr,
-                      static_cast<hipStream_t>(stream), false, nullptr, lse, !lse);
+                      static_cast<hipStream_t>(stream), false, nullptr, lse, !lse, true);
 }
 
 }  // namespace
@@ -651,9 +684,10 @@ int snapkv_debug_set_wait_limit(long long polls) {
 }
 
 int snapkv_set_scoring_scheme(int scheme) {
-    if (scheme < 0 || scheme > 3) return SNAPKV_ERR_INVALID_ARG;
+    if (scheme < 0 || scheme > 7) return SNAPKV_ERR_INVALID_ARG;
     g_allow_fused = (scheme & 1) == 0;
     g_allow_pool_select = (scheme & 2) == 0;
+    g_fused_slot_cap = (scheme & 4) ? 16 : 0;
     return SNAPKV_OK;
 }
 
@@ -665,7 +699,7 @@ int64_t snapkv_sync_timeouts(void) {
 int snapkv_num_stages(void) { return kNumStageMarks - 1; }
 
 const char* snapkv_stage_name(int stage) {
-    static const char* names[] = {"prepare_scratch", "score_pass1", "reduce_rows", "score_pass2", "score_fused",
+    static const char* names[] = {"prepare_scratch", "score_pass1", "reduce_rows", "score_fused", "score_pass2",
                                   "pool_group", "select_topk", "gather_rows"};
     return stage >= 0 && stage < kNumStageMarks - 1 ? names[stage] : "";
 }

@@ -436,7 +436,7 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
 #pragma unroll
     for (int x = 0; x < L2PT; ++x) {
         const int idx = tid + x * NT;
-        p2_ok[x] = idx < R * NBP && (idx & (NBP - 1)) < F.NB;
+        p2_ok[x] = idx < R * NBP && (idx & (NBP - 1)) < F.NBX;
         p2_at[x] = p2_ok[x] ? idx : 0;   // word 0 always exists: every wave waits for at least that one
     }
 
@@ -551,6 +551,8 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
                     const int i = (ru % F.UH) * 16 + (row & 15);
                     const bool real = ru < F.RU && i < G.W && zz > 0.f;
                     sm_fin[it % 3][row] = real ? make_float2(mm, 1.0f / zz) : make_float2(0.f, 0.f);
+                    if (S.lse_out && wg == 0 && real)   // for whoever scores further keys of these rows
+                        S.lse_out[((int64_t)unit_p2 * F.gs + ru / F.UH) * G.W + i] = (mm + log2f(zz)) * 0.6931471805599453f;
                 }
             }
         }
@@ -1083,6 +1085,10 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
 constexpr unsigned kSpinLimit = 1u << 15;   // polls before a hand-off wait gives up (tens of ms)
 
 static int g_cu_count[64] = {0};
+int g_fused_slot_cap = 0;
+
+// Workgroups of the single-read kernel that are resident together, given how many fit a compute unit.
+static int64_t resident_slots(int occ);
 
 static int cu_count() {
     int dev = 0;
@@ -1093,6 +1099,11 @@ static int cu_count() {
         g_cu_count[dev] = n;
     }
     return g_cu_count[dev];
+}
+
+static int64_t resident_slots(int occ) {
+    const int64_t slots = (int64_t)cu_count() * occ;
+    return g_fused_slot_cap > 0 && slots > g_fused_slot_cap ? g_fused_slot_cap : slots;
 }
 
 constexpr int kFusedWaves = 8;          // waves per workgroup (two per SIMD): measured best
@@ -1121,6 +1132,7 @@ static bool fused_shape_nw(const ScoreGeom& G, int NW, int split, FusedGeom* F, 
     F->Gg = (int)Gg;
     F->NG = split;
     F->NB = (int)((Gg + 31) / 32);
+    F->NBX = F->NB;
     F->ntiles = ntiles;
     F->units = G.Hkv * split;
     F->split = split;
@@ -1201,6 +1213,7 @@ size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, v
         S->part = reinterpret_cast<float2*>(b);
         S->l1 = reinterpret_cast<float2*>(b + part);
         S->gave_up_flag = nullptr;
+        S->lse_out = nullptr;
     }
     return up(part + l1);
 }
@@ -1301,7 +1314,7 @@ static bool fused_plan_for(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
             (void)hipGetLastError();
             continue;
         }
-        const int64_t slots = (int64_t)cu_count() * occ;   // workgroups that are resident together
+        const int64_t slots = resident_slots(occ);
         if (slots <= 0 || F->Gg > slots) continue;          // one unit's logits do not fit on the chip
         int64_t NG = slots / F->Gg;
         if (NG > F->units) NG = F->units;
@@ -1315,6 +1328,75 @@ static bool fused_plan_for(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
         return true;
     }
     return false;
+}
+
+// ---- prompts longer than the chip's registers hold: a front part read once, the rest read twice
+bool long_plan(int dtype, int D, const ScoreGeom& G, LongPlan* P) {
+    if (G.k_table) return false;   // the rest starts at a row offset into K: not with paged rows
+    int cand[8];
+    const int nc = fused_split_candidates(G, cand);
+    for (int c = 0; c < nc; ++c) {
+        FusedGeom F;
+        if (!fused_shape_nw(G, kFusedWaves, cand[c], &F, false)) continue;
+        int occ = 0;
+        if (fused_dispatch(dtype, D, F.NW, F.RUW, nullptr, &occ) != hipSuccess) {
+            (void)hipGetLastError();
+            continue;
+        }
+        const int64_t wg_keys = (int64_t)F.NW * F.KT * 16;
+        int64_t Gg = resident_slots(occ);
+        // one level-1 word per row is kept for the rest's statistics
+        if (Gg > kSlicesPerBlock * (kL1BlocksPadded - 1)) Gg = kSlicesPerBlock * (kL1BlocksPadded - 1);
+        Gg -= Gg % 8;
+        // the rest is a prompt of its own: the window and at least one key before it
+        while (Gg >= 8 && G.L - Gg * wg_keys <= G.W) Gg -= 8;
+        if (Gg < 8) continue;
+        P->front = Gg * wg_keys;
+        P->Gf = G;
+        P->Gf.L = P->front;   // every key of the front part is before the window: no causal mask, all are voted on
+        P->Gf.n = P->front;
+        if (!fused_shape_nw(P->Gf, kFusedWaves, cand[c], &P->Ff, true) || P->Ff.Gg != Gg) continue;
+        P->Ff.NG = 1;
+        P->Ff.NBX = P->Ff.NB + 1;
+        P->Gr = G;
+        P->Gr.L = G.L - P->front;
+        P->Gr.n = G.n - P->front;
+        if (!lse_plan(dtype, D, P->Gr, &P->Fr) || P->Fr.split != P->Ff.split || P->Fr.RUW != P->Ff.RUW) continue;
+        return true;
+    }
+    return false;
+}
+
+// Per window row of a unit: the (max, sum-exp) pairs of the rest's slices merged in a fixed order into the
+// level-1 word behind the single-read kernel's own.  One workgroup per unit; 1024 / R threads share a row.
+__global__ __launch_bounds__(1024) void publish_rest(const float2* __restrict__ part, float2* __restrict__ l1,
+                                                    const int slices, const int R, const int slot) {
+    __shared__ float2 sh[1024];
+    const int unit = blockIdx.x, tid = threadIdx.x;
+    const int S = 1024 / R;
+    const int row = tid % R, sub = tid / R;
+    float m = -INFINITY, z = 0.f;
+    if (sub < S)
+        for (int sl = sub; sl < slices; sl += S) {
+            const float2 pc = part[((int64_t)unit * slices + sl) * R + row];
+            merge_pair(m, z, pc.x, pc.y);
+        }
+    sh[tid] = make_float2(m, z);
+    __syncthreads();
+    if (sub == 0) {
+        for (int c = 1; c < S; ++c) {
+            const float2 pc = sh[c * R + row];
+            merge_pair(m, z, pc.x, pc.y);
+        }
+        publish_pair(&l1[(int64_t)unit * (R * kL1BlocksPadded) + row * kL1BlocksPadded + slot], m, z);
+    }
+}
+
+hipError_t launch_publish_rest(const float2* stat_part, const FusedSync& S, const LongPlan& P, hipStream_t st) {
+    if (P.Ff.NBX != P.Ff.NB + 1 || P.Ff.NBX > kL1BlocksPadded || P.Fr.units != P.Ff.units) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(publish_rest, dim3(P.Ff.units), dim3(1024), 0, st, stat_part, S.l1, P.Fr.Gg, P.Ff.RUW * 16,
+                       P.Ff.NB);
+    return hipGetLastError();
 }
 
 // ---- several prompts in one launch
@@ -1607,6 +1689,7 @@ hipError_t launch_row_lse(int dtype, int D, const void* q, const void* k, const 
     hipError_t e = lse_dispatch<true>(dtype, D, F.RUW, &call, nullptr);
     if (e != hipSuccess) return e;
     stage_done(st, kStagePass1);
+    if (!lse_out) return hipGetLastError();
     hipLaunchKernelGGL(lse_from_parts, dim3(F.units), dim3(1024), 0, st, stat_part, lse_out, G, F);
     stage_done(st, kStageReduce);
     return hipGetLastError();

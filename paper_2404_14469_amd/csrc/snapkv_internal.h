@@ -55,6 +55,8 @@ __device__ __forceinline__ int64_t physical_row(const int32_t* table, int page, 
 // KT tiles of 16 keys per row unit; Gg workgroups share one unit's keys; NG groups run at once.
 struct FusedGeom {
     int RU, UH, RUW, KT, NW, Gg, NG, NB, units;   // NW waves per workgroup; NB blocks of 32 slices per row
+    int NBX;                 // level-1 words per row a reader merges: NB, or NB + 1 when the word behind them is
+                             // published before the launch (statistics of keys this launch does not read)
     int split, gs;           // units per KV head; query heads per unit (g = split * gs)
     int BH;                  // 1, or: every 32-row block of the window is a query head of its own to the
                              // kernel (BH blocks per real head; g, split and gs then count such blocks)
@@ -66,6 +68,8 @@ struct FusedSync {
     float2* part;            // [units][Gg][RUW*16] per-slice (row max, row sum-exp), base-2 domain
     float2* l1;              // [units][RUW*16][NB] the same merged over blocks of 32 slices
     unsigned* gave_up_flag;  // null, or a word of the call's scratch that is set when a bounded wait gives up
+    float* lse_out;          // null, or [query heads][W]: the window rows' natural log-sum-exp, stored by the
+                             // first workgroup of every group
 };
 
 // Scratch of the chunked top-k selection (snapkv_topk.hip), per head h of H heads.
@@ -107,7 +111,7 @@ size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base);
 // Stage boundaries for the optional per-stage timing (snapkv_profile_start/stop): when timing is
 // active, stage_done records an event on the stream after the stage's launch; otherwise it is a
 // no-op.  kStageBegin marks the start of a call.
-enum Stage { kStageBegin = 0, kStagePrepare, kStagePass1, kStageReduce, kStagePass2, kStageFused,
+enum Stage { kStageBegin = 0, kStagePrepare, kStagePass1, kStageReduce, kStageFused, kStagePass2,
              kStagePool, kStageSelect, kStageGather, kNumStageMarks };
 void stage_done(hipStream_t st, int stage);
 
@@ -119,6 +123,21 @@ size_t fused_sync_bytes(const ScoreGeom& G);
 // of their own (F->BH > 1); the votes then have one row per block (NV = g * BH, VB = BH).
 bool fused_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F, bool allow_blocks = false);
 size_t fused_sync_layout(const ScoreGeom& G, const FusedGeom& F, FusedSync* S, void* base);
+// A prompt of which one head's logits do not fit the chip's registers: the single-read kernel takes the
+// first `front` keys (geometry Gf, plan Ff: as many as stay resident), the streaming kernels the rest
+// (Gr, Fr: a prompt of L - front keys that ends in the same window), whose keys are so read twice.
+// Order of the launches: row statistics of the rest; their merge into one hand-off word per row
+// (launch_publish_rest); the single-read kernel, which merges that word with its own slices', votes on
+// its keys and stores the rows' log-sum-exp; the streaming pass that votes on the rest from it.
+struct LongPlan {
+    ScoreGeom Gf, Gr;
+    FusedGeom Ff, Fr;
+    int64_t front;
+};
+bool long_plan(int dtype, int D, const ScoreGeom& G, LongPlan* P);
+hipError_t launch_publish_rest(const float2* stat_part, const FusedSync& S, const LongPlan& P, hipStream_t st);
+// (test hook) 0, or the number of workgroups the plans of the single-read kernel may count as resident
+extern int g_fused_slot_cap;
 // Several prompts of one model in one launch of the single-read kernel (snapkv_fused.hip).
 constexpr int kMaxJointPrompts = 8;
 int fused_joint_plan(int dtype, int D, int count, const ScoreGeom* G, FusedGeom* F, int* take, int* wg_begin,
@@ -146,6 +165,7 @@ bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
 hipError_t launch_score_lse(int dtype, int D, const void* q, const void* k, const float* lse,
                             const ScoreGeom& G, const FusedGeom& F, float* vote, hipStream_t st);
 size_t stream_stat_bytes(const ScoreGeom& G);
+// lse_out == nullptr: the per-slice statistics only
 hipError_t launch_row_lse(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                           const FusedGeom& F, float2* stat_part, float* lse_out, hipStream_t st);
 // Pooling and selection in one cooperative launch (reads votes, writes the kept positions).

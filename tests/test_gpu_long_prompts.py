@@ -1,0 +1,101 @@
+"""Prompts of which one head's window logits do not fit the chip's registers: the single-read kernel scores
+the keys that fit, two streaming passes the rest, and the two parts share one softmax (Eq. 1).  With scheme
+bit 2 the plans count 16 resident workgroups, so prompts of a few thousand tokens take that path and the
+oracle checks every head; the full-size cases check sampled heads."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2404_14469_amd import workloads
+from paper_2404_14469_amd.workloads import Workload
+from parity import check_against_oracle, gpu_vs_oracle, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture()
+def few_slots(snapkv):
+    snapkv.snapkv_set_scoring_scheme(4)
+    try:
+        yield snapkv
+    finally:
+        snapkv.snapkv_set_scoring_scheme(0)
+
+
+BASE = dict(L=20000, Hq=8, Hkv=8, D=128, W=32, pool_kind=0, p=7, C=512, dtype="bf16", clusters=(6, 6), radius=6,
+            layers=1, seed=5200)
+
+# front part: 16 workgroups of 512 keys (two row units), 1024 (one) or fewer (more row units per unit)
+SHAPES = {
+    "mha_w32": dict(),
+    "mha_w32_rest_shorter_than_a_tile": dict(L=8192 + 32 + 5),
+    "mha_w32_rest_is_window_plus_one": dict(L=8192 + 33),
+    "mha_w16_avg": dict(W=16, p=5, pool_kind=1, L=30011, C=300),
+    "gqa4_w32": dict(Hq=16, Hkv=4, L=17000),
+    "gqa4_w16": dict(Hq=16, Hkv=4, W=16, L=9000, C=200),
+    "gqa2_w8": dict(Hq=8, Hkv=4, W=8, L=12345, C=128),
+    "w64_p13": dict(W=64, p=13, L=9999, C=600),
+    "f16_d64": dict(dtype="f16", D=64, L=13000),
+    "f32": dict(dtype="f32", Hq=4, Hkv=4, L=11000, C=256),
+}
+
+
+@pytest.mark.parametrize("name", list(SHAPES))
+def test_front_and_rest_share_one_softmax(few_slots, name):
+    kw = dict(BASE)
+    kw.update(SHAPES[name])
+    w = Workload("long_" + name, **kw)
+    gpu_vs_oracle(few_slots, w)
+    assert few_slots.snapkv_sync_timeouts() == 0
+
+
+def test_same_selection_as_two_streaming_passes(few_slots):
+    """The path changes how the keys are read, not what is kept: positions equal the two-pass path's wherever
+    that one's scores are not within rounding of the threshold (checked through the oracle band on both)."""
+    w = Workload("long_cmp", **dict(BASE, L=25000, Hq=4, Hkv=4))
+    case = workloads.generate(w, device="cuda")
+    q, k, v = case["q_win"], case["k"], case["v"]
+    a = run_gpu(few_slots, q, k, v, w.pool_kind, w.p, w.C)
+    few_slots.snapkv_set_scoring_scheme(1)
+    b = run_gpu(few_slots, q, k, v, w.pool_kind, w.p, w.C)
+    few_slots.snapkv_set_scoring_scheme(4)
+    assert np.abs(a[0] - b[0]).max() <= 2e-6 * np.abs(b[0]).max()
+    for hk in range(w.Hkv):
+        assert len(set(a[3][hk].tolist()) ^ set(b[3][hk].tolist())) <= 4
+    check_against_oracle(q, k, v, w.pool_kind, w.p, w.C, *a)
+
+
+def test_layers_entry_and_repeated_calls(few_slots):
+    """Stacked layers pass as one layer of more heads through the same launches; calls in a row reuse the
+    hand-off words the gather re-arms."""
+    w = Workload("long_layers", **dict(BASE, L=12000, Hq=4, Hkv=4, C=256))
+    cases = [workloads.generate(w, layer=l, device="cuda") for l in range(3)]
+    q, k, v = (torch.stack([c[n] for c in cases]).contiguous() for n in ("q_win", "k", "v"))
+    for _ in range(3):
+        ok = torch.zeros((3, w.Hkv, w.C, w.D), dtype=k.dtype, device="cuda")
+        ov = torch.zeros_like(ok)
+        oi = torch.full((3, w.Hkv, w.C), -1, dtype=torch.int32, device="cuda")
+        few_slots.snapkv_compress_layers(list(q), list(k), list(v), w.pool_kind, w.p, w.C, list(ok), list(ov), list(oi))
+        torch.cuda.synchronize()
+        for l in range(3):
+            ref = run_gpu(few_slots, q[l], k[l], v[l], w.pool_kind, w.p, w.C)
+            assert np.array_equal(oi[l].cpu().numpy(), ref[3])
+            assert torch.equal(ok[l], ref[1]) and torch.equal(ov[l], ref[2])
+    check_against_oracle(q[2], k[2], v[2], w.pool_kind, w.p, w.C, *ref)
+    assert few_slots.snapkv_sync_timeouts() == 0
+
+
+@pytest.mark.parametrize("L,W,p,C,heads", [(262144, 32, 7, 4096, [0, 5]), (380000, 16, 5, 1024, [1, 6])])
+def test_full_size_long_prompts(snapkv, L, W, p, C, heads):
+    """262144 tokens at the long-context setting's window, and the 380K-token setting of Sec. 5.1.1
+    (C = 1024, max pooling over 5, W = 16), eight heads resident, sampled heads against the oracle."""
+    w = workloads.LONG_131K.with_(name=f"long_{L}", L=L, W=W, p=p, C=C, Hq=8, Hkv=8, clusters=(16, 16), seed=78)
+    case = workloads.generate(w, device="cuda")
+    q, k, v = case["q_win"], case["k"], case["v"]
+    res = run_gpu(snapkv, q, k, v, w.pool_kind, w.p, w.C)
+    check_against_oracle(q, k, v, w.pool_kind, w.p, w.C, *res, heads=heads)
+    idx = res[3]
+    for hk, pos in enumerate(case["needle_pos"]):
+        lo, hi = max(0, pos - w.p // 2), min(w.n - 1, pos + w.p // 2)
+        assert set(range(lo, hi + 1)) <= set(idx[hk].tolist())
+    assert snapkv.snapkv_sync_timeouts() == 0
