@@ -239,13 +239,20 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
         Gp.VB = F.BH;
     } else if (split_read) {
         const char* k_rest = static_cast<const char*>(k) + LP.front * G.k_rs;
-        if (launch_row_lse(dtype, D, q_win, k_rest, LP.Gr, LP.Fr, ws.stat_part, nullptr, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        // where a key's window logits are fewer bytes than its K row, the rest's keys are read once too: the
+        // statistics pass keeps its logits and the votes come from those
+        const bool keep_logits = LP.Fr.RUW == 1 && LP.Fr.gs == 1 && ws.long_logit &&
+                                 (size_t)LP.Fr.units * (size_t)long_logit_keys(LP.Fr) * 16 * sizeof(float) <= ws.long_logit_bytes;
+        if (launch_row_lse(dtype, D, q_win, k_rest, LP.Gr, LP.Fr, ws.stat_part, nullptr, st,
+                           keep_logits ? ws.long_logit : nullptr) != hipSuccess)
+            return SNAPKV_ERR_HIP;
         if (launch_publish_rest(ws.stat_part, S, LP, st) != hipSuccess) return SNAPKV_ERR_HIP;
         stage_done(st, kStageReduce);
         S.lse_out = ws.lse;
         if (launch_score_fused(dtype, D, q_win, k, LP.Gf, LP.Ff, S, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
         stage_done(st, kStageFused);
-        if (launch_score_lse(dtype, D, q_win, k_rest, ws.lse, LP.Gr, LP.Fr, ws.vote + LP.front, st) != hipSuccess)
+        if ((keep_logits ? launch_votes_from_logits(ws.long_logit, ws.lse, ws.vote + LP.front, LP, st)
+                         : launch_score_lse(dtype, D, q_win, k_rest, ws.lse, LP.Gr, LP.Fr, ws.vote + LP.front, st)) != hipSuccess)
             return SNAPKV_ERR_HIP;
         stage_done(st, kStagePass2);
         Gp.NV = G.g;

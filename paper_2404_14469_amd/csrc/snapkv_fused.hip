@@ -939,6 +939,18 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
                     }
             }
         }
+        if constexpr (STAT && RUW == 1) {
+            // (`vote` in this mode: null, or where the masked logits are kept for a reader that turns them
+            // into votes once the rows' normalisers are known; a wave stores 1 KB per tile)
+            if (vote) {
+                float* lb = vote + (int64_t)unit * ((int64_t)F.Gg * NW * KT * 16) * 16;
+#pragma unroll
+                for (int t = 0; t < KT; ++t) {
+                    const int64_t j = ((int64_t)t * TS + tile0) * 16 + n16;
+                    __builtin_nontemporal_store(e[0][t], reinterpret_cast<f32x4*>(lb + j * 16 + kg * 4));
+                }
+            }
+        }
         if constexpr (STAT) {
             // row maxima and sums of exponentials of this wave's keys (base-2 domain), left in LDS
             // for the merge over the waves after the barrier
@@ -1682,10 +1694,67 @@ hipError_t launch_score_lse(int dtype, int D, const void* q, const void* k, cons
 }
 
 // The rows' log-sum-exp by one streaming pass over K and a small merge.
+int64_t long_logit_keys(const FusedGeom& F) { return (int64_t)F.Gg * F.NW * F.KT * 16; }
+
+size_t long_logit_bytes(const ScoreGeom& G) {
+    // one row unit per unit: a key's 16 logits are 64 bytes against the 2 * D bytes or more of its K row
+    if (G.W > 16 || G.g != 1) return 0;
+    int64_t slots = resident_slots(1);
+    slots -= slots % 8;
+    const int64_t wg_keys = (int64_t)kFusedWaves * kFusedSlots * 16;
+    if (slots < 8 || G.L <= slots * wg_keys) return 0;   // short enough for the single-read kernel alone
+    const int64_t rest = G.L - slots * wg_keys + wg_keys;   // rounded up to the workgroups' tile grid
+    return ((size_t)G.Hkv * (size_t)rest * 16 * sizeof(float) + 255) & ~(size_t)255;
+}
+
+// One quad of lanes per key: each lane exponentiates four rows' logits, the quad's sum is the vote.  A workgroup
+// takes kVflKeys consecutive keys of a unit, eight per quad, all loads in flight before the first is used.
+constexpr int kVflKeys = 512;
+__global__ __launch_bounds__(256) void votes_from_logits(const float* __restrict__ logit, const float* __restrict__ lse,
+                                                        float* __restrict__ vote, const int64_t keys, const int64_t n,
+                                                        const int W, const float c2, const int64_t vpitch) {
+    const int unit = blockIdx.y, part = threadIdx.x & 3, quad = threadIdx.x >> 2;
+    const int64_t j0 = (int64_t)blockIdx.x * kVflKeys + quad;
+    constexpr float kLog2e = 1.4426950408889634f;
+    float l2[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = part * 4 + r;
+        l2[r] = i < W ? lse[(int64_t)unit * W + i] * kLog2e : INFINITY;   // rows beyond the window vote nothing
+    }
+    const float* base = logit + (int64_t)unit * keys * 16 + part * 4;
+    f32x4 x[kVflKeys / 64];
+#pragma unroll
+    for (int c = 0; c < kVflKeys / 64; ++c) {
+        const int64_t j = j0 + c * 64;   // inside the unit's logits (they cover whole workgroup strides of keys)
+        x[c] = __builtin_nontemporal_load(reinterpret_cast<const f32x4*>(base + (j < keys ? j : keys - 1) * 16));
+    }
+#pragma unroll
+    for (int c = 0; c < kVflKeys / 64; ++c) {
+        float s = 0.f;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s += __builtin_amdgcn_exp2f(fmaf(x[c][r], c2, -l2[r]));
+        s += __shfl_xor(s, 1, 64);
+        s += __shfl_xor(s, 2, 64);
+        const int64_t j = j0 + c * 64;
+        if (part == 0 && j < n) VOTE_STORE(&vote[(int64_t)unit * vpitch + j], s);
+    }
+}
+
+hipError_t launch_votes_from_logits(const float* logit, const float* lse, float* vote, const LongPlan& P,
+                                    hipStream_t st) {
+    if (P.Fr.RUW != 1 || P.Fr.gs != 1 || P.Gr.n <= 0 || P.Fr.units > 65535) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)((P.Gr.n + kVflKeys - 1) / kVflKeys), (unsigned)P.Fr.units);
+    hipLaunchKernelGGL(votes_from_logits, grid, dim3(256), 0, st, logit, lse, vote, long_logit_keys(P.Fr), P.Gr.n, P.Gr.W,
+                       P.Gr.c2, P.Gr.vpitch);
+    return hipGetLastError();
+}
+
 hipError_t launch_row_lse(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
-                          const FusedGeom& F, float2* stat_part, float* lse_out, hipStream_t st) {
+                          const FusedGeom& F, float2* stat_part, float* lse_out, hipStream_t st, float* logit_out) {
     if (G.n <= 0) return hipSuccess;
-    const LseCall call{q, k, nullptr, &G, &F, nullptr, stat_part, st};
+    if (logit_out && F.RUW != 1) return hipErrorInvalidValue;
+    const LseCall call{q, k, nullptr, &G, &F, logit_out, stat_part, st};
     hipError_t e = lse_dispatch<true>(dtype, D, F.RUW, &call, nullptr);
     if (e != hipSuccess) return e;
     stage_done(st, kStagePass1);

@@ -102,6 +102,8 @@ struct Workspace {
     char* fused;     // hand-off buffers of the single-read path (see fused_sync_layout)
     float2* stat_part;   // [units][Gg][R] per-slice (row max, row sum-exp) of the streaming statistics pass
     float* lse;          // [Hq][W] the window rows' log-sum-exp computed from them
+    float* long_logit;   // null, or [units][keys][16] masked window logits of the keys a long prompt's single-read
+    size_t long_logit_bytes;   // launch does not take (windows of at most 16 rows, one query head per KV head)
     SelectScratch sel;
 };
 
@@ -165,9 +167,19 @@ bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
 hipError_t launch_score_lse(int dtype, int D, const void* q, const void* k, const float* lse,
                             const ScoreGeom& G, const FusedGeom& F, float* vote, hipStream_t st);
 size_t stream_stat_bytes(const ScoreGeom& G);
-// lse_out == nullptr: the per-slice statistics only
+// lse_out == nullptr: the per-slice statistics only.  logit_out (may be null; plans with one row unit only):
+// the pass also stores its masked logits there, [units][long_logit_keys(F)][16] floats (rows beyond the window
+// hold what the padding produced and are ignored by the reader).
 hipError_t launch_row_lse(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
-                          const FusedGeom& F, float2* stat_part, float* lse_out, hipStream_t st);
+                          const FusedGeom& F, float2* stat_part, float* lse_out, hipStream_t st,
+                          float* logit_out = nullptr);
+int64_t long_logit_keys(const FusedGeom& F);
+// Bytes that hold the logits of the rest of any long prompt of this shape on the current device (0: shapes whose
+// logits are not kept: it is then cheaper, or as cheap, to read the rest's keys again).
+size_t long_logit_bytes(const ScoreGeom& G);
+// Votes of the rest from its kept logits and the rows' log-sum-exp (in place of the second streaming pass).
+hipError_t launch_votes_from_logits(const float* logit, const float* lse, float* vote, const LongPlan& P,
+                                    hipStream_t st);
 // Pooling and selection in one cooperative launch (reads votes, writes the kept positions).
 // pool_select_ok says whether the shape fits and the grid can be resident on the current device.
 bool pool_select_ok(const ScoreGeom& G, int pool_kind, int p, int64_t kcount);

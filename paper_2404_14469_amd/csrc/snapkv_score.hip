@@ -334,6 +334,7 @@ size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base) {
     const size_t score = align_up(sizeof(float) * (size_t)Hsel * (size_t)(G.n > 0 ? G.n : 1));
     const size_t stat = stream_stat_bytes(G);
     const size_t lse = align_up(sizeof(float) * (size_t)G.Hkv * G.g * G.W);
+    const size_t logit = long_logit_bytes(G);
     const size_t off = counters + fused;
     if (ws) {
         ws->status_flag = reinterpret_cast<unsigned*>(base);
@@ -344,12 +345,14 @@ size_t workspace_layout(const ScoreGeom& G, Workspace* ws, void* base) {
         ws->score = reinterpret_cast<float*>(b + off + part + mz + vote);
         ws->stat_part = reinterpret_cast<float2*>(b + off + part + mz + vote + score);
         ws->lse = reinterpret_cast<float*>(b + off + part + mz + vote + score + stat);
+        ws->long_logit = logit ? reinterpret_cast<float*>(b + off + part + mz + vote + score + stat + lse) : nullptr;
+        ws->long_logit_bytes = logit;
     }
     const size_t sel = select_layout(Hsel, G.n, ws ? &ws->sel : nullptr,
-                                     ws ? b + off + part + mz + vote + score + stat + lse : nullptr, false,
+                                     ws ? b + off + part + mz + vote + score + stat + lse + logit : nullptr, false,
                                      ws ? b : nullptr);
     if (ws) ws->sel.ps_flag = ws->status_flag;
-    return kHeader + off + part + mz + vote + score + stat + lse + sel;
+    return kHeader + off + part + mz + vote + score + stat + lse + logit + sel;
 }
 
 template <typename T, int D>
