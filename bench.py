@@ -65,7 +65,7 @@ def measured_traffic(workload: str, kernel: str):
 def algorithmic_bytes(w):
     """Bytes the method must move per call: K once, the kept K/V rows read and written, the kept
     positions, the window queries.  V is never streamed, only gathered."""
-    e = 2 if w.dtype == "bf16" else 4
+    e = 4 if w.dtype == "f32" else 2
     scan = w.Hkv * w.L * w.D * e + w.Hq * w.W * w.D * e
     gather = w.Hkv * (4 * w.C * w.D * e + 4 * w.C)
     return scan, gather
@@ -362,6 +362,19 @@ def config_lines(args, torch, np, snapkv, workloads, dev):
     r1 = run_single(torch, snapkv, workloads, w, 4, steps, warmup, dev, stages=False)
     out.append(entry(w, "one layer, one snapkv_compress call", r1["ms"], 1, None))
     del r1
+    # beyond the five configurations: the longest context the paper reports (Sec. 5.1.1: 380K tokens, C = 1024,
+    # max pooling over 5, W = 16), at the long-context configuration's heads; longer than the single-read kernel holds
+    w = workloads.CONFIGS["long_131k"].with_(name="long_380k", L=380000, W=16, p=5, C=1024, layers=1)
+    r = run_single(torch, snapkv, workloads, w, 2, 10, 2, dev, stages=False)
+
+    def gpu_idx_380(l, r=r):
+        r["step"](l)
+        torch.cuda.synchronize()
+        return r["out_idx"].cpu().numpy()
+
+    cpu = None if args.no_cpu_baseline else oracle_leg(np, workloads, c_oracle, w, r["layers"], gpu_idx_380, budget=3e10)
+    out.append(entry(w, "one layer, one snapkv_compress call", r["ms"], 1, cpu))
+    del r
     # the batch of eight prompts of different lengths
     ws = workloads.varlen_prompts()
     cases = [workloads.generate(x, device=dev) for x in ws]
