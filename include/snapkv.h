@@ -230,13 +230,16 @@ int snapkv_compress_varlen(int dtype, int n_prompts, const void* const* q_win, c
 /*
  * The compression step for several layers of one prompt in one call (Listing 1 runs once per layer; the
  * layers of a prompt have the same shape and are independent of each other, Sec. 4.1).  Every layer gets
- * exactly the result of its own snapkv_compress call.  What the call saves: layers whose tensors lie one
- * directly behind the other in memory (slices of stacked [layers, heads, ...] tensors, for q_win, k, v,
- * out_k, out_v and out_idx alike) go through the kernels as ONE layer with that many more heads, so the
- * scoring kernel streams all their keys in a single launch and pays its start-up and drain once, and
- * pooling, selection and gather run as a few large launches instead of three per layer.  With the whole
- * uncompressed prompt cache resident (68.7 GB at 32 layers x 32 heads x 131072 tokens: this is what 288 GB
- * of HBM are for) that is the fastest form of the step.  Layers that do not lie that way are done one by one.
+ * exactly the result of its own snapkv_compress call.  What the call saves: the layers go through the
+ * kernels as ONE layer with that many more heads, so the scoring kernel streams all their keys in a single
+ * launch and pays its start-up and drain once, and pooling, selection and gather run as a few large launches
+ * instead of three per layer.  With the whole uncompressed prompt cache resident (68.7 GB at 32 layers x
+ * 32 heads x 131072 tokens: this is what 288 GB of HBM are for) that is the fastest form of the step.
+ * Layers whose tensors lie one directly behind the other in memory (slices of stacked [layers, heads, ...]
+ * tensors, for q_win, k, v, out_k, out_v and out_idx alike) are taken as they lie; layers that are separate
+ * allocations are reached through a table of their addresses, up to 32 of them per run of launches (two-byte
+ * element types; prompts the single-read scoring kernel takes whole, windows of at most 32 rows or of 48-128
+ * rows in its plain form).  What fits neither is done one layer after the other inside the call.
  *
  *   n_layers >= 0
  *   q_win, k, v, out_k, out_v, out_idx   HOST arrays of n_layers DEVICE pointers, each as the argument of the

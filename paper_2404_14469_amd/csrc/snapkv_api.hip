@@ -190,13 +190,30 @@ int scoring_path(int dtype, int D, const ScoreGeom& G, bool lse_given, bool allo
     return lse_plan(dtype, D, G, F) ? kPathStream : kPathOld;
 }
 
+// Whether the heads of several separately allocated layers can go through the kernels as one call: the
+// single-read kernel must take the whole prompt in its plain form (no 32-row blocks), in the form that reads
+// its Q and K rows through a table of layers.
+bool layers_table_ok(int dtype, int D, const ScoreGeom& G, int kv_heads_per_layer) {
+    FusedGeom F;
+    LongPlan LP;
+    if (scoring_path(dtype, D, G, false, false, false, &F, &LP) != kPathFused || F.BH != 1) return false;
+    ScoreLayers probe{};
+    probe.count = G.Hkv / kv_heads_per_layer;
+    probe.kv_heads = kv_heads_per_layer;
+    if (probe.count < 1 || probe.count > kMaxLayerPtrs) return false;
+    const hipError_t e = launch_score_fused_layers(dtype, D, probe, G, F, FusedSync{}, nullptr, nullptr, true);
+    if (e != hipSuccess) (void)hipGetLastError();
+    return e == hipSuccess;
+}
+
 int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGeom& G,
                const Workspace& ws, int pool_kind, int p, float* score, unsigned* minmax,
                bool prepare_select, ScoreGeom* Gv, hipStream_t st, bool already_prepared = false,
                CleanJob* clean = nullptr, const float* lse = nullptr, bool allow_blocks = false,
-               bool allow_long = false) {
+               bool allow_long = false, const ScoreLayers* layers = nullptr) {
     FusedGeom F;
     ScoreGeom Gp = G;
+    if (layers && (lse || allow_blocks)) return SNAPKV_ERR_UNSUPPORTED;
     if (lse) {   // the rows' normalisers are given: one streaming pass, nothing handed between workgroups
         if (!lse_plan(dtype, D, G, &F)) return SNAPKV_ERR_UNSUPPORTED;
         if (!already_prepared) {
@@ -217,6 +234,7 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
     LongPlan LP;
     const int path = scoring_path(dtype, D, G, false, allow_blocks, allow_long, &F, &LP);
     const bool fused = path == kPathFused, split_read = path == kPathLong;
+    if (layers && !fused) return SNAPKV_ERR_UNSUPPORTED;   // (callers ask layers_table_ok first)
     FusedSync S;
     if (fused) fused_sync_layout(G, F, &S, ws.fused);
     if (split_read) fused_sync_layout(LP.Gf, F, &S, ws.fused);   // F is the front part's plan
@@ -233,7 +251,9 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
         clean->nones = fused_sync_pairs(F);
     }
     if (fused) {   // K is read once; otherwise two passes over K, or over the part of it the chip cannot hold
-        if (launch_score_fused(dtype, D, q_win, k, G, F, S, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        if ((layers ? launch_score_fused_layers(dtype, D, *layers, G, F, S, ws.vote, st)
+                    : launch_score_fused(dtype, D, q_win, k, G, F, S, ws.vote, st)) != hipSuccess)
+            return SNAPKV_ERR_HIP;
         stage_done(st, kStageFused);
         Gp.NV = G.g * F.BH;   // one vote row per query head, or per 32-row block of its window
         Gp.VB = F.BH;
@@ -287,6 +307,10 @@ struct CompressOptions {
     bool per_query_head = false;        // one selection and one cache per query head
     PageMap pm;                         // paged K and V
     int32_t* status = nullptr;          // device word of the caller's that receives the call's verdict
+    // the heads are those of several separately allocated layers (Hq and Hkv count all of them; q_win, k, v and
+    // the outputs are then taken from these tables, library's own scratch only)
+    const ScoreLayers* score_layers = nullptr;
+    const GatherLayers* gather_layers = nullptr;
 };
 
 int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v, int64_t L, int Hq,
@@ -339,12 +363,20 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     G.k_page = pm.page;
     G.k_pages = pm.pages;
     const size_t need = workspace_layout(G, nullptr, nullptr);
+    const size_t need_up = (need + 255) & ~(size_t)255;
     void* base = workspace;
     CleanState was_clean;
     unsigned* sticky = nullptr;
+    const ScoreLayers* const score_layers = opt.score_layers;
+    const GatherLayers* const gather_layers = opt.gather_layers;
+    if ((score_layers != nullptr) != (gather_layers != nullptr)) return SNAPKV_ERR_INVALID_ARG;
+    if (score_layers && (!own_scratch || per_query_head || lse || k_layout || v_layout || pm.table)) return SNAPKV_ERR_UNSUPPORTED;
+    // separately allocated layers: the kept positions of all heads go to one array behind the workspace, from
+    // which the gather copies them to the layers' own
+    const size_t idx_tmp_bytes = score_layers ? ((size_t)Hout * (size_t)C * sizeof(int32_t) + 255) & ~(size_t)255 : 0;
     if (own_scratch) {
         if (capturing(st)) return SNAPKV_ERR_UNSUPPORTED;
-        rc = internal_scratch(need, &base, &was_clean, &sticky);
+        rc = internal_scratch(need_up + idx_tmp_bytes, &base, &was_clean, &sticky);
         if (rc != SNAPKV_OK) return rc;
         // An earlier call on this scratch whose kernels have finished by now had a bounded wait give up: its
         // results were invalid.  Said once, here, since that call had already returned when it happened.
@@ -358,6 +390,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     }
     Workspace ws;
     workspace_layout(G, &ws, base);
+    int32_t* const idx_dst = score_layers ? reinterpret_cast<int32_t*>(static_cast<char*>(base) + need_up) : out_idx;
     stage_done(st, kStageBegin);
     const bool chunked = select_chunked_ok(G.n);
     hipError_t se;
@@ -373,7 +406,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     // single-read and streaming kernels produce), so pooling and selection see Hq heads of one.
     // a window of 64, 96, ... rows may be scored block by block (one vote row per 32-row block); the
     // per-query-head form and the handed-in log-sum-exp keep one vote row per query head
-    const bool blocks_ok = !per_query_head && !lse;
+    const bool blocks_ok = !per_query_head && !lse && !score_layers;
     ScoreGeom Gsel = G;
     if (per_query_head) {
         FusedGeom Ft;
@@ -388,7 +421,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
         FusedGeom Fp;
         // which scoring path run_scores will take (the state of the 32x32 two-pass kernels is not tracked)
         LongPlan LPp;
-        const int path = scoring_path(dtype, D, G, lse != nullptr, blocks_ok, true, &Fp, &LPp);
+        const int path = scoring_path(dtype, D, G, lse != nullptr, blocks_ok, !score_layers, &Fp, &LPp);
         streaming = path == kPathStream;
         if (own_scratch && path != kPathOld) {
             int dev = 0;
@@ -409,10 +442,10 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
         }
         ScoreGeom Gv = G;
         rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, true, &Gv, st, prepared,
-                        mine ? &clean : nullptr, lse, blocks_ok, true);
+                        mine ? &clean : nullptr, lse, blocks_ok, !score_layers, score_layers);
         if (rc != SNAPKV_OK) return rc;
         if (per_query_head) Gv = Gsel;
-        se = launch_pool_select(Gv, ws.vote, pool_kind, p, C - W, C, W, out_idx, ws.sel, st);
+        se = launch_pool_select(Gv, ws.vote, pool_kind, p, C - W, C, W, idx_dst, ws.sel, st);
         if (mine) {
             clean.zeros = ws.sel.ps_arrive;
             clean.nzeros = ws.sel.ps_zero_words;
@@ -429,15 +462,16 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
             stage_done(st, kStagePool);
         } else {
             rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr,
-                            chunked, nullptr, st, false, nullptr, lse, blocks_ok, true);
+                            chunked, nullptr, st, false, nullptr, lse, blocks_ok, !score_layers, score_layers);
             if (rc != SNAPKV_OK) return rc;
         }
-        se = chunked ? launch_select_chunked(ws.score, Hout, G.n, C - W, C, W, out_idx, ws.sel, pool_tiles(G.n), st)
-                     : launch_select(ws.score, Hout, G.n, C - W, C, W, out_idx, st);
+        se = chunked ? launch_select_chunked(ws.score, Hout, G.n, C - W, C, W, idx_dst, ws.sel, pool_tiles(G.n), st)
+                     : launch_select(ws.score, Hout, G.n, C - W, C, W, idx_dst, st);
     }
     if (se != hipSuccess) return SNAPKV_ERR_HIP;
     stage_done(st, kStageSelect);
-    if (launch_gather(k, v, out_idx, Hout, L, C, C, row_bytes, out_k, out_v, kl, vl, clean, st, head_div, pm) != hipSuccess)
+    if ((gather_layers ? launch_gather_layers(*gather_layers, idx_dst, L, C, C, row_bytes, clean, st)
+                       : launch_gather(k, v, out_idx, Hout, L, C, C, row_bytes, out_k, out_v, kl, vl, clean, st, head_div, pm)) != hipSuccess)
         return SNAPKV_ERR_HIP;
     if (mine && (clean.ones || streaming) && clean.zeros) {
         std::lock_guard<std::mutex> lock(g_mu);
@@ -948,10 +982,46 @@ int snapkv_compress_layers(int dtype, int n_layers, const void* const* q_win, co
     most = most < 1 ? 1 : most;
     if ((int64_t)most * Hkv > 65535) most = 65535 / Hkv;
     if (L <= C) most = 1;                  // prompts that fit are copied layer by layer (out rows [L, C) stay untouched)
+    // Layers that are separate allocations go through the same launches by a table of their addresses (at most
+    // kMaxLayerPtrs per run), where the single-read scoring kernel takes the prompt in that form; otherwise
+    // one by one.
+    int most_sep = most < kMaxLayerPtrs ? most : kMaxLayerPtrs;
+    if (L <= C || (elem_bytes(dtype) != 2)) most_sep = 1;
     int i = 0;
     while (i < n_layers) {
         int r = 1;
         while (i + r < n_layers && r < most && follows(i + r - 1)) ++r;
+        if (r == 1 && most_sep > 1) {   // a run of layers none of which lies behind its predecessor
+            int t = 1;
+            while (i + t < n_layers && t < most_sep && !follows(i + t - 1) && (i + t + 1 >= n_layers || !follows(i + t))) ++t;
+            if (t > 1) {
+                ScoreGeom Gt = make_geom(L, Hq * t, Hkv * t, D, W);
+                Gt.k_rs = (int64_t)D * e;
+                Gt.k_hs = Gt.k_rs * L;
+                if (layers_table_ok(dtype, D, Gt, Hkv)) {
+                    ScoreLayers SL{};
+                    GatherLayers GL{};
+                    SL.count = GL.count = t;
+                    SL.kv_heads = GL.heads = Hkv;
+                    for (int x = 0; x < t; ++x) {
+                        SL.q[x] = q_win[i + x];
+                        SL.k[x] = GL.k[x] = k[i + x];
+                        GL.v[x] = v[i + x];
+                        GL.out_k[x] = out_k[i + x];
+                        GL.out_v[x] = out_v[i + x];
+                        GL.out_idx[x] = out_idx[i + x];
+                    }
+                    CompressOptions opt;
+                    opt.score_layers = &SL;
+                    opt.gather_layers = &GL;
+                    const int64_t got = compress_impl(dtype, q_win[i], k[i], v[i], L, Hq * t, Hkv * t, D, W, pool_kind, p, C,
+                                                      out_k[i], out_v[i], out_idx[i], stream, opt);
+                    if (got < 0) return (int)got;
+                    i += t;
+                    continue;
+                }
+            }
+        }
         const int64_t got = compress_impl(dtype, q_win[i], k[i], v[i], L, Hq * r, Hkv * r, D, W, pool_kind, p, C, out_k[i],
                                           out_v[i], out_idx[i], stream);
         if (got < 0) return (int)got;

@@ -247,10 +247,14 @@ template <typename T, int D, int RUW, int NW> constexpr int fused_lds_bytes() {
     return 3 * RUW * (D * esize<T>::value / 64) * 64 * 16 + (fused_parks<RUW>::value ? 2 * kFusedSlots * NW * 64 * 16 : 0);
 }
 
-template <typename T, int D, int RUW, int KT, int NW>
+// LAYERS: the heads are those of several layers of one prompt that are separate allocations; the Q and K
+// rows of head h then start at SL->q / SL->k [h / heads per layer] instead of behind one another after
+// qv / kv (which are then unused).
+template <typename T, int D, int RUW, int KT, int NW, bool LAYERS = false>
 __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, const void* __restrict__ kv,
                                                  float* __restrict__ vote, const FusedSync& S,
-                                                 const ScoreGeom& G, const FusedGeom& F, const int bid) {
+                                                 const ScoreGeom& G, const FusedGeom& F, const int bid,
+                                                 const ScoreLayers* SL = nullptr) {
     constexpr int R = RUW * 16;          // window rows a workgroup tracks per unit
     constexpr int NT = NW * 64;
     constexpr int NSLOT = RUW * KT;      // accumulator tiles per lane per unit
@@ -301,13 +305,28 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
     // Per-lane row addresses; they advance by one group stride per iteration.  Loads are
     // unconditional (out-of-range tiles and padding rows re-read a valid row and are masked or
     // ignored later) so that the number of loads in flight behind a hand-off word is fixed.
+    // first K row of KV head h, first Q row of query head qh
+    auto k_head = [&](const int h) -> const char* {
+        if constexpr (LAYERS)
+            return static_cast<const char*>(SL->k[h / SL->kv_heads]) + (int64_t)(h % SL->kv_heads) * G.k_hs;
+        else
+            return static_cast<const char*>(kv) + (int64_t)h * G.k_hs;
+    };
+    auto q_head = [&](const int qh) -> const char* {
+        if constexpr (LAYERS) {
+            const int per_layer = SL->kv_heads * G.g;
+            return static_cast<const char*>(SL->q[qh / per_layer]) + (int64_t)(qh % per_layer) * G.W * D * ES;
+        } else {
+            return static_cast<const char*>(qv) + (int64_t)qh * G.W * D * ES;
+        }
+    };
     const char* kp[KT];
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
         int64_t j = ((int64_t)t * TS + tile0) * 16 + n16;
         j = j < G.L ? j : G.L - 1;
         j = physical_row(G.k_table, G.k_page, G.k_pages, j);
-        kp[t] = static_cast<const char*>(kv) + (int64_t)(group / F.split) * G.k_hs + j * G.k_rs + kg * 16;
+        kp[t] = k_head(group / F.split) + j * G.k_rs + kg * 16;
     }
     // Q is shared by the waves: each fetches QPW of the unit's 1 KB chunks (chunk c = row unit c / NP,
     // piece c % NP, lane l = row l % 16, contraction slice l / 16) and leaves them in LDS.
@@ -320,7 +339,7 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
         int head = ru / F.UH, i = (ru % F.UH) * 16 + n16;
         head = head < F.gs ? head : F.gs - 1;
         i = i < G.W ? i : G.W - 1;
-        qp[x] = static_cast<const char*>(qv) + ((int64_t)(group * F.gs + head) * G.W + i) * D * ES + (4 * pc + kg) * 16;
+        qp[x] = q_head(group * F.gs + head) + (int64_t)i * D * ES + (4 * pc + kg) * 16;
     }
     // The KV head of unit u is u / split, and a group's units are NG apart.  Where whole KV heads run
     // side by side (NG a multiple of split) the K pointers move by the same amount every iteration;
@@ -330,10 +349,15 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
     const bool even_steps = F.NG % F.split == 0;
     const int64_t kstep_even = (int64_t)(F.NG / F.split) * G.k_hs;
     auto kstep_to = [&](const int itn) -> int64_t {   // from the K of the group's unit itn - 1 to that of unit itn
+        if constexpr (LAYERS) return k_head((group + itn * F.NG) / F.split) - k_head((group + (itn - 1) * F.NG) / F.split);
         if (even_steps) return kstep_even;
         return (int64_t)((group + itn * F.NG) / F.split - (group + (itn - 1) * F.NG) / F.split) * G.k_hs;
     };
-    const int64_t qstep = (int64_t)F.NG * F.gs * G.W * D * ES;
+    const int64_t qstep_even = (int64_t)F.NG * F.gs * G.W * D * ES;
+    auto qstep_to = [&](const int itn) -> int64_t {   // the same for Q (a unit's query heads lie in one layer)
+        if constexpr (LAYERS) return q_head((group + itn * F.NG) * F.gs) - q_head((group + (itn - 1) * F.NG) * F.gs);
+        return qstep_even;
+    };
 
     // K tiles are consumed in two halves so that the memory pipeline never runs dry: the lower
     // KL tiles of a unit meet Q at the end of the previous iteration (their accumulators take
@@ -406,7 +430,7 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
     // MFMAs at the end of an iteration (first half of the lower tiles, for the unit two ahead),
     // point 0 comes a quarter of an iteration later (their second half, by then for the next
     // unit), points 1 and 2 re-request the halves of the upper tiles for the next unit.
-    auto issue_q = [&]() {
+    auto issue_q = [&](const int64_t qstep) {
 #pragma unroll
         for (int x = 0; x < QPW; ++x) {
             qp[x] += qstep;
@@ -474,7 +498,7 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
         __builtin_amdgcn_sched_barrier(0);
 
         // ---- C. the next unit's Q and upper K tiles follow in portions between the steps below
-        SNAPKV_ISSUE(kNext1, issue_q());
+        SNAPKV_ISSUE(kNext1, issue_q(qstep_to(it + 1)));
 
         float mref[RUW][4], zs[RUW][4];
         if (has_p1) {
@@ -739,6 +763,13 @@ __global__ __launch_bounds__(NW * 64) void score_fused(const void* __restrict__ 
                                                        float* __restrict__ vote, const FusedSync S,
                                                        const ScoreGeom G, const FusedGeom F) {
     score_fused_body<T, D, RUW, KT, NW>(qv, kv, vote, S, G, F, (int)blockIdx.x);
+}
+
+template <typename T, int D, int RUW, int KT, int NW>
+__global__ __launch_bounds__(NW * 64) void score_fused_layers(float* __restrict__ vote, const FusedSync S,
+                                                              const ScoreGeom G, const FusedGeom F,
+                                                              const ScoreLayers SL) {
+    score_fused_body<T, D, RUW, KT, NW, true>(nullptr, nullptr, vote, S, G, F, (int)blockIdx.x, &SL);
 }
 
 // Several prompts of one model in one launch: every prompt has its own groups of workgroups
@@ -1554,6 +1585,55 @@ hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, co
     if (F.BH > 1 && !block_geom(G, &Gl)) return hipErrorInvalidValue;
     const FusedCall call{q, k, &Gl, &F, &S, vote, st};
     return fused_dispatch(dtype, D, F.NW, F.RUW, &call, nullptr);
+}
+
+// ---- the heads of several separately allocated layers in one launch
+template <typename T, int D, int RUW>
+static hipError_t layers_instance(const ScoreLayers& SL, const ScoreGeom& G, const FusedGeom& F, const FusedSync& S,
+                                  float* vote, hipStream_t st, bool probe_only) {
+    constexpr int NW = kFusedWaves, KT = kFusedSlots / RUW;
+    auto kern = score_fused_layers<T, D, RUW, KT, NW>;
+    constexpr int kQueueBytes = fused_lds_bytes<T, D, RUW, NW>();
+    static int cached_occ = -1;
+    if (cached_occ < 0) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kQueueBytes);
+        if (e != hipSuccess) return e;
+        int n = 0;
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kern, NW * 64, kQueueBytes);
+        if (e != hipSuccess) return e;
+        cached_occ = n;
+    }
+    if ((int64_t)F.NG * F.Gg > resident_slots(cached_occ)) return hipErrorCooperativeLaunchTooLarge;
+    if (probe_only) return hipSuccess;
+    hipLaunchKernelGGL(kern, dim3(F.NG * F.Gg), dim3(NW * 64), kQueueBytes, st, vote, S, G, F, SL);
+    return hipGetLastError();
+}
+
+template <typename T, int D>
+static hipError_t layers_by_rows(const ScoreLayers& SL, const ScoreGeom& G, const FusedGeom& F, const FusedSync& S,
+                                 float* vote, hipStream_t st, bool probe_only) {
+    switch (F.RUW) {
+        case 1: return layers_instance<T, D, 1>(SL, G, F, S, vote, st, probe_only);
+        case 2: return layers_instance<T, D, 2>(SL, G, F, S, vote, st, probe_only);
+        case 4: return layers_instance<T, D, 4>(SL, G, F, S, vote, st, probe_only);
+        case 8: return layers_instance<T, D, 8>(SL, G, F, S, vote, st, probe_only);
+    }
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_score_fused_layers(int dtype, int D, const ScoreLayers& SL, const ScoreGeom& G, const FusedGeom& F,
+                                     const FusedSync& S, float* vote, hipStream_t st, bool probe_only) {
+    if (SL.count < 1 || SL.count > kMaxLayerPtrs || SL.kv_heads < 1 || SL.count * SL.kv_heads != G.Hkv) return hipErrorInvalidValue;
+    if (F.BH != 1 || F.NW != kFusedWaves || G.k_table || G.n <= 0) return hipErrorInvalidValue;
+    if (dtype == 0) {
+        if (D == 128) return layers_by_rows<bf16_k, 128>(SL, G, F, S, vote, st, probe_only);
+        if (D == 64) return layers_by_rows<bf16_k, 64>(SL, G, F, S, vote, st, probe_only);
+    } else if (dtype == 2) {
+        if (D == 128) return layers_by_rows<f16_k, 128>(SL, G, F, S, vote, st, probe_only);
+        if (D == 64) return layers_by_rows<f16_k, 64>(SL, G, F, S, vote, st, probe_only);
+    }
+    return hipErrorInvalidValue;
 }
 
 // ---- the streaming kernel: probabilities from a given log-sum-exp, or the row statistics that give it

@@ -49,6 +49,23 @@ __device__ __forceinline__ int64_t physical_row(const int32_t* table, int page, 
     return pg * page + j % page;
 }
 
+// Layers of one prompt that are separate allocations (passed to kernels by value).  Head h of the call is head
+// h % kv_heads of layer h / kv_heads; every layer has the contiguous [heads, rows, D] layout.
+constexpr int kMaxLayerPtrs = 32;
+struct ScoreLayers {
+    int count, kv_heads;
+    const void* q[kMaxLayerPtrs];
+    const void* k[kMaxLayerPtrs];
+};
+struct GatherLayers {
+    int count, heads;        // heads: output heads per layer
+    const void* k[kMaxLayerPtrs];
+    const void* v[kMaxLayerPtrs];
+    void* out_k[kMaxLayerPtrs];
+    void* out_v[kMaxLayerPtrs];
+    int32_t* out_idx[kMaxLayerPtrs];
+};
+
 // Plan of the single-read scoring kernel (snapkv_fused.hip).  A unit is a KV head or one of
 // `split` equal parts of its query heads; its window
 // rows form RU units of 16 rows (UH per query head), padded to RUW, a power of two; a wave keeps
@@ -149,6 +166,10 @@ hipError_t launch_score_fused_joint(int dtype, int D, int count, const void* con
                                     const int* wg_begin, int grid, hipStream_t st);
 hipError_t launch_score_fused(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                               const FusedGeom& F, const FusedSync& S, float* vote, hipStream_t st);
+// The same launch over the heads of SL.count layers (two-byte element types, F.BH == 1); returns
+// hipErrorCooperativeLaunchTooLarge when this form of the kernel cannot keep the plan's grid resident.
+hipError_t launch_score_fused_layers(int dtype, int D, const ScoreLayers& SL, const ScoreGeom& G, const FusedGeom& F,
+                                     const FusedSync& S, float* vote, hipStream_t st, bool probe_only = false);
 unsigned read_sync_timeouts();
 bool reset_sync_timeouts();     // (test hook) both synchronise the device
 bool reset_select_timeouts();
@@ -260,6 +281,10 @@ hipError_t launch_gather(const void* k, const void* v, const int32_t* idx, int H
                          int64_t rows, int64_t out_stride, int row_bytes, void* out_k, void* out_v,
                          const RowLayout& kl, const RowLayout& vl, const CleanJob& clean, hipStream_t st,
                          int head_div = 1, const PageMap& pm = PageMap{});
+// The gather over the heads of GL.count separately allocated layers (contiguous rows, not paged): positions come
+// from idx [GL.count * GL.heads, out_stride] and are copied to the layers' own out_idx as well.
+hipError_t launch_gather_layers(const GatherLayers& GL, const int32_t* idx, int64_t L, int64_t rows, int64_t out_stride,
+                                int row_bytes, const CleanJob& clean, hipStream_t st);
 
 }  // namespace snapkv
 #endif

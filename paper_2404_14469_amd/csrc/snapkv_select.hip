@@ -2,6 +2,7 @@
 // (Eq. 2; Listing 1, the topk call) and the gather of the kept rows (Listing 1, the two
 // gathers and concatenations).
 #include "snapkv_internal.h"
+#include <type_traits>
 
 namespace snapkv {
 
@@ -399,27 +400,39 @@ hipError_t launch_iota(int H, int64_t rows, int64_t out_stride, int32_t* out_idx
 
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4_nt;
 
+struct NoLayers {};
+
 // Each thread moves 16 bytes of a K row and the matching 16 bytes of the V row; consecutive
 // threads cover consecutive pieces of a row, so a 256-byte row is one coalesced 16-lane access.
 // Every row is read once and written once: the non-temporal policy keeps both out of the way of
-// the next call's K stream.
-__global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
-                                                   const uint4* __restrict__ v,
-                                                   const int32_t* __restrict__ idx,
-                                                   const int64_t L /* rows per head of k and v */,
-                                                   const int64_t rows, const int64_t out_stride,
-                                                   const int pieces /* 16-byte pieces per row */,
-                                                   uint4* __restrict__ out_k,
-                                                   uint4* __restrict__ out_v, const RowLayout kl,
-                                                   const RowLayout vl /* strides in 16-byte pieces */,
-                                                   const int head_div /* output heads per source head */,
-                                                   const PageMap pm, const CleanJob clean) {
+// the next call's K stream.  LY = GatherLayers: head h is head h % ly.heads of the separately allocated
+// layer h / ly.heads (k, v, out_k and out_v are then unused) and the positions are copied to that layer's
+// out_idx as well.
+template <typename LY>
+__device__ __forceinline__ void gather_body(const uint4* __restrict__ k, const uint4* __restrict__ v,
+                                            const int32_t* __restrict__ idx, const int64_t L, const int64_t rows,
+                                            const int64_t out_stride, const int pieces, uint4* __restrict__ out_k,
+                                            uint4* __restrict__ out_v, const RowLayout& kl, const RowLayout& vl,
+                                            const int head_div, const PageMap& pm, const CleanJob& clean, const LY& ly) {
+    constexpr bool LAYERS = std::is_same<LY, GatherLayers>::value;
     const int h = blockIdx.y;
     const int64_t total = rows * pieces;
-    const uint4* kb = k + (int64_t)(h / head_div) * kl.head_stride;
-    const uint4* vb = v + (int64_t)(h / head_div) * vl.head_stride;
-    uint4* okb = out_k + (int64_t)h * out_stride * pieces;
-    uint4* ovb = out_v + (int64_t)h * out_stride * pieces;
+    const uint4 *kb, *vb;
+    uint4 *okb, *ovb;
+    int32_t* ob = nullptr;
+    if constexpr (LAYERS) {
+        const int layer = h / ly.heads, hh = h % ly.heads;
+        kb = static_cast<const uint4*>(ly.k[layer]) + (int64_t)(hh / head_div) * kl.head_stride;
+        vb = static_cast<const uint4*>(ly.v[layer]) + (int64_t)(hh / head_div) * vl.head_stride;
+        okb = static_cast<uint4*>(ly.out_k[layer]) + (int64_t)hh * out_stride * pieces;
+        ovb = static_cast<uint4*>(ly.out_v[layer]) + (int64_t)hh * out_stride * pieces;
+        ob = ly.out_idx[layer] + (int64_t)hh * out_stride;
+    } else {
+        kb = k + (int64_t)(h / head_div) * kl.head_stride;
+        vb = v + (int64_t)(h / head_div) * vl.head_stride;
+        okb = out_k + (int64_t)h * out_stride * pieces;
+        ovb = out_v + (int64_t)h * out_stride * pieces;
+    }
     const int32_t* ib = idx + (int64_t)h * out_stride;
     // Four pieces per thread and pass, a grid stride apart: the positions are fetched first, then all
     // eight loads are in flight together, then the stores; a thread's two dependent memory latencies
@@ -429,6 +442,7 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
     for (int64_t e0 = (int64_t)blockIdx.x * 256 + threadIdx.x; e0 < total; e0 += U * stride) {
         int64_t r[U], src[U];
         int c[U];
+        int32_t raw[U];
         bool on[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -436,7 +450,8 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
             on[u] = e < total;
             r[u] = on[u] ? e / pieces : 0;
             c[u] = on[u] ? (int)(e - r[u] * pieces) : 0;
-            int64_t pos = ib[r[u]];
+            raw[u] = ib[r[u]];
+            int64_t pos = raw[u];
             pos = pos < 0 ? 0 : (pos < L ? pos : L - 1);   // whatever idx holds, the read stays inside the prompt
             src[u] = pos;
         }
@@ -452,6 +467,8 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
             if (on[u]) {
                 __builtin_nontemporal_store(a[u], reinterpret_cast<u32x4_nt*>(&okb[r[u] * pieces + c[u]]));
                 __builtin_nontemporal_store(b[u], reinterpret_cast<u32x4_nt*>(&ovb[r[u] * pieces + c[u]]));
+                if constexpr (LAYERS)
+                    if (c[u] == 0) ob[r[u]] = raw[u];
             }
     }
     // the call's scratch is no longer read by anything: leave it ready for the next call
@@ -465,6 +482,27 @@ __global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
         if (gave_up && clean.sticky) __hip_atomic_store(clean.sticky, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         if (clean.flag) *clean.flag = 0u;
     }
+}
+
+__global__ __launch_bounds__(256) void gather_rows(const uint4* __restrict__ k,
+                                                   const uint4* __restrict__ v,
+                                                   const int32_t* __restrict__ idx,
+                                                   const int64_t L /* rows per head of k and v */,
+                                                   const int64_t rows, const int64_t out_stride,
+                                                   const int pieces /* 16-byte pieces per row */,
+                                                   uint4* __restrict__ out_k,
+                                                   uint4* __restrict__ out_v, const RowLayout kl,
+                                                   const RowLayout vl /* strides in 16-byte pieces */,
+                                                   const int head_div /* output heads per source head */,
+                                                   const PageMap pm, const CleanJob clean) {
+    gather_body(k, v, idx, L, rows, out_stride, pieces, out_k, out_v, kl, vl, head_div, pm, clean, NoLayers{});
+}
+
+__global__ __launch_bounds__(256) void gather_rows_layers(const GatherLayers ly, const int32_t* __restrict__ idx,
+                                                          const int64_t L, const int64_t rows, const int64_t out_stride,
+                                                          const int pieces, const RowLayout kl, const RowLayout vl,
+                                                          const CleanJob clean) {
+    gather_body(nullptr, nullptr, idx, L, rows, out_stride, pieces, nullptr, nullptr, kl, vl, 1, PageMap{}, clean, ly);
 }
 
 // Per-head valid prefix lengths of a batch: head h of the batch belongs to prompt h / Hkv.
@@ -517,6 +555,21 @@ hipError_t launch_gather_batch(const BatchDesc& B, const int32_t* idx, int64_t C
     unsigned bx = (unsigned)((total + 255) / 256);
     if (bx > 1024) bx = 1024;
     hipLaunchKernelGGL(gather_rows_batch, dim3(bx, B.count * B.Hkv), dim3(256), 0, st, B, idx, C, pieces, clean);
+    return hipGetLastError();
+}
+
+hipError_t launch_gather_layers(const GatherLayers& GL, const int32_t* idx, int64_t L, int64_t rows, int64_t out_stride,
+                                int row_bytes, const CleanJob& clean, hipStream_t st) {
+    if (GL.count < 1 || GL.count > kMaxLayerPtrs || GL.heads < 1 || L < 1 || (int64_t)GL.count * GL.heads > 65535)
+        return hipErrorInvalidValue;
+    if (rows <= 0) return hipSuccess;
+    const int pieces = row_bytes / 16;
+    const int64_t total = rows * pieces;
+    unsigned bx = (unsigned)((total + 1023) / 1024);
+    if (bx > 4096) bx = 4096;
+    const RowLayout rl{L * pieces, pieces};   // contiguous [heads, L, D] in 16-byte pieces
+    hipLaunchKernelGGL(gather_rows_layers, dim3(bx, GL.count * GL.heads), dim3(256), 0, st, GL, idx, L, rows, out_stride,
+                       pieces, rl, rl, clean);
     return hipGetLastError();
 }
 

@@ -113,3 +113,29 @@ def test_bad_layer_is_refused_before_anything_runs(snapkv):
         snapkv.snapkv_compress_layers(list(q), list(k), list(v), 0, 6, w.C, oks, ovs, ois)
     torch.cuda.synchronize()
     assert all(int(t.min()) == -7 and int(t.max()) == -7 for t in ois)
+
+
+def test_many_separate_layers_more_heads_than_stay_resident(snapkv):
+    """40 separately allocated layers: two runs through the table of layer addresses (at most 32 layers each), with
+    more heads than the cooperative selection keeps resident."""
+    w, cases = layer_cases(40, Hq=8, Hkv=8, L=1500, C=160)
+    oks, ovs, ois = outputs(w, 40, cases[0]["k"].dtype, stack=False)
+    snapkv.snapkv_compress_layers([c["q_win"] for c in cases], [c["k"] for c in cases], [c["v"] for c in cases],
+                                  w.pool_kind, w.p, w.C, oks, ovs, ois)
+    torch.cuda.synchronize()
+    compare(snapkv, w, cases, oks, ovs, ois, oracle_on=(0, 39))
+    assert snapkv.snapkv_sync_timeouts() == 0
+
+
+@pytest.mark.parametrize("name", ["gqa_avg_w16", "d64_f16", "w64_p13", "f32_tiny"])
+def test_separate_layers_of_other_shapes(snapkv, name):
+    """Grouped-query heads, 16-row windows, D = 64 (table of layers); W = 64 and fp32 (one by one inside the call)."""
+    kw = dict(SHAPES[name])
+    n_layers = kw.pop("n_layers")
+    w, cases = layer_cases(n_layers, **kw)
+    oks, ovs, ois = outputs(w, n_layers, cases[0]["k"].dtype, stack=False)
+    snapkv.snapkv_compress_layers([c["q_win"] for c in cases], [c["k"] for c in cases], [c["v"] for c in cases],
+                                  w.pool_kind, w.p, w.C, oks, ovs, ois)
+    torch.cuda.synchronize()
+    compare(snapkv, w, cases, oks, ovs, ois, oracle_on=(n_layers - 1,))
+    assert snapkv.snapkv_sync_timeouts() == 0
