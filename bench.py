@@ -255,20 +255,29 @@ def time_steps(torch, step, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
-def run_layers(torch, snapkv, workloads, w, nlay, steps, warmup, dev, stages=True):
-    """All `nlay` layers resident as stacked tensors; a step is one snapkv_compress_layers call over them."""
+def run_layers(torch, snapkv, workloads, w, nlay, steps, warmup, dev, stages=True, separate=False):
+    """All `nlay` layers resident, as stacked tensors or (separate) with q_win, k and v of every layer an
+    allocation of its own; a step is one snapkv_compress_layers call over them."""
     tdt = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}[w.dtype]
-    K = torch.empty((nlay, w.Hkv, w.L, w.D), device=dev, dtype=tdt)
-    V = torch.empty_like(K)
-    Q = torch.empty((nlay, w.Hq, w.W, w.D), device=dev, dtype=tdt)
     needles = []
-    for l in range(nlay):
-        c = workloads.generate(w, layer=l, device=dev)
-        K[l].copy_(c["k"])
-        V[l].copy_(c["v"])
-        Q[l].copy_(c["q_win"])
-        needles.append(c["needle_pos"])
-        del c
+    if separate:
+        Q, K, V, gaps = [], [], [], []
+        for l in range(nlay):
+            c = workloads.generate(w, layer=l, device=dev)
+            Q.append(c["q_win"]), K.append(c["k"]), V.append(c["v"])
+            gaps.append(torch.empty(4096 + 512 * l, dtype=torch.uint8, device=dev))   # keeps the allocations apart
+            needles.append(c["needle_pos"])
+    else:
+        K = torch.empty((nlay, w.Hkv, w.L, w.D), device=dev, dtype=tdt)
+        V = torch.empty_like(K)
+        Q = torch.empty((nlay, w.Hq, w.W, w.D), device=dev, dtype=tdt)
+        for l in range(nlay):
+            c = workloads.generate(w, layer=l, device=dev)
+            K[l].copy_(c["k"])
+            V[l].copy_(c["v"])
+            Q[l].copy_(c["q_win"])
+            needles.append(c["needle_pos"])
+            del c
     ok = torch.empty((nlay, w.Hkv, w.C, w.D), dtype=tdt, device=dev)
     ov = torch.empty_like(ok)
     oi = torch.full((nlay, w.Hkv, w.C), -1, dtype=torch.int32, device=dev)
@@ -426,6 +435,9 @@ def main() -> int:
                          "single: a step is one snapkv_compress call on one layer, steps cycle over the resident layers")
     ap.add_argument("--resident-layers", type=int, default=0,
                     help="layers kept in HBM (default: all layers of the workload in layers mode, 4 in single mode)")
+    ap.add_argument("--separate-layers", action="store_true",
+                    help="layers mode: q_win, k and v of every layer are allocations of their own instead of slices of "
+                         "stacked tensors (the call then reaches them through its table of layer addresses)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-configs", action="store_true", help="leave out the other configurations' lines (`configs`)")
     ap.add_argument("--scheme", type=int, default=0,
@@ -649,7 +661,7 @@ def bench_layers(args, torch, np, snapkv, workloads, w, dev) -> int:
     long-context configuration), a step is ONE snapkv_compress_layers call that runs the whole hot path
     (score -> vote -> pool -> top-k -> gather) over all of them."""
     nlay = max(1, args.resident_layers or w.layers)
-    r = run_layers(torch, snapkv, workloads, w, nlay, args.steps, args.warmup, dev)
+    r = run_layers(torch, snapkv, workloads, w, nlay, args.steps, args.warmup, dev, separate=args.separate_layers)
     if snapkv.snapkv_sync_timeouts() != 0:
         print("bench.py: a bounded wait inside a kernel gave up during the timed calls", file=sys.stderr)
         return 1
@@ -665,7 +677,7 @@ def bench_layers(args, torch, np, snapkv, workloads, w, dev) -> int:
     path_achieved = nlay * (scan_b + gather_b) / (ms_per_step * 1e-3) / 1e9
     kernel = "+".join(score_names)
     traffic, traffic_note = (None, "not looked up")
-    if nlay == w.layers and args.scheme == 0:
+    if nlay == w.layers and args.scheme == 0 and not args.separate_layers:
         traffic, traffic_note = measured_traffic(w.name, kernel)
     roofline = {
         "bound": "hbm",
@@ -735,6 +747,7 @@ def bench_layers(args, torch, np, snapkv, workloads, w, dev) -> int:
                    "pool": ("max" if w.pool_kind == 0 else "avg"), "p": w.p, "C": w.C,
                    "step": f"{nlay} layers, one snapkv_compress_layers call", "layers_per_step": nlay,
                    "ms_per_layer": round(ms_per_layer, 4), "entry": "compress_layers", "layout": "head_major",
+                   "layer_tensors": "separate allocations" if args.separate_layers else "stacked",
                    "resident_layers": nlay, "resident_kv_bytes": 2 * nlay * w.Hkv * w.L * w.D * 2, "scheme": args.scheme,
                    "needle_kept": needle_kept, "token_layers_per_s": round(nlay * w.L / (ms_per_step * 1e-3), 1)},
         "roofline": roofline,
