@@ -66,7 +66,9 @@ const char* snapkv_strerror(int code);
  *
  *   q_win   [Hq, W, D]   device, bf16: the last W prompt queries of every query head
  *   k, v    [Hkv, L, D]  device, bf16: all prompt keys / values
- *   L       prompt length; Hq, Hkv head counts (Hq % Hkv == 0); D in {64, 128}; W window length
+ *   L       prompt length; Hq, Hkv head counts (Hq % Hkv == 0); D in {64, 128}; W window length:
+ *           1..128 rows, or more in whole blocks of 32 rows (160, 192, ...; such a window is scored block by
+ *           block); other lengths return SNAPKV_ERR_UNSUPPORTED (the paper's settings are 16, 32 and 64)
  *   pool_kind SNAPKV_POOL_MAX or SNAPKV_POOL_AVG; p odd pooling width (1..129); C capacity (>= W)
  *   out_k, out_v [Hkv, C, D] device, bf16: kept rows, prefix rows in ascending position order
  *                            followed by the W window rows

@@ -8,7 +8,7 @@ import sys
 PKG = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libsnapkv.so")
-SOURCES = ["snapkv_api.hip", "snapkv_score.hip", "snapkv_fused.hip", "snapkv_select.hip", "snapkv_topk.hip",
+SOURCES = ["snapkv_api.hip", "snapkv_geom.hip", "snapkv_fused.hip", "snapkv_select.hip", "snapkv_topk.hip",
            "snapkv_decode.hip", "snapkv_hitrate.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # Packed-fp32 instruction selection is switched off for all device code.

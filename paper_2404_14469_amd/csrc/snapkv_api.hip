@@ -177,7 +177,7 @@ int static_scratch(void** out) {
 // single-read kernel on the front part of a prompt too long for it and streaming passes on the rest (the
 // same, *F = LP->Ff), two streaming passes (the hand-off words stay untouched; *F is their plan), or the
 // 32x32 two-pass kernels.
-enum { kPathOld = 0, kPathFused = 1, kPathStream = 2, kPathLong = 3 };
+enum { kPathNone = 0, kPathFused = 1, kPathStream = 2, kPathLong = 3 };
 int scoring_path(int dtype, int D, const ScoreGeom& G, bool lse_given, bool allow_blocks, bool allow_long,
                  FusedGeom* F, LongPlan* LP) {
     if (!lse_given && g_allow_fused) {
@@ -187,7 +187,7 @@ int scoring_path(int dtype, int D, const ScoreGeom& G, bool lse_given, bool allo
             return kPathLong;
         }
     }
-    return lse_plan(dtype, D, G, F) ? kPathStream : kPathOld;
+    return lse_plan(dtype, D, G, F, allow_blocks && !lse_given) ? kPathStream : kPathNone;
 }
 
 // Whether the heads of several separately allocated layers can go through the kernels as one call: the
@@ -277,16 +277,16 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
         stage_done(st, kStagePass2);
         Gp.NV = G.g;
         Gp.VB = 1;
-    } else if (lse_plan(dtype, D, G, &F)) {
+    } else if (path == kPathStream) {
         // two streaming passes over K with nothing handed between workgroups: the rows'
         // log-sum-exp first, then the probabilities from it
         if (launch_row_lse(dtype, D, q_win, k, G, F, ws.stat_part, ws.lse, st) != hipSuccess) return SNAPKV_ERR_HIP;
         if (launch_score_lse(dtype, D, q_win, k, ws.lse, G, F, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
         stage_done(st, kStagePass2);
-        Gp.NV = G.g;
-        Gp.VB = 1;
-    } else if (launch_score(dtype, D, q_win, k, G, ws, st) != hipSuccess) {   // more window rows than a wave tracks
-        return SNAPKV_ERR_HIP;
+        Gp.NV = G.g * F.BH;
+        Gp.VB = F.BH;
+    } else {   // a window of more than 128 rows that is not a whole number of 32-row blocks, or whose caller needs one vote row per head
+        return SNAPKV_ERR_UNSUPPORTED;
     }
     if (Gv) *Gv = Gp;
     if (!score) return SNAPKV_OK;
@@ -416,14 +416,19 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
         Gsel.NV = 1;
         Gsel.VB = 1;
     }
+    // which scoring path run_scores will take, and how many vote rows per query head it leaves
+    FusedGeom Fp;
+    LongPlan LPp;
+    const int path = scoring_path(dtype, D, G, lse != nullptr, blocks_ok, !score_layers, &Fp, &LPp);
+    if (path == kPathNone) return SNAPKV_ERR_UNSUPPORTED;
+    if (!per_query_head && (path == kPathFused || path == kPathStream)) {
+        Gsel.VB = Fp.BH;
+        Gsel.NV = G.g * Fp.BH;
+    }
     if (g_allow_pool_select && pool_select_ok(Gsel, pool_kind, p, C - W)) {   // pooling and selection in one launch
         bool prepared = false;
-        FusedGeom Fp;
-        // which scoring path run_scores will take (the state of the 32x32 two-pass kernels is not tracked)
-        LongPlan LPp;
-        const int path = scoring_path(dtype, D, G, lse != nullptr, blocks_ok, !score_layers, &Fp, &LPp);
         streaming = path == kPathStream;
-        if (own_scratch && path != kPathOld) {
+        if (own_scratch && path != kPathNone) {
             int dev = 0;
             if (hipGetDevice(&dev) == hipSuccess && dev >= 0 && dev < kMaxDevices) {
                 // the streaming path does not touch the hand-off words

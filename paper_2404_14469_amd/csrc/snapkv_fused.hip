@@ -965,7 +965,8 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
                 for (int ru = 0; ru < RUW; ++ru)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
-                        const int i = (ru % F.UH) * 16 + kg * 4 + r;
+                        // the row's place in the window (blocks of a longer window are heads to this kernel)
+                        const int i = (ru % F.UH) * 16 + kg * 4 + r + ((unit * F.gs + ru / F.UH) % F.BH) * 32;
                         if (j > nn + i || j >= LL) e[ru][t][r] = -INFINITY;   // prompt-phase causal mask
                     }
             }
@@ -1193,9 +1194,7 @@ static bool block_geom(const ScoreGeom& G, ScoreGeom* Gs) {
     *Gs = G;
     Gs->g = G.g * G.BH;
     Gs->W = 32;
-    Gs->mode16 = 0;
     Gs->BH = 1;
-    Gs->R32 = Gs->g;
     Gs->VB = 1;
     Gs->NV = Gs->g;
     return true;
@@ -1727,7 +1726,20 @@ static hipError_t lse_dispatch(int dtype, int D, int RUW, const LseCall* call, i
 // Launch plan of the streaming kernel (both modes share it).  Nothing waits across workgroups, so
 // residency is not a condition and the prompt length is not limited by the chip; the grid is still
 // sized to what is resident so that every workgroup streams from start to end.
-bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
+static bool lse_plan_for(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
+
+bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F, bool allow_blocks) {
+    if (lse_plan_for(dtype, D, G, F)) return true;
+    // more window rows than a wave tracks: every 32-row block of the window as a query head of its own
+    ScoreGeom Gs;
+    if (allow_blocks && block_geom(G, &Gs) && lse_plan_for(dtype, D, Gs, F)) {
+        F->BH = G.BH;
+        return true;
+    }
+    return false;
+}
+
+static bool lse_plan_for(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
     int cand[8];
     const int nc = fused_split_candidates(G, cand);
     for (int c = 0; c < nc; ++c) {
@@ -1754,14 +1766,19 @@ bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
 
 // Bytes of per-slice row statistics that cover whichever split lse_plan ends up choosing.
 size_t stream_stat_bytes(const ScoreGeom& G) {
-    int cand[8];
-    const int nc = fused_split_candidates(G, cand);
     size_t most = 0;
-    for (int i = 0; i < nc; ++i) {
-        FusedGeom F;
-        if (!fused_shape_nw(G, kFusedWaves, cand[i], &F, false)) continue;
-        const size_t b = sizeof(float2) * (size_t)F.units * F.Gg * F.RUW * 16;
-        most = b > most ? b : most;
+    ScoreGeom Gs;
+    const ScoreGeom* geoms[2] = {&G, block_geom(G, &Gs) ? &Gs : nullptr};
+    for (const ScoreGeom* g : geoms) {
+        if (!g) continue;
+        int cand[8];
+        const int nc = fused_split_candidates(*g, cand);
+        for (int i = 0; i < nc; ++i) {
+            FusedGeom F;
+            if (!fused_shape_nw(*g, kFusedWaves, cand[i], &F, false)) continue;
+            const size_t b = sizeof(float2) * (size_t)F.units * F.Gg * F.RUW * 16;
+            most = b > most ? b : most;
+        }
     }
     return (most + 255) & ~(size_t)255;
 }
@@ -1769,7 +1786,9 @@ size_t stream_stat_bytes(const ScoreGeom& G) {
 hipError_t launch_score_lse(int dtype, int D, const void* q, const void* k, const float* lse,
                             const ScoreGeom& G, const FusedGeom& F, float* vote, hipStream_t st) {
     if (G.n <= 0) return hipSuccess;
-    const LseCall call{q, k, lse, &G, &F, vote, nullptr, st};
+    ScoreGeom Gl = G;
+    if (F.BH > 1 && !block_geom(G, &Gl)) return hipErrorInvalidValue;
+    const LseCall call{q, k, lse, &Gl, &F, vote, nullptr, st};
     return lse_dispatch<false>(dtype, D, F.RUW, &call, nullptr);
 }
 
@@ -1834,12 +1853,15 @@ hipError_t launch_row_lse(int dtype, int D, const void* q, const void* k, const 
                           const FusedGeom& F, float2* stat_part, float* lse_out, hipStream_t st, float* logit_out) {
     if (G.n <= 0) return hipSuccess;
     if (logit_out && F.RUW != 1) return hipErrorInvalidValue;
-    const LseCall call{q, k, nullptr, &G, &F, logit_out, stat_part, st};
+    ScoreGeom Gl = G;
+    if (F.BH > 1 && !block_geom(G, &Gl)) return hipErrorInvalidValue;
+    const LseCall call{q, k, nullptr, &Gl, &F, logit_out, stat_part, st};
     hipError_t e = lse_dispatch<true>(dtype, D, F.RUW, &call, nullptr);
     if (e != hipSuccess) return e;
     stage_done(st, kStagePass1);
     if (!lse_out) return hipGetLastError();
-    hipLaunchKernelGGL(lse_from_parts, dim3(F.units), dim3(1024), 0, st, stat_part, lse_out, G, F);
+    // (with blocks, row i of block b of a head is row 32 b + i of its window: the same place in lse_out)
+    hipLaunchKernelGGL(lse_from_parts, dim3(F.units), dim3(1024), 0, st, stat_part, lse_out, Gl, F);
     stage_done(st, kStageReduce);
     return hipGetLastError();
 }

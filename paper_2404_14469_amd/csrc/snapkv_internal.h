@@ -9,27 +9,17 @@
 
 namespace snapkv {
 
-// Keys per wave-task in the scoring kernels: KT tiles of 32 keys.
-constexpr int kTileKeys = 32;
-constexpr int kTilesPerChunk = 4;
-constexpr int kChunkKeys = kTileKeys * kTilesPerChunk;
-
-// How the g*W observation-window rows of one KV head are laid onto 32-row MFMA blocks.
-//   W <= 16 ("mode16"): a block holds two query heads, 16 rows each (rows >= W are padding).
-//   W  > 16           : a head takes BH = ceil(W/32) blocks of its own (rows >= W are padding).
-// A "vote row" is one fp32 vector of length n produced by one block (or half block in mode16).
+// Geometry of a scoring call.  A "vote row" is one fp32 vector of length n: one per query head, or (windows of
+// 64, 96, ... rows scored block by block) one per 32-row block of a query head's window.
 struct ScoreGeom {
     int64_t L;       // prompt length
     int64_t n;       // prefix length L - W
     int W;           // observation window
     int g;           // query heads per KV head
     int Hkv;         // KV heads
-    int mode16;      // 1 when W <= 16
-    int BH;          // 32-row blocks per query head (when !mode16)
-    int R32;         // 32-row blocks per KV head
+    int BH;          // 32-row blocks per query head, ceil(W / 32)
     int NV;          // vote rows per KV head
     int VB;          // vote rows per query head
-    int nchunks;     // ceil(L / kChunkKeys)
     float c2;        // log2(e) / sqrt(D): logits are kept in the base-2 domain
     int64_t k_hs;    // bytes between the K rows of consecutive KV heads (contiguous: L * D * element size)
     int64_t k_rs;    // bytes between consecutive K rows of a head (contiguous: D * element size)
@@ -112,9 +102,7 @@ struct SelectScratch {
 struct Workspace {
     unsigned* status_flag;   // first word of the block: set by a kernel whose bounded wait gave up, read and cleared by
                              // the call's last kernel
-    float2* part;    // [Hkv][nchunks][R32][32] per-chunk (row max, row sum-exp) in base-2 domain
-    float2* mz;      // [Hkv][R32][32]          (row max, 1 / row sum-exp); (0, 0) for padding rows
-    float* vote;     // [Hkv][NV][n]  (two-pass path) or [Hkv][g][n] (single-read path)
+    float* vote;     // [Hkv][NV][n]
     float* score;    // [Hkv][n]
     char* fused;     // hand-off buffers of the single-read path (see fused_sync_layout)
     float2* stat_part;   // [units][Gg][R] per-slice (row max, row sum-exp) of the streaming statistics pass
@@ -135,8 +123,6 @@ enum Stage { kStageBegin = 0, kStagePrepare, kStagePass1, kStageReduce, kStageFu
 void stage_done(hipStream_t st, int stage);
 
 // All launchers enqueue on `st` and return the launch status.
-hipError_t launch_score(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
-                        const Workspace& ws, hipStream_t st);
 size_t fused_sync_bytes(const ScoreGeom& G);
 // allow_blocks: the plan may treat the 32-row blocks of a window longer than 32 rows as query heads
 // of their own (F->BH > 1); the votes then have one row per block (NV = g * BH, VB = BH).
@@ -184,7 +170,8 @@ hipError_t launch_select_init(const SelectScratch& S, int H, hipStream_t st);
 hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, int H, hipStream_t st,
                           unsigned* flag = nullptr);
 int64_t fused_sync_pairs(const FusedGeom& F);
-bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F);
+// allow_blocks: as for fused_plan, taken only where a window has more rows than the plain form tracks
+bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F, bool allow_blocks = false);
 hipError_t launch_score_lse(int dtype, int D, const void* q, const void* k, const float* lse,
                             const ScoreGeom& G, const FusedGeom& F, float* vote, hipStream_t st);
 size_t stream_stat_bytes(const ScoreGeom& G);

@@ -499,3 +499,20 @@ def test_random_shapes_with_long_windows(snapkv, w):
     """Windows of two, three and four 32-row blocks: the single-read kernel scores them block by block
     (one vote row per block, summed before pooling); head counts, lengths, pooling and capacities as above."""
     gpu_vs_oracle(snapkv, w)
+
+
+def test_window_lengths_the_kernels_do_not_take_are_refused(snapkv):
+    """More than 128 window rows go through the kernels in whole 32-row blocks; other lengths are refused
+    before anything is enqueued (outputs untouched)."""
+    w = small("w130", W=130, L=900, C=300)
+    case = workloads.generate(w, device="cuda")
+    out_k = torch.zeros((w.Hkv, w.C, w.D), dtype=case["k"].dtype, device="cuda")
+    out_v = torch.zeros_like(out_k)
+    out_idx = torch.full((w.Hkv, w.C), -7, dtype=torch.int32, device="cuda")
+    with pytest.raises(snapkv.SnapKVError):
+        snapkv.snapkv_compress(case["q_win"], case["k"], case["v"], w.pool_kind, w.p, w.C, out_k, out_v, out_idx)
+    torch.cuda.synchronize()
+    assert int(out_idx.min()) == -7 and int(out_idx.max()) == -7
+    sc = torch.zeros((w.Hkv, w.n), dtype=torch.float32, device="cuda")
+    with pytest.raises(snapkv.SnapKVError):
+        snapkv.snapkv_pooled_scores(case["q_win"], case["k"], w.pool_kind, w.p, sc)
