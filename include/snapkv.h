@@ -49,7 +49,7 @@ extern "C" {
 
 #define SNAPKV_OK 0
 #define SNAPKV_ERR_INVALID_ARG (-1) /* null pointer, L<1, W<1, W>L, W>C, even p, bad pool_kind, Hq%Hkv!=0 */
-#define SNAPKV_ERR_UNSUPPORTED (-2) /* D not in {64,128}, p>129, L>=2^31, too many window rows */
+#define SNAPKV_ERR_UNSUPPORTED (-2) /* D not in {64,128}, p>129, L-W>2^24, a window length the kernels do not take */
 #define SNAPKV_ERR_MISALIGNED (-3)  /* a q/k/v/out_k/out_v pointer is not 16-byte aligned */
 #define SNAPKV_ERR_WORKSPACE (-4)   /* workspace missing or smaller than snapkv_workspace_bytes() */
 #define SNAPKV_ERR_HIP (-5)         /* a HIP call (allocation or launch) failed */
@@ -66,7 +66,7 @@ const char* snapkv_strerror(int code);
  *
  *   q_win   [Hq, W, D]   device, bf16: the last W prompt queries of every query head
  *   k, v    [Hkv, L, D]  device, bf16: all prompt keys / values
- *   L       prompt length; Hq, Hkv head counts (Hq % Hkv == 0); D in {64, 128}; W window length:
+ *   L       prompt length (L - W <= 2^24); Hq, Hkv head counts (Hq % Hkv == 0); D in {64, 128}; W window length:
  *           1..128 rows, or more in whole blocks of 32 rows (160, 192, ...; such a window is scored block by
  *           block); other lengths return SNAPKV_ERR_UNSUPPORTED (the paper's settings are 16, 32 and 64)
  *   pool_kind SNAPKV_POOL_MAX or SNAPKV_POOL_AVG; p odd pooling width (1..129); C capacity (>= W)
@@ -349,7 +349,7 @@ int snapkv_decode_attention(int dtype, const void* q, const void* k_cache, const
  * Top-(kcount) selection alone (Eq. 2), exposed for testing the selector on arbitrary scores:
  *   scores [H, n] device float32, all values >= +0 (their bit patterns are compared as unsigned
  *   integers); out_idx [H, kcount] device int32: the kcount best positions per row under
- *   (score descending, position ascending), emitted ascending.  0 <= kcount <= n < 2^31.
+ *   (score descending, position ascending), emitted ascending.  0 <= kcount <= n <= 2^24.
  */
 int snapkv_select_topk(const float* scores, int H, int64_t n, int64_t kcount, int32_t* out_idx,
                        void* stream);

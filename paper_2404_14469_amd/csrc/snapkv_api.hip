@@ -94,6 +94,7 @@ int check_score_args(const void* q_win, const void* k, int64_t L, int Hq, int Hk
     if (D != 64 && D != 128) return SNAPKV_ERR_UNSUPPORTED;
     if (p > 129) return SNAPKV_ERR_UNSUPPORTED;
     if (L >= (int64_t)1 << 31) return SNAPKV_ERR_UNSUPPORTED;
+    if (L > W && !select_chunked_ok(L - W)) return SNAPKV_ERR_UNSUPPORTED;   // prefixes of more than 2^24 positions
     if ((int64_t)(Hq / Hkv) * ((W + 31) / 32) > 4096) return SNAPKV_ERR_UNSUPPORTED;
     if (Hkv > 65535) return SNAPKV_ERR_UNSUPPORTED;
     if (!aligned16(q_win) || !aligned16(k)) return SNAPKV_ERR_MISALIGNED;
@@ -392,7 +393,6 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     workspace_layout(G, &ws, base);
     int32_t* const idx_dst = score_layers ? reinterpret_cast<int32_t*>(static_cast<char*>(base) + need_up) : out_idx;
     stage_done(st, kStageBegin);
-    const bool chunked = select_chunked_ok(G.n);
     hipError_t se;
     CleanJob clean;
     clean.flag = ws.status_flag;
@@ -458,20 +458,19 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     } else {
         if (per_query_head) {   // votes first, then pooled per query head
             ScoreGeom Gv = G;
-            rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, chunked, &Gv, st, false, nullptr, lse,
+            rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, true, &Gv, st, false, nullptr, lse,
                             false, true);
             if (rc != SNAPKV_OK) return rc;
             if (Gv.VB != 1 || Gv.NV != G.g) return SNAPKV_ERR_UNSUPPORTED;
-            if (launch_pool(Gsel, ws.vote, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr, st) != hipSuccess)
+            if (launch_pool(Gsel, ws.vote, pool_kind, p, ws.score, ws.sel.minmax, st) != hipSuccess)
                 return SNAPKV_ERR_HIP;
             stage_done(st, kStagePool);
         } else {
-            rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, chunked ? ws.sel.minmax : nullptr,
-                            chunked, nullptr, st, false, nullptr, lse, blocks_ok, !score_layers, score_layers);
+            rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, ws.sel.minmax,
+                            true, nullptr, st, false, nullptr, lse, blocks_ok, !score_layers, score_layers);
             if (rc != SNAPKV_OK) return rc;
         }
-        se = chunked ? launch_select_chunked(ws.score, Hout, G.n, C - W, C, W, idx_dst, ws.sel, pool_tiles(G.n), st)
-                     : launch_select(ws.score, Hout, G.n, C - W, C, W, idx_dst, st);
+        se = launch_select_chunked(ws.score, Hout, G.n, C - W, C, W, idx_dst, ws.sel, pool_tiles(G.n), st);
     }
     if (se != hipSuccess) return SNAPKV_ERR_HIP;
     stage_done(st, kStageSelect);
@@ -1059,11 +1058,9 @@ int snapkv_select_topk(const float* scores, int H, int64_t n, int64_t kcount, in
                        void* stream) {
     if (!scores || !out_idx) return SNAPKV_ERR_INVALID_ARG;
     if (H < 1 || n < 1 || kcount < 0 || kcount > n) return SNAPKV_ERR_INVALID_ARG;
-    if (n >= (int64_t)1 << 31) return SNAPKV_ERR_UNSUPPORTED;
+    if (!select_chunked_ok(n)) return SNAPKV_ERR_UNSUPPORTED;
     if (kcount == 0) return SNAPKV_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (!select_chunked_ok(n))
-        return launch_select(scores, H, n, kcount, kcount, 0, out_idx, st) == hipSuccess ? SNAPKV_OK : SNAPKV_ERR_HIP;
     void* base = nullptr;
     const int rc = internal_scratch(select_layout(H, n, nullptr, nullptr), &base);
     if (rc != SNAPKV_OK) return rc;

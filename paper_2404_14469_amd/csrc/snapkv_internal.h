@@ -164,7 +164,7 @@ hipError_t launch_pool(const ScoreGeom& G, const float* vote, int pool_kind, int
 size_t select_counter_bytes(int H);
 size_t select_layout(int H, int64_t n, SelectScratch* S, void* base, bool own_counters = true,
                      void* counters = nullptr);
-bool select_chunked_ok(int64_t n);
+bool select_chunked_ok(int64_t n);   // rows of up to 4096 x 4096 positions
 hipError_t launch_select_init(const SelectScratch& S, int H, hipStream_t st);
 // flag (may be null): the status word of the call's scratch, cleared too (default: S->ps_flag).
 hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, int H, hipStream_t st,
@@ -214,8 +214,6 @@ hipError_t launch_select_chunked(const float* score, int H, int64_t n, int64_t k
                                  int64_t out_stride, int W_tail, int32_t* out_idx,
                                  const SelectScratch& S, int minmax_parts, hipStream_t st);
 int pool_tiles(int64_t n);
-hipError_t launch_select(const float* score, int H, int64_t n, int64_t kcount, int64_t out_stride,
-                         int W_tail, int32_t* out_idx, hipStream_t st);
 hipError_t launch_iota(int H, int64_t rows, int64_t out_stride, int32_t* out_idx, hipStream_t st);
 // Scratch a call's last kernel puts back into the state the next call expects (hand-off words
 // all-ones, counters zero); all-null = nothing to do.

@@ -1,6 +1,5 @@
-// Pooling + group sum (Sec. 4.3; Listing 1, the pool1d call), per-head top-k selection
-// (Eq. 2; Listing 1, the topk call) and the gather of the kept rows (Listing 1, the two
-// gathers and concatenations).
+// Pooling + group sum (Sec. 4.3; Listing 1, the pool1d call) as a kernel of its own, and the gather of the
+// kept rows (Listing 1, the two gathers and concatenations).  The top-k selection is in snapkv_topk.hip.
 #include "snapkv_internal.h"
 #include <type_traits>
 
@@ -226,157 +225,6 @@ hipError_t launch_pool(const ScoreGeom& G, const float* vote, int pool_kind, int
         case 13: hipLaunchKernelGGL(pool_group<13>, grid, dim3(256), 0, st, vote, score, G, pool_kind, p, minmax); break;
         default: hipLaunchKernelGGL(pool_group<0>, grid, dim3(256), 0, st, vote, score, G, pool_kind, p, minmax); break;
     }
-    return hipGetLastError();
-}
-
-// ------------------------------------------------------------------------------------------
-// Selection.  Scores are >= +0, so their fp32 bit patterns order like unsigned integers.  One
-// workgroup of 1024 threads per head finds the bit pattern T of the kcount-th largest score
-// by three most-significant-digit-first histogram passes (11 + 11 + 10 bits), then emits, in
-// position order, every position with pattern > T and the first (kcount - #greater) positions
-// with pattern == T.  That is exactly the top-kcount under (score descending, position
-// ascending), already sorted by position.  No floating-point arithmetic, no atomics on
-// floats: the result is deterministic.
-// ------------------------------------------------------------------------------------------
-constexpr int kSelThreads = 1024;
-constexpr int kSelWaves = kSelThreads / 64;
-
-// Among bins [0, nb) of hist (nb = bins_per_thread * 1024), walking from the top bin down, find
-// the bin where the running count first reaches krem.  Thread 0 owns the highest bins.
-template <int BPT>
-__device__ __forceinline__ void find_bin(const unsigned* hist, unsigned krem, unsigned* sh_wave,
-                                         unsigned* sh_out /* [2]: bin, remaining */) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    constexpr int NB = BPT * kSelThreads;
-    unsigned mine = 0;
-#pragma unroll
-    for (int e = 0; e < BPT; ++e) mine += hist[NB - 1 - (tid * BPT + e)];
-    unsigned incl = mine;                       // inclusive scan within the wave
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const unsigned up = __shfl_up(incl, d, 64);
-        if (lane >= d) incl += up;
-    }
-    if (lane == 63) sh_wave[wave] = incl;
-    __syncthreads();
-    unsigned base = 0;
-    for (int w = 0; w < wave; ++w) base += sh_wave[w];
-    unsigned above = base + incl - mine;        // elements in strictly higher bins than mine
-#pragma unroll
-    for (int e = 0; e < BPT; ++e) {
-        const int b = NB - 1 - (tid * BPT + e);
-        const unsigned c = hist[b];
-        if (above < krem && krem <= above + c) {
-            sh_out[0] = (unsigned)b;
-            sh_out[1] = krem - above;
-        }
-        above += c;
-    }
-    __syncthreads();
-}
-
-__global__ __launch_bounds__(kSelThreads) void select_topk(const float* __restrict__ score,
-                                                          const int64_t n, const int64_t kcount,
-                                                          const int64_t out_stride, const int W_tail,
-                                                          int32_t* __restrict__ out_idx) {
-    __shared__ unsigned hist[2048];
-    __shared__ unsigned sh_wave[kSelWaves];
-    __shared__ unsigned sh_out[2];
-    __shared__ unsigned sh_gt[kSelWaves], sh_eq[kSelWaves];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const unsigned* s = reinterpret_cast<const unsigned*>(score) + (int64_t)blockIdx.x * n;
-    int32_t* out = out_idx + (int64_t)blockIdx.x * out_stride;
-
-    // window positions n .. n + W_tail - 1 follow the selected prefix positions
-    for (int t = tid; t < W_tail; t += kSelThreads) out[kcount + t] = (int32_t)(n + t);
-    if (kcount <= 0) return;
-
-    // ---- digit 1: bits 31..21 (bit 31 is the sign, zero for scores >= +0; a pattern with it
-    // set would simply order above all others, as an unsigned integer does)
-    for (int b = tid; b < 2048; b += kSelThreads) hist[b] = 0;
-    __syncthreads();
-    for (int64_t j = tid; j < n; j += kSelThreads) atomicAdd(&hist[s[j] >> 21], 1u);
-    __syncthreads();
-    find_bin<2>(hist, (unsigned)kcount, sh_wave, sh_out);
-    const unsigned d1 = sh_out[0];
-    unsigned krem = sh_out[1];
-    __syncthreads();
-
-    // ---- digit 2: bits 20..10 among patterns whose top 11 bits equal d1
-    for (int b = tid; b < 2048; b += kSelThreads) hist[b] = 0;
-    __syncthreads();
-    for (int64_t j = tid; j < n; j += kSelThreads) {
-        const unsigned x = s[j];
-        if ((x >> 21) == d1) atomicAdd(&hist[(x >> 10) & 2047u], 1u);
-    }
-    __syncthreads();
-    find_bin<2>(hist, krem, sh_wave, sh_out);
-    const unsigned d2 = sh_out[0];
-    krem = sh_out[1];
-    __syncthreads();
-    const unsigned top22 = (d1 << 11) | d2;
-
-    // ---- digit 3: bits 9..0 among patterns whose top 22 bits equal top22
-    for (int b = tid; b < 1024; b += kSelThreads) hist[b] = 0;
-    __syncthreads();
-    for (int64_t j = tid; j < n; j += kSelThreads) {
-        const unsigned x = s[j];
-        if ((x >> 10) == top22) atomicAdd(&hist[x & 1023u], 1u);
-    }
-    __syncthreads();
-    find_bin<1>(hist, krem, sh_wave, sh_out);
-    const unsigned T = (top22 << 10) | sh_out[0];
-    const unsigned need_eq = sh_out[1];         // how many positions equal to T are taken (>= 1)
-
-    // ---- ordered emission: wave w owns positions [w * seg, (w + 1) * seg)
-    const int64_t seg = ((n + kSelWaves - 1) / kSelWaves + 63) / 64 * 64;
-    const int64_t a = (int64_t)wave * seg;
-    const int64_t b = a + seg < n ? a + seg : n;
-    unsigned cgt = 0, ceq = 0;
-    for (int64_t j = a + lane; j < b; j += 64) {
-        const unsigned x = s[j];
-        cgt += x > T;
-        ceq += x == T;
-    }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        cgt += __shfl_xor(cgt, d, 64);
-        ceq += __shfl_xor(ceq, d, 64);
-    }
-    if (lane == 0) {
-        sh_gt[wave] = cgt;
-        sh_eq[wave] = ceq;
-    }
-    __syncthreads();
-    unsigned base_gt = 0, base_eq = 0;
-    for (int w = 0; w < wave; ++w) {
-        base_gt += sh_gt[w];
-        base_eq += sh_eq[w];
-    }
-    const unsigned long long lt_mask = (1ull << lane) - 1ull;
-    for (int64_t j0 = a; j0 < b; j0 += 64) {
-        const int64_t j = j0 + lane;
-        const unsigned x = j < b ? s[j] : 0u;
-        const bool gt = j < b && x > T;
-        const bool eq = j < b && x == T;
-        const unsigned long long mgt = __ballot(gt);
-        const unsigned long long meq = __ballot(eq);
-        const unsigned gt_before = base_gt + (unsigned)__popcll(mgt & lt_mask);
-        const unsigned eq_before = base_eq + (unsigned)__popcll(meq & lt_mask);
-        if (gt || (eq && eq_before < need_eq)) {
-            const unsigned pos = gt_before + (eq_before < need_eq ? eq_before : need_eq);
-            out[pos] = (int32_t)j;
-        }
-        base_gt += (unsigned)__popcll(mgt);
-        base_eq += (unsigned)__popcll(meq);
-    }
-}
-
-hipError_t launch_select(const float* score, int H, int64_t n, int64_t kcount, int64_t out_stride,
-                         int W_tail, int32_t* out_idx, hipStream_t st) {
-    if (H <= 0) return hipSuccess;
-    hipLaunchKernelGGL(select_topk, dim3(H), dim3(kSelThreads), 0, st, score, n, kcount, out_stride,
-                       W_tail, out_idx);
     return hipGetLastError();
 }
 

@@ -49,7 +49,7 @@ def compress_code(**kw):
     (dict(L=0), -1), (dict(W=0), -1), (dict(W=5000), -1), (dict(W=64, C=32), -1),
     (dict(p=4), -1), (dict(p=0), -1), (dict(p=-3), -1), (dict(kind=2), -1), (dict(Hq=12, Hkv=8), -1),
     (dict(Hkv=0), -1), (dict(C=0), -1),
-    (dict(D=96), -2), (dict(D=256), -2), (dict(p=131), -2), (dict(L=2**31), -2),
+    (dict(D=96), -2), (dict(D=256), -2), (dict(p=131), -2), (dict(L=2**31), -2), (dict(L=2**24 + 33), -2),
     (dict(q=ODD), -3), (dict(k=ODD), -3), (dict(v=ODD), -3), (dict(ok=ODD), -3), (dict(ov=ODD), -3),
     (dict(oi=0x1002), -3),
 ])
