@@ -592,7 +592,7 @@ def main() -> int:
 
     scan_b, gather_b = algorithmic_bytes(w)
     stage_ms = {n: v for n, v in stage_ms.items() if v > 0.0}      # stages this workload ran
-    score_names = [n for n in stage_ms if n.startswith("score") or n == "reduce_rows"]
+    score_names = [n for n in stage_ms if n.startswith("score")]
     score_ms = sum(stage_ms[n] for n in score_names)
     kernel_achieved = scan_b / (score_ms * 1e-3) / 1e9 if score_ms > 0 else 0.0
     path_achieved = (scan_b + gather_b) / (ms_per_step * 1e-3) / 1e9
@@ -671,7 +671,7 @@ def bench_layers(args, torch, np, snapkv, workloads, w, dev) -> int:
     value = positions / (ms_per_step * 1e-3)
     scan_b, gather_b = algorithmic_bytes(w)
     stage_ms = r["stage_ms"]
-    score_names = [n for n in stage_ms if n.startswith("score") or n == "reduce_rows"]
+    score_names = [n for n in stage_ms if n.startswith("score")]
     score_ms = sum(stage_ms[n] for n in score_names)          # one launch per call: all layers' keys
     kernel_achieved = nlay * scan_b / (score_ms * 1e-3) / 1e9 if score_ms > 0 else 0.0
     path_achieved = nlay * (scan_b + gather_b) / (ms_per_step * 1e-3) / 1e9

@@ -744,7 +744,7 @@ int64_t snapkv_sync_timeouts(void) {
 int snapkv_num_stages(void) { return kNumStageMarks - 1; }
 
 const char* snapkv_stage_name(int stage) {
-    static const char* names[] = {"prepare_scratch", "score_pass1", "reduce_rows", "score_fused", "score_pass2",
+    static const char* names[] = {"prepare_scratch", "score_stats", "score_merge", "score_fused", "score_stream",
                                   "pool_group", "select_topk", "gather_rows"};
     return stage >= 0 && stage < kNumStageMarks - 1 ? names[stage] : "";
 }

@@ -116,7 +116,7 @@ def test_grouped_query_prompts_whose_parts_follow_one_another(snapkv, L, heads):
     snapkv.snapkv_profile_start(4)
     _run(snapkv, w, 1, heads)
     ms, calls = snapkv.snapkv_profile_stop()
-    assert ms.get("score_fused", 0.0) > 0.0 and ms.get("score_pass2", 0.0) == 0.0, ms
+    assert ms.get("score_fused", 0.0) > 0.0 and ms.get("score_stream", 0.0) == 0.0, ms
     torch.cuda.empty_cache()
 
 
