@@ -99,3 +99,44 @@ def test_full_size_long_prompts(snapkv, L, W, p, C, heads):
         lo, hi = max(0, pos - w.p // 2), min(w.n - 1, pos + w.p // 2)
         assert set(range(lo, hi + 1)) <= set(idx[hk].tolist())
     assert snapkv.snapkv_sync_timeouts() == 0
+
+
+def test_other_entries_on_prompts_beyond_the_single_read_length(few_slots):
+    """Token-major K (the rest starts at a row offset, whatever the row stride), paged K (which takes two
+    streaming passes over all keys instead) and one cache per query head: each equals the plain call."""
+    from test_gpu_parity import _paged
+    snapkv = few_slots
+    w = Workload("long_entries", **dict(BASE, L=12000, Hq=8, Hkv=4, C=384))
+    case = workloads.generate(w, device="cuda")
+    q, k, v = case["q_win"], case["k"], case["v"]
+    ref = run_gpu(snapkv, q, k, v, w.pool_kind, w.p, w.C)
+    check_against_oracle(q, k, v, w.pool_kind, w.p, w.C, *ref)
+
+    def fresh():
+        return (torch.zeros_like(ref[1]), torch.zeros_like(ref[2]),
+                torch.full(ref[3].shape, -1, dtype=torch.int32, device="cuda"))
+
+    k_tm = k.permute(1, 0, 2).contiguous().permute(1, 0, 2)            # storage [L, Hkv, D]
+    v_tm = v.permute(1, 0, 2).contiguous().permute(1, 0, 2)
+    ok, ov, oi = fresh()
+    assert snapkv.snapkv_compress_strided(q, k_tm, v_tm, w.pool_kind, w.p, w.C, ok, ov, oi) == w.C
+    torch.cuda.synchronize()
+    assert np.array_equal(oi.cpu().numpy(), ref[3]) and torch.equal(ok, ref[1]) and torch.equal(ov, ref[2])
+
+    kp, vp, table = _paged(case, w, 16, seed=5)
+    ok, ov, oi = fresh()
+    assert snapkv.snapkv_compress_paged(q, kp, vp, table, w.L, w.pool_kind, w.p, w.C, ok, ov, oi) == w.C
+    torch.cuda.synchronize()
+    # (another scoring path: positions may differ where scores are within rounding of the threshold)
+    check_against_oracle(q, k, v, w.pool_kind, w.p, w.C, ref[0], ok, ov, oi.cpu().numpy(), w.C, own_topk_exact=False)
+
+    okq = torch.zeros((w.Hq, w.C, w.D), dtype=k.dtype, device="cuda")
+    ovq = torch.zeros_like(okq)
+    oiq = torch.full((w.Hq, w.C), -1, dtype=torch.int32, device="cuda")
+    assert snapkv.snapkv_compress_per_query_head(q, k, v, w.pool_kind, w.p, w.C, okq, ovq, oiq) == w.C
+    torch.cuda.synchronize()
+    g = w.Hq // w.Hkv
+    for h in range(w.Hq):          # each query head alone is a prompt of one head over its KV head's keys
+        one = run_gpu(snapkv, q[h:h + 1], k[h // g:h // g + 1], v[h // g:h // g + 1], w.pool_kind, w.p, w.C)
+        assert len(set(oiq[h].cpu().numpy().tolist()) ^ set(one[3][0].tolist())) <= 4
+    assert snapkv.snapkv_sync_timeouts() == 0
