@@ -970,8 +970,6 @@ int snapkv_compress_layers(int dtype, int n_layers, const void* const* q_win, co
     // seven arguments) are to the kernels one layer with that many more heads: heads are independent, and
     // a head's result does not depend on how many others the call has.
     const int64_t e = elem_bytes(dtype);
-    const int64_t rows = L <= C ? L : C;   // rows a head writes
-    (void)rows;
     const int64_t dq = (int64_t)Hq * W * D * e, dk = (int64_t)Hkv * L * D * e, dok = (int64_t)Hkv * C * D * e,
                   di = (int64_t)Hkv * C * (int64_t)sizeof(int32_t);
     auto follows = [&](int i) {   // layer i + 1 lies directly behind layer i in all seven tensors
@@ -997,7 +995,8 @@ int snapkv_compress_layers(int dtype, int n_layers, const void* const* q_win, co
         while (i + r < n_layers && r < most && follows(i + r - 1)) ++r;
         if (r == 1 && most_sep > 1) {   // a run of layers none of which lies behind its predecessor
             int t = 1;
-            while (i + t < n_layers && t < most_sep && !follows(i + t - 1) && (i + t + 1 >= n_layers || !follows(i + t))) ++t;
+            // (a layer that starts a stacked run is left to that run)
+            while (i + t < n_layers && t < most_sep && (i + t + 1 >= n_layers || !follows(i + t))) ++t;
             if (t > 1) {
                 ScoreGeom Gt = make_geom(L, Hq * t, Hkv * t, D, W);
                 Gt.k_rs = (int64_t)D * e;
