@@ -139,3 +139,38 @@ def test_separate_layers_of_other_shapes(snapkv, name):
     torch.cuda.synchronize()
     compare(snapkv, w, cases, oks, ovs, ois, oracle_on=(n_layers - 1,))
     assert snapkv.snapkv_sync_timeouts() == 0
+
+
+def _random_layer_shapes(seed, count):
+    import random
+    rng = random.Random(seed)
+    out = []
+    for it in range(count):
+        g = rng.choice([1, 1, 2, 4])
+        Hkv = rng.choice([1, 2, 4, 8])
+        W = rng.choice([8, 16, 32, 32, 48, 64])
+        n = rng.choice([300, 1000, 2049, 4100, 9000])
+        out.append(dict(n_layers=rng.choice([2, 3, 5, 7]), Hq=Hkv * g, Hkv=Hkv, W=W, L=W + n, D=rng.choice([64, 128]),
+                        dtype=rng.choice(["bf16", "f16", "f32"]), pool_kind=rng.choice([0, 1]), p=rng.choice([1, 5, 7, 13]),
+                        C=W + rng.choice([1, max(1, n // 8), max(1, n // 2)]), seed=4200 + it,
+                        mix=rng.choice(["separate", "separate", "stacked", "outputs_separate"])))
+    return out
+
+
+@pytest.mark.parametrize("kw", _random_layer_shapes(5, 24), ids=lambda kw: f"{kw['mix']}_{kw['seed']}")
+def test_random_layer_lists(snapkv, kw):
+    """Layer lists nobody picked by hand (separate allocations, stacked tensors, stacked inputs with separate outputs;
+    head counts, windows, lengths, storage types): every layer equals its own call, the last one the oracle."""
+    kw = dict(kw)
+    n_layers, mix = kw.pop("n_layers"), kw.pop("mix")
+    w, cases = layer_cases(n_layers, **kw)
+    if mix == "separate":
+        q, k, v = ([c[n] for c in cases] for n in ("q_win", "k", "v"))
+        oks, ovs, ois = outputs(w, n_layers, cases[0]["k"].dtype, stack=False)
+    else:
+        q, k, v = (list(stacked(cases, n)) for n in ("q_win", "k", "v"))
+        oks, ovs, ois = outputs(w, n_layers, cases[0]["k"].dtype, stack=mix == "stacked")
+    snapkv.snapkv_compress_layers(q, k, v, w.pool_kind, w.p, w.C, oks, ovs, ois)
+    torch.cuda.synchronize()
+    compare(snapkv, w, [dict(q_win=a, k=b, v=c) for a, b, c in zip(q, k, v)], oks, ovs, ois, oracle_on=(n_layers - 1,))
+    assert snapkv.snapkv_sync_timeouts() == 0

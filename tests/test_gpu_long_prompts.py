@@ -140,3 +140,30 @@ def test_other_entries_on_prompts_beyond_the_single_read_length(few_slots):
         one = run_gpu(snapkv, q[h:h + 1], k[h // g:h // g + 1], v[h // g:h // g + 1], w.pool_kind, w.p, w.C)
         assert len(set(oiq[h].cpu().numpy().tolist()) ^ set(one[3][0].tolist())) <= 4
     assert snapkv.snapkv_sync_timeouts() == 0
+
+
+def _random_long_shapes(seed, count):
+    import random
+    rng = random.Random(seed)
+    out = []
+    for it in range(count):
+        g = rng.choice([1, 1, 2, 4])
+        Hkv = rng.choice([1, 2, 4])
+        W = rng.choice([8, 16, 16, 32, 32, 64, 128, 160])
+        n = rng.choice([4200, 8193, 9000, 12288, 16385, 17000, 20011, 33000])
+        C = W + rng.choice([1, 64, max(1, n // 9), max(1, n // 2), n - 1])
+        out.append(Workload(f"randomlong{seed}_{it}", Hq=Hkv * g, Hkv=Hkv, D=rng.choice([64, 128]), L=W + n, W=W,
+                            pool_kind=rng.choice([0, 1]), p=rng.choice([1, 5, 7, 13]), C=C,
+                            dtype=rng.choice(["bf16", "bf16", "f16", "f32"]), clusters=(2, 6),
+                            radius=rng.choice([1, 4, 9]), seed=3000 + it))
+    return out
+
+
+@pytest.mark.parametrize("w", _random_long_shapes(11, 40), ids=lambda w: w.name)
+def test_random_shapes_with_few_resident_workgroups(few_slots, w):
+    """Shapes nobody picked by hand, with the plans counting 16 resident workgroups: most of them are longer than
+    the single-read launch holds (a front of 4096-16384 keys and a rest; the kept logits with 8- and 16-row windows
+    of one query head per KV head), some fit it, windows of 160 rows take two streaming passes; each against the
+    oracle."""
+    gpu_vs_oracle(few_slots, w)
+    assert few_slots.snapkv_sync_timeouts() == 0
