@@ -167,3 +167,29 @@ def test_random_shapes_with_few_resident_workgroups(few_slots, w):
     oracle."""
     gpu_vs_oracle(few_slots, w)
     assert few_slots.snapkv_sync_timeouts() == 0
+
+
+def test_callers_workspace_and_static_scratch_on_the_long_path(few_slots):
+    """The forms that do not allocate take the same launches: a caller's workspace (sized by
+    snapkv_workspace_bytes, which includes the kept logits of a 16-row window) and the library's static array."""
+    snapkv = few_slots
+    for kw in (dict(L=12000, Hq=4, Hkv=4, C=256), dict(L=20000, W=16, p=5, Hq=4, Hkv=4, C=200)):
+        w = Workload("long_ws", **dict(BASE, **kw))
+        case = workloads.generate(w, device="cuda")
+        q, k, v = case["q_win"], case["k"], case["v"]
+        ref = run_gpu(snapkv, q, k, v, w.pool_kind, w.p, w.C)
+        nbytes = snapkv.snapkv_workspace_bytes(w.L, w.Hq, w.Hkv, w.D, w.W)
+        ws = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+        for _ in range(2):      # the second call finds the workspace as the first left it
+            ok, ov = torch.zeros_like(ref[1]), torch.zeros_like(ref[2])
+            oi = torch.full(ref[3].shape, -1, dtype=torch.int32, device="cuda")
+            assert snapkv.snapkv_compress(q, k, v, w.pool_kind, w.p, w.C, ok, ov, oi, workspace=ws) == w.C
+            torch.cuda.synchronize()
+            assert np.array_equal(oi.cpu().numpy(), ref[3]) and torch.equal(ok, ref[1]) and torch.equal(ov, ref[2])
+        assert nbytes <= snapkv.STATIC_SCRATCH_BYTES
+        ok, ov = torch.zeros_like(ref[1]), torch.zeros_like(ref[2])
+        oi = torch.full(ref[3].shape, -1, dtype=torch.int32, device="cuda")
+        assert snapkv.snapkv_compress_static(q, k, v, w.pool_kind, w.p, w.C, ok, ov, oi) == w.C
+        torch.cuda.synchronize()
+        assert np.array_equal(oi.cpu().numpy(), ref[3]) and torch.equal(ok, ref[1]) and torch.equal(ov, ref[2])
+    assert snapkv.snapkv_sync_timeouts() == 0
