@@ -294,14 +294,19 @@ def run_layers(torch, snapkv, workloads, w, nlay, steps, warmup, dev, stages=Tru
 
     ms = time_steps(torch, step, steps, warmup)
     stage_ms = {}
+    launches_per_step = 1.0
     if stages:
-        snapkv.snapkv_profile_start(max(1, steps))
+        # a step is one call of the entry, which may cut its layers into several runs of launches (its scratch is
+        # capped): the stage times are per step, i.e. summed over the runs
+        snapkv.snapkv_profile_start(min(4096, max(1, steps) * 64))
         for i in range(steps):
             step(i)
-        stage_ms, _ = snapkv.snapkv_profile_stop()
-        stage_ms = {n: v for n, v in stage_ms.items() if v > 0.0}
+        stage_ms, ncalls = snapkv.snapkv_profile_stop()
+        launches_per_step = ncalls / max(1, steps)
+        stage_ms = {n: v * launches_per_step for n, v in stage_ms.items() if v > 0.0}
     torch.cuda.synchronize()
-    return {"ms": ms, "stage_ms": stage_ms, "Q": Q, "K": K, "V": V, "oi": oi, "needles": needles, "step": step}
+    return {"ms": ms, "stage_ms": stage_ms, "Q": Q, "K": K, "V": V, "oi": oi, "needles": needles, "step": step,
+            "launches_per_step": launches_per_step}
 
 
 def run_single(torch, snapkv, workloads, w, nres, steps, warmup, dev, stages=True):
@@ -670,6 +675,7 @@ def bench_layers(args, torch, np, snapkv, workloads, w, dev) -> int:
         print("bench.py: a bounded wait inside a kernel gave up during the timed calls", file=sys.stderr)
         return 1
     ms_per_step = r["ms"]
+    r_runs = round(r["launches_per_step"], 2)
     ms_per_layer = ms_per_step / nlay
     positions = nlay * w.Hkv * w.L
     value = positions / (ms_per_step * 1e-3)
@@ -681,7 +687,7 @@ def bench_layers(args, torch, np, snapkv, workloads, w, dev) -> int:
     path_achieved = nlay * (scan_b + gather_b) / (ms_per_step * 1e-3) / 1e9
     kernel = "+".join(score_names)
     traffic, traffic_note = (None, "not looked up")
-    if nlay == w.layers and args.scheme == 0 and not args.separate_layers:
+    if nlay == w.layers and args.scheme == 0 and not args.separate_layers and r_runs == 1:
         traffic, traffic_note = measured_traffic(w.name, kernel)
     roofline = {
         "bound": "hbm",
@@ -753,6 +759,7 @@ def bench_layers(args, torch, np, snapkv, workloads, w, dev) -> int:
                    "ms_per_layer": round(ms_per_layer, 4), "entry": "compress_layers", "layout": "head_major",
                    "layer_tensors": "separate allocations" if args.separate_layers else "stacked",
                    "resident_layers": nlay, "resident_kv_bytes": 2 * nlay * w.Hkv * w.L * w.D * 2, "scheme": args.scheme,
+                   "runs_of_launches_per_step": r_runs,
                    "needle_kept": needle_kept, "token_layers_per_s": round(nlay * w.L / (ms_per_step * 1e-3), 1)},
         "roofline": roofline,
         "cpu_baseline": cpu,
