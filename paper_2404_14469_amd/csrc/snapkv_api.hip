@@ -259,7 +259,8 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
         Gp.NV = G.g * F.BH;   // one vote row per query head, or per 32-row block of its window
         Gp.VB = F.BH;
     } else if (split_read) {
-        const char* k_rest = static_cast<const char*>(k) + LP.front * G.k_rs;
+        // the rest's key 0 is key `front` of the prompt: an address offset, or (paged K) a logical row offset
+        const char* k_rest = static_cast<const char*>(k) + (G.k_table ? 0 : LP.front * G.k_rs);
         // where a key's window logits are fewer bytes than its K row, the rest's keys are read once too: the
         // statistics pass keeps its logits and the votes come from those
         const bool keep_logits = LP.Fr.RUW == 1 && LP.Fr.gs == 1 && ws.long_logit &&

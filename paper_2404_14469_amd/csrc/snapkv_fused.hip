@@ -325,7 +325,7 @@ __device__ __forceinline__ void score_fused_body(const void* __restrict__ qv, co
     for (int t = 0; t < KT; ++t) {
         int64_t j = ((int64_t)t * TS + tile0) * 16 + n16;
         j = j < G.L ? j : G.L - 1;
-        j = physical_row(G.k_table, G.k_page, G.k_pages, j);
+        j = physical_row(G.k_table, G.k_page, G.k_pages, j + G.k_row0);
         kp[t] = k_head(group / F.split) + j * G.k_rs + kg * 16;
     }
     // Q is shared by the waves: each fetches QPW of the unit's 1 KB chunks (chunk c = row unit c / NP,
@@ -852,7 +852,7 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
     for (int t = 0; t < KT; ++t) {
         int64_t j = ((int64_t)t * TS + tile0) * 16 + n16;
         j = j < G.L ? j : G.L - 1;
-        j = physical_row(G.k_table, G.k_page, G.k_pages, j);
+        j = physical_row(G.k_table, G.k_page, G.k_pages, j + G.k_row0);
         kp[t] = static_cast<const char*>(kv) + (int64_t)(group / F.split) * G.k_hs + j * G.k_rs + kg * 16;
     }
     const char* qp[QPW];
@@ -1374,7 +1374,6 @@ static bool fused_plan_for(int dtype, int D, const ScoreGeom& G, FusedGeom* F) {
 
 // ---- prompts longer than the chip's registers hold: a front part read once, the rest read twice
 bool long_plan(int dtype, int D, const ScoreGeom& G, LongPlan* P) {
-    if (G.k_table) return false;   // the rest starts at a row offset into K: not with paged rows
     int cand[8];
     const int nc = fused_split_candidates(G, cand);
     for (int c = 0; c < nc; ++c) {
@@ -1403,6 +1402,7 @@ bool long_plan(int dtype, int D, const ScoreGeom& G, LongPlan* P) {
         P->Gr = G;
         P->Gr.L = G.L - P->front;
         P->Gr.n = G.n - P->front;
+        if (G.k_table) P->Gr.k_row0 = G.k_row0 + P->front;   // paged rows: the rest starts at a logical row, not at an address
         if (!lse_plan(dtype, D, P->Gr, &P->Fr) || P->Fr.split != P->Ff.split || P->Fr.RUW != P->Ff.RUW) continue;
         return true;
     }

@@ -21,6 +21,7 @@ ScoreGeom make_geom(int64_t L, int Hq, int Hkv, int D, int W) {
     G.k_table = nullptr;
     G.k_page = 1;
     G.k_pages = 0;
+    G.k_row0 = 0;
     return G;
 }
 

@@ -28,6 +28,7 @@ struct ScoreGeom {
     const int32_t* k_table;
     int k_page;
     int64_t k_pages;
+    int64_t k_row0;  // paged K only: logical row of the cache at which this call's key 0 sits (the rest of a long prompt)
 };
 
 // Physical row of logical row j of a possibly paged tensor; page ids outside [0, pages) are clamped
