@@ -113,7 +113,10 @@ int snapkv_pooled_scores_f16(const void* q_win, const void* k, int64_t L, int Hq
 
 /*
  * Bytes of device scratch one call with these shapes needs (0 if the shapes are invalid).
- * The size does not depend on dtype, pooling or C.
+ * The size does not depend on dtype, pooling or C; for prompts longer than the single-read scoring kernel
+ * holds it includes room for the window logits of the keys that kernel does not take (windows of at most
+ * 16 rows with Hq == Hkv), which depends on the compute units of the CURRENT device: ask on the device
+ * the call will run on.
  */
 size_t snapkv_workspace_bytes(int64_t L, int Hq, int Hkv, int D, int W);
 
