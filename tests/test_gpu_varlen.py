@@ -94,3 +94,21 @@ def test_empty_batch_and_bad_prompt(snapkv):
                                       0, 6, 256, oks, ovs, ois)
     torch.cuda.synchronize()
     assert all(int(t.min()) == -7 and int(t.max()) == -7 for t in ois)
+
+
+def test_batch_with_prompts_the_single_read_launch_does_not_hold(snapkv):
+    """With the plans counting 16 resident workgroups the longer prompts of a batch are beyond the single-read
+    launch: inside a batch they take two streaming passes (another rounding than the single call's path, so the
+    reference is the oracle, prompt by prompt)."""
+    snapkv.snapkv_set_scoring_scheme(4)
+    try:
+        ws = prompts([12000, 3000, 20000, 700], C=300)
+        cases, oks, ovs, ois, kept = run_batch(snapkv, ws)
+        for w, c, ok, ov, oi, kp in zip(ws, cases, oks, ovs, ois, kept):
+            sc = torch.empty((w.Hkv, w.n), dtype=torch.float32, device="cuda")
+            snapkv.snapkv_pooled_scores(c["q_win"], c["k"], w.pool_kind, w.p, sc)
+            check_against_oracle(c["q_win"], c["k"], c["v"], w.pool_kind, w.p, w.C, sc.cpu().numpy(), ok, ov,
+                                 oi.cpu().numpy(), kp, own_topk_exact=False)
+        assert snapkv.snapkv_sync_timeouts() == 0
+    finally:
+        snapkv.snapkv_set_scoring_scheme(0)
