@@ -1,5 +1,6 @@
-"""CPU-only sanitizer target: the plain-C oracle and a host-side bounds model of the selection kernel's
-ordered emission, compiled with -fsanitize=address,undefined and run on small inputs.  A memory error or
+"""CPU-only sanitizer target: the plain-C oracle, a host-side bounds model of the selection kernel's
+ordered emission and one of the cut of a long prompt into the part read once and the rest (which keys each launch
+votes on, where the kept logits go), compiled with -fsanitize=address,undefined and run on small inputs.  A memory error or
 undefined behaviour in either ends the program with a non-zero status and a report."""
 import os
 import shutil
@@ -32,5 +33,11 @@ def test_c_oracle_under_address_and_undefined_behaviour_sanitizers(tmp_path):
 
 def test_emission_offsets_model_under_sanitizers(tmp_path):
     r = build_and_run(tmp_path, "emission_model", [os.path.join(ROOT, "tests", "sanitize", "emission_model.c")])
+    assert r.returncode == 0, r.stdout + r.stderr
+    assert "all cases passed" in r.stdout
+
+
+def test_long_prompt_plan_model_under_sanitizers(tmp_path):
+    r = build_and_run(tmp_path, "long_plan_model", [os.path.join(ROOT, "tests", "sanitize", "long_plan_model.c")])
     assert r.returncode == 0, r.stdout + r.stderr
     assert "all cases passed" in r.stdout
