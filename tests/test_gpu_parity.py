@@ -516,3 +516,43 @@ def test_window_lengths_the_kernels_do_not_take_are_refused(snapkv):
     sc = torch.zeros((w.Hkv, w.n), dtype=torch.float32, device="cuda")
     with pytest.raises(snapkv.SnapKVError):
         snapkv.snapkv_pooled_scores(case["q_win"], case["k"], w.pool_kind, w.p, sc)
+
+
+def test_random_sweep_across_schemes(snapkv):
+    """400 more drawn shapes in one test, each under a drawn kernel scheme (single-read or two streaming passes,
+    cooperative or chunked selection, the plans counting 16 resident workgroups or all), each against the oracle;
+    every third one also as a list of separately allocated layers, which must equal the single call bit for bit."""
+    import random
+    rng = random.Random(20240414)
+    for it in range(400):
+        scheme = rng.choice([0, 0, 0, 1, 2, 4, 4, 5, 6])
+        g, Hkv = rng.choice([1, 1, 2, 4, 8]), rng.choice([1, 2, 3, 4, 8])
+        W = rng.choice([1, 2, 7, 8, 15, 16, 17, 31, 32, 33, 48, 64, 96, 128, 160])
+        n = rng.choice([1, 2, 5, 17, 63, 64, 65, 255, 300, 511, 512, 513, 1000, 2047, 2048, 2049, 3000, 4100, 5000, 7001, 9000,
+                        12289, 16400, 20000])
+        C = W + rng.choice([0, 1, 2, max(1, n // 7), max(1, n // 2), max(0, n - 1), n, n + 5])
+        w = Workload(f"sweep{it}", Hq=Hkv * g, Hkv=Hkv, D=rng.choice([64, 128]), L=W + n, W=W, pool_kind=rng.choice([0, 1]),
+                     p=rng.choice([1, 3, 5, 7, 13, 21, 129]), C=C, dtype=rng.choice(["bf16", "bf16", "f16", "f32"]),
+                     clusters=(1, 4), radius=rng.choice([1, 4, 9]), seed=rng.randrange(1 << 30))
+        what = f"case {it}: scheme {scheme}, {w}"
+        snapkv.snapkv_set_scoring_scheme(scheme)
+        try:
+            case = workloads.generate(w, device="cuda")
+            q, k, v = case["q_win"], case["k"], case["v"]
+            res = run_gpu(snapkv, q, k, v, w.pool_kind, w.p, w.C)
+            try:
+                check_against_oracle(q, k, v, w.pool_kind, w.p, w.C, *res, own_topk_exact=(scheme & 1) == 0)
+            except AssertionError as e:
+                raise AssertionError(f"{what}: {e}") from e
+            if w.L > w.C and it % 3 == 0:
+                qs, ks, vs = ([t.clone() for _ in range(2)] for t in (q, k, v))
+                oks, ovs = [torch.zeros_like(res[1]) for _ in range(2)], [torch.zeros_like(res[2]) for _ in range(2)]
+                ois = [torch.full(res[3].shape, -1, dtype=torch.int32, device="cuda") for _ in range(2)]
+                snapkv.snapkv_compress_layers(qs, ks, vs, w.pool_kind, w.p, w.C, oks, ovs, ois)
+                torch.cuda.synchronize()
+                for l in range(2):
+                    assert np.array_equal(ois[l].cpu().numpy(), res[3]), what
+                    assert torch.equal(oks[l], res[1]) and torch.equal(ovs[l], res[2]), what
+        finally:
+            snapkv.snapkv_set_scoring_scheme(0)
+    assert snapkv.snapkv_sync_timeouts() == 0
