@@ -243,8 +243,9 @@ int snapkv_compress_varlen(int dtype, int n_prompts, const void* const* q_win, c
  * Layers whose tensors lie one directly behind the other in memory (slices of stacked [layers, heads, ...]
  * tensors, for q_win, k, v, out_k, out_v and out_idx alike) are taken as they lie; layers that are separate
  * allocations are reached through a table of their addresses, up to 32 of them per run of launches (two-byte
- * element types; prompts the single-read scoring kernel takes whole, windows of at most 32 rows or of 48-128
- * rows in its plain form).  What fits neither is done one layer after the other inside the call.
+ * element types; every prompt length; windows that a single call would not score in 32-row blocks, i.e. of
+ * at most 32 rows, or of 33-128 rows that are not a whole number of such blocks).  What fits neither is done
+ * one layer after the other inside the call.
  *
  *   n_layers >= 0
  *   q_win, k, v, out_k, out_v, out_idx   HOST arrays of n_layers DEVICE pointers, each as the argument of the

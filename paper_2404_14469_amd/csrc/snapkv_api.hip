@@ -191,18 +191,22 @@ int scoring_path(int dtype, int D, const ScoreGeom& G, bool lse_given, bool allo
     return lse_plan(dtype, D, G, F, allow_blocks && !lse_given) ? kPathStream : kPathNone;
 }
 
-// Whether the heads of several separately allocated layers can go through the kernels as one call: the
-// single-read kernel must take the whole prompt in its plain form (no 32-row blocks), in the form that reads
-// its Q and K rows through a table of layers.
+// Whether the heads of several separately allocated layers can go through the kernels as one call: the scoring
+// kernels must take the prompt in their plain form (no 32-row blocks), and the single-read kernel, where it is
+// used, must keep its grid resident in the form that reads its Q and K rows through a table of layers.
 bool layers_table_ok(int dtype, int D, const ScoreGeom& G, int kv_heads_per_layer) {
     FusedGeom F;
     LongPlan LP;
-    if (scoring_path(dtype, D, G, false, false, false, &F, &LP) != kPathFused || F.BH != 1) return false;
+    // (a window that a single call would score in 32-row blocks is left to single calls: the table form has no blocks)
+    const int path = scoring_path(dtype, D, G, false, true, true, &F, &LP);
+    if (path == kPathNone || F.BH != 1) return false;
     ScoreLayers probe{};
     probe.count = G.Hkv / kv_heads_per_layer;
     probe.kv_heads = kv_heads_per_layer;
     if (probe.count < 1 || probe.count > kMaxLayerPtrs) return false;
-    const hipError_t e = launch_score_fused_layers(dtype, D, probe, G, F, FusedSync{}, nullptr, nullptr, true);
+    if (path == kPathStream) return true;   // nothing there needs a resident grid
+    // (for a long prompt F is the plan of the front part)
+    const hipError_t e = launch_score_fused_layers(dtype, D, probe, path == kPathLong ? LP.Gf : G, F, FusedSync{}, nullptr, nullptr, true);
     if (e != hipSuccess) (void)hipGetLastError();
     return e == hipSuccess;
 }
@@ -235,7 +239,7 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
     LongPlan LP;
     const int path = scoring_path(dtype, D, G, false, allow_blocks, allow_long, &F, &LP);
     const bool fused = path == kPathFused, split_read = path == kPathLong;
-    if (layers && !fused) return SNAPKV_ERR_UNSUPPORTED;   // (callers ask layers_table_ok first)
+    if (layers && (path == kPathNone || F.BH != 1)) return SNAPKV_ERR_UNSUPPORTED;   // (callers ask layers_table_ok first)
     FusedSync S;
     if (fused) fused_sync_layout(G, F, &S, ws.fused);
     if (split_read) fused_sync_layout(LP.Gf, F, &S, ws.fused);   // F is the front part's plan
@@ -265,16 +269,25 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
         // statistics pass keeps its logits and the votes come from those
         const bool keep_logits = LP.Fr.RUW == 1 && LP.Fr.gs == 1 && ws.long_logit &&
                                  (size_t)LP.Fr.units * (size_t)long_logit_keys(LP.Fr) * 16 * sizeof(float) <= ws.long_logit_bytes;
+        ScoreLayers rest_layers;   // separately allocated layers: every layer's rest starts `front` rows into its K
+        if (layers) {
+            rest_layers = *layers;
+            for (int x = 0; x < rest_layers.count; ++x)
+                rest_layers.k[x] = static_cast<const char*>(layers->k[x]) + LP.front * G.k_rs;
+        }
+        const ScoreLayers* const rl = layers ? &rest_layers : nullptr;
         if (launch_row_lse(dtype, D, q_win, k_rest, LP.Gr, LP.Fr, ws.stat_part, nullptr, st,
-                           keep_logits ? ws.long_logit : nullptr) != hipSuccess)
+                           keep_logits ? ws.long_logit : nullptr, rl) != hipSuccess)
             return SNAPKV_ERR_HIP;
         if (launch_publish_rest(ws.stat_part, S, LP, st) != hipSuccess) return SNAPKV_ERR_HIP;
         stage_done(st, kStageReduce);
         S.lse_out = ws.lse;
-        if (launch_score_fused(dtype, D, q_win, k, LP.Gf, LP.Ff, S, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        if ((layers ? launch_score_fused_layers(dtype, D, *layers, LP.Gf, LP.Ff, S, ws.vote, st)
+                    : launch_score_fused(dtype, D, q_win, k, LP.Gf, LP.Ff, S, ws.vote, st)) != hipSuccess)
+            return SNAPKV_ERR_HIP;
         stage_done(st, kStageFused);
         if ((keep_logits ? launch_votes_from_logits(ws.long_logit, ws.lse, ws.vote + LP.front, LP, st)
-                         : launch_score_lse(dtype, D, q_win, k_rest, ws.lse, LP.Gr, LP.Fr, ws.vote + LP.front, st)) != hipSuccess)
+                         : launch_score_lse(dtype, D, q_win, k_rest, ws.lse, LP.Gr, LP.Fr, ws.vote + LP.front, st, rl)) != hipSuccess)
             return SNAPKV_ERR_HIP;
         stage_done(st, kStagePass2);
         Gp.NV = G.g;
@@ -282,8 +295,8 @@ int run_scores(int dtype, const void* q_win, const void* k, int D, const ScoreGe
     } else if (path == kPathStream) {
         // two streaming passes over K with nothing handed between workgroups: the rows'
         // log-sum-exp first, then the probabilities from it
-        if (launch_row_lse(dtype, D, q_win, k, G, F, ws.stat_part, ws.lse, st) != hipSuccess) return SNAPKV_ERR_HIP;
-        if (launch_score_lse(dtype, D, q_win, k, ws.lse, G, F, ws.vote, st) != hipSuccess) return SNAPKV_ERR_HIP;
+        if (launch_row_lse(dtype, D, q_win, k, G, F, ws.stat_part, ws.lse, st, nullptr, layers) != hipSuccess) return SNAPKV_ERR_HIP;
+        if (launch_score_lse(dtype, D, q_win, k, ws.lse, G, F, ws.vote, st, layers) != hipSuccess) return SNAPKV_ERR_HIP;
         stage_done(st, kStagePass2);
         Gp.NV = G.g * F.BH;
         Gp.VB = F.BH;
@@ -420,7 +433,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
     // which scoring path run_scores will take, and how many vote rows per query head it leaves
     FusedGeom Fp;
     LongPlan LPp;
-    const int path = scoring_path(dtype, D, G, lse != nullptr, blocks_ok, !score_layers, &Fp, &LPp);
+    const int path = scoring_path(dtype, D, G, lse != nullptr, blocks_ok, true, &Fp, &LPp);
     if (path == kPathNone) return SNAPKV_ERR_UNSUPPORTED;
     if (!per_query_head && (path == kPathFused || path == kPathStream)) {
         Gsel.VB = Fp.BH;
@@ -448,7 +461,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
         }
         ScoreGeom Gv = G;
         rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, nullptr, nullptr, true, &Gv, st, prepared,
-                        mine ? &clean : nullptr, lse, blocks_ok, !score_layers, score_layers);
+                        mine ? &clean : nullptr, lse, blocks_ok, true, score_layers);
         if (rc != SNAPKV_OK) return rc;
         if (per_query_head) Gv = Gsel;
         se = launch_pool_select(Gv, ws.vote, pool_kind, p, C - W, C, W, idx_dst, ws.sel, st);
@@ -468,7 +481,7 @@ int64_t compress_impl(int dtype, const void* q_win, const void* k, const void* v
             stage_done(st, kStagePool);
         } else {
             rc = run_scores(dtype, q_win, k, D, G, ws, pool_kind, p, ws.score, ws.sel.minmax,
-                            true, nullptr, st, false, nullptr, lse, blocks_ok, !score_layers, score_layers);
+                            true, nullptr, st, false, nullptr, lse, blocks_ok, true, score_layers);
             if (rc != SNAPKV_OK) return rc;
         }
         se = launch_select_chunked(ws.score, Hout, G.n, C - W, C, W, idx_dst, ws.sel, pool_tiles(G.n), st);

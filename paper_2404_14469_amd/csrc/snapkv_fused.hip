@@ -817,13 +817,11 @@ __device__ __forceinline__ void lds_barrier() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
 }
 
-template <typename T, int D, int RUW, int KT, int NW, bool STAT>
-__global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv,
-                                                     const void* __restrict__ kv,
-                                                     const float* __restrict__ lse,
-                                                     float* __restrict__ vote,
-                                                     float2* __restrict__ stat_part, const ScoreGeom G,
-                                                     const FusedGeom F) {
+template <typename T, int D, int RUW, int KT, int NW, bool STAT, bool LAYERS>
+__device__ __forceinline__ void score_lse_body(const void* __restrict__ qv, const void* __restrict__ kv,
+                                               const float* __restrict__ lse, float* __restrict__ vote,
+                                               float2* __restrict__ stat_part, const ScoreGeom& G,
+                                               const FusedGeom& F, const ScoreLayers* SL) {
     constexpr int R = RUW * 16;
     constexpr int NT = NW * 64;
     constexpr int ES = esize<T>::value;
@@ -847,13 +845,28 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
     if (nu == 0) return;
     const bool special = ((int64_t)(KT - 1) * TS + tile0 + 1) * 16 > G.n;
 
+    // first K row of KV head h, first Q row of query head qh (LAYERS: as in score_fused_body)
+    auto k_head = [&](const int h) -> const char* {
+        if constexpr (LAYERS)
+            return static_cast<const char*>(SL->k[h / SL->kv_heads]) + (int64_t)(h % SL->kv_heads) * G.k_hs;
+        else
+            return static_cast<const char*>(kv) + (int64_t)h * G.k_hs;
+    };
+    auto q_head = [&](const int qh) -> const char* {
+        if constexpr (LAYERS) {
+            const int per_layer = SL->kv_heads * G.g;
+            return static_cast<const char*>(SL->q[qh / per_layer]) + (int64_t)(qh % per_layer) * G.W * D * ES;
+        } else {
+            return static_cast<const char*>(qv) + (int64_t)qh * G.W * D * ES;
+        }
+    };
     const char* kp[KT];
 #pragma unroll
     for (int t = 0; t < KT; ++t) {
         int64_t j = ((int64_t)t * TS + tile0) * 16 + n16;
         j = j < G.L ? j : G.L - 1;
         j = physical_row(G.k_table, G.k_page, G.k_pages, j + G.k_row0);
-        kp[t] = static_cast<const char*>(kv) + (int64_t)(group / F.split) * G.k_hs + j * G.k_rs + kg * 16;
+        kp[t] = k_head(group / F.split) + j * G.k_rs + kg * 16;
     }
     const char* qp[QPW];
 #pragma unroll
@@ -864,15 +877,24 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
         int head = ru / F.UH, i = (ru % F.UH) * 16 + n16;
         head = head < F.gs ? head : F.gs - 1;
         i = i < G.W ? i : G.W - 1;
-        qp[x] = static_cast<const char*>(qv) + ((int64_t)(group * F.gs + head) * G.W + i) * D * ES + (4 * pc + kg) * 16;
+        qp[x] = q_head(group * F.gs + head) + (int64_t)i * D * ES + (4 * pc + kg) * 16;
     }
     // the window row whose log-sum-exp this thread stages (threads beyond R re-read row 0)
     const int lrow = tid < R ? tid : 0;
     const int lru = lrow >> 4, lhead = lru / F.UH, li = (lru % F.UH) * 16 + (lrow & 15);
     const bool lreal = tid < R && lru < F.RU && lhead < F.gs && li < G.W;
     const float* lp = lse + (int64_t)(group * F.gs + (lhead < F.gs ? lhead : F.gs - 1)) * G.W + (li < G.W ? li : G.W - 1);
-    const int64_t kstep = (int64_t)(F.NG / F.split) * G.k_hs;
-    const int64_t qstep = (int64_t)F.NG * F.gs * G.W * D * ES;
+    // from the rows of the group's unit itn - 1 to those of unit itn (NG is a multiple of split here)
+    const int64_t kstep_even = (int64_t)(F.NG / F.split) * G.k_hs;
+    const int64_t qstep_even = (int64_t)F.NG * F.gs * G.W * D * ES;
+    auto kstep_to = [&](const int itn) -> int64_t {
+        if constexpr (LAYERS) return k_head((group + itn * F.NG) / F.split) - k_head((group + (itn - 1) * F.NG) / F.split);
+        return kstep_even;
+    };
+    auto qstep_to = [&](const int itn) -> int64_t {
+        if constexpr (LAYERS) return q_head((group + itn * F.NG) * F.gs) - q_head((group + (itn - 1) * F.NG) * F.gs);
+        return qstep_even;
+    };
     const int64_t lstep = (int64_t)F.NG * F.gs * G.W;
     constexpr float kLog2e = 1.4426950408889634f;
 
@@ -923,7 +945,7 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
     using ICUA = std::integral_constant<int, KL + (KT - KL + 1) / 2>;
     mfma_tiles(IC0{}, ICL{}, 0);
     __builtin_amdgcn_sched_barrier(0);
-    issue_tiles(IC0{}, ICLA{}, nu > 1 ? kstep : 0);   // unconditional: see score_fused
+    issue_tiles(IC0{}, ICLA{}, nu > 1 ? kstep_to(1) : 0);   // unconditional: see score_fused
     __builtin_amdgcn_sched_barrier(0);
 
 #define SNAPKV_LSE_ISSUE(cond_, what_)                                       \
@@ -937,12 +959,13 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
         constexpr bool kNext1 = (decltype(MODE)::value & 1) != 0;
         constexpr bool kNext2 = (decltype(MODE)::value & 2) != 0;
         const int unit = group + it * F.NG;
+        const int64_t kstep = kNext1 ? kstep_to(it + 1) : 0;
         mfma_tiles(ICL{}, ICT{}, it & 1);
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (kNext1) {   // the next unit's Q chunk and log-sum-exp
 #pragma unroll
             for (int x = 0; x < QPW; ++x) {
-                qp[x] += qstep;
+                qp[x] += qstep_to(it + 1);
                 qland[x] = *reinterpret_cast<const uint4*>(qp[x]);
             }
             if constexpr (!STAT) {
@@ -1113,7 +1136,7 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (kNext1) mfma_tiles(IC0{}, ICL{}, (it + 1) & 1);
         __builtin_amdgcn_sched_barrier(0);
-        if constexpr (kNext2) issue_tiles(IC0{}, ICLA{}, kstep);   // point 3
+        if constexpr (kNext2) issue_tiles(IC0{}, ICLA{}, kstep_to(it + 2));   // point 3
         __builtin_amdgcn_sched_barrier(0);
     };
 #undef SNAPKV_LSE_ISSUE
@@ -1121,6 +1144,24 @@ __global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv
     for (; it + 2 < nu; ++it) iteration(std::integral_constant<int, 3>{}, it);
     for (; it + 1 < nu; ++it) iteration(std::integral_constant<int, 1>{}, it);
     for (; it < nu; ++it) iteration(std::integral_constant<int, 0>{}, it);
+}
+
+template <typename T, int D, int RUW, int KT, int NW, bool STAT>
+__global__ __launch_bounds__(NW * 64) void score_lse(const void* __restrict__ qv,
+                                                     const void* __restrict__ kv,
+                                                     const float* __restrict__ lse,
+                                                     float* __restrict__ vote,
+                                                     float2* __restrict__ stat_part, const ScoreGeom G,
+                                                     const FusedGeom F) {
+    score_lse_body<T, D, RUW, KT, NW, STAT, false>(qv, kv, lse, vote, stat_part, G, F, nullptr);
+}
+
+// The same over the heads of several separately allocated layers (see score_fused_layers).
+template <typename T, int D, int RUW, int KT, int NW, bool STAT>
+__global__ __launch_bounds__(NW * 64) void score_lse_layers(const float* __restrict__ lse, float* __restrict__ vote,
+                                                            float2* __restrict__ stat_part, const ScoreGeom G,
+                                                            const FusedGeom F, const ScoreLayers SL) {
+    score_lse_body<T, D, RUW, KT, NW, STAT, true>(nullptr, nullptr, lse, vote, stat_part, G, F, &SL);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1672,7 +1713,27 @@ struct LseCall {
     float* vote;
     float2* stat_part;
     hipStream_t st;
+    const ScoreLayers* layers = nullptr;   // the heads are those of separately allocated layers (q and k unused)
 };
+
+// The launch over a table of layers (two-byte element types; nothing waits across workgroups, so any grid runs).
+template <typename T, int D, int RUW, int NW, bool STAT>
+static hipError_t lse_layers_instance(const LseCall* call) {
+    constexpr int KT = kFusedSlots / RUW;
+    auto kern = score_lse_layers<T, D, RUW, KT, NW, STAT>;
+    constexpr int kQBytes = 2 * RUW * (D * esize<T>::value / 64) * 64 * 16;
+    static bool ready = false;
+    if (!ready) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kQBytes);
+        if (e != hipSuccess) return e;
+        ready = true;
+    }
+    const FusedGeom& F = *call->F;
+    hipLaunchKernelGGL(kern, dim3(F.NG * F.Gg), dim3(NW * 64), kQBytes, call->st, call->lse, call->vote,
+                       call->stat_part, *call->G, F, *call->layers);
+    return hipGetLastError();
+}
 
 template <typename T, int D, int RUW, int NW, bool STAT>
 static hipError_t lse_instance(const LseCall* call, int* occ) {
@@ -1691,6 +1752,10 @@ static hipError_t lse_instance(const LseCall* call, int* occ) {
     }
     if (occ) *occ = cached_occ;
     if (!call) return hipSuccess;
+    if (call->layers) {
+        if constexpr (esize<T>::value == 2) return lse_layers_instance<T, D, RUW, NW, STAT>(call);
+        else return hipErrorInvalidValue;
+    }
     const FusedGeom& F = *call->F;
     hipLaunchKernelGGL(kern, dim3(F.NG * F.Gg), dim3(NW * 64), kQBytes, call->st, call->q, call->k,
                        call->lse, call->vote, call->stat_part, *call->G, F);
@@ -1783,12 +1848,19 @@ size_t stream_stat_bytes(const ScoreGeom& G) {
     return (most + 255) & ~(size_t)255;
 }
 
+static bool layers_fit(const ScoreLayers* SL, const ScoreGeom& G, const FusedGeom& F) {
+    return !SL || (SL->count >= 1 && SL->count <= kMaxLayerPtrs && SL->kv_heads >= 1 && SL->count * SL->kv_heads == G.Hkv &&
+                   F.BH == 1 && !G.k_table);
+}
+
 hipError_t launch_score_lse(int dtype, int D, const void* q, const void* k, const float* lse,
-                            const ScoreGeom& G, const FusedGeom& F, float* vote, hipStream_t st) {
+                            const ScoreGeom& G, const FusedGeom& F, float* vote, hipStream_t st,
+                            const ScoreLayers* layers) {
     if (G.n <= 0) return hipSuccess;
+    if (!layers_fit(layers, G, F)) return hipErrorInvalidValue;
     ScoreGeom Gl = G;
     if (F.BH > 1 && !block_geom(G, &Gl)) return hipErrorInvalidValue;
-    const LseCall call{q, k, lse, &Gl, &F, vote, nullptr, st};
+    const LseCall call{q, k, lse, &Gl, &F, vote, nullptr, st, layers};
     return lse_dispatch<false>(dtype, D, F.RUW, &call, nullptr);
 }
 
@@ -1850,12 +1922,14 @@ hipError_t launch_votes_from_logits(const float* logit, const float* lse, float*
 }
 
 hipError_t launch_row_lse(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
-                          const FusedGeom& F, float2* stat_part, float* lse_out, hipStream_t st, float* logit_out) {
+                          const FusedGeom& F, float2* stat_part, float* lse_out, hipStream_t st, float* logit_out,
+                          const ScoreLayers* layers) {
     if (G.n <= 0) return hipSuccess;
     if (logit_out && F.RUW != 1) return hipErrorInvalidValue;
+    if (!layers_fit(layers, G, F)) return hipErrorInvalidValue;
     ScoreGeom Gl = G;
     if (F.BH > 1 && !block_geom(G, &Gl)) return hipErrorInvalidValue;
-    const LseCall call{q, k, nullptr, &Gl, &F, logit_out, stat_part, st};
+    const LseCall call{q, k, nullptr, &Gl, &F, logit_out, stat_part, st, layers};
     hipError_t e = lse_dispatch<true>(dtype, D, F.RUW, &call, nullptr);
     if (e != hipSuccess) return e;
     stage_done(st, kStagePass1);

@@ -173,15 +173,17 @@ hipError_t launch_prepare(void* pairs, int64_t npairs, const SelectScratch* S, i
 int64_t fused_sync_pairs(const FusedGeom& F);
 // allow_blocks: as for fused_plan, taken only where a window has more rows than the plain form tracks
 bool lse_plan(int dtype, int D, const ScoreGeom& G, FusedGeom* F, bool allow_blocks = false);
+// layers (may be null; two-byte element types): the heads are those of separately allocated layers, q and k unused
 hipError_t launch_score_lse(int dtype, int D, const void* q, const void* k, const float* lse,
-                            const ScoreGeom& G, const FusedGeom& F, float* vote, hipStream_t st);
+                            const ScoreGeom& G, const FusedGeom& F, float* vote, hipStream_t st,
+                            const ScoreLayers* layers = nullptr);
 size_t stream_stat_bytes(const ScoreGeom& G);
 // lse_out == nullptr: the per-slice statistics only.  logit_out (may be null; plans with one row unit only):
 // the pass also stores its masked logits there, [units][long_logit_keys(F)][16] floats (rows beyond the window
 // hold what the padding produced and are ignored by the reader).
 hipError_t launch_row_lse(int dtype, int D, const void* q, const void* k, const ScoreGeom& G,
                           const FusedGeom& F, float2* stat_part, float* lse_out, hipStream_t st,
-                          float* logit_out = nullptr);
+                          float* logit_out = nullptr, const ScoreLayers* layers = nullptr);
 int64_t long_logit_keys(const FusedGeom& F);
 // Bytes that hold the logits of the rest of any long prompt of this shape on the current device (0: shapes whose
 // logits are not kept: it is then cheaper, or as cheap, to read the rest's keys again).

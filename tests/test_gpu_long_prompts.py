@@ -192,3 +192,37 @@ def test_callers_workspace_and_static_scratch_on_the_long_path(few_slots):
         torch.cuda.synchronize()
         assert np.array_equal(oi.cpu().numpy(), ref[3]) and torch.equal(ok, ref[1]) and torch.equal(ov, ref[2])
     assert snapkv.snapkv_sync_timeouts() == 0
+
+
+@pytest.mark.parametrize("scheme,kw", [
+    (4, dict(L=12000, Hq=4, Hkv=4, C=256)),                           # front and rest, both through the table of layers
+    (4, dict(L=20000, W=16, p=5, Hq=4, Hkv=4, C=200)),                # ... with the rest's kept logits
+    (4, dict(L=11000, Hq=16, Hkv=4, C=300, D=64, dtype="f16")),       # grouped-query heads
+    (1, dict(L=6000, Hq=8, Hkv=4, C=256)),                            # two streaming passes through the table
+], ids=["front_rest", "kept_logits", "gqa_f16_d64", "streaming"])
+def test_separately_allocated_layers_of_long_prompts(snapkv, scheme, kw):
+    """Layers that are allocations of their own share the launches of the long-prompt path too: every layer
+    equals its own call bit for bit, one of them is checked against the oracle."""
+    snapkv.snapkv_set_scoring_scheme(scheme)
+    try:
+        w = Workload("long_sep", **dict(BASE, layers=3, **kw))
+        cases = [workloads.generate(w, layer=l, device="cuda") for l in range(3)]
+        pads = [torch.empty(3000 + 100 * l, device="cuda") for l in range(3)]       # keeps the allocations apart
+        oks = [torch.zeros((w.Hkv, w.C, w.D), dtype=cases[0]["k"].dtype, device="cuda") for _ in range(3)]
+        ovs = [torch.zeros_like(t) for t in oks]
+        ois = [torch.full((w.Hkv, w.C), -1, dtype=torch.int32, device="cuda") for _ in range(3)]
+        snapkv.snapkv_profile_start(16)
+        snapkv.snapkv_compress_layers([c["q_win"] for c in cases], [c["k"] for c in cases], [c["v"] for c in cases],
+                                      w.pool_kind, w.p, w.C, oks, ovs, ois)
+        _, runs = snapkv.snapkv_profile_stop()
+        assert runs == 1, "the three layers were meant to share one run of launches"
+        for l, c in enumerate(cases):
+            ref = run_gpu(snapkv, c["q_win"], c["k"], c["v"], w.pool_kind, w.p, w.C)
+            assert np.array_equal(ois[l].cpu().numpy(), ref[3]), f"layer {l}"
+            assert torch.equal(oks[l], ref[1]) and torch.equal(ovs[l], ref[2]), f"layer {l}"
+        check_against_oracle(c["q_win"], c["k"], c["v"], w.pool_kind, w.p, w.C, ref[0], oks[2], ovs[2],
+                             ois[2].cpu().numpy(), w.C, own_topk_exact=scheme != 1)
+        assert snapkv.snapkv_sync_timeouts() == 0
+        del pads
+    finally:
+        snapkv.snapkv_set_scoring_scheme(0)
