@@ -154,3 +154,48 @@ def test_a_call_on_another_stream_prepares_the_scratch_again(snapkv):
     torch.cuda.synchronize()
     for i in (1, 2):
         assert torch.equal(outs[i][2], outs[0][2]) and torch.equal(outs[i][0], outs[0][0]) and torch.equal(outs[i][1], outs[0][1])
+
+
+def test_long_prompt_path_replays_in_a_graph(snapkv):
+    """The launches of a prompt longer than the single-read launch holds (statistics of the rest, the published
+    word, the single-read kernel on the front, the votes of the rest, selection, gather) are plain kernel launches
+    on the caller's workspace: captured once, replayed on other inputs, every replay equals the eager call."""
+    snapkv.snapkv_set_scoring_scheme(4)
+    try:
+        for kw in (dict(W=32, p=7), dict(W=16, p=5)):        # the second keeps the rest's logits
+            w = Workload("graph_long", Hq=4, Hkv=4, D=128, L=12000 if kw["W"] == 32 else 20000, pool_kind=0, C=384,
+                         dtype="bf16", clusters=(6, 6), radius=6, seed=71, **kw)
+            cases = [workloads.generate(w, layer=l, device="cuda") for l in range(2)]
+            q, k, v = (torch.empty_like(cases[0][n]) for n in ("q_win", "k", "v"))
+            ws = torch.empty(snapkv.snapkv_workspace_bytes(w.L, w.Hq, w.Hkv, w.D, w.W), dtype=torch.uint8, device="cuda")
+            out_k = torch.zeros((w.Hkv, w.C, w.D), dtype=k.dtype, device="cuda")
+            out_v = torch.zeros_like(out_k)
+            out_idx = torch.zeros((w.Hkv, w.C), dtype=torch.int32, device="cuda")
+
+            def load(c):
+                q.copy_(c["q_win"]); k.copy_(c["k"]); v.copy_(c["v"])
+
+            load(cases[0])
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                snapkv.snapkv_compress(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx, workspace=ws)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                snapkv.snapkv_compress(q, k, v, w.pool_kind, w.p, w.C, out_k, out_v, out_idx, workspace=ws)
+            for rep in range(4):
+                c = cases[rep % 2]
+                load(c)
+                out_idx.fill_(-1); out_k.zero_(); out_v.zero_()
+                graph.replay()
+                torch.cuda.synchronize()
+                ek = torch.zeros_like(out_k); ev = torch.zeros_like(out_v); ei = torch.zeros_like(out_idx)
+                snapkv.snapkv_compress(c["q_win"], c["k"], c["v"], w.pool_kind, w.p, w.C, ek, ev, ei)
+                torch.cuda.synchronize()
+                assert torch.equal(out_idx, ei), f"replay {rep}"
+                assert torch.equal(out_k, ek) and torch.equal(out_v, ev), f"replay {rep}"
+        assert snapkv.snapkv_sync_timeouts() == 0
+    finally:
+        snapkv.snapkv_set_scoring_scheme(0)
